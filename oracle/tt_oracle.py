@@ -1,0 +1,175 @@
+"""Python face of the CPU oracle (oracle/tt_emb_oracle.c).
+
+TEST INFRASTRUCTURE ONLY: the tests, the smoke check and the CPU-baseline leg of the benchmark
+may import this module; nothing on the product path does.  It never imports the GPU package.
+
+Two shared objects are built from the one C source with gcc:
+  * ``libtt_oracle_f64.so``  every accumulator is a double; this is the parity reference;
+  * ``libtt_oracle_f32.so``  the same loops with float accumulators; only ever timed.
+Both use OpenMP over batch positions.
+
+Arrays are numpy, cores are fp32 in slice-contiguous layout:
+  g1[n1, d1, r1], g2[n2, r1, d2, r2], g3[n3, r2, d3].
+"""
+from __future__ import annotations
+
+import ctypes
+import os
+import subprocess
+from dataclasses import dataclass
+
+import numpy as np
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+_SRC = os.path.join(_HERE, "tt_emb_oracle.c")
+
+
+class _CShape(ctypes.Structure):
+    _fields_ = [("n", ctypes.c_int64 * 3), ("d", ctypes.c_int32 * 3), ("r", ctypes.c_int32 * 2)]
+
+
+@dataclass(frozen=True)
+class Shape:
+    """Factorisation of the table: N = n1*n2*n3 rows of D = d1*d2*d3 floats, ranks (1, r1, r2, 1)."""
+
+    n: tuple
+    d: tuple
+    r: tuple
+
+    @property
+    def N(self) -> int:
+        return int(self.n[0]) * int(self.n[1]) * int(self.n[2])
+
+    @property
+    def D(self) -> int:
+        return int(self.d[0]) * int(self.d[1]) * int(self.d[2])
+
+    def core_shapes(self):
+        (n1, n2, n3), (d1, d2, d3), (r1, r2) = self.n, self.d, self.r
+        return (n1, d1, r1), (n2, r1, d2, r2), (n3, r2, d3)
+
+    def _c(self) -> _CShape:
+        c = _CShape()
+        for k in range(3):
+            c.n[k] = int(self.n[k])
+            c.d[k] = int(self.d[k])
+        c.r[0], c.r[1] = int(self.r[0]), int(self.r[1])
+        return c
+
+
+def build(force: bool = False) -> None:
+    """Compile both shared objects with gcc (a few seconds)."""
+    for tag, acc in (("f64", "double"), ("f32", "float")):
+        out = os.path.join(_HERE, f"libtt_oracle_{tag}.so")
+        if not force and os.path.exists(out) and os.path.getmtime(out) >= os.path.getmtime(_SRC):
+            continue
+        cmd = ["gcc", "-O3", "-march=native", "-fopenmp", "-fPIC", "-shared", "-std=c11",
+               f"-DTT_ACC={acc}", _SRC, "-o", out]
+        subprocess.run(cmd, check=True)
+
+
+_LIBS: dict = {}
+
+
+def _lib(tag: str):
+    if tag in _LIBS:
+        return _LIBS[tag]
+    build()
+    lib = ctypes.CDLL(os.path.join(_HERE, f"libtt_oracle_{tag}.so"))
+    vp, i64 = ctypes.c_void_p, ctypes.c_int64
+    sp = ctypes.POINTER(_CShape)
+    lib.tto_param_count.restype = i64
+    lib.tto_param_count.argtypes = [sp]
+    lib.tto_decompose.restype = ctypes.c_int
+    lib.tto_decompose.argtypes = [sp, i64] + [ctypes.POINTER(i64)] * 3
+    lib.tto_forward.restype = None
+    lib.tto_forward.argtypes = [sp, vp, vp, vp, vp, i64, vp]
+    lib.tto_forward_acc.restype = None
+    lib.tto_forward_acc.argtypes = [sp, vp, vp, vp, vp, i64, vp]
+    lib.tto_grads.restype = None
+    lib.tto_grads.argtypes = [sp, vp, vp, vp, vp, i64, vp, vp, vp, vp]
+    lib.tto_backward_update.restype = None
+    lib.tto_backward_update.argtypes = [sp, vp, vp, vp, vp, i64, vp, ctypes.c_float]
+    lib.tto_threads.restype = ctypes.c_int
+    lib.tto_acc_bytes.restype = ctypes.c_int
+    _LIBS[tag] = lib
+    return lib
+
+
+def _p(a: np.ndarray):
+    return ctypes.c_void_p(a.ctypes.data)
+
+
+def _check_cores(shape: Shape, g1, g2, g3):
+    for g, cs in zip((g1, g2, g3), shape.core_shapes()):
+        assert g.dtype == np.float32 and g.flags.c_contiguous, "cores are C-contiguous fp32"
+        assert tuple(g.shape) == tuple(cs), (g.shape, cs)
+
+
+def _ids(ids) -> np.ndarray:
+    return np.ascontiguousarray(ids, dtype=np.int64)
+
+
+def threads(tag: str = "f64") -> int:
+    return int(_lib(tag).tto_threads())
+
+
+def param_count(shape: Shape) -> int:
+    c = shape._c()
+    return int(_lib("f64").tto_param_count(ctypes.byref(c)))
+
+
+def decompose(shape: Shape, node_id: int):
+    """(i1, i2, i3) of a node id, or None when the id is outside the table."""
+    c = shape._c()
+    a, b, d = ctypes.c_int64(), ctypes.c_int64(), ctypes.c_int64()
+    ok = _lib("f64").tto_decompose(ctypes.byref(c), int(node_id), ctypes.byref(a), ctypes.byref(b),
+                                   ctypes.byref(d))
+    return (a.value, b.value, d.value) if ok else None
+
+
+def forward(shape: Shape, g1, g2, g3, ids, tag: str = "f64") -> np.ndarray:
+    """Embedding rows out[B, D] in fp32 (accumulated in the build's accumulator type)."""
+    _check_cores(shape, g1, g2, g3)
+    ids = _ids(ids)
+    out = np.empty((ids.size, shape.D), dtype=np.float32)
+    c = shape._c()
+    _lib(tag).tto_forward(ctypes.byref(c), _p(g1), _p(g2), _p(g3), _p(ids), ids.size, _p(out))
+    return out
+
+
+def forward_f64(shape: Shape, g1, g2, g3, ids) -> np.ndarray:
+    """Embedding rows out[B, D] kept in fp64 (no rounding)."""
+    _check_cores(shape, g1, g2, g3)
+    ids = _ids(ids)
+    out = np.empty((ids.size, shape.D), dtype=np.float64)
+    c = shape._c()
+    _lib("f64").tto_forward_acc(ctypes.byref(c), _p(g1), _p(g2), _p(g3), _p(ids), ids.size, _p(out))
+    return out
+
+
+def grads(shape: Shape, g1, g2, g3, ids, grad, tag: str = "f64"):
+    """Core gradients (dG1, dG2, dG3) of L = sum_b <grad_b, row_b>, in the accumulator type."""
+    _check_cores(shape, g1, g2, g3)
+    ids = _ids(ids)
+    grad = np.ascontiguousarray(grad, dtype=np.float32)
+    assert grad.shape == (ids.size, shape.D)
+    dt = np.float64 if tag == "f64" else np.float32
+    dg = [np.empty(cs, dtype=dt) for cs in shape.core_shapes()]
+    c = shape._c()
+    _lib(tag).tto_grads(ctypes.byref(c), _p(g1), _p(g2), _p(g3), _p(ids), ids.size, _p(grad),
+                        _p(dg[0]), _p(dg[1]), _p(dg[2]))
+    return tuple(dg)
+
+
+def backward_update(shape: Shape, g1, g2, g3, ids, grad, lr: float, tag: str = "f64"):
+    """One SGD step; returns NEW core arrays (the inputs are left untouched)."""
+    _check_cores(shape, g1, g2, g3)
+    ids = _ids(ids)
+    grad = np.ascontiguousarray(grad, dtype=np.float32)
+    assert grad.shape == (ids.size, shape.D)
+    n1, n2, n3 = g1.copy(), g2.copy(), g3.copy()
+    c = shape._c()
+    _lib(tag).tto_backward_update(ctypes.byref(c), _p(n1), _p(n2), _p(n3), _p(ids), ids.size,
+                                  _p(grad), ctypes.c_float(lr))
+    return n1, n2, n3

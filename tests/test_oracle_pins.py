@@ -1,0 +1,313 @@
+"""Pins for the CPU oracle: every check here is fixed by the paper or by mathematics, none by the
+oracle's own formulas.  A dropped term, a wrong sign or index, or a transposed operand anywhere in
+oracle/tt_emb_oracle.c fails at least one of them.
+
+  index split      the paper's worked example (48 nodes, id 46), the 10x10x10 sharing pattern,
+                   round trips                                        [Section 3; Section 4.2]
+  forward          element-by-element dense reconstruction from Eq. "tt-embedding" (different loop
+                   structure: scalar triple product per table entry), the Kronecker special case
+                   at ranks (1,1,1,1) against numpy.kron, multilinearity, the rank bound on rows
+                   that share an (i1,i2) prefix                       [Section 3; Section 4.2]
+  sizes            parameter counts and memory reductions of Table "ogb-dim-tt"
+  backward         central finite differences of L in fp64 (exact here, because L is affine in
+                   every single core entry), Euler's identity <dGk, Gk> = L for each core
+  update           lr = 0, untouched slices, G_new - G_old = -lr*dG, affinity in lr
+"""
+import itertools
+import os
+
+import numpy as np
+import pytest
+
+from oracle import tt_oracle as ora
+from oracle.tt_oracle import Shape
+
+GOLDEN = os.path.join(os.path.dirname(__file__), "golden")
+
+
+def _rand_cores(shape, rng, std=1.0):
+    return tuple((rng.standard_normal(cs) * std).astype(np.float32) for cs in shape.core_shapes())
+
+
+def _golden_rows(name):
+    rows = []
+    with open(os.path.join(GOLDEN, name)) as f:
+        for line in f:
+            line = line.strip()
+            if line and not line.startswith("#"):
+                rows.append(line.split())
+    return rows
+
+
+# ----------------------------------------------------------------------------- index split
+
+def test_worked_index_example_and_its_factorisation():
+    (nodes, node_id, i1, i2, i3), = [[int(x) for x in r] for r in _golden_rows("index_example.txt")]
+    # enumerate every ordered factorisation of 48 into three factors; exactly one reproduces the
+    # printed coordinate, so the example pins both the formula and the (unprinted) factors
+    hits = []
+    for m1, m2 in itertools.product(range(1, nodes + 1), repeat=2):
+        if nodes % (m1 * m2):
+            continue
+        m3 = nodes // (m1 * m2)
+        got = ora.decompose(Shape((m1, m2, m3), (1, 1, 1), (1, 1)), node_id)
+        if got == (i1, i2, i3):
+            hits.append((m1, m2, m3))
+    assert hits == [(3, 4, 4)]
+
+
+def test_sharing_pattern_of_the_1000_node_figure():
+    # Fig. "node-index": 10x10x10; ten consecutive ids share (i1,i2), a hundred share i1
+    s = Shape((10, 10, 10), (2, 2, 2), (4, 4))
+    coords = [ora.decompose(s, i) for i in range(1000)]
+    for base in range(0, 1000, 10):
+        assert len({c[:2] for c in coords[base:base + 10]}) == 1
+        assert [c[2] for c in coords[base:base + 10]] == list(range(10))
+    for base in range(0, 1000, 100):
+        assert len({c[0] for c in coords[base:base + 100]}) == 1
+    assert len({c[:2] for c in coords}) == 100
+
+
+@pytest.mark.parametrize("n", [(3, 4, 4), (10, 10, 10), (7, 3, 5), (480, 480, 482)])
+def test_index_round_trip_and_range(n):
+    s = Shape(n, (1, 1, 1), (1, 1))
+    N = s.N
+    probe = list(range(min(N, 300))) + [N - 1, N // 2, N - n[2], N - n[2] - 1]
+    for i in probe:
+        i1, i2, i3 = ora.decompose(s, i)
+        assert 0 <= i1 < n[0] and 0 <= i2 < n[1] and 0 <= i3 < n[2]
+        assert (i1 * n[1] + i2) * n[2] + i3 == i          # Eq. "tt-embedding": i = sum i_p prod m_q
+    assert ora.decompose(s, N) is None and ora.decompose(s, -1) is None
+
+
+# ----------------------------------------------------------------------------- forward
+
+def dense_table_elementwise(shape, g1, g2, g3):
+    """W(i, j) = G1(:,i1,j1,:) G2(:,i2,j2,:) G3(:,i3,j3,:) entry by entry, in fp64, from cores put
+    back into the paper's index order (R_{k-1}, m_k, n_k, R_k)."""
+    (n1, n2, n3), (d1, d2, d3) = shape.n, shape.d
+    G1 = g1.astype(np.float64)[None]                                               # (1,n1,d1,r1)
+    G2 = np.transpose(g2.astype(np.float64), (1, 0, 2, 3))                          # (r1,n2,d2,r2)
+    G3 = np.transpose(g3.astype(np.float64), (1, 0, 2))[..., None]                  # (r2,n3,d3,1)
+    W = np.zeros((shape.N, shape.D))
+    for i1 in range(n1):
+        for i2 in range(n2):
+            for i3 in range(n3):
+                i = (i1 * n2 + i2) * n3 + i3
+                for j1 in range(d1):
+                    row = G1[:, i1, j1, :]                      # 1 x r1
+                    for j2 in range(d2):
+                        mat = G2[:, i2, j2, :]                  # r1 x r2
+                        for j3 in range(d3):
+                            col = G3[:, i3, j3, :]              # r2 x 1
+                            j = (j1 * d2 + j2) * d3 + j3
+                            W[i, j] = (row @ mat @ col)[0, 0]
+    return W
+
+
+@pytest.mark.parametrize("n,d,r", [((3, 4, 4), (2, 3, 2), (3, 5)), ((5, 2, 3), (1, 2, 4), (2, 2)),
+                                   ((4, 4, 4), (2, 2, 2), (4, 4))])
+def test_forward_equals_dense_table_small(n, d, r):
+    s = Shape(n, d, r)
+    rng = np.random.default_rng(1)
+    g = _rand_cores(s, rng)
+    W = dense_table_elementwise(s, *g)
+    ids = rng.permutation(s.N)
+    out = ora.forward_f64(s, *g, ids)
+    np.testing.assert_allclose(out, W[ids], rtol=1e-12, atol=1e-13)
+    out32 = ora.forward(s, *g, ids)
+    np.testing.assert_array_equal(out32, W[ids].astype(np.float32))
+
+
+def test_forward_equals_dense_table_config1_in_full():
+    # the tiny benchmark configuration, all 1000 x 8 entries
+    s = Shape((10, 10, 10), (2, 2, 2), (4, 4))
+    rng = np.random.default_rng(2)
+    g = _rand_cores(s, rng, 0.1)
+    W = dense_table_elementwise(s, *g)
+    out = ora.forward_f64(s, *g, np.arange(s.N))
+    np.testing.assert_allclose(out, W, rtol=1e-12, atol=1e-15)
+
+
+def test_kronecker_special_case():
+    # ranks (1,1,1,1): W = G1 (x) G2 (x) G3 with Gk the n_k x d_k matrices
+    s = Shape((4, 3, 5), (2, 3, 2), (1, 1))
+    rng = np.random.default_rng(3)
+    g1, g2, g3 = _rand_cores(s, rng)
+    K = np.kron(np.kron(g1[:, :, 0].astype(np.float64), g2[:, 0, :, 0].astype(np.float64)),
+                g3[:, 0, :].astype(np.float64))
+    out = ora.forward_f64(s, g1, g2, g3, np.arange(s.N))
+    np.testing.assert_allclose(out, K, rtol=1e-13, atol=0)
+
+
+def test_forward_is_multilinear_in_the_cores():
+    s = Shape((3, 4, 4), (2, 2, 3), (3, 2))
+    rng = np.random.default_rng(4)
+    g1, g2, g3 = _rand_cores(s, rng)
+    ids = np.arange(s.N)
+    base = ora.forward_f64(s, g1, g2, g3, ids)
+    # powers of two scale fp32 inputs exactly
+    np.testing.assert_allclose(ora.forward_f64(s, g1, g2 * np.float32(4), g3, ids), 4 * base, rtol=1e-14)
+    np.testing.assert_allclose(ora.forward_f64(s, g1 * np.float32(.5), g2, g3 * np.float32(8), ids),
+                               4 * base, rtol=1e-14)
+    h1 = _rand_cores(s, rng)[0]
+    summed = ora.forward_f64(s, g1, g2, g3, ids) + ora.forward_f64(s, h1, g2, g3, ids)
+    both = ora.forward_f64(s, (g1.astype(np.float64) + h1).astype(np.float32), g2, g3, ids)
+    np.testing.assert_allclose(both, summed, rtol=1e-5, atol=1e-6)   # g1+h1 is rounded to fp32
+
+
+def test_rows_sharing_a_prefix_have_rank_at_most_r2():
+    # Section 4.2: ids in [i - i3, i + m3 - i3) are one fixed (d1 d2 x r2) matrix times G3[i3]
+    s = Shape((3, 3, 9), (2, 3, 4), (3, 2))
+    rng = np.random.default_rng(5)
+    g = _rand_cores(s, rng)
+    out = ora.forward_f64(s, *g, np.arange(s.N))
+    for q in range(s.n[0] * s.n[1]):
+        block = out[q * s.n[2]:(q + 1) * s.n[2]]                      # n3 rows, D columns
+        stacked = block.reshape(s.n[2], s.d[0] * s.d[1], s.d[2])
+        stacked = np.transpose(stacked, (1, 0, 2)).reshape(s.d[0] * s.d[1], -1)
+        sv = np.linalg.svd(stacked, compute_uv=False)
+        assert (sv > 1e-10 * sv[0]).sum() <= s.r[1]
+
+
+def test_duplicate_and_out_of_range_ids():
+    s = Shape((3, 4, 4), (2, 2, 2), (2, 3))
+    rng = np.random.default_rng(6)
+    g = _rand_cores(s, rng)
+    ids = np.array([5, 5, 47, -1, 48, 0, 5], dtype=np.int64)
+    out = ora.forward(s, *g, ids)
+    np.testing.assert_array_equal(out[0], out[1])
+    np.testing.assert_array_equal(out[0], out[6])
+    assert not out[3].any() and not out[4].any() and out[2].any()
+
+
+# ----------------------------------------------------------------------------- sizes
+
+def test_parameter_counts_and_memory_reduction_table():
+    for row in _golden_rows("param_counts.txt"):
+        name, nodes, dim = row[0], int(row[1]), int(row[2])
+        m1, n1, m2, n2, m3, n3 = [int(x) for x in row[3:9]]
+        params = [int(x) for x in row[9:12]]
+        reductions = [int(x) for x in row[12:15]]
+        assert n1 * n2 * n3 == dim and m1 * m2 * m3 >= nodes
+        for R, p_ref, red_ref in zip((16, 32, 64), params, reductions):
+            p = ora.param_count(Shape((m1, m2, m3), (n1, n2, n3), (R, R)))
+            assert p == p_ref, (name, R)
+            # the products row of the printed table is consistent with width 128, not its listed
+            # 100 (2,449,029*128/198,400 = 1580); the other two rows use their listed width
+            width = 128 if name == "ogbn-products" else dim
+            assert abs(nodes * width / p - red_ref) < 1.0, (name, R)
+    # unequal inner ranks: sum_k R_{k-1} m_k n_k R_k written out
+    assert ora.param_count(Shape((3, 4, 5), (2, 3, 2), (3, 5))) == 1 * 3 * 2 * 3 + 3 * 4 * 3 * 5 + 5 * 5 * 2 * 1
+    # "81,362x" for papers100M at rank 8 (Section 5)
+    p8 = ora.param_count(Shape((480, 500, 500), (8, 4, 4), (8, 8)))
+    assert abs(111059956 * 128 / p8 - 81362) < 1.0
+
+
+# ----------------------------------------------------------------------------- backward
+
+def _loss(shape, g, ids, grad):
+    return float((ora.forward_f64(shape, *g, ids) * grad.astype(np.float64)).sum())
+
+
+@pytest.mark.parametrize("n,d,r", [((3, 4, 4), (2, 3, 2), (3, 5)), ((10, 10, 10), (2, 2, 2), (4, 4))])
+def test_gradients_against_central_differences(n, d, r):
+    s = Shape(n, d, r)
+    rng = np.random.default_rng(7)
+    g = list(_rand_cores(s, rng, 0.5))
+    # duplicates, shared prefixes, shared i3, and ids that are never drawn
+    ids = np.concatenate([rng.integers(0, s.N, 40), [7, 7, 7, 8, 9, 7 + s.n[2]], [-3, s.N]])
+    grad = rng.standard_normal((ids.size, s.D)).astype(np.float32)
+    dg = ora.grads(s, *g, ids, grad)
+    h = np.float32(0.25)                       # exactly representable; L is affine in each entry
+    for k in range(3):
+        flat = g[k].reshape(-1)
+        num = np.zeros(flat.size)
+        for e in range(flat.size):
+            keep = flat[e]
+            flat[e] = keep + h
+            xp = float(flat[e])                # the fp32 value actually stored
+            up = _loss(s, g, ids, grad)
+            flat[e] = keep - h
+            xm = float(flat[e])
+            dn = _loss(s, g, ids, grad)
+            flat[e] = keep
+            num[e] = (up - dn) / (xp - xm)
+        scale = np.abs(num).max()
+        np.testing.assert_allclose(dg[k].reshape(-1), num, rtol=0, atol=1e-9 * scale)
+
+
+@pytest.mark.parametrize("cfg", [1, 2])
+def test_euler_identity_on_benchmark_shapes(cfg):
+    # L is linear in each core separately, hence <dGk, Gk> = L for k = 1, 2, 3
+    import workloads as wl
+    w = wl.CONFIGS[cfg]
+    s = Shape(w.n, w.d, w.r)
+    B = min(w.batch, 4000)
+    g = wl.make_cores(w, cfg)
+    ids = wl.make_ids(w, cfg, B)
+    grad = wl.make_grads(w, cfg, B)
+    L = _loss(s, g, ids, grad)
+    dg = ora.grads(s, *g, ids, grad)
+    for k in range(3):
+        assert abs(float((dg[k] * g[k].astype(np.float64)).sum()) - L) <= 1e-10 * max(1.0, abs(L))
+
+
+def test_gradient_of_duplicates_adds():
+    s = Shape((3, 4, 4), (2, 2, 2), (2, 3))
+    rng = np.random.default_rng(8)
+    g = _rand_cores(s, rng)
+    ids = np.array([11, 11, 11], dtype=np.int64)
+    grad = rng.standard_normal((3, s.D)).astype(np.float32)
+    a = ora.grads(s, *g, ids, grad)
+    b = ora.grads(s, *g, ids[:1], grad.astype(np.float64).sum(0, keepdims=True).astype(np.float32))
+    for x, y in zip(a, b):
+        np.testing.assert_allclose(x, y, rtol=1e-6, atol=1e-7)   # the summed grad is rounded to fp32
+
+
+# ----------------------------------------------------------------------------- update
+
+def test_update_properties():
+    s = Shape((5, 4, 6), (2, 2, 3), (3, 4))
+    rng = np.random.default_rng(9)
+    g = _rand_cores(s, rng)
+    ids = np.array([0, 1, 1, 30, 31, 7, 7, 7], dtype=np.int64)        # touches i1 in {0,1} only
+    grad = rng.standard_normal((ids.size, s.D)).astype(np.float32)
+    lr = np.float32(0.01)
+
+    same = ora.backward_update(s, *g, ids, grad, 0.0)
+    for a, b in zip(same, g):
+        np.testing.assert_array_equal(a, b)                           # lr = 0: bit-identical
+
+    new = ora.backward_update(s, *g, ids, grad, float(lr))
+    dg = ora.grads(s, *g, ids, grad)
+    coords = [ora.decompose(s, int(i)) for i in ids]
+    for k in range(3):
+        touched = sorted({c[k] for c in coords})
+        untouched = [x for x in range(s.n[k]) if x not in touched]
+        np.testing.assert_array_equal(new[k][untouched], g[k][untouched])
+        assert all(np.any(new[k][t] != g[k][t]) for t in touched)
+        want = (g[k].astype(np.float64) - float(lr) * dg[k]).astype(np.float32)
+        np.testing.assert_array_equal(new[k], want)                   # G_new = G_old - lr*dG
+
+    twice = ora.backward_update(s, *g, ids, grad, float(np.float32(2) * lr))
+    for k in range(3):
+        d1 = new[k].astype(np.float64) - g[k]
+        d2 = twice[k].astype(np.float64) - g[k]
+        np.testing.assert_allclose(d2, 2 * d1, rtol=0, atol=4e-7 * np.abs(g[k]).max())
+
+
+def test_f32_build_agrees_with_f64_build():
+    # the timed build is the same loops with float accumulators
+    import workloads as wl
+    w = wl.CONFIGS[1]
+    s = Shape(w.n, w.d, w.r)
+    g = wl.make_cores(w, 1)
+    ids = wl.make_ids(w, 1)
+    grad = wl.make_grads(w, 1)
+    np.testing.assert_allclose(ora.forward(s, *g, ids, tag="f32"), ora.forward(s, *g, ids),
+                               rtol=1e-5, atol=1e-7)
+    a = ora.backward_update(s, *g, ids, grad, w.lr, tag="f32")
+    b = ora.backward_update(s, *g, ids, grad, w.lr)
+    for x, y in zip(a, b):
+        np.testing.assert_allclose(x, y, rtol=1e-5, atol=1e-7)

@@ -1,0 +1,125 @@
+"""Seeded synthetic inputs for the TT-embedding path.
+
+This module holds no arithmetic of the method: it only draws shapes, node ids, core values and
+upstream gradients.  The same arrays feed the CPU oracle and the GPU library.
+
+The five workloads stand in for the graphs the paper trains on (ogbn-arxiv, ogbn-products,
+ogbn-papers100M), which are not available here: table shapes are those graphs' node counts rounded
+to near-cubes, embedding widths and TT ranks are the paper's, and the id streams imitate a sampled
+minibatch (uniform with replacement), a degree-skewed minibatch (bounded Zipf over a random
+relabelling) and a partition-ordered minibatch (draws clustered in contiguous id blocks).
+"""
+from __future__ import annotations
+
+import math
+from dataclasses import dataclass, field
+
+import numpy as np
+
+
+@dataclass(frozen=True)
+class Workload:
+    name: str
+    n: tuple          # node factors (n1, n2, n3)
+    d: tuple          # embedding-dimension factors (d1, d2, d3)
+    r: tuple          # inner TT ranks (r1, r2)
+    batch: int        # rows per step, duplicates counted
+    ids: str          # "uniform" | "zipf_perm" | "zipf_affine" | "clusters"
+    zipf_s: float = 0.0
+    init_std: float = 0.0
+    lr: float = 0.01
+    extra: dict = field(default_factory=dict)
+
+    @property
+    def N(self) -> int:
+        return self.n[0] * self.n[1] * self.n[2]
+
+    @property
+    def D(self) -> int:
+        return self.d[0] * self.d[1] * self.d[2]
+
+    def core_shapes(self):
+        (n1, n2, n3), (d1, d2, d3), (r1, r2) = self.n, self.d, self.r
+        return (n1, d1, r1), (n2, r1, d2, r2), (n3, r2, d3)
+
+
+CONFIGS = {
+    1: Workload("c1_tiny_1k_r4", (10, 10, 10), (2, 2, 2), (4, 4), 256, "uniform", init_std=0.1),
+    2: Workload("c2_175k_r16", (56, 56, 56), (4, 4, 4), (16, 16), 50_000, "uniform",
+                init_std=1 / math.sqrt(16)),
+    3: Workload("c3_2p5m_r32_zipf1.1", (136, 136, 136), (4, 4, 8), (32, 32), 200_000, "zipf_perm",
+                zipf_s=1.1, init_std=1 / math.sqrt(32)),
+    4: Workload("c4_111m_r16_zipf1.0", (480, 480, 482), (4, 4, 8), (16, 16), 500_000,
+                "zipf_affine", zipf_s=1.0, init_std=1 / math.sqrt(16)),
+    5: Workload("c5_111m_r64_clusters", (480, 480, 482), (4, 4, 8), (64, 64), 500_000, "clusters",
+                init_std=1 / math.sqrt(64), extra={"blocks": 500, "block_len": 1000}),
+}
+
+
+def bounded_zipf_ranks(rng: np.random.Generator, N: int, s: float, size: int) -> np.ndarray:
+    """Ranks in [0, N) with P(rank k) proportional to (k+1)^-s, by inverting the exact CDF."""
+    w = np.arange(1, N + 1, dtype=np.float64)
+    np.power(w, -s, out=w)
+    np.cumsum(w, out=w)
+    w /= w[-1]
+    ranks = np.searchsorted(w, rng.random(size), side="left")
+    return np.minimum(ranks, N - 1).astype(np.int64)
+
+
+def make_ids(w: Workload, seed: int, batch: int | None = None) -> np.ndarray:
+    """int64 node ids of one minibatch."""
+    B = w.batch if batch is None else batch
+    rng = np.random.default_rng(seed)
+    N = w.N
+    if w.ids == "uniform":
+        return rng.integers(0, N, size=B, dtype=np.int64)
+    if w.ids == "zipf_perm":
+        ranks = bounded_zipf_ranks(rng, N, w.zipf_s, B)
+        perm = rng.permutation(N)
+        return perm[ranks].astype(np.int64)
+    if w.ids == "zipf_affine":
+        ranks = bounded_zipf_ranks(rng, N, w.zipf_s, B)
+        # id = (a*rank + c) mod N with gcd(a, N) = 1: a bijection that scatters hot ranks
+        a = int(rng.integers(N // 3, N // 2))
+        while math.gcd(a, N) != 1:
+            a += 1
+        c = int(rng.integers(0, N))
+        assert N < 2**31  # ranks*a stays far below 2^63
+        return ((ranks * a + c) % N).astype(np.int64)
+    if w.ids == "clusters":
+        blocks, blen = w.extra["blocks"], w.extra["block_len"]
+        per = B // blocks
+        starts = rng.integers(0, N - blen + 1, size=blocks, dtype=np.int64)
+        offs = rng.integers(0, blen, size=(blocks, per), dtype=np.int64)
+        ids = (starts[:, None] + offs).reshape(-1)
+        if ids.size < B:  # B not a multiple of the block count: top up from the last block
+            extra = starts[-1] + rng.integers(0, blen, size=B - ids.size, dtype=np.int64)
+            ids = np.concatenate([ids, extra])
+        return ids.astype(np.int64)
+    raise ValueError(w.ids)
+
+
+def make_cores(w: Workload, seed: int):
+    """fp32 cores g1[n1,d1,r1], g2[n2,r1,d2,r2], g3[n3,r2,d3], i.i.d. N(0, init_std^2)."""
+    rng = np.random.default_rng(seed + 7919)
+    return tuple((rng.standard_normal(cs, dtype=np.float32) * np.float32(w.init_std))
+                 for cs in w.core_shapes())
+
+
+def make_grads(w: Workload, seed: int, batch: int | None = None) -> np.ndarray:
+    """fp32 upstream gradients grad[B, D], i.i.d. N(0, 1)."""
+    B = w.batch if batch is None else batch
+    rng = np.random.default_rng(seed + 104729)
+    return rng.standard_normal((B, w.D), dtype=np.float32)
+
+
+def batch_structure(w: Workload, ids: np.ndarray) -> dict:
+    """Counts that describe a batch: unique ids U, unique (i1,i2) prefixes Q, hottest multiplicity."""
+    ids = np.asarray(ids, dtype=np.int64)
+    ok = ids[(ids >= 0) & (ids < w.N)]
+    u, cnt = np.unique(ok, return_counts=True)
+    q = np.unique(u // w.n[2])
+    return {"B": int(ids.size), "U": int(u.size), "Q": int(q.size),
+            "max_multiplicity": int(cnt.max()) if cnt.size else 0,
+            "i1": int(np.unique(q // w.n[1]).size), "i2": int(np.unique(q % w.n[1]).size),
+            "i3": int(np.unique(u % w.n[2]).size)}
