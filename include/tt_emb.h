@@ -1,0 +1,126 @@
+/*
+ * tt_emb.h - C ABI of the MI355X (gfx950) tensor-train embedding library.
+ *
+ * The library implements the minibatch hot path of TT-compressed node embeddings:
+ *   forward          ids -> rows of the table W, W[i,:] = G1[i1] G2[i2] G3[i3]
+ *                    (paper: Section 3, Eq. "tt-embedding" and the paragraph after it that
+ *                    evaluates a row by d-1 = 2 matrix products over unfolded core slices;
+ *                    Section 4.2 for the split i1 = i/(n2 n3), i2 = (i/n3) mod n2, i3 = i mod n3)
+ *   backward_update  dL/drows -> gradients of the three cores, summed over the batch, followed by
+ *                    the parameter update on the device (paper: Section 5, the "bwd" and "upd"
+ *                    phases of the timing breakdown; the paper prints no formula and names no
+ *                    optimiser, so this is the chain rule through the two products and plain SGD)
+ *
+ * Naming.  The table has N = n1*n2*n3 rows (paper: M = m1 m2 m3) of D = d1*d2*d3 floats
+ * (paper: N = n1 n2 n3); the TT ranks are (1, r1, r2, 1) (paper: R_0..R_3 with R_0 = R_3 = 1).
+ *
+ * Core storage (defined by this library).  fp32, each slice contiguous and stored as the
+ * unfolding matrix that the row construction multiplies:
+ *   g1[n1][d1][r1]        G1[i1] is d1 x r1            paper G_1(0, i1, j1, a)
+ *   g2[n2][r1][d2][r2]    G2[i2] is r1 x (d2*r2)       paper G_2(a, i2, j2, b)
+ *   g3[n3][r2][d3]        G3[i3] is r2 x d3            paper G_3(b, i3, j3, 0)
+ * Output column order is j = (j1*d2 + j2)*d3 + j3 (Eq. "tt-embedding").
+ *
+ * Memory.  Every pointer named "device" is HIP device memory owned by the caller; the library
+ * borrows it and never allocates or frees device memory.  The handle owns host bookkeeping only.
+ * All calls are asynchronous on the given HIP stream unless stated otherwise.  A handle must not
+ * be used from two threads or two streams at once.
+ *
+ * Errors.  Every function returns TT_EMB_OK (0) or a negative code and never aborts.
+ */
+#ifndef TT_EMB_H
+#define TT_EMB_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef struct tt_emb* tt_emb_t; /* opaque handle */
+
+enum {
+  TT_EMB_OK = 0,
+  TT_EMB_EINVAL = -1,    /* null pointer, non-positive factor, unsupported size, B < 0          */
+  TT_EMB_ENOSPC = -2,    /* B > max_batch, or the workspace is smaller than workspace_bytes()   */
+  TT_EMB_ESTATE = -3,    /* backward_update without a pending forward                           */
+  TT_EMB_EHIP = -4,      /* a HIP call failed; tt_emb_strerror(code) carries HIP's message      */
+  TT_EMB_ERANGE = -5,    /* get_stats only: some id of the last batch was outside [0, N)        */
+  TT_EMB_EINTERNAL = -6  /* get_stats only: a kernel met an index it could not have produced    */
+};
+
+enum {
+  TT_EMB_FLAG_CHECK_RANGE = 1u /* get_stats returns TT_EMB_ERANGE when an id was out of range */
+};
+
+typedef struct {
+  int64_t n[3];      /* node factors n1,n2,n3 (paper m_k); N = n1*n2*n3 must be below 2^31;
+                        n2 and n3 at most 2048                                                  */
+  int32_t d[3];      /* embedding-dimension factors d1,d2,d3 (paper n_k); D = d1*d2*d3 <= 4096  */
+  int32_t r[2];      /* inner TT ranks r1, r2 (paper R_1, R_2)                                  */
+  int64_t max_batch; /* upper bound on B, sizes the workspace; 1 <= max_batch < 2^30            */
+  int32_t device;    /* HIP device ordinal the buffers live on                                  */
+  uint32_t flags;    /* TT_EMB_FLAG_*                                                           */
+} tt_emb_config;
+
+/* Bytes of device workspace that tt_emb_create needs for this configuration. */
+int tt_emb_workspace_bytes(const tt_emb_config* cfg, size_t* bytes);
+
+/*
+ * Creates a handle over caller-owned cores (device, layout above, updated in place by
+ * backward_update) and a caller-owned workspace (device, at least workspace_bytes(), 256-byte
+ * aligned).  Both must stay alive until tt_emb_destroy.  Host-only: enqueues nothing.
+ */
+int tt_emb_create(tt_emb_t* out, const tt_emb_config* cfg, float* g1, float* g2, float* g3,
+                  void* workspace, size_t workspace_bytes);
+
+/*
+ * Forward (Section 3, Eq. "tt-embedding"; Section 4.2).  ids: device int64[B]; out: device
+ * fp32[B][D], row-major.  Row b receives the embedding of ids[b]; repeated ids give repeated rows;
+ * an id outside [0, N) gives a zero row and takes no part in the backward pass.  0 <= B <=
+ * max_batch; B = 0 is a no-op.  The index structures and prefix products G1[i1] G2[i2] of this
+ * batch are kept in the workspace for the next backward_update; ids may be released once the
+ * stream has passed this call.  hip_stream is a hipStream_t (0 = the null stream).
+ */
+int tt_emb_forward(tt_emb_t h, const int64_t* ids, int64_t B, float* out, void* hip_stream);
+
+/*
+ * Backward and update (Section 5, phases "bwd" and "upd").  grad_out: device fp32[B][D] for the
+ * batch of the latest forward.  Forms dG1, dG2, dG3 of L = sum_b <grad_out[b], out[b]> from the
+ * cores as they are when the call starts (all positions add, no averaging), then applies
+ * Gk[s] <- Gk[s] - lr*dGk[s] to every slice s the batch touches; other slices are not written.
+ * Sums are formed in a fixed order: the same inputs give bit-identical cores.  Consumes the
+ * pending forward (a second call without a new forward returns TT_EMB_ESTATE).
+ */
+int tt_emb_backward_update(tt_emb_t h, const float* grad_out, float lr, void* hip_stream);
+
+/*
+ * Counters of the latest forward: U = distinct in-range ids, Q = distinct (i1,i2) prefixes,
+ * out_of_range = number of ids outside [0, N).  Any pointer may be null.  Synchronises the stream
+ * of that forward.  Returns TT_EMB_ERANGE (flag CHECK_RANGE set and out_of_range > 0) or
+ * TT_EMB_EINTERNAL after filling the outputs.
+ */
+int tt_emb_get_stats(tt_emb_t h, int64_t* U, int64_t* Q, int64_t* out_of_range);
+
+/*
+ * Per-kernel timing for benchmarks.  While enabled, every kernel launch is bracketed by a pair of
+ * HIP events on the launch stream (this slows a step down; never enable it inside a throughput
+ * measurement).  tt_emb_profile_read synchronises, then reports for kernel slot k (0 <= k < n,
+ * n = return value of tt_emb_profile_slots) its name, the number of launches and their summed
+ * duration in milliseconds since profiling was enabled or last read; it then resets the sums.
+ */
+int tt_emb_profile_enable(tt_emb_t h, int enable);
+int tt_emb_profile_slots(void);
+int tt_emb_profile_read(tt_emb_t h, int slot, const char** name, int64_t* launches, double* ms);
+
+/* Frees the handle (host memory only). */
+int tt_emb_destroy(tt_emb_t h);
+
+/* Static description of a code; for TT_EMB_EHIP the text of the most recent HIP failure. */
+const char* tt_emb_strerror(int code);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* TT_EMB_H */

@@ -1,0 +1,377 @@
+// C ABI of libtt_emb.so: argument checks, workspace carving, launch sequences, timing slots.
+#include <algorithm>
+#include <cstdio>
+#include <cstring>
+#include <new>
+#include <string>
+#include <vector>
+
+#include "tt_emb_internal.h"
+
+namespace ttemb {
+
+// launchers defined next to their kernels
+void launch_sort_pass(const Plan&, const Workspace&, const int64_t* ids, int B, int pass, hipStream_t,
+                      int which);
+void launch_seg_count(const Plan&, const Workspace&, int B, hipStream_t);
+void launch_seg_write(const Plan&, const Workspace&, int B, hipStream_t);
+void launch_group(const Plan&, const Workspace&, int B, hipStream_t);
+void launch_prefix_fwd(const Plan&, const Workspace&, const float* g1, const float* g2, int B,
+                       hipStream_t);
+void launch_row_fwd(const Plan&, const Workspace&, const float* g3, int B, float* out, hipStream_t);
+void launch_gsum(const Plan&, const Workspace&, const float* grad, int B, hipStream_t);
+void launch_gsum_fix(const Plan&, const Workspace&, int B, hipStream_t);
+void launch_u_bwd(const Plan&, const Workspace&, const float* g3, const float* grad, int B,
+                  hipStream_t);
+void launch_dg3(const Plan&, const Workspace&, const float* grad, int B, hipStream_t);
+void launch_prefix_bwd(const Plan&, const Workspace&, const float* g1, const float* g2, int B,
+                       hipStream_t);
+void launch_sgd(const Plan&, const Workspace&, float* g1, float* g2, float* g3, float lr,
+                hipStream_t);
+
+static const char* const kSlotNames[kSlotCount] = {
+    "sort_hist", "sort_scatter", "seg_count", "seg_write", "group",      "prefix_fwd", "row_fwd",
+    "gsum",      "gsum_fix",     "u_bwd",     "dg3",       "prefix_bwd", "sgd"};
+
+static thread_local std::string g_hip_error = "HIP call failed";
+
+static inline int64_t cdiv64(int64_t a, int64_t b) { return (a + b - 1) / b; }
+
+static int bits_for(uint32_t v) {  // number of bits needed to write v (at least 1)
+  int b = 1;
+  while ((v >> b) != 0 && b < 32) ++b;
+  return b;
+}
+
+static int make_plan(const tt_emb_config* c, Plan* pl) {
+  if (c == nullptr) return TT_EMB_EINVAL;
+  for (int k = 0; k < 3; ++k)
+    if (c->n[k] <= 0 || c->d[k] <= 0 || c->n[k] >= (int64_t(1) << 31) || c->d[k] > 4096)
+      return TT_EMB_EINVAL;
+  if (c->r[0] <= 0 || c->r[1] <= 0 || c->r[0] > 4096 || c->r[1] > 4096) return TT_EMB_EINVAL;
+  if (c->max_batch < 1 || c->max_batch >= (int64_t(1) << 30)) return TT_EMB_EINVAL;
+  const int64_t n12 = c->n[0] * c->n[1];
+  if (n12 >= (int64_t(1) << 31)) return TT_EMB_EINVAL;
+  const int64_t N = n12 * c->n[2];
+  if (N >= (int64_t(1) << 31)) return TT_EMB_EINVAL;
+  if (c->n[1] > kMaxBins || c->n[2] > kMaxBins) return TT_EMB_EINVAL;
+  const int64_t D = (int64_t)c->d[0] * c->d[1] * c->d[2];
+  if (D > 4096) return TT_EMB_EINVAL;
+  const int64_t S2 = (int64_t)c->r[0] * c->d[1] * c->r[1];
+  const int64_t PN = (int64_t)c->d[0] * c->d[1] * c->r[1];
+  if (S2 > (1 << 24) || PN > (1 << 24)) return TT_EMB_EINVAL;
+
+  Shape& s = pl->sh;
+  s.n1 = (uint32_t)c->n[0];
+  s.n2 = (uint32_t)c->n[1];
+  s.n3 = (uint32_t)c->n[2];
+  s.N = (uint32_t)N;
+  s.d1 = c->d[0];
+  s.d2 = c->d[1];
+  s.d3 = c->d[2];
+  s.r1 = c->r[0];
+  s.r2 = c->r[1];
+  s.M = s.d1 * s.d2;
+  s.W = s.d2 * s.r2;
+  s.PN = s.d1 * s.W;
+  s.D = (int)D;
+  s.S1 = s.d1 * s.r1;
+  s.S2 = s.r1 * s.W;
+  s.S3 = s.r2 * s.d3;
+
+  pl->maxB = c->max_batch;
+  pl->maxQ = std::min<int64_t>(c->max_batch, n12);
+  pl->sortBlocksMax = (int)cdiv64(pl->maxB, kSortItems);
+  pl->segBlocksMax = (int)cdiv64(pl->maxB, kSegItems);
+  pl->uBlocksMax = (int)cdiv64(pl->maxB, kSortItems);
+  pl->qBlocksMax = (int)cdiv64(pl->maxQ, kSortItems);
+  pl->tilesMax = (int)cdiv64(pl->maxB, kTileSlots);
+  pl->maxChunk3 = cdiv64(pl->maxB, kChunk3) + s.n3;
+  pl->maxChunk2 = cdiv64(pl->maxQ, kChunk2) + s.n2;
+  pl->keyBits = bits_for(s.N);  // the sentinel N itself must be representable
+  pl->passes = (pl->keyBits + 10) / 11;
+  pl->bitsPerPass = (pl->keyBits + pl->passes - 1) / pl->passes;
+  pl->bits2 = bits_for(s.n2 - 1);
+  pl->bits3 = bits_for(s.n3 - 1);
+  return TT_EMB_OK;
+}
+
+// Walks the workspace layout; with base == nullptr only the size is computed.
+static size_t carve(const Plan& pl, char* base, Workspace* ws) {
+  size_t off = 0;
+  auto take = [&](size_t bytes) -> char* {
+    char* p = base ? base + off : nullptr;
+    off += (bytes + 255) & ~size_t(255);
+    return p;
+  };
+  const Shape& s = pl.sh;
+  const size_t mB = (size_t)pl.maxB, mQ = (size_t)pl.maxQ;
+  Workspace w;
+  w.ctr = (Counters*)take(sizeof(Counters));
+  for (int k = 0; k < 2; ++k) w.key[k] = (uint32_t*)take(mB * 4);
+  for (int k = 0; k < 2; ++k) w.val[k] = (uint32_t*)take(mB * 4);
+  w.cnt = (uint32_t*)take((size_t)pl.sortBlocksMax * kMaxBins * 4);
+  w.seg_nu = (uint32_t*)take((size_t)pl.segBlocksMax * 4);
+  w.seg_nq = (uint32_t*)take((size_t)pl.segBlocksMax * 4);
+  w.s_u = (int*)take(mB * 4);
+  w.u_rs = (int*)take((mB + 1) * 4);
+  w.u_i3 = (int*)take(mB * 4);
+  w.u_q = (int*)take(mB * 4);
+  w.q_us = (int*)take((mQ + 1) * 4);
+  w.q_i1 = (int*)take(mQ * 4);
+  w.q_i2 = (int*)take(mQ * 4);
+  w.cnt3 = (uint32_t*)take((size_t)pl.uBlocksMax * s.n3 * 4);
+  w.cnt2 = (uint32_t*)take((size_t)pl.qBlocksMax * s.n2 * 4);
+  w.g3_list = (int*)take(mB * 4);
+  w.g3_start = (int*)take(((size_t)s.n3 + 1) * 4);
+  w.c3_start = (int*)take(((size_t)s.n3 + 1) * 4);
+  w.g2_list = (int*)take(mQ * 4);
+  w.g2_start = (int*)take(((size_t)s.n2 + 1) * 4);
+  w.c2_start = (int*)take(((size_t)s.n2 + 1) * 4);
+  w.P = (float*)take(mQ * s.PN * 4);
+  w.gsum = (float*)take(mB * s.D * 4);
+  w.carry = (float*)take((size_t)pl.tilesMax * 2 * s.D * 4);
+  w.dPsum = (float*)take(mQ * s.PN * 4);
+  w.dg1part = (float*)take(mQ * s.S1 * 4);
+  w.part3 = (float*)take((size_t)pl.maxChunk3 * s.S3 * 4);
+  w.part2 = (float*)take((size_t)pl.maxChunk2 * s.S2 * 4);
+  if (ws) *ws = w;
+  return off;
+}
+
+struct EventPair {
+  int slot;
+  hipEvent_t a, b;
+};
+
+}  // namespace ttemb
+
+using namespace ttemb;
+
+struct tt_emb {
+  tt_emb_config cfg;
+  Plan plan;
+  Workspace ws;
+  float *g1, *g2, *g3;
+  int64_t pending_B;  // -1: no forward pending
+  int64_t last_B;     // batch size of the latest forward
+  bool have_forward;
+  hipStream_t last_stream;
+  bool profiling;
+  std::vector<EventPair> events;
+  int64_t prof_launches[kSlotCount];
+  double prof_ms[kSlotCount];
+};
+
+static int hip_fail(hipError_t e) {
+  g_hip_error = std::string("HIP: ") + hipGetErrorString(e);
+  return TT_EMB_EHIP;
+}
+
+// Runs one launcher; with profiling on, brackets it with events on the same stream.
+template <class F>
+static int run_slot(tt_emb* h, int slot, hipStream_t st, F&& f) {
+  EventPair ev{slot, nullptr, nullptr};
+  if (h->profiling) {
+    hipError_t e = hipEventCreate(&ev.a);
+    if (e != hipSuccess) return hip_fail(e);
+    e = hipEventCreate(&ev.b);
+    if (e != hipSuccess) return hip_fail(e);
+    e = hipEventRecord(ev.a, st);
+    if (e != hipSuccess) return hip_fail(e);
+  }
+  f();
+  hipError_t e = hipGetLastError();
+  if (e != hipSuccess) return hip_fail(e);
+  if (h->profiling) {
+    e = hipEventRecord(ev.b, st);
+    if (e != hipSuccess) return hip_fail(e);
+    h->events.push_back(ev);
+  }
+  return TT_EMB_OK;
+}
+
+static int drain_events(tt_emb* h) {
+  int rc = TT_EMB_OK;
+  for (EventPair& ev : h->events) {
+    hipError_t e = hipEventSynchronize(ev.b);
+    float ms = 0.f;
+    if (e == hipSuccess) e = hipEventElapsedTime(&ms, ev.a, ev.b);
+    if (e == hipSuccess) {
+      h->prof_ms[ev.slot] += ms;
+      h->prof_launches[ev.slot] += 1;
+    } else {
+      rc = hip_fail(e);
+    }
+    (void)hipEventDestroy(ev.a);
+    (void)hipEventDestroy(ev.b);
+  }
+  h->events.clear();
+  return rc;
+}
+
+extern "C" {
+
+int tt_emb_workspace_bytes(const tt_emb_config* cfg, size_t* bytes) {
+  Plan pl;
+  int rc = make_plan(cfg, &pl);
+  if (rc != TT_EMB_OK) return rc;
+  if (bytes == nullptr) return TT_EMB_EINVAL;
+  *bytes = carve(pl, nullptr, nullptr);
+  return TT_EMB_OK;
+}
+
+int tt_emb_create(tt_emb_t* out, const tt_emb_config* cfg, float* g1, float* g2, float* g3,
+                  void* workspace, size_t workspace_bytes) {
+  if (out == nullptr || g1 == nullptr || g2 == nullptr || g3 == nullptr || workspace == nullptr)
+    return TT_EMB_EINVAL;
+  Plan pl;
+  int rc = make_plan(cfg, &pl);
+  if (rc != TT_EMB_OK) return rc;
+  if (((uintptr_t)workspace & 255u) != 0) return TT_EMB_EINVAL;
+  if (workspace_bytes < carve(pl, nullptr, nullptr)) return TT_EMB_ENOSPC;
+  tt_emb* h = new (std::nothrow) tt_emb();
+  if (h == nullptr) return TT_EMB_EINVAL;
+  h->cfg = *cfg;
+  h->plan = pl;
+  carve(pl, (char*)workspace, &h->ws);
+  h->g1 = g1;
+  h->g2 = g2;
+  h->g3 = g3;
+  h->pending_B = -1;
+  h->last_B = 0;
+  h->have_forward = false;
+  h->last_stream = nullptr;
+  h->profiling = false;
+  std::memset(h->prof_launches, 0, sizeof(h->prof_launches));
+  std::memset(h->prof_ms, 0, sizeof(h->prof_ms));
+  *out = h;
+  return TT_EMB_OK;
+}
+
+int tt_emb_forward(tt_emb_t h, const int64_t* ids, int64_t B64, float* out, void* hip_stream) {
+  if (h == nullptr || B64 < 0) return TT_EMB_EINVAL;
+  if (B64 > h->plan.maxB) return TT_EMB_ENOSPC;
+  hipStream_t st = (hipStream_t)hip_stream;
+  h->last_stream = st;
+  if (B64 == 0) {
+    h->pending_B = 0;
+    h->have_forward = false;
+    return TT_EMB_OK;
+  }
+  if (ids == nullptr || out == nullptr) return TT_EMB_EINVAL;
+  const int B = (int)B64;
+  const Plan& pl = h->plan;
+  const Workspace& ws = h->ws;
+  h->pending_B = -1;
+  int rc;
+  for (int pass = 0; pass < pl.passes; ++pass) {
+    rc = run_slot(h, kSlotSortHist, st, [&] { launch_sort_pass(pl, ws, ids, B, pass, st, 0); });
+    if (rc) return rc;
+    rc = run_slot(h, kSlotSortScatter, st, [&] { launch_sort_pass(pl, ws, ids, B, pass, st, 1); });
+    if (rc) return rc;
+  }
+  rc = run_slot(h, kSlotSegCount, st, [&] { launch_seg_count(pl, ws, B, st); });
+  if (rc) return rc;
+  rc = run_slot(h, kSlotSegWrite, st, [&] { launch_seg_write(pl, ws, B, st); });
+  if (rc) return rc;
+  rc = run_slot(h, kSlotGroup, st, [&] { launch_group(pl, ws, B, st); });
+  if (rc) return rc;
+  rc = run_slot(h, kSlotPrefixFwd, st, [&] { launch_prefix_fwd(pl, ws, h->g1, h->g2, B, st); });
+  if (rc) return rc;
+  rc = run_slot(h, kSlotRowFwd, st, [&] { launch_row_fwd(pl, ws, h->g3, B, out, st); });
+  if (rc) return rc;
+  h->pending_B = B;
+  h->last_B = B;
+  h->have_forward = true;
+  return TT_EMB_OK;
+}
+
+int tt_emb_backward_update(tt_emb_t h, const float* grad_out, float lr, void* hip_stream) {
+  if (h == nullptr) return TT_EMB_EINVAL;
+  if (h->pending_B < 0) return TT_EMB_ESTATE;
+  const int B = (int)h->pending_B;
+  h->pending_B = -1;
+  if (B == 0) return TT_EMB_OK;
+  if (grad_out == nullptr) return TT_EMB_EINVAL;
+  hipStream_t st = (hipStream_t)hip_stream;
+  const Plan& pl = h->plan;
+  const Workspace& ws = h->ws;
+  int rc;
+  rc = run_slot(h, kSlotGsum, st, [&] { launch_gsum(pl, ws, grad_out, B, st); });
+  if (rc) return rc;
+  rc = run_slot(h, kSlotGsumFix, st, [&] { launch_gsum_fix(pl, ws, B, st); });
+  if (rc) return rc;
+  rc = run_slot(h, kSlotUBwd, st, [&] { launch_u_bwd(pl, ws, h->g3, grad_out, B, st); });
+  if (rc) return rc;
+  rc = run_slot(h, kSlotDg3, st, [&] { launch_dg3(pl, ws, grad_out, B, st); });
+  if (rc) return rc;
+  rc = run_slot(h, kSlotPrefixBwd, st, [&] { launch_prefix_bwd(pl, ws, h->g1, h->g2, B, st); });
+  if (rc) return rc;
+  rc = run_slot(h, kSlotSgd, st, [&] { launch_sgd(pl, ws, h->g1, h->g2, h->g3, lr, st); });
+  return rc;
+}
+
+int tt_emb_get_stats(tt_emb_t h, int64_t* U, int64_t* Q, int64_t* out_of_range) {
+  if (h == nullptr) return TT_EMB_EINVAL;
+  Counters c;
+  std::memset(&c, 0, sizeof(c));
+  int64_t oob = 0;
+  if (h->have_forward) {
+    hipError_t e = hipStreamSynchronize(h->last_stream);
+    if (e != hipSuccess) return hip_fail(e);
+    e = hipMemcpy(&c, h->ws.ctr, sizeof(c), hipMemcpyDeviceToHost);
+    if (e != hipSuccess) return hip_fail(e);
+    oob = h->last_B - (int64_t)c.nvalid;
+  }
+  if (U) *U = c.U;
+  if (Q) *Q = c.Q;
+  if (out_of_range) *out_of_range = oob;
+  if (c.err != 0) return TT_EMB_EINTERNAL;
+  if ((h->cfg.flags & TT_EMB_FLAG_CHECK_RANGE) && oob > 0) return TT_EMB_ERANGE;
+  return TT_EMB_OK;
+}
+
+int tt_emb_profile_enable(tt_emb_t h, int enable) {
+  if (h == nullptr) return TT_EMB_EINVAL;
+  int rc = drain_events(h);
+  h->profiling = enable != 0;
+  std::memset(h->prof_launches, 0, sizeof(h->prof_launches));
+  std::memset(h->prof_ms, 0, sizeof(h->prof_ms));
+  return rc;
+}
+
+int tt_emb_profile_slots(void) { return kSlotCount; }
+
+int tt_emb_profile_read(tt_emb_t h, int slot, const char** name, int64_t* launches, double* ms) {
+  if (h == nullptr || slot < 0 || slot >= kSlotCount) return TT_EMB_EINVAL;
+  int rc = drain_events(h);
+  if (name) *name = kSlotNames[slot];
+  if (launches) *launches = h->prof_launches[slot];
+  if (ms) *ms = h->prof_ms[slot];
+  h->prof_launches[slot] = 0;
+  h->prof_ms[slot] = 0.0;
+  return rc;
+}
+
+int tt_emb_destroy(tt_emb_t h) {
+  if (h == nullptr) return TT_EMB_EINVAL;
+  (void)drain_events(h);
+  delete h;
+  return TT_EMB_OK;
+}
+
+const char* tt_emb_strerror(int code) {
+  switch (code) {
+    case TT_EMB_OK: return "ok";
+    case TT_EMB_EINVAL: return "invalid argument (null pointer, non-positive or unsupported size)";
+    case TT_EMB_ENOSPC: return "batch larger than max_batch, or workspace too small";
+    case TT_EMB_ESTATE: return "backward_update without a pending forward";
+    case TT_EMB_EHIP: return g_hip_error.c_str();
+    case TT_EMB_ERANGE: return "an id of the last batch was outside [0, N)";
+    case TT_EMB_EINTERNAL: return "internal error: a kernel met an impossible index";
+    default: return "unknown error code";
+  }
+}
+
+}  // extern "C"

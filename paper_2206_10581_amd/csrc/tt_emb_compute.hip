@@ -1,0 +1,418 @@
+// Arithmetic kernels of the TT-embedding path for any table shape (gfx950, fp32 on the vector ALUs).
+//
+// Forward (paper Section 3, the row construction after Eq. "tt-embedding"):
+//   P_q = G1[i1] G2[i2]            once per distinct (i1,i2) prefix q, kept for the backward pass
+//   E_u = reshape(P_q) G3[i3]      once per run of equal ids inside a tile of sorted slots,
+//                                  written to every batch position that holds the id
+// Backward (chain rule through the two products) and update (plain SGD):
+//   g_u     = sum of grad_out over the positions of unique id u
+//   dPsum_q = sum over u in q of g_u G3[i3(u)]^T
+//   dG3[i3] = sum over u with that i3 of P_q(u)^T g_u         (chunked partial sums)
+//   dG1[i1] = sum over q with that i1 of dPsum_q G2[i2(q)]^T  (one term per q)
+//   dG2[i2] = sum over q with that i2 of G1[i1(q)]^T dPsum_q  (chunked partial sums)
+//   Gk[s]  -= lr * dGk[s] for touched slices, after every gradient has been formed
+// Every sum runs over a list whose order the index pipeline fixed, so results are reproducible
+// bit for bit.
+#include <algorithm>
+
+#include "tt_emb_internal.h"
+
+namespace ttemb {
+
+constexpr int kThreads = 256;
+constexpr int kWavesPerBlock = kThreads / kWave;
+
+__device__ __forceinline__ void flag_error(Counters* ctr, int bit) { atomicOr(&ctr->err, bit); }
+
+// Gradient row of unique id u: the batch row itself when the id occurs once, else its sum.
+__device__ __forceinline__ const float* grad_of_unique(int u, const int* __restrict__ u_rs,
+                                                       const uint32_t* __restrict__ perm,
+                                                       const float* __restrict__ grad,
+                                                       const float* __restrict__ gsum, int D) {
+  const int rs = u_rs[u];
+  return (u_rs[u + 1] - rs == 1) ? grad + (size_t)perm[rs] * D : gsum + (size_t)u * D;
+}
+
+// ---------------------------------------------------------------------------------------------
+// forward
+
+// P_q = A * Bm, A = G1[i1] (d1 x r1), Bm = G2[i2] (r1 x d2*r2).  Prefixes are visited in by-i2
+// order so that neighbouring blocks read the same G2 slice.
+__global__ __launch_bounds__(kThreads) void k_prefix_fwd(Shape sh, const float* __restrict__ g1,
+                                                         const float* __restrict__ g2,
+                                                         const int* __restrict__ g2_list,
+                                                         const int* __restrict__ q_i1,
+                                                         const int* __restrict__ q_i2,
+                                                         float* __restrict__ P,
+                                                         const Counters* __restrict__ ctr) {
+  const int Q = ctr->Q;
+  for (int k = blockIdx.x; k < Q; k += gridDim.x) {
+    const int q = g2_list[k];
+    const float* A = g1 + (size_t)q_i1[q] * sh.S1;
+    const float* Bm = g2 + (size_t)q_i2[q] * sh.S2;
+    float* Pq = P + (size_t)q * sh.PN;
+    for (int o = threadIdx.x; o < sh.PN; o += kThreads) {
+      const int j1 = o / sh.W, col = o % sh.W;
+      float acc = 0.f;
+      for (int a = 0; a < sh.r1; ++a) acc = fmaf(A[j1 * sh.r1 + a], Bm[a * sh.W + col], acc);
+      Pq[o] = acc;
+    }
+  }
+}
+
+// One wavefront per tile of kTileSlots sorted slots: E = reshape(P_q) * G3[i3] when the id changes,
+// then one row store per slot.  Out-of-range ids get zero rows.
+__global__ __launch_bounds__(kThreads) void k_row_fwd(Shape sh, int B, const float* __restrict__ g3,
+                                                      const float* __restrict__ P,
+                                                      const int* __restrict__ s_u,
+                                                      const uint32_t* __restrict__ perm,
+                                                      const int* __restrict__ u_i3,
+                                                      const int* __restrict__ u_q,
+                                                      float* __restrict__ out, Counters* ctr) {
+  extern __shared__ float lds[];
+  const int w = threadIdx.x / kWave, lane = threadIdx.x % kWave;
+  float* E = lds + (size_t)w * sh.D;
+  const int ntiles = (B + kTileSlots - 1) / kTileSlots;
+  for (int tile = blockIdx.x * kWavesPerBlock + w; tile < ntiles;
+       tile += gridDim.x * kWavesPerBlock) {
+    const int s1 = min((tile + 1) * kTileSlots, B);
+    int cur = -2;
+    for (int s = tile * kTileSlots; s < s1; ++s) {
+      const int u = s_u[s];
+      const uint32_t b = perm[s];
+      if (b >= (uint32_t)B) {
+        flag_error(ctr, 1);
+        continue;
+      }
+      float* o = out + (size_t)b * sh.D;
+      if (u < 0) {
+        for (int e = lane; e < sh.D; e += kWave) o[e] = 0.f;
+        continue;
+      }
+      if (u != cur) {
+        cur = u;
+        const float* Pq = P + (size_t)u_q[u] * sh.PN;
+        const float* C = g3 + (size_t)u_i3[u] * sh.S3;
+        for (int e = lane; e < sh.D; e += kWave) {
+          const int m = e / sh.d3, j3 = e % sh.d3;
+          float acc = 0.f;
+          for (int c = 0; c < sh.r2; ++c) acc = fmaf(Pq[m * sh.r2 + c], C[c * sh.d3 + j3], acc);
+          E[e] = acc;
+        }
+      }
+      for (int e = lane; e < sh.D; e += kWave) o[e] = E[e];
+    }
+  }
+}
+
+// ---------------------------------------------------------------------------------------------
+// backward
+
+// Sums grad_out over runs of equal ids, one wavefront per tile of sorted slots.  A run inside one
+// tile is finished here; a run that crosses tiles leaves one partial per tile in carry[tile][h]
+// (h = 0: the run began in an earlier tile, h = 1: it begins here and continues).
+__global__ __launch_bounds__(kThreads) void k_gsum(Shape sh, int B, const float* __restrict__ grad,
+                                                   const int* __restrict__ s_u,
+                                                   const uint32_t* __restrict__ perm,
+                                                   const int* __restrict__ u_rs,
+                                                   float* __restrict__ gsum,
+                                                   float* __restrict__ carry, Counters* ctr) {
+  extern __shared__ float lds[];
+  const int w = threadIdx.x / kWave, lane = threadIdx.x % kWave;
+  float* acc = lds + (size_t)w * sh.D;
+  const int D = sh.D;
+  const int ntiles = (B + kTileSlots - 1) / kTileSlots;
+  for (int tile = blockIdx.x * kWavesPerBlock + w; tile < ntiles;
+       tile += gridDim.x * kWavesPerBlock) {
+    const int t0 = tile * kTileSlots, t1 = t0 + kTileSlots;
+    const int s1 = min(t1, B);
+    int cur = -2;  // no run open (-1 is the marker of an out-of-range slot)
+    for (int s = t0; s <= s1; ++s) {
+      const int u = (s < s1) ? s_u[s] : -1;
+      if (u != cur) {
+        if (cur >= 0) {  // close the run of cur
+          const int rs = u_rs[cur], re = u_rs[cur + 1];
+          if (rs >= t0 && re <= t1) {
+            if (re - rs > 1)
+              for (int e = lane; e < D; e += kWave) gsum[(size_t)cur * D + e] = acc[e];
+          } else {
+            float* c = carry + ((size_t)tile * 2 + (rs < t0 ? 0 : 1)) * D;
+            for (int e = lane; e < D; e += kWave) c[e] = acc[e];
+          }
+        }
+        if (u < 0) break;  // out-of-range ids fill the tail of the sorted order
+        cur = u;
+        for (int e = lane; e < D; e += kWave) acc[e] = 0.f;
+      }
+      const uint32_t b = perm[s];
+      if (b >= (uint32_t)B) {
+        flag_error(ctr, 2);
+        continue;
+      }
+      const float* g = grad + (size_t)b * D;
+      for (int e = lane; e < D; e += kWave) acc[e] += g[e];
+    }
+  }
+}
+
+// Finishes the runs that cross tiles: the tile in which such a run begins adds up its partials in
+// tile order.
+__global__ __launch_bounds__(kThreads) void k_gsum_fix(Shape sh, const int* __restrict__ s_u,
+                                                       const int* __restrict__ u_rs,
+                                                       const float* __restrict__ carry,
+                                                       float* __restrict__ gsum,
+                                                       const Counters* __restrict__ ctr) {
+  const int nvalid = ctr->nvalid, D = sh.D;
+  const int ntiles = (nvalid + kTileSlots - 1) / kTileSlots;
+  for (int tile = blockIdx.x; tile < ntiles; tile += gridDim.x) {
+    const int t0 = tile * kTileSlots, t1 = t0 + kTileSlots;
+    const int u = s_u[min(t1, nvalid) - 1];
+    const int rs = u_rs[u], re = u_rs[u + 1];
+    if (rs < t0 || re <= t1) continue;
+    const int tl = (re - 1) / kTileSlots;
+    for (int e = threadIdx.x; e < D; e += kThreads) {
+      float a = carry[((size_t)tile * 2 + 1) * D + e];
+      for (int t = tile + 1; t <= tl; ++t) a += carry[((size_t)t * 2) * D + e];
+      gsum[(size_t)u * D + e] = a;
+    }
+  }
+}
+
+// dPsum_q = sum over the unique ids u of prefix q of g_u * G3[i3(u)]^T, g_u read as (d1*d2) x d3.
+__global__ __launch_bounds__(kThreads) void k_u_bwd(Shape sh, const float* __restrict__ g3,
+                                                    const float* __restrict__ grad,
+                                                    const float* __restrict__ gsum,
+                                                    const uint32_t* __restrict__ perm,
+                                                    const int* __restrict__ u_rs,
+                                                    const int* __restrict__ u_i3,
+                                                    const int* __restrict__ q_us,
+                                                    float* __restrict__ dPsum,
+                                                    const Counters* __restrict__ ctr) {
+  const int Q = ctr->Q;
+  for (int q = blockIdx.x; q < Q; q += gridDim.x) {
+    const int u0 = q_us[q], u1 = q_us[q + 1];
+    for (int o = threadIdx.x; o < sh.PN; o += kThreads) {
+      const int m = o / sh.r2, c = o % sh.r2;
+      float acc = 0.f;
+      for (int u = u0; u < u1; ++u) {
+        const float* g = grad_of_unique(u, u_rs, perm, grad, gsum, sh.D) + m * sh.d3;
+        const float* C = g3 + (size_t)u_i3[u] * sh.S3 + c * sh.d3;
+        for (int j3 = 0; j3 < sh.d3; ++j3) acc = fmaf(g[j3], C[j3], acc);
+      }
+      dPsum[(size_t)q * sh.PN + o] = acc;
+    }
+  }
+}
+
+// Index of the group that owns chunk c: the last bin with chunk_start[bin] <= c.
+__device__ __forceinline__ int bin_of_chunk(const int* __restrict__ chunk_start, int bins, int c) {
+  int lo = 0, hi = bins;  // invariant: chunk_start[lo] <= c < chunk_start[hi]
+  while (hi - lo > 1) {
+    const int mid = (lo + hi) >> 1;
+    if (chunk_start[mid] <= c) lo = mid; else hi = mid;
+  }
+  return lo;
+}
+
+// part3[c] = sum over the unique ids u of chunk c (all with one i3) of P_q(u)^T g_u   (r2 x d3)
+__global__ __launch_bounds__(kThreads) void k_dg3(Shape sh, const float* __restrict__ P,
+                                                  const float* __restrict__ grad,
+                                                  const float* __restrict__ gsum,
+                                                  const uint32_t* __restrict__ perm,
+                                                  const int* __restrict__ u_rs,
+                                                  const int* __restrict__ u_q,
+                                                  const int* __restrict__ g3_list,
+                                                  const int* __restrict__ g3_start,
+                                                  const int* __restrict__ c3_start,
+                                                  float* __restrict__ part3,
+                                                  const Counters* __restrict__ ctr) {
+  const int nchunk = ctr->nchunk3;
+  for (int c = blockIdx.x; c < nchunk; c += gridDim.x) {
+    const int bin = bin_of_chunk(c3_start, (int)sh.n3, c);
+    const int k0 = g3_start[bin] + (c - c3_start[bin]) * kChunk3;
+    const int k1 = min(k0 + kChunk3, g3_start[bin + 1]);
+    for (int o = threadIdx.x; o < sh.S3; o += kThreads) {
+      const int cc = o / sh.d3, j3 = o % sh.d3;
+      float acc = 0.f;
+      for (int k = k0; k < k1; ++k) {
+        const int u = g3_list[k];
+        const float* Pq = P + (size_t)u_q[u] * sh.PN + cc;
+        const float* g = grad_of_unique(u, u_rs, perm, grad, gsum, sh.D) + j3;
+        for (int m = 0; m < sh.M; ++m) acc = fmaf(Pq[m * sh.r2], g[m * sh.d3], acc);
+      }
+      part3[(size_t)c * sh.S3 + o] = acc;
+    }
+  }
+}
+
+// For the prefixes q of chunk c (all with one i2, Bm = G2[i2]):
+//   dg1part[q] = dPsum_q * Bm^T                      (d1 x r1), one per prefix
+//   part2[c]   = sum over q of G1[i1(q)]^T * dPsum_q  (r1 x d2*r2)
+__global__ __launch_bounds__(kThreads) void k_prefix_bwd(Shape sh, const float* __restrict__ g1,
+                                                         const float* __restrict__ g2,
+                                                         const float* __restrict__ dPsum,
+                                                         const int* __restrict__ q_i1,
+                                                         const int* __restrict__ g2_list,
+                                                         const int* __restrict__ g2_start,
+                                                         const int* __restrict__ c2_start,
+                                                         float* __restrict__ dg1part,
+                                                         float* __restrict__ part2,
+                                                         const Counters* __restrict__ ctr) {
+  const int nchunk = ctr->nchunk2;
+  for (int c = blockIdx.x; c < nchunk; c += gridDim.x) {
+    const int bin = bin_of_chunk(c2_start, (int)sh.n2, c);
+    const int k0 = g2_start[bin] + (c - c2_start[bin]) * kChunk2;
+    const int k1 = min(k0 + kChunk2, g2_start[bin + 1]);
+    const float* Bm = g2 + (size_t)bin * sh.S2;
+    for (int k = k0; k < k1; ++k) {
+      const int q = g2_list[k];
+      const float* dP = dPsum + (size_t)q * sh.PN;
+      for (int o = threadIdx.x; o < sh.S1; o += kThreads) {
+        const int j1 = o / sh.r1, a = o % sh.r1;
+        float acc = 0.f;
+        for (int col = 0; col < sh.W; ++col)
+          acc = fmaf(dP[j1 * sh.W + col], Bm[a * sh.W + col], acc);
+        dg1part[(size_t)q * sh.S1 + o] = acc;
+      }
+    }
+    for (int o = threadIdx.x; o < sh.S2; o += kThreads) {
+      const int a = o / sh.W, col = o % sh.W;
+      float acc = 0.f;
+      for (int k = k0; k < k1; ++k) {
+        const int q = g2_list[k];
+        const float* A = g1 + (size_t)q_i1[q] * sh.S1 + a;
+        const float* dP = dPsum + (size_t)q * sh.PN + col;
+        for (int j1 = 0; j1 < sh.d1; ++j1) acc = fmaf(A[j1 * sh.r1], dP[j1 * sh.W], acc);
+      }
+      part2[(size_t)c * sh.S2 + o] = acc;
+    }
+  }
+}
+
+__device__ __forceinline__ int lower_bound_i(const int* __restrict__ a, int n, int v) {
+  int lo = 0, hi = n;
+  while (lo < hi) {
+    const int mid = (lo + hi) >> 1;
+    if (a[mid] < v) lo = mid + 1; else hi = mid;
+  }
+  return lo;
+}
+
+constexpr int kSgdSpan = 1024;  // outputs of one G2 slice handled by one job
+
+// Adds up the partial gradients of every touched slice in list order and applies the SGD step.
+// Jobs: [0, n3) G3 slices, then n2*ceil(S2/kSgdSpan) pieces of G2 slices, then n1 G1 slices.
+__global__ __launch_bounds__(kThreads) void k_sgd(Shape sh, float lr, float* __restrict__ g1,
+                                                  float* __restrict__ g2, float* __restrict__ g3,
+                                                  const float* __restrict__ part3,
+                                                  const int* __restrict__ c3_start,
+                                                  const float* __restrict__ part2,
+                                                  const int* __restrict__ c2_start,
+                                                  const float* __restrict__ dg1part,
+                                                  const int* __restrict__ q_i1,
+                                                  const Counters* __restrict__ ctr) {
+  const int spans = (sh.S2 + kSgdSpan - 1) / kSgdSpan;
+  const int jobs3 = (int)sh.n3, jobs2 = (int)sh.n2 * spans, jobs1 = (int)sh.n1;
+  const int Q = ctr->Q;
+  for (int job = blockIdx.x; job < jobs3 + jobs2 + jobs1; job += gridDim.x) {
+    if (job < jobs3) {
+      const int c0 = c3_start[job], c1 = c3_start[job + 1];
+      if (c1 == c0) continue;
+      float* G = g3 + (size_t)job * sh.S3;
+      for (int o = threadIdx.x; o < sh.S3; o += kThreads) {
+        float acc = 0.f;
+        for (int c = c0; c < c1; ++c) acc += part3[(size_t)c * sh.S3 + o];
+        G[o] = fmaf(-lr, acc, G[o]);
+      }
+    } else if (job < jobs3 + jobs2) {
+      const int bin = (job - jobs3) / spans, span = (job - jobs3) % spans;
+      const int c0 = c2_start[bin], c1 = c2_start[bin + 1];
+      if (c1 == c0) continue;
+      float* G = g2 + (size_t)bin * sh.S2;
+      const int o1 = min((span + 1) * kSgdSpan, sh.S2);
+      for (int o = span * kSgdSpan + threadIdx.x; o < o1; o += kThreads) {
+        float acc = 0.f;
+        for (int c = c0; c < c1; ++c) acc += part2[(size_t)c * sh.S2 + o];
+        G[o] = fmaf(-lr, acc, G[o]);
+      }
+    } else {
+      const int i1 = job - jobs3 - jobs2;
+      const int q0 = lower_bound_i(q_i1, Q, i1), q1 = lower_bound_i(q_i1, Q, i1 + 1);
+      if (q1 == q0) continue;
+      float* G = g1 + (size_t)i1 * sh.S1;
+      for (int o = threadIdx.x; o < sh.S1; o += kThreads) {
+        float acc = 0.f;
+        for (int q = q0; q < q1; ++q) acc += dg1part[(size_t)q * sh.S1 + o];
+        G[o] = fmaf(-lr, acc, G[o]);
+      }
+    }
+  }
+}
+
+// ---------------------------------------------------------------------------------------------
+// host-side launchers
+
+static inline int cdiv(int64_t a, int64_t b) { return (int)((a + b - 1) / b); }
+static inline int grid_for(int64_t work_items, int cap) {
+  return (int)std::max<int64_t>(1, std::min<int64_t>(work_items, cap));
+}
+constexpr int kGridCap = 256 * 8;  // persistent blocks: 8 per compute unit
+
+void launch_prefix_fwd(const Plan& pl, const Workspace& ws, const float* g1, const float* g2, int B,
+                       hipStream_t st) {
+  const int grid = grid_for(std::min<int64_t>(B, pl.maxQ), kGridCap);
+  k_prefix_fwd<<<grid, kThreads, 0, st>>>(pl.sh, g1, g2, ws.g2_list, ws.q_i1, ws.q_i2, ws.P, ws.ctr);
+}
+
+void launch_row_fwd(const Plan& pl, const Workspace& ws, const float* g3, int B, float* out,
+                    hipStream_t st) {
+  const int tiles = cdiv(B, kTileSlots);
+  const int grid = grid_for(cdiv(tiles, kWavesPerBlock), kGridCap);
+  const size_t lds = (size_t)kWavesPerBlock * pl.sh.D * sizeof(float);
+  k_row_fwd<<<grid, kThreads, lds, st>>>(pl.sh, B, g3, ws.P, ws.s_u, ws.val[(pl.passes - 1) & 1],
+                                         ws.u_i3, ws.u_q, out, ws.ctr);
+}
+
+void launch_gsum(const Plan& pl, const Workspace& ws, const float* grad, int B, hipStream_t st) {
+  const int tiles = cdiv(B, kTileSlots);
+  const int grid = grid_for(cdiv(tiles, kWavesPerBlock), kGridCap);
+  const size_t lds = (size_t)kWavesPerBlock * pl.sh.D * sizeof(float);
+  k_gsum<<<grid, kThreads, lds, st>>>(pl.sh, B, grad, ws.s_u, ws.val[(pl.passes - 1) & 1], ws.u_rs,
+                                      ws.gsum, ws.carry, ws.ctr);
+}
+
+void launch_gsum_fix(const Plan& pl, const Workspace& ws, int B, hipStream_t st) {
+  const int grid = grid_for(cdiv(B, kTileSlots), kGridCap);
+  k_gsum_fix<<<grid, kThreads, 0, st>>>(pl.sh, ws.s_u, ws.u_rs, ws.carry, ws.gsum, ws.ctr);
+}
+
+void launch_u_bwd(const Plan& pl, const Workspace& ws, const float* g3, const float* grad, int B,
+                  hipStream_t st) {
+  const int grid = grid_for(std::min<int64_t>(B, pl.maxQ), kGridCap);
+  k_u_bwd<<<grid, kThreads, 0, st>>>(pl.sh, g3, grad, ws.gsum, ws.val[(pl.passes - 1) & 1], ws.u_rs,
+                                     ws.u_i3, ws.q_us, ws.dPsum, ws.ctr);
+}
+
+void launch_dg3(const Plan& pl, const Workspace& ws, const float* grad, int B, hipStream_t st) {
+  const int grid = grid_for(cdiv(B, kChunk3) + pl.sh.n3, kGridCap);
+  k_dg3<<<grid, kThreads, 0, st>>>(pl.sh, ws.P, grad, ws.gsum, ws.val[(pl.passes - 1) & 1], ws.u_rs,
+                                   ws.u_q, ws.g3_list, ws.g3_start, ws.c3_start, ws.part3, ws.ctr);
+}
+
+void launch_prefix_bwd(const Plan& pl, const Workspace& ws, const float* g1, const float* g2, int B,
+                       hipStream_t st) {
+  const int grid = grid_for(cdiv(std::min<int64_t>(B, pl.maxQ), kChunk2) + pl.sh.n2, kGridCap);
+  k_prefix_bwd<<<grid, kThreads, 0, st>>>(pl.sh, g1, g2, ws.dPsum, ws.q_i1, ws.g2_list, ws.g2_start,
+                                          ws.c2_start, ws.dg1part, ws.part2, ws.ctr);
+}
+
+void launch_sgd(const Plan& pl, const Workspace& ws, float* g1, float* g2, float* g3, float lr,
+                hipStream_t st) {
+  const int spans = cdiv(pl.sh.S2, kSgdSpan);
+  const int64_t jobs = (int64_t)pl.sh.n3 + (int64_t)pl.sh.n2 * spans + pl.sh.n1;
+  k_sgd<<<grid_for(jobs, kGridCap), kThreads, 0, st>>>(pl.sh, lr, g1, g2, g3, ws.part3, ws.c3_start,
+                                                      ws.part2, ws.c2_start, ws.dg1part, ws.q_i1,
+                                                      ws.ctr);
+}
+
+}  // namespace ttemb

@@ -1,0 +1,449 @@
+// Index pipeline of the TT-embedding forward pass (gfx950).
+//
+//   ids --split--> sort keys --stable LSD radix sort--> sorted slots
+//       --segment scan--> unique ids (U) and unique (i1,i2) prefixes (Q) with their extents
+//       --stable bucket passes--> unique ids grouped by i3, prefixes grouped by i2
+//
+// The split is i1 = i/(n2 n3), i2 = (i/n3) mod n2, i3 = i mod n3 (paper Section 4.2).  Sorting by
+// the id itself makes every sharing level of the paper's Fig. "node-index" a contiguous run: equal
+// ids, ids with a common (i1,i2) prefix (they share G1[i1] G2[i2]), ids with a common i1.
+// Everything here is integer work and is bit-exact; all orders are stable, so the floating-point
+// sums that later follow these lists are formed in a fixed order.
+#include <algorithm>
+
+#include "tt_emb_internal.h"
+
+namespace ttemb {
+
+__device__ __forceinline__ uint32_t key_of_id(int64_t id, uint32_t N) {
+  // ids outside [0, N) (negative ones included) become the sentinel N and sort to the end
+  return ((uint64_t)id < (uint64_t)N) ? (uint32_t)id : N;
+}
+
+// In-place exclusive scan of arr[0..n) by one block of kSortThreads threads; returns the total.
+// scratch holds kSortThreads words.  Ends with a barrier.
+__device__ uint32_t block_exclusive_scan(uint32_t* arr, int n, uint32_t* scratch) {
+  const int tid = threadIdx.x;
+  const int per = (n + kSortThreads - 1) / kSortThreads;
+  const int lo = min(tid * per, n), hi = min(lo + per, n);
+  uint32_t s = 0;
+  for (int i = lo; i < hi; ++i) s += arr[i];
+  scratch[tid] = s;
+  __syncthreads();
+  for (int off = 1; off < kSortThreads; off <<= 1) {
+    uint32_t v = tid >= off ? scratch[tid - off] : 0u;
+    __syncthreads();
+    scratch[tid] += v;
+    __syncthreads();
+  }
+  uint32_t run = scratch[tid] - s;
+  const uint32_t total = scratch[kSortThreads - 1];
+  for (int i = lo; i < hi; ++i) {
+    uint32_t t = arr[i];
+    arr[i] = run;
+    run += t;
+  }
+  __syncthreads();
+  return total;
+}
+
+struct ScatterLds {
+  uint32_t wh[kSortWaves][kMaxBins];  // per-wavefront histograms, then running output cursors
+  uint32_t tot[kMaxBins];             // bucket totals, then this block's first output per bucket
+  uint32_t scratch[kSortThreads];
+};
+
+// One block's share of a stable counting-sort pass over n_items items (block blk owns items
+// [blk*kSortItems, +kSortItems)).  cnt[b][bin] holds every block's bucket counts; the block sums
+// the table itself (buckets before, blocks before) instead of waiting for a separate scan launch.
+// ItemOps: Item load(int idx); int digit(Item); void emit(uint32_t pos, Item).
+// When starts != nullptr block 0 also writes the bins+1 bucket offsets, and with chunk > 0 the
+// offsets of the buckets' chunk lists (ceil(count/chunk) chunks per bucket) plus their total.
+template <class ItemOps>
+__device__ void stable_scatter_block(ScatterLds& L, int blk, int n_items, int bins, int nbits,
+                                     const uint32_t* __restrict__ cnt, ItemOps ops, int* starts,
+                                     int chunk, int* chunk_starts, int* n_chunks) {
+  const int tid = threadIdx.x;
+  const int nblk = (n_items + kSortItems - 1) / kSortItems;
+  const bool writes_starts = (starts != nullptr && blk == 0);
+  if (blk >= nblk && !writes_starts) return;  // uniform for the whole block
+
+  for (int bin = tid; bin < bins; bin += kSortThreads) {
+    uint32_t before = 0, total = 0;
+    for (int b2 = 0; b2 < nblk; ++b2) {
+      uint32_t c = cnt[(size_t)b2 * bins + bin];
+      total += c;
+      if (b2 < blk) before += c;
+    }
+    L.tot[bin] = total;
+    L.wh[0][bin] = before;
+    if (chunk > 0) L.wh[1][bin] = (total + chunk - 1) / chunk;
+  }
+  __syncthreads();
+  const uint32_t total_items = block_exclusive_scan(L.tot, bins, L.scratch);
+  if (writes_starts) {
+    for (int bin = tid; bin < bins; bin += kSortThreads) starts[bin] = (int)L.tot[bin];
+    if (tid == 0) starts[bins] = (int)total_items;
+    if (chunk > 0) {
+      const uint32_t total_chunks = block_exclusive_scan(L.wh[1], bins, L.scratch);
+      for (int bin = tid; bin < bins; bin += kSortThreads) chunk_starts[bin] = (int)L.wh[1][bin];
+      if (tid == 0) {
+        chunk_starts[bins] = (int)total_chunks;
+        *n_chunks = (int)total_chunks;
+      }
+    }
+  }
+  if (blk >= nblk) return;
+  for (int bin = tid; bin < bins; bin += kSortThreads) L.tot[bin] += L.wh[0][bin];
+  __syncthreads();
+  for (int i = tid; i < kSortWaves * kMaxBins; i += kSortThreads) (&L.wh[0][0])[i] = 0u;
+  __syncthreads();
+
+  const int w = tid / kWave, lane = tid % kWave;
+  const int wbase = blk * kSortItems + w * kSortWaveItems;
+  for (int step = 0; step < kSortWaveItems / kWave; ++step) {
+    const int idx = wbase + step * kWave + lane;
+    if (idx < n_items) atomicAdd(&L.wh[w][ops.digit(ops.load(idx))], 1u);
+  }
+  __syncthreads();
+  for (int bin = tid; bin < bins; bin += kSortThreads) {
+    uint32_t run = L.tot[bin];
+    for (int k = 0; k < kSortWaves; ++k) {
+      uint32_t c = L.wh[k][bin];
+      L.wh[k][bin] = run;
+      run += c;
+    }
+  }
+  __syncthreads();
+
+  // Each wavefront walks its items in order, 64 at a time.  Lanes holding the same digit find each
+  // other with one ballot per digit bit; the lowest of them advances the bucket cursor for all.
+  const unsigned long long lt_mask = (1ull << lane) - 1ull;
+  for (int step = 0; step < kSortWaveItems / kWave; ++step) {
+    const int idx = wbase + step * kWave + lane;
+    const bool valid = idx < n_items;
+    typename ItemOps::Item it = ops.load(valid ? idx : 0);
+    const int digit = valid ? ops.digit(it) : 0;
+    unsigned long long peers = __ballot(valid);
+    for (int bit = 0; bit < nbits; ++bit) {
+      const bool one = (digit >> bit) & 1;
+      const unsigned long long vote = __ballot(one);
+      peers &= one ? vote : ~vote;
+    }
+    const int leader = valid ? (__ffsll((long long)peers) - 1) : lane;
+    uint32_t base = 0;
+    if (valid && lane == leader) base = atomicAdd(&L.wh[w][digit], (uint32_t)__popcll(peers));
+    base = __shfl(base, leader);
+    if (valid) ops.emit(base + (uint32_t)__popcll(peers & lt_mask), it);
+  }
+}
+
+// ---------------------------------------------------------------------------------------------
+// LSD radix sort of (key = id or sentinel, value = batch position)
+
+struct KV {
+  uint32_t key, val;
+};
+
+template <bool FROM_IDS>
+struct SortOps {
+  using Item = KV;
+  const int64_t* ids;
+  const uint32_t* kin;
+  const uint32_t* vin;
+  uint32_t* kout;
+  uint32_t* vout;
+  uint32_t N;
+  int shift;
+  uint32_t mask;
+  __device__ Item load(int idx) const {
+    if (FROM_IDS) return KV{key_of_id(ids[idx], N), (uint32_t)idx};
+    return KV{kin[idx], vin[idx]};
+  }
+  __device__ int digit(Item it) const { return (int)((it.key >> shift) & mask); }
+  __device__ void emit(uint32_t pos, Item it) const {
+    kout[pos] = it.key;
+    vout[pos] = it.val;
+  }
+};
+
+// Bucket counts of one radix digit per block.  The first pass also clears the tables that later
+// kernels of the same forward add into.
+template <bool FROM_IDS>
+__global__ __launch_bounds__(kSortThreads) void k_sort_hist(const int64_t* __restrict__ ids,
+                                                            const uint32_t* __restrict__ kin, int B,
+                                                            uint32_t N, int shift, int bits,
+                                                            uint32_t* __restrict__ cnt,
+                                                            uint32_t* zero_a, int zero_a_n,
+                                                            uint32_t* zero_b, int zero_b_n,
+                                                            Counters* ctr) {
+  __shared__ uint32_t h[kMaxBins];
+  const int tid = threadIdx.x, bins = 1 << bits;
+  const uint32_t mask = (uint32_t)bins - 1u;
+  if (FROM_IDS) {
+    const int gtid = blockIdx.x * kSortThreads + tid, gn = gridDim.x * kSortThreads;
+    for (int i = gtid; i < zero_a_n; i += gn) zero_a[i] = 0u;
+    for (int i = gtid; i < zero_b_n; i += gn) zero_b[i] = 0u;
+    if (gtid == 0) ctr->err = 0;
+  }
+  for (int i = tid; i < bins; i += kSortThreads) h[i] = 0u;
+  __syncthreads();
+  const int base = blockIdx.x * kSortItems;
+  for (int i = tid; i < kSortItems; i += kSortThreads) {
+    const int idx = base + i;
+    if (idx < B) {
+      const uint32_t key = FROM_IDS ? key_of_id(ids[idx], N) : kin[idx];
+      atomicAdd(&h[(key >> shift) & mask], 1u);
+    }
+  }
+  __syncthreads();
+  for (int i = tid; i < bins; i += kSortThreads) cnt[(size_t)blockIdx.x * bins + i] = h[i];
+}
+
+template <bool FROM_IDS>
+__global__ __launch_bounds__(kSortThreads) void k_sort_scatter(SortOps<FROM_IDS> ops, int B,
+                                                               int bits,
+                                                               const uint32_t* __restrict__ cnt) {
+  __shared__ ScatterLds L;
+  stable_scatter_block(L, (int)blockIdx.x, B, 1 << bits, bits, cnt, ops, nullptr, 0, nullptr,
+                       nullptr);
+}
+
+// ---------------------------------------------------------------------------------------------
+// Segment discovery over the sorted keys
+
+struct SegFlags {
+  uint32_t key[4];
+  bool valid[4], newu[4], newq[4], last_valid[4];
+};
+
+__device__ __forceinline__ SegFlags seg_flags(const uint32_t* __restrict__ skey, int B, uint32_t N,
+                                              uint32_t n3, int s0) {
+  SegFlags f;
+  uint32_t prev = (s0 > 0 && s0 - 1 < B) ? skey[s0 - 1] : 0xffffffffu;
+  for (int j = 0; j < 4; ++j) {
+    const int s = s0 + j;
+    const uint32_t k = s < B ? skey[s] : 0xffffffffu;
+    const uint32_t next = (s + 1 < B) ? skey[s + 1] : 0xffffffffu;
+    f.key[j] = k;
+    f.valid[j] = (s < B) && (k < N);
+    const bool first = (s == 0);
+    f.newu[j] = f.valid[j] && (first || k != prev);
+    f.newq[j] = f.valid[j] && (first || (k / n3) != (prev / n3));
+    f.last_valid[j] = f.valid[j] && !(next < N);
+    prev = k;
+  }
+  return f;
+}
+
+__global__ __launch_bounds__(kSegThreads) void k_seg_count(const uint32_t* __restrict__ skey, int B,
+                                                           uint32_t N, uint32_t n3,
+                                                           uint32_t* __restrict__ seg_nu,
+                                                           uint32_t* __restrict__ seg_nq) {
+  __shared__ uint32_t su, sq;
+  if (threadIdx.x == 0) su = sq = 0u;
+  __syncthreads();
+  const SegFlags f = seg_flags(skey, B, N, n3, (int)blockIdx.x * kSegItems + (int)threadIdx.x * 4);
+  uint32_t cu = 0, cq = 0;
+  for (int j = 0; j < 4; ++j) {
+    cu += f.newu[j];
+    cq += f.newq[j];
+  }
+  if (cu) atomicAdd(&su, cu);
+  if (cq) atomicAdd(&sq, cq);
+  __syncthreads();
+  if (threadIdx.x == 0) {
+    seg_nu[blockIdx.x] = su;
+    seg_nq[blockIdx.x] = sq;
+  }
+}
+
+// Exclusive scan of one value per thread across a block of kSegThreads threads.
+__device__ uint32_t seg_block_scan(uint32_t v, uint32_t* lds) {
+  const int tid = threadIdx.x;
+  lds[tid] = v;
+  __syncthreads();
+  for (int off = 1; off < kSegThreads; off <<= 1) {
+    uint32_t t = tid >= off ? lds[tid - off] : 0u;
+    __syncthreads();
+    lds[tid] += t;
+    __syncthreads();
+  }
+  const uint32_t r = lds[tid] - v;
+  __syncthreads();
+  return r;
+}
+
+__device__ uint32_t seg_block_sum(uint32_t v, uint32_t* lds) {
+  const int tid = threadIdx.x;
+  lds[tid] = v;
+  __syncthreads();
+  for (int off = kSegThreads / 2; off > 0; off >>= 1) {
+    if (tid < off) lds[tid] += lds[tid + off];
+    __syncthreads();
+  }
+  const uint32_t r = lds[0];
+  __syncthreads();
+  return r;
+}
+
+// Numbers the unique ids and prefixes in sorted order, records their extents and coordinates, and
+// counts them per (block of 4096, i3) resp. (block of 4096, i2) for the grouping pass.
+__global__ __launch_bounds__(kSegThreads) void k_seg_write(
+    const uint32_t* __restrict__ skey, int B, Shape sh, const uint32_t* __restrict__ seg_nu,
+    const uint32_t* __restrict__ seg_nq, int* __restrict__ s_u, int* __restrict__ u_rs,
+    int* __restrict__ u_i3, int* __restrict__ u_q, int* __restrict__ q_us, int* __restrict__ q_i1,
+    int* __restrict__ q_i2, uint32_t* __restrict__ cnt3, uint32_t* __restrict__ cnt2,
+    Counters* __restrict__ ctr) {
+  __shared__ uint32_t lds[kSegThreads];
+  const int tid = threadIdx.x, blk = blockIdx.x;
+  uint32_t pu = 0, pq = 0;
+  for (int b2 = tid; b2 < blk; b2 += kSegThreads) {
+    pu += seg_nu[b2];
+    pq += seg_nq[b2];
+  }
+  const uint32_t offu = seg_block_sum(pu, lds);
+  const uint32_t offq = seg_block_sum(pq, lds);
+
+  const int s0 = blk * kSegItems + tid * 4;
+  const SegFlags f = seg_flags(skey, B, sh.N, sh.n3, s0);
+  uint32_t cu = 0, cq = 0;
+  for (int j = 0; j < 4; ++j) {
+    cu += f.newu[j];
+    cq += f.newq[j];
+  }
+  uint32_t ru = offu + seg_block_scan(cu, lds);  // unique ids before this thread's slots
+  uint32_t rq = offq + seg_block_scan(cq, lds);
+
+  if (blk == 0 && tid == 0 && !f.valid[0]) {  // no in-range id at all
+    ctr->U = 0;
+    ctr->Q = 0;
+    ctr->nvalid = 0;
+    u_rs[0] = 0;
+    q_us[0] = 0;
+  }
+  for (int j = 0; j < 4; ++j) {
+    const int s = s0 + j;
+    if (s >= B) break;
+    if (!f.valid[j]) {
+      s_u[s] = -1;
+      continue;
+    }
+    ru += f.newu[j];
+    rq += f.newq[j];
+    const int u = (int)ru - 1, q = (int)rq - 1;
+    s_u[s] = u;
+    const uint32_t k = f.key[j];
+    if (f.newu[j]) {
+      const uint32_t i3 = k % sh.n3;
+      u_rs[u] = s;
+      u_i3[u] = (int)i3;
+      u_q[u] = q;
+      atomicAdd(&cnt3[(size_t)(u / kSortItems) * sh.n3 + i3], 1u);
+    }
+    if (f.newq[j]) {
+      const uint32_t p = k / sh.n3;  // prefix number i1*n2 + i2
+      const uint32_t i2 = p % sh.n2;
+      q_us[q] = u;
+      q_i1[q] = (int)(p / sh.n2);
+      q_i2[q] = (int)i2;
+      atomicAdd(&cnt2[(size_t)(q / kSortItems) * sh.n2 + i2], 1u);
+    }
+    if (f.last_valid[j]) {
+      ctr->U = u + 1;
+      ctr->Q = q + 1;
+      ctr->nvalid = s + 1;
+      u_rs[u + 1] = s + 1;
+      q_us[q + 1] = u + 1;
+    }
+  }
+}
+
+// ---------------------------------------------------------------------------------------------
+// Grouping: unique ids by i3 (for the G3 gradient), prefixes by i2 (for G2 and the prefix product)
+
+struct GroupOps {
+  using Item = int;
+  const int* digit_of;
+  int* list;
+  __device__ Item load(int idx) const { return idx; }
+  __device__ int digit(Item it) const { return digit_of[it]; }
+  __device__ void emit(uint32_t pos, Item it) const { list[pos] = it; }
+};
+
+__global__ __launch_bounds__(kSortThreads) void k_group(Shape sh, int u_blocks, int bits3, int bits2,
+                                                        const uint32_t* __restrict__ cnt3,
+                                                        const uint32_t* __restrict__ cnt2,
+                                                        const int* __restrict__ u_i3,
+                                                        const int* __restrict__ q_i2,
+                                                        int* g3_list, int* g3_start, int* c3_start,
+                                                        int* g2_list, int* g2_start, int* c2_start,
+                                                        Counters* ctr) {
+  __shared__ ScatterLds L;
+  if ((int)blockIdx.x < u_blocks) {
+    GroupOps ops{u_i3, g3_list};
+    stable_scatter_block(L, (int)blockIdx.x, ctr->U, (int)sh.n3, bits3, cnt3, ops, g3_start,
+                         kChunk3, c3_start, &ctr->nchunk3);
+  } else {
+    GroupOps ops{q_i2, g2_list};
+    stable_scatter_block(L, (int)blockIdx.x - u_blocks, ctr->Q, (int)sh.n2, bits2, cnt2, ops,
+                         g2_start, kChunk2, c2_start, &ctr->nchunk2);
+  }
+}
+
+// ---------------------------------------------------------------------------------------------
+// host-side launchers
+
+static inline int cdiv(int64_t a, int64_t b) { return (int)((a + b - 1) / b); }
+
+void launch_sort_pass(const Plan& pl, const Workspace& ws, const int64_t* ids, int B, int pass,
+                      hipStream_t st, int which /*0 = histogram, 1 = scatter*/) {
+  const int blocks = cdiv(B, kSortItems);
+  const int shift = pass * pl.bitsPerPass;
+  const int bits = std::min(pl.bitsPerPass, pl.keyBits - shift);
+  const uint32_t N = pl.sh.N;
+  if (pass == 0) {
+    if (which == 0) {
+      k_sort_hist<true><<<blocks, kSortThreads, 0, st>>>(
+          ids, nullptr, B, N, shift, bits, ws.cnt, ws.cnt3, pl.uBlocksMax * (int)pl.sh.n3, ws.cnt2,
+          pl.qBlocksMax * (int)pl.sh.n2, ws.ctr);
+    } else {
+      SortOps<true> ops{ids, nullptr, nullptr, ws.key[0], ws.val[0], N, shift, (1u << bits) - 1u};
+      k_sort_scatter<true><<<blocks, kSortThreads, 0, st>>>(ops, B, bits, ws.cnt);
+    }
+  } else {
+    const int src = (pass - 1) & 1, dst = pass & 1;
+    if (which == 0) {
+      k_sort_hist<false><<<blocks, kSortThreads, 0, st>>>(nullptr, ws.key[src], B, N, shift, bits,
+                                                          ws.cnt, nullptr, 0, nullptr, 0, ws.ctr);
+    } else {
+      SortOps<false> ops{nullptr, ws.key[src], ws.val[src], ws.key[dst], ws.val[dst], N, shift,
+                         (1u << bits) - 1u};
+      k_sort_scatter<false><<<blocks, kSortThreads, 0, st>>>(ops, B, bits, ws.cnt);
+    }
+  }
+}
+
+void launch_seg_count(const Plan& pl, const Workspace& ws, int B, hipStream_t st) {
+  const uint32_t* skey = ws.key[(pl.passes - 1) & 1];
+  k_seg_count<<<cdiv(B, kSegItems), kSegThreads, 0, st>>>(skey, B, pl.sh.N, pl.sh.n3, ws.seg_nu,
+                                                         ws.seg_nq);
+}
+
+void launch_seg_write(const Plan& pl, const Workspace& ws, int B, hipStream_t st) {
+  const uint32_t* skey = ws.key[(pl.passes - 1) & 1];
+  k_seg_write<<<cdiv(B, kSegItems), kSegThreads, 0, st>>>(skey, B, pl.sh, ws.seg_nu, ws.seg_nq,
+                                                         ws.s_u, ws.u_rs, ws.u_i3, ws.u_q, ws.q_us,
+                                                         ws.q_i1, ws.q_i2, ws.cnt3, ws.cnt2, ws.ctr);
+}
+
+void launch_group(const Plan& pl, const Workspace& ws, int B, hipStream_t st) {
+  // blocks are sized from upper bounds (U <= B, Q <= min(B, n1*n2)); surplus blocks return at once
+  const int ub = cdiv(B, kSortItems);
+  const int qb = cdiv(std::min((int64_t)B, pl.maxQ), kSortItems);
+  k_group<<<ub + qb, kSortThreads, 0, st>>>(pl.sh, ub, pl.bits3, pl.bits2, ws.cnt3, ws.cnt2, ws.u_i3,
+                                           ws.q_i2, ws.g3_list, ws.g3_start, ws.c3_start,
+                                           ws.g2_list, ws.g2_start, ws.c2_start, ws.ctr);
+}
+
+}  // namespace ttemb

@@ -1,0 +1,110 @@
+// Internal declarations shared by the translation units of libtt_emb.so (not part of the ABI).
+#pragma once
+
+#include <hip/hip_runtime.h>
+#include <stddef.h>
+#include <stdint.h>
+
+#include "tt_emb.h"
+
+namespace ttemb {
+
+constexpr int kWave = 64;
+
+// stable counting-sort blocks: 4 wavefronts, each owning 1024 consecutive items of the block
+constexpr int kSortThreads = 256;
+constexpr int kSortWaves = 4;
+constexpr int kSortWaveItems = 1024;
+constexpr int kSortItems = kSortWaves * kSortWaveItems;  // 4096 items per block
+constexpr int kMaxBins = 2048;                            // digit / bucket count limit per pass
+
+constexpr int kSegThreads = 256;
+constexpr int kSegItems = 1024;  // sorted slots per block in the segment kernels (4 per thread)
+
+constexpr int kTileSlots = 32;   // sorted slots per wavefront tile in the row kernels
+constexpr int kChunk3 = 32;      // unique ids per partial sum of a G3 slice gradient
+constexpr int kChunk2 = 16;      // unique prefixes per partial sum of a G2 slice gradient
+
+// Table and slice geometry, passed to kernels by value.
+struct Shape {
+  uint32_t n1, n2, n3, N;  // node factors and N = n1*n2*n3
+  int d1, d2, d3, r1, r2;
+  int M;   // d1*d2       rows of the partial product
+  int W;   // d2*r2       columns of the unfolded G2 slice
+  int PN;  // d1*d2*r2    floats of one prefix product
+  int D;   // d1*d2*d3    floats of one embedding row
+  int S1;  // d1*r1       floats of one G1 slice
+  int S2;  // r1*d2*r2    floats of one G2 slice
+  int S3;  // r2*d3       floats of one G3 slice
+};
+
+// Device-side counters of the latest forward (first bytes of the workspace).
+struct Counters {
+  int U;        // distinct in-range ids
+  int Q;        // distinct (i1,i2) prefixes
+  int nvalid;   // in-range batch positions (they occupy sorted slots [0, nvalid))
+  int nchunk3;  // partial-sum chunks over the by-i3 grouping of unique ids
+  int nchunk2;  // partial-sum chunks over the by-i2 grouping of unique prefixes
+  int err;      // nonzero: a kernel met an impossible index (bit mask of sites)
+  int pad[2];
+};
+
+// All device arrays carved out of the caller's workspace.
+struct Workspace {
+  Counters* ctr;
+  uint32_t* key[2];   // radix-sort ping-pong keys      [maxB]
+  uint32_t* val[2];   // radix-sort ping-pong positions [maxB]
+  uint32_t* cnt;      // per-block digit histograms     [sortBlocks * kMaxBins]
+  uint32_t* seg_nu;   // new-id flags per segment block     [segBlocks]
+  uint32_t* seg_nq;   // new-prefix flags per segment block [segBlocks]
+  int* s_u;           // sorted slot -> unique-id index (-1 for out-of-range ids) [maxB]
+  int* u_rs;          // unique id -> first sorted slot  [maxB+1]
+  int* u_i3;          // unique id -> i3                 [maxB]
+  int* u_q;           // unique id -> prefix index       [maxB]
+  int* q_us;          // prefix -> first unique id       [maxQ+1]
+  int* q_i1;          // prefix -> i1                    [maxQ]
+  int* q_i2;          // prefix -> i2                    [maxQ]
+  uint32_t* cnt3;     // per-block histograms of i3 over unique ids   [uBlocks * n3]
+  uint32_t* cnt2;     // per-block histograms of i2 over prefixes     [qBlocks * n2]
+  int* g3_list;       // unique ids grouped by i3 (stable)  [maxB]
+  int* g3_start;      // [n3+1]
+  int* c3_start;      // first chunk of each i3 group [n3+1]
+  int* g2_list;       // prefixes grouped by i2 (stable) [maxQ]
+  int* g2_start;      // [n2+1]
+  int* c2_start;      // [n2+1]
+  float* P;           // prefix products G1[i1] G2[i2]   [maxQ][PN]
+  float* gsum;        // per unique id, sum of its rows' gradients [maxB][D]
+  float* carry;       // per tile: head and tail partial sums [tiles][2][D]
+  float* dPsum;       // per prefix: gradient of its product  [maxQ][PN]
+  float* dg1part;     // per prefix: its term of dG1[i1]      [maxQ][S1]
+  float* part3;       // per chunk: partial dG3 slice         [maxChunk3][S3]
+  float* part2;       // per chunk: partial dG2 slice         [maxChunk2][S2]
+};
+
+struct Plan {
+  Shape sh;
+  int64_t maxB, maxQ;
+  int sortBlocksMax, segBlocksMax, uBlocksMax, qBlocksMax, tilesMax;
+  int64_t maxChunk3, maxChunk2;
+  int keyBits, passes, bitsPerPass;
+  int bits2, bits3;  // bits of n2-1, n3-1 (for the ballot match in the grouping scatter)
+};
+
+enum KernelSlot {
+  kSlotSortHist = 0,
+  kSlotSortScatter,
+  kSlotSegCount,
+  kSlotSegWrite,
+  kSlotGroup,
+  kSlotPrefixFwd,
+  kSlotRowFwd,
+  kSlotGsum,
+  kSlotGsumFix,
+  kSlotUBwd,
+  kSlotDg3,
+  kSlotPrefixBwd,
+  kSlotSgd,
+  kSlotCount
+};
+
+}  // namespace ttemb

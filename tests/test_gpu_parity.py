@@ -1,0 +1,207 @@
+"""GPU parity: the HIP library (through its C ABI) against the CPU oracle, element by element.
+
+Tolerances (fp32 path, fp64 oracle), written out here:
+  rows   max over rows b of ||gpu_b - ora_b||_inf / ||ora_b||_inf          <= 1e-5
+  cores  per core ||gpu - ora||_inf / ||ora||_inf                          <= 1e-4
+  step   per core, with dG = (G_old - G_new)/lr recovered from both sides,
+         ||dG_gpu - dG_ora||_inf / ||dG_ora||_inf                          <= 1e-4
+The third line is stricter than the second (a step is lr = 0.01 times a gradient, so a wrong
+gradient on a cold slice would hide inside the second).  Integer results (U, Q, out-of-range
+count) are compared exactly.
+"""
+import numpy as np
+import pytest
+
+import workloads as wl
+from oracle import tt_oracle as ora
+from oracle.tt_oracle import Shape
+
+pytestmark = pytest.mark.gpu
+
+ROW_TOL = 1e-5
+CORE_TOL = 1e-4
+STEP_TOL = 1e-4
+
+
+def _torch():
+    import torch
+    assert torch.cuda.is_available(), "these tests need the GPU"
+    return torch
+
+
+def row_error(gpu, ref):
+    """max_b ||gpu_b - ref_b||_inf / ||ref_b||_inf (rows whose reference is all zero must match exactly)."""
+    gpu = np.asarray(gpu, dtype=np.float64)
+    ref = np.asarray(ref, dtype=np.float64)
+    num = np.abs(gpu - ref).max(axis=1)
+    den = np.abs(ref).max(axis=1)
+    zero = den == 0
+    assert not num[zero].any(), "a row that must be zero is not"
+    return float((num[~zero] / den[~zero]).max()) if (~zero).any() else 0.0
+
+
+def core_error(gpu, ref):
+    ref = np.asarray(ref, dtype=np.float64)
+    return float(np.abs(np.asarray(gpu, dtype=np.float64) - ref).max() / np.abs(ref).max())
+
+
+def run_gpu(n, d, r, cores, ids, grad, lr, max_batch=None, flags=0):
+    """One forward + backward_update through the C ABI; returns rows, new cores, stats."""
+    torch = _torch()
+    from paper_2206_10581_amd import TTEmbedding
+    B = int(ids.size)
+    emb = TTEmbedding(n, d, r, max_batch or max(B, 1), cores, flags=flags)
+    t_ids = torch.from_numpy(np.ascontiguousarray(ids, dtype=np.int64)).cuda()
+    out = emb.forward(t_ids)
+    stats = emb.stats(check=False)
+    t_grad = torch.from_numpy(np.ascontiguousarray(grad, dtype=np.float32)).cuda()
+    emb.backward_update(t_grad, lr)
+    torch.cuda.synchronize()
+    emb.stats(check=False)  # raises on an internal-error flag
+    res = out.cpu().numpy(), [c.cpu().numpy() for c in emb.cores], stats
+    emb.close()
+    return res
+
+
+def check_against_oracle(n, d, r, cores, ids, grad, lr, **kw):
+    s = Shape(tuple(n), tuple(d), tuple(r))
+    out, new, stats = run_gpu(n, d, r, cores, ids, grad, lr, **kw)
+    ref_out = ora.forward(s, *cores, ids)
+    assert row_error(out, ref_out) <= ROW_TOL
+    ref_new = ora.backward_update(s, *cores, ids, grad, lr)
+    ok = ids[(ids >= 0) & (ids < s.N)]
+    assert stats["U"] == np.unique(ok).size
+    assert stats["Q"] == np.unique(ok // n[2]).size
+    assert stats["out_of_range"] == ids.size - ok.size
+    for k in range(3):
+        if ok.size == 0:
+            np.testing.assert_array_equal(new[k], cores[k])
+            continue
+        assert core_error(new[k], ref_new[k]) <= CORE_TOL, f"core {k + 1}"
+        step_gpu = (cores[k].astype(np.float64) - new[k]) / lr
+        step_ref = (cores[k].astype(np.float64) - ref_new[k]) / lr
+        # the recovered step carries the rounding of G itself: allow 2 ulp of |G| / lr on top
+        slack = 2 * np.finfo(np.float32).eps * np.abs(cores[k]).max() / lr
+        err = np.abs(step_gpu - step_ref).max()
+        assert err <= STEP_TOL * np.abs(step_ref).max() + slack, f"step of core {k + 1}"
+        # slices no id touches are not written at all
+        touched = np.zeros(n[k], dtype=bool)
+        coord = [ok // (n[1] * n[2]), (ok // n[2]) % n[1], ok % n[2]][k]
+        touched[coord] = True
+        np.testing.assert_array_equal(new[k][~touched], cores[k][~touched])
+    return out, new, stats
+
+
+def _workload(cfg, seed=None, batch=None):
+    w = wl.CONFIGS[cfg]
+    seed = cfg if seed is None else seed
+    return w, wl.make_cores(w, seed), wl.make_ids(w, seed, batch), wl.make_grads(w, seed, batch)
+
+
+# ----------------------------------------------------------------------------- small, in full
+
+def test_config1_tiny_in_full():
+    w, cores, ids, grad = _workload(1)
+    check_against_oracle(w.n, w.d, w.r, cores, ids, grad, w.lr)
+
+
+@pytest.mark.parametrize("n,d,r,B", [
+    ((3, 4, 4), (2, 3, 2), (3, 5), 200),       # odd factors, r1 != r2, every id many times
+    ((7, 5, 9), (1, 2, 5), (2, 7), 1000),
+    ((5, 300, 6), (3, 1, 2), (6, 1), 5000),    # wide middle factor, rank-1 tail
+    ((40, 33, 70), (2, 2, 3), (8, 8), 4097),   # one item past a 4096 sort block
+])
+def test_generic_shapes(n, d, r, B):
+    rng = np.random.default_rng(B)
+    s = Shape(n, d, r)
+    cores = tuple((rng.standard_normal(cs) * 0.5).astype(np.float32) for cs in s.core_shapes())
+    ids = rng.integers(0, s.N, size=B, dtype=np.int64)
+    grad = rng.standard_normal((B, s.D)).astype(np.float32)
+    check_against_oracle(n, d, r, cores, ids, grad, 0.01)
+
+
+@pytest.mark.parametrize("B", [1, 2, 31, 32, 33, 63, 64, 65, 1023, 1025, 4095, 4096, 8193])
+def test_ragged_batch_sizes(B):
+    w, cores, _, _ = _workload(2)
+    ids = wl.make_ids(w, 100 + B, B)
+    grad = wl.make_grads(w, 100 + B, B)
+    check_against_oracle(w.n, w.d, w.r, cores, ids, grad, w.lr, max_batch=10_000)
+
+
+def test_duplicates_out_of_range_and_one_hot_id():
+    w, cores, _, _ = _workload(2)
+    rng = np.random.default_rng(5)
+    hot = np.full(3000, 12345, dtype=np.int64)                    # one id, thousands of times
+    near = 12345 + rng.integers(-40, 40, size=500)                # same and neighbouring prefixes
+    bad = np.array([-1, w.N, w.N + 5, -2**40, 2**40], dtype=np.int64)
+    ids = np.concatenate([hot, near, bad, rng.integers(0, w.N, 2000)]).astype(np.int64)
+    rng.shuffle(ids)
+    grad = rng.standard_normal((ids.size, w.D)).astype(np.float32)
+    out, _, stats = check_against_oracle(w.n, w.d, w.r, cores, ids, grad, w.lr)
+    assert stats["out_of_range"] == 5
+    assert not out[(ids < 0) | (ids >= w.N)].any()
+
+
+def test_all_ids_out_of_range_and_empty_batch():
+    w, cores, _, _ = _workload(1)
+    ids = np.array([-5, w.N, w.N + 1], dtype=np.int64)
+    grad = np.ones((3, w.D), dtype=np.float32)
+    out, new, stats = run_gpu(w.n, w.d, w.r, cores, ids, grad, w.lr)
+    assert not out.any() and stats == {"U": 0, "Q": 0, "out_of_range": 3}
+    for a, b in zip(new, cores):
+        np.testing.assert_array_equal(a, b)
+    out, new, stats = run_gpu(w.n, w.d, w.r, cores, ids[:0], grad[:0], w.lr)
+    assert out.shape == (0, w.D) and stats == {"U": 0, "Q": 0, "out_of_range": 0}
+    for a, b in zip(new, cores):
+        np.testing.assert_array_equal(a, b)
+
+
+def test_config2_in_full():
+    w, cores, ids, grad = _workload(2)
+    _, _, stats = check_against_oracle(w.n, w.d, w.r, cores, ids, grad, w.lr)
+    assert stats["Q"] == 56 * 56
+
+
+# ----------------------------------------------------------------------------- properties
+
+def test_bit_reproducible_and_lr_zero():
+    w, cores, ids, grad = _workload(3, batch=60_000)
+    a = run_gpu(w.n, w.d, w.r, cores, ids, grad, w.lr)
+    b = run_gpu(w.n, w.d, w.r, cores, ids, grad, w.lr)
+    np.testing.assert_array_equal(a[0], b[0])
+    for x, y in zip(a[1], b[1]):
+        np.testing.assert_array_equal(x, y)
+    c = run_gpu(w.n, w.d, w.r, cores, ids, grad, 0.0)
+    for x, y in zip(c[1], cores):
+        np.testing.assert_array_equal(x, y)
+
+
+def test_abi_error_codes():
+    torch = _torch()
+    import paper_2206_10581_amd as lib
+    from paper_2206_10581_amd.binding import (TT_EMB_EINVAL, TT_EMB_ENOSPC, TT_EMB_ESTATE,
+                                              TT_EMB_ERANGE, TT_EMB_FLAG_CHECK_RANGE, make_config)
+    w, cores, ids, grad = _workload(1)
+    assert lib.tt_emb_workspace_bytes(make_config((0, 10, 10), w.d, w.r, 10))[0] == TT_EMB_EINVAL
+    assert lib.tt_emb_workspace_bytes(make_config((2000, 2000, 2000), w.d, w.r, 10))[0] == TT_EMB_EINVAL
+    assert lib.tt_emb_workspace_bytes(make_config(w.n, w.d, (0, 4), 10))[0] == TT_EMB_EINVAL
+    assert lib.tt_emb_workspace_bytes(make_config(w.n, w.d, w.r, 0))[0] == TT_EMB_EINVAL
+    emb = lib.TTEmbedding(w.n, w.d, w.r, 100, cores, flags=TT_EMB_FLAG_CHECK_RANGE)
+    t_grad = torch.from_numpy(grad[:100]).cuda()
+    assert lib.tt_emb_backward_update(emb.handle, t_grad.data_ptr(), 0.01, 0) == TT_EMB_ESTATE
+    t_ids = torch.from_numpy(ids).cuda()
+    out = torch.empty((ids.size, w.D), device="cuda")
+    assert lib.tt_emb_forward(emb.handle, t_ids.data_ptr(), ids.size, out.data_ptr(), 0) == TT_EMB_ENOSPC
+    assert lib.tt_emb_forward(emb.handle, t_ids.data_ptr(), -1, out.data_ptr(), 0) == TT_EMB_EINVAL
+    assert lib.tt_emb_forward(emb.handle, 0, 10, out.data_ptr(), 0) == TT_EMB_EINVAL
+    bad = t_ids[:100].clone()
+    bad[7] = w.N
+    emb.forward(bad)
+    rc, U, Q, oob = lib.tt_emb_get_stats(emb.handle)
+    assert rc == TT_EMB_ERANGE and oob == 1
+    emb.backward_update(t_grad, 0.01)
+    assert lib.tt_emb_backward_update(emb.handle, t_grad.data_ptr(), 0.01, 0) == TT_EMB_ESTATE
+    torch.cuda.synchronize()
+    emb.close()
+    rc, _ = lib.tt_emb_create(make_config(w.n, w.d, w.r, 100), 0, 0, 0, 0, 0)
+    assert rc == TT_EMB_EINVAL
