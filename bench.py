@@ -1,0 +1,208 @@
+#!/usr/bin/env python3
+"""Benchmark of the TT-embedding hot path on one MI355X.
+
+A step is one whole pass of the path over one synthetic minibatch that is already resident in HBM:
+tt_emb_forward (index split, sort, dedup, prefix products, rows) followed by
+tt_emb_backward_update (gradient sums, core gradients, SGD).  The metric is rows per second,
+duplicates counted.  The default workload is the 2.5M-node rank-32 table with a 200,000-row Zipf
+batch; `--config K` picks another of the five synthetic workloads.
+
+Inside the timed region every step also restores the cores from a snapshot with one device-side
+copy (a few MB): repeated SGD steps on the same random gradients would otherwise overflow within a
+few steps.  The copy is extra work that is counted against the measured rate.
+
+Prints ONE JSON line.  `roofline` describes the kernel with the largest share of the step, timed
+with HIP events on its own stream by the library's profiling hook in a separate, untimed leg;
+`cpu_baseline` is the CPU oracle (fp32 build, OpenMP) on a prefix of the same batch.
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+HBM_PEAK = 8.0e12        # bytes/s, MI355X HBM3E
+FP32_PEAK = 157.3e12     # flop/s, MI355X fp32 (vector with packed ops, or fp32 MFMA)
+
+
+def kernel_work(slot: str, w, B: int, U: int, Q: int, touched_bytes: int, passes: int):
+    """Algorithmic (HBM bytes, fp32 flops) one step asks of a kernel slot.  Bytes are the slot's
+    share of the path's compulsory traffic, 8 + 8*D per row plus touched core slices twice;
+    intermediates that are meant to stay in cache count for nothing."""
+    d1, d2, d3 = w.d
+    r1, r2 = w.r
+    D = w.D
+    F1 = 2 * d1 * r1 * d2 * r2          # one prefix product
+    F2 = 2 * d1 * d2 * r2 * d3          # one row product
+    table = {
+        "sort_hist": (8 * B, 0),        # reads the int64 ids (first pass)
+        "sort_scatter": (0, 0),
+        "seg_count": (0, 0),
+        "seg_write": (0, 0),
+        "group": (0, 0),
+        "prefix_fwd": (0, Q * F1),
+        "row_fwd": (4 * D * B, U * F2),
+        "gsum": (4 * D * B, (B - U) * D),
+        "gsum_fix": (0, 0),
+        "u_bwd": (0, U * F2),
+        "dg3": (0, U * F2),
+        "prefix_bwd": (0, 2 * Q * F1),
+        "sgd": (2 * touched_bytes, 0),
+    }
+    return table.get(slot, (0, 0))
+
+
+def main() -> int:
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=200)
+    ap.add_argument("--warmup", type=int, default=20)
+    ap.add_argument("--config", type=int, default=3, choices=[1, 2, 3, 4, 5])
+    ap.add_argument("--seed", type=int, default=None)
+    ap.add_argument("--profile-steps", type=int, default=20)
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        print("bench.py: this build runs on ONE GPU (replicated-core data parallelism is described "
+              "in DESIGN.md, not built); run with --gpus 1", file=sys.stderr)
+        return 2
+
+    import numpy as np
+    import torch
+    import workloads as wl
+    from paper_2206_10581_amd import TTEmbedding
+
+    if not torch.cuda.is_available():
+        print("bench.py: no GPU visible", file=sys.stderr)
+        return 3
+    dev = torch.device("cuda:0")
+    w = wl.CONFIGS[args.config]
+    seed = args.config if args.seed is None else args.seed
+    B, D = w.batch, w.D
+    cores_np = wl.make_cores(w, seed)
+    ids_np = wl.make_ids(w, seed)
+    grad_np = wl.make_grads(w, seed)
+    struct = wl.batch_structure(w, ids_np)
+
+    # cores live in one flat buffer so that the per-step restore is a single device copy
+    sizes = [c.size for c in cores_np]
+    offs = [0]
+    for s in sizes:
+        offs.append(offs[-1] + ((s + 63) // 64) * 64)
+    flat = torch.zeros(offs[-1], dtype=torch.float32, device=dev)
+    cores = [flat[offs[k]:offs[k] + sizes[k]].view(cores_np[k].shape) for k in range(3)]
+    for t, c in zip(cores, cores_np):
+        t.copy_(torch.from_numpy(c))
+    snapshot = flat.clone()
+    ids = torch.from_numpy(ids_np).to(dev)
+    grad = torch.from_numpy(grad_np).to(dev)
+    out = torch.empty((B, D), dtype=torch.float32, device=dev)
+    emb = TTEmbedding(w.n, w.d, w.r, B, cores, device=dev)
+
+    def step():
+        flat.copy_(snapshot)
+        emb.forward(ids, out)
+        emb.backward_update(grad, w.lr)
+
+    for _ in range(args.warmup):
+        step()
+    torch.cuda.synchronize()
+    stats = emb.stats()
+    assert stats["U"] == struct["U"] and stats["Q"] == struct["Q"], (stats, struct)
+
+    t0 = time.perf_counter()
+    for _ in range(args.steps):
+        step()
+    torch.cuda.synchronize()
+    t1 = time.perf_counter()
+    ms_per_step = (t1 - t0) * 1e3 / args.steps
+    rows_per_s = B / (ms_per_step * 1e-3)
+
+    # untimed leg: per-kernel durations from HIP events recorded on the launch stream
+    emb.profile(True)
+    for _ in range(args.profile_steps):
+        step()
+    torch.cuda.synchronize()
+    prof = emb.profile_read()
+    emb.profile(False)
+
+    U, Q = stats["U"], stats["Q"]
+    ok = ids_np[(ids_np >= 0) & (ids_np < w.N)]
+    n2, n3 = w.n[1], w.n[2]
+    (d1, d2, d3), (r1, r2) = w.d, w.r
+    touched_bytes = 4 * (np.unique(ok // (n2 * n3)).size * d1 * r1
+                         + np.unique((ok // n3) % n2).size * r1 * d2 * r2
+                         + np.unique(ok % n3).size * r2 * d3)
+    kernels = {}
+    for name, rec in prof.items():
+        if rec["launches"] == 0:
+            continue
+        per_step_us = rec["ms"] * 1e3 / args.profile_steps
+        launches = rec["launches"] / args.profile_steps
+        by, fl = kernel_work(name, w, B, U, Q, touched_bytes, 0)
+        kernels[name] = {"us_per_step": round(per_step_us, 2), "launches_per_step": launches,
+                         "alg_bytes": int(by), "alg_flops": int(fl)}
+    dom = max(kernels, key=lambda k: kernels[k]["us_per_step"])
+    kd = kernels[dom]
+    launch_s = kd["us_per_step"] * 1e-6 / kd["launches_per_step"]
+    by = kd["alg_bytes"] / kd["launches_per_step"]
+    fl = kd["alg_flops"] / kd["launches_per_step"]
+    if by / HBM_PEAK >= fl / FP32_PEAK:
+        roofline = {"kernel": dom, "bound": "hbm", "achieved": by / launch_s / 1e9,
+                    "peak": HBM_PEAK / 1e9, "unit": "GB/s", "frac": by / launch_s / HBM_PEAK,
+                    "traffic": None}
+    else:
+        roofline = {"kernel": dom, "bound": "alu", "achieved": fl / launch_s / 1e12,
+                    "peak": FP32_PEAK / 1e12, "unit": "TFLOP/s", "frac": fl / launch_s / FP32_PEAK,
+                    "traffic": None}
+    roofline["avg_launch_us"] = round(launch_s * 1e6, 2)
+
+    # the path as a whole against its binding bound
+    F1, F2 = 2 * d1 * r1 * d2 * r2, 2 * d1 * d2 * r2 * d3
+    alg_bytes = B * (8 + 8 * D) + 2 * touched_bytes
+    alg_flops = 3 * (Q * F1 + U * F2) + (B - U) * D
+    t_hbm, t_alu = alg_bytes / HBM_PEAK, alg_flops / FP32_PEAK
+    path = {"alg_bytes": int(alg_bytes), "alg_flops": int(alg_flops),
+            "t_hbm_us": round(t_hbm * 1e6, 2), "t_fp32_us": round(t_alu * 1e6, 2),
+            "bound": "hbm" if t_hbm >= t_alu else "alu",
+            "frac": max(t_hbm, t_alu) / (ms_per_step * 1e-3),
+            "kernel_sum_us": round(sum(k["us_per_step"] for k in kernels.values()), 2)}
+
+    cpu = None
+    if not args.no_cpu_baseline:
+        from oracle import tt_oracle as ora
+        s = ora.Shape(w.n, w.d, w.r)
+        sample = min(B, {1: 256, 2: 50_000, 3: 40_000, 4: 100_000, 5: 10_000}[args.config])
+        ora.forward(s, *cores_np, ids_np[:256], tag="f32")          # loads the library
+        c0 = time.perf_counter()
+        ora.forward(s, *cores_np, ids_np[:sample], tag="f32")
+        ora.backward_update(s, *cores_np, ids_np[:sample], grad_np[:sample], w.lr, tag="f32")
+        c1 = time.perf_counter()
+        cpu = {"value": sample / (c1 - c0), "unit": "rows/s", "cores": ora.threads("f32"),
+               "kind": "oracle",
+               "sample": f"first {sample} rows of the same batch, fp32 OpenMP build of the oracle, "
+                         f"forward + backward + update, {c1 - c0:.2f} s"}
+
+    line = {
+        "metric": "TT-embedding rows/s (fwd+bwd+update)", "value": rows_per_s, "unit": "rows/s",
+        "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": ms_per_step,
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "f32",
+        "data": "synthetic",
+        "config": {"workload": w.name, "N": w.N, "n": list(w.n), "d": list(w.d), "ranks": list(w.r),
+                   "batch": B, "ids": w.ids, "zipf_s": w.zipf_s, "seed": seed, "lr": w.lr,
+                   "U": U, "Q": Q, "max_multiplicity": struct["max_multiplicity"]},
+        "roofline": roofline, "cpu_baseline": cpu, "path_roofline": path, "kernels": kernels,
+    }
+    print(json.dumps(line))
+    emb.close()
+    return 0
+
+
+if __name__ == "__main__":
+    sys.exit(main())

@@ -39,6 +39,9 @@ def load_library():
     if not os.path.exists(_LIB_PATH):
         raise ImportError(f"{_LIB_PATH} is missing: run `python -m paper_2206_10581_amd.build` "
                           "(there is no CPU fallback)")
+    # PyTorch carries its own copy of the HIP runtime; importing it first makes this library bind
+    # to that same copy (one runtime per process), whatever order the caller imports things in.
+    import torch  # noqa: F401
     lib = ctypes.CDLL(_LIB_PATH)
     cfgp = POINTER(TTEmbConfig)
     lib.tt_emb_workspace_bytes.argtypes = [cfgp, POINTER(c_size_t)]
@@ -138,7 +141,11 @@ class TTEmbedding:
         shapes = ((n[0], d[0], r[0]), (n[1], r[0], d[1], r[1]), (n[2], r[1], d[2]))
         self.cores = []
         for c, s in zip(cores, shapes):
-            t = torch.as_tensor(c).to(device=self.device, dtype=torch.float32).contiguous().clone()
+            if (isinstance(c, torch.Tensor) and c.device == self.device and c.dtype == torch.float32
+                    and c.is_contiguous()):
+                t = c                      # caller-owned device tensor: borrowed, updated in place
+            else:
+                t = torch.as_tensor(c).to(device=self.device, dtype=torch.float32).contiguous().clone()
             if tuple(t.shape) != tuple(s):
                 raise ValueError(f"core shape {tuple(t.shape)} != {s}")
             self.cores.append(t)
