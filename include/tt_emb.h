@@ -22,7 +22,8 @@
  * Output column order is j = (j1*d2 + j2)*d3 + j3 (Eq. "tt-embedding").
  *
  * Memory.  Every pointer named "device" is HIP device memory owned by the caller; the library
- * borrows it and never allocates or frees device memory.  The handle owns host bookkeeping only.
+ * borrows it and never allocates or frees device memory.  Cores, out and grad_out must be 16-byte
+ * aligned, ids 8-byte aligned (TT_EMB_EINVAL otherwise).  The handle owns host bookkeeping only.
  * All calls are asynchronous on the given HIP stream unless stated otherwise.  A handle must not
  * be used from two threads or two streams at once.
  *
@@ -51,7 +52,10 @@ enum {
 };
 
 enum {
-  TT_EMB_FLAG_CHECK_RANGE = 1u /* get_stats returns TT_EMB_ERANGE when an id was out of range */
+  TT_EMB_FLAG_CHECK_RANGE = 1u,    /* get_stats returns TT_EMB_ERANGE when an id was out of range */
+  TT_EMB_FLAG_GENERIC_KERNELS = 2u /* use the any-shape vector-ALU kernels even for shapes that
+                                      have matrix-core kernels (d1 = d2 = 4, r1 = r2 in
+                                      {16,32,64}, d3 in {4,8}); for comparison and testing       */
 };
 
 typedef struct {

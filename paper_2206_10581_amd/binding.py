@@ -15,6 +15,7 @@ _LIB_PATH = os.path.join(_HERE, "libtt_emb.so")
 TT_EMB_OK, TT_EMB_EINVAL, TT_EMB_ENOSPC, TT_EMB_ESTATE, TT_EMB_EHIP, TT_EMB_ERANGE, \
     TT_EMB_EINTERNAL = 0, -1, -2, -3, -4, -5, -6
 TT_EMB_FLAG_CHECK_RANGE = 1
+TT_EMB_FLAG_GENERIC_KERNELS = 2
 
 
 class TTEmbConfig(ctypes.Structure):

@@ -28,6 +28,17 @@ void launch_prefix_bwd(const Plan&, const Workspace&, const float* g1, const flo
                        hipStream_t);
 void launch_sgd(const Plan&, const Workspace&, float* g1, float* g2, float* g3, float lr,
                 hipStream_t);
+// matrix-core variants for the shapes mfma_shape() accepts
+bool mfma_shape(const Shape&);
+void launch_prefix_fwd_mfma(const Plan&, const Workspace&, const float* g1, const float* g2, int B,
+                            hipStream_t);
+void launch_row_fwd_mfma(const Plan&, const Workspace&, const float* g3, int B, float* out,
+                         hipStream_t);
+void launch_u_bwd_mfma(const Plan&, const Workspace&, const float* g3, const float* grad, int B,
+                       hipStream_t);
+void launch_dg3_mfma(const Plan&, const Workspace&, const float* grad, int B, hipStream_t);
+void launch_prefix_bwd_mfma(const Plan&, const Workspace&, const float* g1, const float* g2, int B,
+                            hipStream_t);
 
 static const char* const kSlotNames[kSlotCount] = {
     "sort_hist", "sort_scatter", "seg_count", "seg_write", "group",      "prefix_fwd", "row_fwd",
@@ -158,6 +169,7 @@ struct tt_emb {
   bool have_forward;
   hipStream_t last_stream;
   bool profiling;
+  bool mfma;  // matrix-core kernels apply to this shape and are not switched off
   std::vector<EventPair> events;
   int64_t prof_launches[kSlotCount];
   double prof_ms[kSlotCount];
@@ -229,6 +241,7 @@ int tt_emb_create(tt_emb_t* out, const tt_emb_config* cfg, float* g1, float* g2,
   int rc = make_plan(cfg, &pl);
   if (rc != TT_EMB_OK) return rc;
   if (((uintptr_t)workspace & 255u) != 0) return TT_EMB_EINVAL;
+  if ((((uintptr_t)g1 | (uintptr_t)g2 | (uintptr_t)g3) & 15u) != 0) return TT_EMB_EINVAL;
   if (workspace_bytes < carve(pl, nullptr, nullptr)) return TT_EMB_ENOSPC;
   tt_emb* h = new (std::nothrow) tt_emb();
   if (h == nullptr) return TT_EMB_EINVAL;
@@ -243,6 +256,7 @@ int tt_emb_create(tt_emb_t* out, const tt_emb_config* cfg, float* g1, float* g2,
   h->have_forward = false;
   h->last_stream = nullptr;
   h->profiling = false;
+  h->mfma = mfma_shape(pl.sh) && !(cfg->flags & TT_EMB_FLAG_GENERIC_KERNELS);
   std::memset(h->prof_launches, 0, sizeof(h->prof_launches));
   std::memset(h->prof_ms, 0, sizeof(h->prof_ms));
   *out = h;
@@ -260,6 +274,7 @@ int tt_emb_forward(tt_emb_t h, const int64_t* ids, int64_t B64, float* out, void
     return TT_EMB_OK;
   }
   if (ids == nullptr || out == nullptr) return TT_EMB_EINVAL;
+  if (((uintptr_t)out & 15u) != 0 || ((uintptr_t)ids & 7u) != 0) return TT_EMB_EINVAL;
   const int B = (int)B64;
   const Plan& pl = h->plan;
   const Workspace& ws = h->ws;
@@ -277,9 +292,15 @@ int tt_emb_forward(tt_emb_t h, const int64_t* ids, int64_t B64, float* out, void
   if (rc) return rc;
   rc = run_slot(h, kSlotGroup, st, [&] { launch_group(pl, ws, B, st); });
   if (rc) return rc;
-  rc = run_slot(h, kSlotPrefixFwd, st, [&] { launch_prefix_fwd(pl, ws, h->g1, h->g2, B, st); });
+  rc = run_slot(h, kSlotPrefixFwd, st, [&] {
+    if (h->mfma) launch_prefix_fwd_mfma(pl, ws, h->g1, h->g2, B, st);
+    else launch_prefix_fwd(pl, ws, h->g1, h->g2, B, st);
+  });
   if (rc) return rc;
-  rc = run_slot(h, kSlotRowFwd, st, [&] { launch_row_fwd(pl, ws, h->g3, B, out, st); });
+  rc = run_slot(h, kSlotRowFwd, st, [&] {
+    if (h->mfma) launch_row_fwd_mfma(pl, ws, h->g3, B, out, st);
+    else launch_row_fwd(pl, ws, h->g3, B, out, st);
+  });
   if (rc) return rc;
   h->pending_B = B;
   h->last_B = B;
@@ -293,7 +314,7 @@ int tt_emb_backward_update(tt_emb_t h, const float* grad_out, float lr, void* hi
   const int B = (int)h->pending_B;
   h->pending_B = -1;
   if (B == 0) return TT_EMB_OK;
-  if (grad_out == nullptr) return TT_EMB_EINVAL;
+  if (grad_out == nullptr || ((uintptr_t)grad_out & 15u) != 0) return TT_EMB_EINVAL;
   hipStream_t st = (hipStream_t)hip_stream;
   const Plan& pl = h->plan;
   const Workspace& ws = h->ws;
@@ -302,11 +323,20 @@ int tt_emb_backward_update(tt_emb_t h, const float* grad_out, float lr, void* hi
   if (rc) return rc;
   rc = run_slot(h, kSlotGsumFix, st, [&] { launch_gsum_fix(pl, ws, B, st); });
   if (rc) return rc;
-  rc = run_slot(h, kSlotUBwd, st, [&] { launch_u_bwd(pl, ws, h->g3, grad_out, B, st); });
+  rc = run_slot(h, kSlotUBwd, st, [&] {
+    if (h->mfma) launch_u_bwd_mfma(pl, ws, h->g3, grad_out, B, st);
+    else launch_u_bwd(pl, ws, h->g3, grad_out, B, st);
+  });
   if (rc) return rc;
-  rc = run_slot(h, kSlotDg3, st, [&] { launch_dg3(pl, ws, grad_out, B, st); });
+  rc = run_slot(h, kSlotDg3, st, [&] {
+    if (h->mfma) launch_dg3_mfma(pl, ws, grad_out, B, st);
+    else launch_dg3(pl, ws, grad_out, B, st);
+  });
   if (rc) return rc;
-  rc = run_slot(h, kSlotPrefixBwd, st, [&] { launch_prefix_bwd(pl, ws, h->g1, h->g2, B, st); });
+  rc = run_slot(h, kSlotPrefixBwd, st, [&] {
+    if (h->mfma) launch_prefix_bwd_mfma(pl, ws, h->g1, h->g2, B, st);
+    else launch_prefix_bwd(pl, ws, h->g1, h->g2, B, st);
+  });
   if (rc) return rc;
   rc = run_slot(h, kSlotSgd, st, [&] { launch_sgd(pl, ws, h->g1, h->g2, h->g3, lr, st); });
   return rc;

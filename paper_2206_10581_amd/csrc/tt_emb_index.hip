@@ -70,10 +70,12 @@ __device__ void stable_scatter_block(ScatterLds& L, int blk, int n_items, int bi
 
   for (int bin = tid; bin < bins; bin += kSortThreads) {
     uint32_t before = 0, total = 0;
+    const uint32_t* col = cnt + bin;
+#pragma unroll 8
     for (int b2 = 0; b2 < nblk; ++b2) {
-      uint32_t c = cnt[(size_t)b2 * bins + bin];
+      const uint32_t c = col[(size_t)b2 * bins];
       total += c;
-      if (b2 < blk) before += c;
+      before += (b2 < blk) ? c : 0u;
     }
     L.tot[bin] = total;
     L.wh[0][bin] = before;
@@ -96,18 +98,32 @@ __device__ void stable_scatter_block(ScatterLds& L, int blk, int n_items, int bi
   if (blk >= nblk) return;
   for (int bin = tid; bin < bins; bin += kSortThreads) L.tot[bin] += L.wh[0][bin];
   __syncthreads();
-  for (int i = tid; i < kSortWaves * kMaxBins; i += kSortThreads) (&L.wh[0][0])[i] = 0u;
+  for (int i = tid; i < kSortWaves * bins; i += kSortThreads) L.wh[i / bins][i % bins] = 0u;
   __syncthreads();
 
+  // every lane keeps its 16 items (and their digits) in registers for both walks below
+  constexpr int kSteps = kSortWaveItems / kWave;
   const int w = tid / kWave, lane = tid % kWave;
   const int wbase = blk * kSortItems + w * kSortWaveItems;
-  for (int step = 0; step < kSortWaveItems / kWave; ++step) {
+  typename ItemOps::Item items[kSteps];
+  int digits[kSteps];
+#pragma unroll
+  for (int step = 0; step < kSteps; ++step) {
     const int idx = wbase + step * kWave + lane;
-    if (idx < n_items) atomicAdd(&L.wh[w][ops.digit(ops.load(idx))], 1u);
+    items[step] = ops.load(idx < n_items ? idx : 0);
   }
+#pragma unroll
+  for (int step = 0; step < kSteps; ++step) {
+    const int idx = wbase + step * kWave + lane;
+    digits[step] = (idx < n_items) ? ops.digit(items[step]) : -1;
+  }
+#pragma unroll
+  for (int step = 0; step < kSteps; ++step)
+    if (digits[step] >= 0) atomicAdd(&L.wh[w][digits[step]], 1u);
   __syncthreads();
   for (int bin = tid; bin < bins; bin += kSortThreads) {
     uint32_t run = L.tot[bin];
+#pragma unroll
     for (int k = 0; k < kSortWaves; ++k) {
       uint32_t c = L.wh[k][bin];
       L.wh[k][bin] = run;
@@ -119,14 +135,14 @@ __device__ void stable_scatter_block(ScatterLds& L, int blk, int n_items, int bi
   // Each wavefront walks its items in order, 64 at a time.  Lanes holding the same digit find each
   // other with one ballot per digit bit; the lowest of them advances the bucket cursor for all.
   const unsigned long long lt_mask = (1ull << lane) - 1ull;
-  for (int step = 0; step < kSortWaveItems / kWave; ++step) {
-    const int idx = wbase + step * kWave + lane;
-    const bool valid = idx < n_items;
-    typename ItemOps::Item it = ops.load(valid ? idx : 0);
-    const int digit = valid ? ops.digit(it) : 0;
+#pragma unroll
+  for (int step = 0; step < kSteps; ++step) {
+    const int digit = digits[step];
+    const bool valid = digit >= 0;
     unsigned long long peers = __ballot(valid);
+    if (peers == 0ull) break;  // wave-uniform: the rest of this wavefront's range is empty
     for (int bit = 0; bit < nbits; ++bit) {
-      const bool one = (digit >> bit) & 1;
+      const bool one = valid && ((digit >> bit) & 1);
       const unsigned long long vote = __ballot(one);
       peers &= one ? vote : ~vote;
     }
@@ -134,7 +150,7 @@ __device__ void stable_scatter_block(ScatterLds& L, int blk, int n_items, int bi
     uint32_t base = 0;
     if (valid && lane == leader) base = atomicAdd(&L.wh[w][digit], (uint32_t)__popcll(peers));
     base = __shfl(base, leader);
-    if (valid) ops.emit(base + (uint32_t)__popcll(peers & lt_mask), it);
+    if (valid) ops.emit(base + (uint32_t)__popcll(peers & lt_mask), items[step]);
   }
 }
 

@@ -1,0 +1,461 @@
+// Matrix-core (MFMA, fp32) kernels for the table shapes d1 = d2 = 4, r1 = r2 = R in {16, 32, 64},
+// d3 in {4, 8}: the partial product of a row is then 16 x R, and once ids that share an (i1,i2)
+// prefix, an i2 or an i3 are stacked (paper Section 4.2: they share core slices) every step of the
+// path is a dense contraction with a 16- or 32-wide side.
+//
+// Lane layouts used below (wave64):
+//   v_mfma_f32_32x32x2f32   A[i][k]: i = lane%32, k = lane/32     B[k][j]: k = lane/32, j = lane%32
+//                           D[i][j]: i = 8*(v/4) + 4*(lane/32) + v%4, j = lane%32, v = 0..15
+//   v_mfma_f32_16x16x4f32   A[i][k]: i = lane%16, k = lane/16     B[k][j]: k = lane/16, j = lane%16
+//                           D[i][j]: i = 4*(lane/16) + v, j = lane%16, v = 0..3
+// The summation index k may be enumerated in any order as long as A and B agree, so each lane
+// takes a contiguous run of k (vector loads) instead of the strided one the raw layout suggests.
+#include <algorithm>
+
+#include "tt_emb_internal.h"
+
+namespace ttemb {
+
+typedef float f4 __attribute__((ext_vector_type(4)));
+typedef float f16v __attribute__((ext_vector_type(16)));
+
+constexpr int kMThreads = 256;
+constexpr int kMWaves = kMThreads / kWave;
+
+__device__ __forceinline__ f16v mfma32(float a, float b, f16v c) {
+  return __builtin_amdgcn_mfma_f32_32x32x2f32(a, b, c, 0, 0, 0);
+}
+__device__ __forceinline__ f4 mfma16(float a, float b, f4 c) {
+  return __builtin_amdgcn_mfma_f32_16x16x4f32(a, b, c, 0, 0, 0);
+}
+
+__device__ __forceinline__ int chunk_bin(const int* __restrict__ chunk_start, int bins, int c) {
+  int lo = 0, hi = bins;  // chunk_start[lo] <= c < chunk_start[hi]
+  while (hi - lo > 1) {
+    const int mid = (lo + hi) >> 1;
+    if (chunk_start[mid] <= c) lo = mid; else hi = mid;
+  }
+  return lo;
+}
+
+// Where the gradient row of unique id u lives: >= 0 is a batch row of grad_out (the id occurs
+// once), < 0 encodes row -(x+1) of the per-id sums.
+__device__ __forceinline__ int grad_row_code(int u, const int* __restrict__ u_rs,
+                                             const uint32_t* __restrict__ perm) {
+  const int rs = u_rs[u];
+  return (u_rs[u + 1] - rs == 1) ? (int)perm[rs] : -(u + 1);
+}
+__device__ __forceinline__ const float* grad_row_ptr(int code, const float* __restrict__ grad,
+                                                     const float* __restrict__ gsum, int D) {
+  return code >= 0 ? grad + (size_t)code * D : gsum + (size_t)(-code - 1) * D;
+}
+
+// ---------------------------------------------------------------------------------------------
+// P_q = G1[i1] G2[i2] for the <= 16 prefixes of one by-i2 chunk: rows of up to eight G1 slices
+// stacked (32 x R) times the chunk's G2 slice (R x 4R).  One wavefront per chunk.
+template <int R>
+__global__ __launch_bounds__(kMThreads) void k_prefix_fwd_mfma(
+    Shape sh, const float* __restrict__ g1, const float* __restrict__ g2,
+    const int* __restrict__ g2_list, const int* __restrict__ g2_start,
+    const int* __restrict__ c2_start, const int* __restrict__ q_i1, float* __restrict__ P,
+    const Counters* __restrict__ ctr) {
+  constexpr int W = 4 * R, PN = 16 * R, S1 = 4 * R, S2 = R * W, KH = R / 2, NT = W / 32;
+  const int w = threadIdx.x / kWave, lane = threadIdx.x % kWave;
+  const int half = lane / 32, l32 = lane % 32;
+  const int nchunk = ctr->nchunk2;
+  for (int c = blockIdx.x * kMWaves + w; c < nchunk; c += gridDim.x * kMWaves) {
+    const int bin = chunk_bin(c2_start, (int)sh.n2, c);
+    const int k0 = g2_start[bin] + (c - c2_start[bin]) * kChunk2;
+    const int cnt = min(kChunk2, g2_start[bin + 1] - k0);
+    const int myq = lane < cnt ? g2_list[k0 + lane] : -1;
+    const int myi1 = myq >= 0 ? q_i1[myq] : 0;
+    const float* Bm = g2 + (size_t)bin * S2;
+
+    float a[2][KH];
+#pragma unroll
+    for (int mt = 0; mt < 2; ++mt) {
+      const int ql = mt * 8 + l32 / 4, j1 = l32 % 4;
+      const int q = __shfl(myq, ql), i1 = __shfl(myi1, ql);
+      const f4* src = (const f4*)(g1 + (size_t)i1 * S1 + j1 * R + KH * half);
+#pragma unroll
+      for (int j = 0; j < KH / 4; ++j) {
+        f4 v = q >= 0 ? src[j] : f4{0.f, 0.f, 0.f, 0.f};
+        a[mt][4 * j + 0] = v.x;
+        a[mt][4 * j + 1] = v.y;
+        a[mt][4 * j + 2] = v.z;
+        a[mt][4 * j + 3] = v.w;
+      }
+    }
+    for (int nt = 0; nt < NT; ++nt) {
+      float b[KH];
+#pragma unroll
+      for (int j = 0; j < KH; ++j) b[j] = Bm[(size_t)(KH * half + j) * W + nt * 32 + l32];
+#pragma unroll
+      for (int mt = 0; mt < 2; ++mt) {
+        if (mt * 8 >= cnt) break;
+        f16v acc = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+        for (int j = 0; j < KH; ++j) acc = mfma32(a[mt][j], b[j], acc);
+#pragma unroll
+        for (int v = 0; v < 16; ++v) {
+          const int q = __shfl(myq, mt * 8 + 2 * (v / 4) + half);
+          if (q >= 0) P[(size_t)q * PN + (v % 4) * W + nt * 32 + l32] = acc[v];
+        }
+      }
+    }
+  }
+}
+
+// ---------------------------------------------------------------------------------------------
+// Gradients at prefix level for one by-i2 chunk (<= 16 prefixes q, Bm = G2[i2]); work items are
+// (chunk, part), one wavefront each:
+//   part 0   dg1part[q] = dPsum_q Bm^T     rows of up to eight dPsum_q stacked (32 x 4R) times
+//                                          Bm^T (4R x R)
+//   part 1   part2[c] = sum_q G1[i1(q)]^T dPsum_q    (R x 4 cnt) times (4 cnt x 4R)
+template <int R>
+__global__ __launch_bounds__(kMThreads) void k_prefix_bwd_mfma(
+    Shape sh, const float* __restrict__ g1, const float* __restrict__ g2,
+    const float* __restrict__ dPsum, const int* __restrict__ g2_list,
+    const int* __restrict__ g2_start, const int* __restrict__ c2_start,
+    const int* __restrict__ q_i1, float* __restrict__ dg1part, float* __restrict__ part2,
+    const Counters* __restrict__ ctr) {
+  constexpr int W = 4 * R, PN = 16 * R, S1 = 4 * R, S2 = R * W;
+  const int w = threadIdx.x / kWave, lane = threadIdx.x % kWave;
+  const int half = lane / 32, l32 = lane % 32;
+  const int nitems = ctr->nchunk2 * 2;
+  for (int item = blockIdx.x * kMWaves + w; item < nitems; item += gridDim.x * kMWaves) {
+    const int c = item >> 1, part = item & 1;
+    const int bin = chunk_bin(c2_start, (int)sh.n2, c);
+    const int k0 = g2_start[bin] + (c - c2_start[bin]) * kChunk2;
+    const int cnt = min(kChunk2, g2_start[bin + 1] - k0);
+    const int myq = lane < cnt ? g2_list[k0 + lane] : -1;
+    const int myi1 = myq >= 0 ? q_i1[myq] : 0;
+    const float* Bm = g2 + (size_t)bin * S2;
+
+    if (part == 0) {
+      constexpr int NT = (R + 31) / 32;
+      for (int mt = 0; mt < 2; ++mt) {
+        if (mt * 8 >= cnt) break;
+        const int q = __shfl(myq, mt * 8 + l32 / 4), j1 = l32 % 4;
+        const float* arow = dPsum + (size_t)(q >= 0 ? q : 0) * PN + j1 * W;
+        for (int nt = 0; nt < NT; ++nt) {
+          const int n = nt * 32 + l32;
+          const float* brow = Bm + (size_t)(n < R ? n : 0) * W;
+          f16v acc = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
+          for (int kb = 0; kb < W / 64; ++kb) {
+            const int kbase = kb * 64 + 32 * half;
+            f4 av[8], bv[8];
+#pragma unroll
+            for (int j = 0; j < 8; ++j) {
+              av[j] = ((const f4*)(arow + kbase))[j];
+              bv[j] = ((const f4*)(brow + kbase))[j];
+            }
+#pragma unroll
+            for (int j = 0; j < 8; ++j) {
+              if (q < 0) av[j] = f4{0.f, 0.f, 0.f, 0.f};
+              if (n >= R) bv[j] = f4{0.f, 0.f, 0.f, 0.f};
+              acc = mfma32(av[j].x, bv[j].x, acc);
+              acc = mfma32(av[j].y, bv[j].y, acc);
+              acc = mfma32(av[j].z, bv[j].z, acc);
+              acc = mfma32(av[j].w, bv[j].w, acc);
+            }
+          }
+#pragma unroll
+          for (int v = 0; v < 16; ++v) {
+            const int qv = __shfl(myq, mt * 8 + 2 * (v / 4) + half);
+            if (qv >= 0 && n < R) dg1part[(size_t)qv * S1 + (v % 4) * R + n] = acc[v];
+          }
+        }
+      }
+    } else {
+      constexpr int MT = (R + 31) / 32, NT = W / 32;
+      int qh[8], ih[8];  // the eight prefixes whose rows this half of the wavefront feeds as k
+#pragma unroll
+      for (int jq = 0; jq < 8; ++jq) {
+        qh[jq] = __shfl(myq, 8 * half + jq);
+        ih[jq] = __shfl(myi1, 8 * half + jq);
+      }
+      for (int mt = 0; mt < MT; ++mt) {
+        const int m = mt * 32 + l32;
+        float a[32];
+#pragma unroll
+        for (int j = 0; j < 32; ++j)
+          a[j] = (qh[j / 4] >= 0 && m < R) ? g1[(size_t)ih[j / 4] * S1 + (j % 4) * R + m] : 0.f;
+        for (int nt = 0; nt < NT; ++nt) {
+          const int n = nt * 32 + l32;
+          float b[32];
+#pragma unroll
+          for (int j = 0; j < 32; ++j)
+            b[j] = qh[j / 4] >= 0 ? dPsum[(size_t)qh[j / 4] * PN + (j % 4) * W + n] : 0.f;
+          f16v acc = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+          for (int j = 0; j < 32; ++j) acc = mfma32(a[j], b[j], acc);
+#pragma unroll
+          for (int v = 0; v < 16; ++v) {
+            const int mrow = mt * 32 + 8 * (v / 4) + 4 * half + (v % 4);
+            if (mrow < R) part2[(size_t)c * S2 + (size_t)mrow * W + n] = acc[v];
+          }
+        }
+      }
+    }
+  }
+}
+
+// ---------------------------------------------------------------------------------------------
+// dPsum_q = sum over the unique ids u of prefix q of g_u G3[i3(u)]^T  (16 x D3 times D3 x R).
+// One wavefront per prefix; the ids of a prefix extend the contraction index.
+template <int R, int D3>
+__global__ __launch_bounds__(kMThreads) void k_u_bwd_mfma(
+    const float* __restrict__ g3, const float* __restrict__ grad, const float* __restrict__ gsum,
+    const uint32_t* __restrict__ perm, const int* __restrict__ u_rs, const int* __restrict__ u_i3,
+    const int* __restrict__ q_us, float* __restrict__ dPsum, const Counters* __restrict__ ctr) {
+  constexpr int PN = 16 * R, S3 = R * D3, D = 16 * D3, NT = R / 16, KS = D3 / 4;
+  const int w = threadIdx.x / kWave, lane = threadIdx.x % kWave;
+  const int l16 = lane % 16, kg = lane / 16;
+  const int Q = ctr->Q;
+  for (int q = blockIdx.x * kMWaves + w; q < Q; q += gridDim.x * kMWaves) {
+    const int u0 = q_us[q], u1 = q_us[q + 1];
+    f4 acc[NT];
+#pragma unroll
+    for (int nt = 0; nt < NT; ++nt) acc[nt] = f4{0.f, 0.f, 0.f, 0.f};
+    for (int ub = u0; ub < u1; ub += kWave) {
+      const int n = min(kWave, u1 - ub);
+      const int myi3 = lane < n ? u_i3[ub + lane] : 0;
+      const int mycode = lane < n ? grad_row_code(ub + lane, u_rs, perm) : 0;
+      for (int i = 0; i < n; ++i) {
+        const float* gp = grad_row_ptr(__shfl(mycode, i), grad, gsum, D) + l16 * D3 + KS * kg;
+        const float* cp = g3 + (size_t)__shfl(myi3, i) * S3 + l16 * D3 + KS * kg;
+        float a[KS], b[NT][KS];
+#pragma unroll
+        for (int s = 0; s < KS; ++s) a[s] = gp[s];
+#pragma unroll
+        for (int nt = 0; nt < NT; ++nt)
+#pragma unroll
+          for (int s = 0; s < KS; ++s) b[nt][s] = cp[nt * 16 * D3 + s];
+#pragma unroll
+        for (int nt = 0; nt < NT; ++nt)
+#pragma unroll
+          for (int s = 0; s < KS; ++s) acc[nt] = mfma16(a[s], b[nt][s], acc[nt]);
+      }
+    }
+    float* dst = dPsum + (size_t)q * PN;
+#pragma unroll
+    for (int nt = 0; nt < NT; ++nt)
+#pragma unroll
+      for (int v = 0; v < 4; ++v) dst[(4 * kg + v) * R + nt * 16 + l16] = acc[nt][v];
+  }
+}
+
+// ---------------------------------------------------------------------------------------------
+// part3[c]^T = sum over the <= 16 unique ids u of one by-i3 chunk of g_u^T P_q(u)
+// (D3 x 16 times 16 x R; the D3 rows occupy the first rows of a 16-row tile).
+template <int R, int D3>
+__global__ __launch_bounds__(kMThreads) void k_dg3_mfma(
+    Shape sh, const float* __restrict__ P, const float* __restrict__ grad,
+    const float* __restrict__ gsum, const uint32_t* __restrict__ perm,
+    const int* __restrict__ u_rs, const int* __restrict__ u_q, const int* __restrict__ g3_list,
+    const int* __restrict__ g3_start, const int* __restrict__ c3_start, float* __restrict__ part3,
+    const Counters* __restrict__ ctr) {
+  constexpr int PN = 16 * R, S3 = R * D3, D = 16 * D3, NT = R / 16;
+  const int w = threadIdx.x / kWave, lane = threadIdx.x % kWave;
+  const int l16 = lane % 16, kg = lane / 16;
+  const int nchunk = ctr->nchunk3;
+  for (int c = blockIdx.x * kMWaves + w; c < nchunk; c += gridDim.x * kMWaves) {
+    const int bin = chunk_bin(c3_start, (int)sh.n3, c);
+    const int k0 = g3_start[bin] + (c - c3_start[bin]) * kChunk3;
+    const int cnt = min(kChunk3, g3_start[bin + 1] - k0);
+    const int myu = lane < cnt ? g3_list[k0 + lane] : 0;
+    const int myq = lane < cnt ? u_q[myu] : 0;
+    const int mycode = lane < cnt ? grad_row_code(myu, u_rs, perm) : 0;
+    f4 acc[NT];
+#pragma unroll
+    for (int nt = 0; nt < NT; ++nt) acc[nt] = f4{0.f, 0.f, 0.f, 0.f};
+    for (int i = 0; i < cnt; ++i) {
+      const float* gp = grad_row_ptr(__shfl(mycode, i), grad, gsum, D) + (4 * kg) * D3;
+      const float* pp = P + (size_t)__shfl(myq, i) * PN + (4 * kg) * R + l16;
+      float a[4], b[NT][4];
+#pragma unroll
+      for (int s = 0; s < 4; ++s) a[s] = l16 < D3 ? gp[s * D3 + l16] : 0.f;
+#pragma unroll
+      for (int nt = 0; nt < NT; ++nt)
+#pragma unroll
+        for (int s = 0; s < 4; ++s) b[nt][s] = pp[s * R + nt * 16];
+#pragma unroll
+      for (int nt = 0; nt < NT; ++nt)
+#pragma unroll
+        for (int s = 0; s < 4; ++s) acc[nt] = mfma16(a[s], b[nt][s], acc[nt]);
+    }
+    float* dst = part3 + (size_t)c * S3;
+#pragma unroll
+    for (int nt = 0; nt < NT; ++nt)
+#pragma unroll
+      for (int v = 0; v < 4; ++v) {
+        const int j3 = 4 * kg + v;
+        if (j3 < D3) dst[(nt * 16 + l16) * D3 + j3] = acc[nt][v];
+      }
+  }
+}
+
+// ---------------------------------------------------------------------------------------------
+// Rows: one wavefront per tile of 64 sorted slots.  The distinct ids of a tile are taken in groups
+// of up to 16/D3 that share a prefix: E = P_q (16 x R) times their G3 slices side by side
+// (R x 16).  Each finished row goes through LDS so that one store instruction writes a whole row
+// to every batch position that holds the id.
+template <int R, int D3>
+__global__ __launch_bounds__(kMThreads) void k_row_fwd_mfma(
+    int B, const float* __restrict__ g3, const float* __restrict__ P, const int* __restrict__ s_u,
+    const uint32_t* __restrict__ perm, const int* __restrict__ u_i3, const int* __restrict__ u_q,
+    float* __restrict__ out, Counters* ctr) {
+  constexpr int PN = 16 * R, S3 = R * D3, D = 16 * D3, UPT = 16 / D3, KQ = R / 4, VPL = D / kWave;
+  __shared__ float ebuf[kMWaves][UPT * D];
+  const int w = threadIdx.x / kWave, lane = threadIdx.x % kWave;
+  const int l16 = lane % 16, kg = lane / 16;
+  float* E = ebuf[w];
+  const int ntiles = (B + kWave - 1) / kWave;
+  for (int tile = blockIdx.x * kMWaves + w; tile < ntiles; tile += gridDim.x * kMWaves) {
+    const int s = tile * kWave + lane;
+    const int mysu = s < B ? s_u[s] : -1;
+    const uint32_t myb = s < B ? perm[s] : 0u;
+    if (s < B && myb >= (uint32_t)B) atomicOr(&ctr->err, 4);
+    // out-of-range ids (the tail of the sorted order) get zero rows
+    unsigned long long zero_slots = __ballot(s < B && mysu < 0 && myb < (uint32_t)B);
+    while (zero_slots) {
+      const int sl = __ffsll((long long)zero_slots) - 1;
+      zero_slots &= zero_slots - 1;
+      float* o = out + (size_t)__shfl(myb, sl) * D + lane * VPL;
+#pragma unroll
+      for (int e = 0; e < VPL; ++e) o[e] = 0.f;
+    }
+    const int nv = __popcll(__ballot(mysu >= 0));
+    if (nv == 0) continue;
+    const int u_lo = __shfl(mysu, 0), nu = __shfl(mysu, nv - 1) - u_lo + 1;
+    const int myq = lane < nu ? u_q[u_lo + lane] : -1;
+    const int myi3 = lane < nu ? u_i3[u_lo + lane] : 0;
+    int i = 0;
+    while (i < nu) {
+      const int q = __shfl(myq, i);
+      int g = 1;
+      while (g < UPT && i + g < nu && __shfl(myq, i + g) == q) ++g;
+      // A = P_q: row l16, k = KQ*kg .. KQ*kg + KQ-1
+      float a[KQ], b[KQ];
+      const f4* pa = (const f4*)(P + (size_t)q * PN + l16 * R + KQ * kg);
+#pragma unroll
+      for (int j = 0; j < KQ / 4; ++j) {
+        const f4 v = pa[j];
+        a[4 * j + 0] = v.x;
+        a[4 * j + 1] = v.y;
+        a[4 * j + 2] = v.z;
+        a[4 * j + 3] = v.w;
+      }
+      // B = the group's G3 slices side by side: column l16 -> id l16/D3 of the group, j3 = l16%D3
+      const int ul = l16 / D3, j3 = l16 % D3;
+      const int i3 = __shfl(myi3, min(i + ul, nu - 1));
+      const float* pc = g3 + (size_t)i3 * S3 + (KQ * kg) * D3 + j3;
+#pragma unroll
+      for (int j = 0; j < KQ; ++j) b[j] = ul < g ? pc[j * D3] : 0.f;
+      f4 acc = {0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+      for (int j = 0; j < KQ; ++j) acc = mfma16(a[j], b[j], acc);
+      __builtin_amdgcn_wave_barrier();
+#pragma unroll
+      for (int v = 0; v < 4; ++v) E[ul * D + (4 * kg + v) * D3 + j3] = acc[v];
+      __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+      __builtin_amdgcn_wave_barrier();
+      __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+      for (int k = 0; k < g; ++k) {
+        float e[VPL];
+#pragma unroll
+        for (int x = 0; x < VPL; ++x) e[x] = E[k * D + lane * VPL + x];
+        unsigned long long slots = __ballot(mysu == u_lo + i + k);
+        while (slots) {
+          const int sl = __ffsll((long long)slots) - 1;
+          slots &= slots - 1;
+          const uint32_t b_row = __shfl(myb, sl);
+          if (b_row < (uint32_t)B) {
+            float* o = out + (size_t)b_row * D + lane * VPL;
+#pragma unroll
+            for (int x = 0; x < VPL; ++x) o[x] = e[x];
+          }
+        }
+      }
+      __builtin_amdgcn_wave_barrier();
+      i += g;
+    }
+  }
+}
+
+// ---------------------------------------------------------------------------------------------
+// dispatch
+
+bool mfma_shape(const Shape& s) {
+  return s.d1 == 4 && s.d2 == 4 && s.r1 == s.r2 && (s.r1 == 16 || s.r1 == 32 || s.r1 == 64) &&
+         (s.d3 == 4 || s.d3 == 8);
+}
+
+static inline int cdivi(int64_t a, int64_t b) { return (int)((a + b - 1) / b); }
+static inline int grid_cap(int64_t items, int cap) {
+  return (int)std::max<int64_t>(1, std::min<int64_t>(items, cap));
+}
+constexpr int kMGridCap = 256 * 8;
+
+#define TT_DISPATCH_R(R_, CALL)      \
+  switch (R_) {                      \
+    case 16: { constexpr int R = 16; CALL; } break; \
+    case 32: { constexpr int R = 32; CALL; } break; \
+    default: { constexpr int R = 64; CALL; } break; \
+  }
+#define TT_DISPATCH_RD(R_, D3_, CALL)                 \
+  if ((D3_) == 4) {                                   \
+    constexpr int D3 = 4;                             \
+    TT_DISPATCH_R(R_, CALL)                           \
+  } else {                                            \
+    constexpr int D3 = 8;                             \
+    TT_DISPATCH_R(R_, CALL)                           \
+  }
+
+void launch_prefix_fwd_mfma(const Plan& pl, const Workspace& ws, const float* g1, const float* g2,
+                            int B, hipStream_t st) {
+  const int64_t chunks = cdivi(std::min<int64_t>(B, pl.maxQ), kChunk2) + pl.sh.n2;
+  const int grid = grid_cap(cdivi(chunks, kMWaves), kMGridCap);
+  TT_DISPATCH_R(pl.sh.r1, (k_prefix_fwd_mfma<R><<<grid, kMThreads, 0, st>>>(
+                              pl.sh, g1, g2, ws.g2_list, ws.g2_start, ws.c2_start, ws.q_i1, ws.P,
+                              ws.ctr)));
+}
+
+void launch_prefix_bwd_mfma(const Plan& pl, const Workspace& ws, const float* g1, const float* g2,
+                            int B, hipStream_t st) {
+  const int64_t items = 2 * (cdivi(std::min<int64_t>(B, pl.maxQ), kChunk2) + (int64_t)pl.sh.n2);
+  const int grid = grid_cap(cdivi(items, kMWaves), kMGridCap);
+  TT_DISPATCH_R(pl.sh.r1, (k_prefix_bwd_mfma<R><<<grid, kMThreads, 0, st>>>(
+                              pl.sh, g1, g2, ws.dPsum, ws.g2_list, ws.g2_start, ws.c2_start,
+                              ws.q_i1, ws.dg1part, ws.part2, ws.ctr)));
+}
+
+void launch_u_bwd_mfma(const Plan& pl, const Workspace& ws, const float* g3, const float* grad,
+                       int B, hipStream_t st) {
+  const int grid = grid_cap(cdivi(std::min<int64_t>(B, pl.maxQ), kMWaves), kMGridCap);
+  const uint32_t* perm = ws.val[(pl.passes - 1) & 1];
+  TT_DISPATCH_RD(pl.sh.r1, pl.sh.d3, (k_u_bwd_mfma<R, D3><<<grid, kMThreads, 0, st>>>(
+                                         g3, grad, ws.gsum, perm, ws.u_rs, ws.u_i3, ws.q_us,
+                                         ws.dPsum, ws.ctr)));
+}
+
+void launch_dg3_mfma(const Plan& pl, const Workspace& ws, const float* grad, int B,
+                     hipStream_t st) {
+  const int64_t chunks = cdivi(B, kChunk3) + (int64_t)pl.sh.n3;
+  const int grid = grid_cap(cdivi(chunks, kMWaves), kMGridCap);
+  const uint32_t* perm = ws.val[(pl.passes - 1) & 1];
+  TT_DISPATCH_RD(pl.sh.r1, pl.sh.d3, (k_dg3_mfma<R, D3><<<grid, kMThreads, 0, st>>>(
+                                         pl.sh, ws.P, grad, ws.gsum, perm, ws.u_rs, ws.u_q,
+                                         ws.g3_list, ws.g3_start, ws.c3_start, ws.part3, ws.ctr)));
+}
+
+void launch_row_fwd_mfma(const Plan& pl, const Workspace& ws, const float* g3, int B, float* out,
+                         hipStream_t st) {
+  const int grid = grid_cap(cdivi(cdivi(B, kWave), kMWaves), kMGridCap);
+  const uint32_t* perm = ws.val[(pl.passes - 1) & 1];
+  TT_DISPATCH_RD(pl.sh.r1, pl.sh.d3, (k_row_fwd_mfma<R, D3><<<grid, kMThreads, 0, st>>>(
+                                         B, g3, ws.P, ws.s_u, perm, ws.u_i3, ws.u_q, out, ws.ctr)));
+}
+
+}  // namespace ttemb

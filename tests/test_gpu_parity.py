@@ -120,6 +120,22 @@ def test_generic_shapes(n, d, r, B):
     check_against_oracle(n, d, r, cores, ids, grad, 0.01)
 
 
+@pytest.mark.parametrize("flags", [0, 2])          # 2 = TT_EMB_FLAG_GENERIC_KERNELS
+@pytest.mark.parametrize("R,d3", [(16, 4), (16, 8), (32, 8), (64, 8), (32, 4), (64, 4)])
+@pytest.mark.parametrize("n,B", [((9, 21, 13), 6000), ((40, 50, 60), 5000), ((3, 2, 700), 3000)])
+def test_matrix_core_shape_family(n, B, R, d3, flags):
+    # d1 = d2 = 4 with equal ranks: the shapes that have matrix-core kernels; dense sharing
+    # (small table), sparse sharing (large table) and long runs of ids under one prefix
+    rng = np.random.default_rng(R * d3 + B)
+    d, r = (4, 4, d3), (R, R)
+    s = Shape(n, d, r)
+    cores = tuple((rng.standard_normal(cs) / np.sqrt(R)).astype(np.float32) for cs in s.core_shapes())
+    ids = rng.integers(0, s.N, size=B, dtype=np.int64)
+    ids[: B // 10] = ids[0]
+    grad = rng.standard_normal((B, s.D)).astype(np.float32)
+    check_against_oracle(n, d, r, cores, ids, grad, 0.01, flags=flags)
+
+
 @pytest.mark.parametrize("B", [1, 2, 31, 32, 33, 63, 64, 65, 1023, 1025, 4095, 4096, 8193])
 def test_ragged_batch_sizes(B):
     w, cores, _, _ = _workload(2)
