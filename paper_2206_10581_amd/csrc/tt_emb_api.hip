@@ -15,6 +15,7 @@ void launch_sort_pass(const Plan&, const Workspace&, const int64_t* ids, int B, 
                       int which);
 void launch_seg_count(const Plan&, const Workspace&, int B, hipStream_t);
 void launch_seg_write(const Plan&, const Workspace&, int B, hipStream_t);
+void launch_group_scan(const Plan&, const Workspace&, hipStream_t);
 void launch_group(const Plan&, const Workspace&, int B, hipStream_t);
 void launch_prefix_fwd(const Plan&, const Workspace&, const float* g1, const float* g2, int B,
                        hipStream_t);
@@ -39,10 +40,13 @@ void launch_u_bwd_mfma(const Plan&, const Workspace&, const float* g3, const flo
 void launch_dg3_mfma(const Plan&, const Workspace&, const float* grad, int B, hipStream_t);
 void launch_prefix_bwd_mfma(const Plan&, const Workspace&, const float* g1, const float* g2, int B,
                             hipStream_t);
+void launch_gsum_block(const Plan&, const Workspace&, const float* grad, int B, hipStream_t);
+void launch_gsum_block_fix(const Plan&, const Workspace&, int B, hipStream_t);
 
 static const char* const kSlotNames[kSlotCount] = {
-    "sort_hist", "sort_scatter", "seg_count", "seg_write", "group",      "prefix_fwd", "row_fwd",
-    "gsum",      "gsum_fix",     "u_bwd",     "dg3",       "prefix_bwd", "sgd"};
+    "sort_hist", "sort_scan", "sort_scatter", "seg_count", "seg_write",  "group_scan", "group",
+    "prefix_fwd", "row_fwd",  "gsum",         "gsum_fix",  "u_bwd",      "dg3",        "prefix_bwd",
+    "sgd"};
 
 static thread_local std::string g_hip_error = "HIP call failed";
 
@@ -122,6 +126,7 @@ static size_t carve(const Plan& pl, char* base, Workspace* ws) {
   for (int k = 0; k < 2; ++k) w.key[k] = (uint32_t*)take(mB * 4);
   for (int k = 0; k < 2; ++k) w.val[k] = (uint32_t*)take(mB * 4);
   w.cnt = (uint32_t*)take((size_t)pl.sortBlocksMax * kMaxBins * 4);
+  w.tot = (uint32_t*)take((size_t)kMaxBins * 4);
   w.seg_nu = (uint32_t*)take((size_t)pl.segBlocksMax * 4);
   w.seg_nq = (uint32_t*)take((size_t)pl.segBlocksMax * 4);
   w.s_u = (int*)take(mB * 4);
@@ -133,6 +138,8 @@ static size_t carve(const Plan& pl, char* base, Workspace* ws) {
   w.q_i2 = (int*)take(mQ * 4);
   w.cnt3 = (uint32_t*)take((size_t)pl.uBlocksMax * s.n3 * 4);
   w.cnt2 = (uint32_t*)take((size_t)pl.qBlocksMax * s.n2 * 4);
+  w.tot3 = (uint32_t*)take((size_t)s.n3 * 4);
+  w.tot2 = (uint32_t*)take((size_t)s.n2 * 4);
   w.g3_list = (int*)take(mB * 4);
   w.g3_start = (int*)take(((size_t)s.n3 + 1) * 4);
   w.c3_start = (int*)take(((size_t)s.n3 + 1) * 4);
@@ -283,12 +290,16 @@ int tt_emb_forward(tt_emb_t h, const int64_t* ids, int64_t B64, float* out, void
   for (int pass = 0; pass < pl.passes; ++pass) {
     rc = run_slot(h, kSlotSortHist, st, [&] { launch_sort_pass(pl, ws, ids, B, pass, st, 0); });
     if (rc) return rc;
+    rc = run_slot(h, kSlotSortScan, st, [&] { launch_sort_pass(pl, ws, ids, B, pass, st, 2); });
+    if (rc) return rc;
     rc = run_slot(h, kSlotSortScatter, st, [&] { launch_sort_pass(pl, ws, ids, B, pass, st, 1); });
     if (rc) return rc;
   }
   rc = run_slot(h, kSlotSegCount, st, [&] { launch_seg_count(pl, ws, B, st); });
   if (rc) return rc;
   rc = run_slot(h, kSlotSegWrite, st, [&] { launch_seg_write(pl, ws, B, st); });
+  if (rc) return rc;
+  rc = run_slot(h, kSlotGroupScan, st, [&] { launch_group_scan(pl, ws, st); });
   if (rc) return rc;
   rc = run_slot(h, kSlotGroup, st, [&] { launch_group(pl, ws, B, st); });
   if (rc) return rc;
@@ -319,9 +330,15 @@ int tt_emb_backward_update(tt_emb_t h, const float* grad_out, float lr, void* hi
   const Plan& pl = h->plan;
   const Workspace& ws = h->ws;
   int rc;
-  rc = run_slot(h, kSlotGsum, st, [&] { launch_gsum(pl, ws, grad_out, B, st); });
+  rc = run_slot(h, kSlotGsum, st, [&] {
+    if (h->mfma) launch_gsum_block(pl, ws, grad_out, B, st);
+    else launch_gsum(pl, ws, grad_out, B, st);
+  });
   if (rc) return rc;
-  rc = run_slot(h, kSlotGsumFix, st, [&] { launch_gsum_fix(pl, ws, B, st); });
+  rc = run_slot(h, kSlotGsumFix, st, [&] {
+    if (h->mfma) launch_gsum_block_fix(pl, ws, B, st);
+    else launch_gsum_fix(pl, ws, B, st);
+  });
   if (rc) return rc;
   rc = run_slot(h, kSlotUBwd, st, [&] {
     if (h->mfma) launch_u_bwd_mfma(pl, ws, h->g3, grad_out, B, st);

@@ -298,10 +298,14 @@ __device__ __forceinline__ int lower_bound_i(const int* __restrict__ a, int n, i
   return lo;
 }
 
-constexpr int kSgdSpan = 1024;  // outputs of one G2 slice handled by one job
+constexpr int kSgdCols = 32;                    // slice entries handled by one job
+constexpr int kSgdParts = kThreads / kSgdCols;  // the job's list of partials is split 8 ways
 
-// Adds up the partial gradients of every touched slice in list order and applies the SGD step.
-// Jobs: [0, n3) G3 slices, then n2*ceil(S2/kSgdSpan) pieces of G2 slices, then n1 G1 slices.
+// Adds up the partial gradients of every touched slice and applies the SGD step.  A job owns
+// kSgdCols consecutive entries of one slice; its list of partials (chunks for G3 and G2, prefixes
+// for G1) is dealt round-robin to kSgdParts groups of threads whose sums are then added in group
+// order, so the order of every sum depends on the list length only.
+// Jobs: n3*cdiv(S3) for G3, then n2*cdiv(S2) for G2, then n1*cdiv(S1) for G1.
 __global__ __launch_bounds__(kThreads) void k_sgd(Shape sh, float lr, float* __restrict__ g1,
                                                   float* __restrict__ g2, float* __restrict__ g3,
                                                   const float* __restrict__ part3,
@@ -311,41 +315,69 @@ __global__ __launch_bounds__(kThreads) void k_sgd(Shape sh, float lr, float* __r
                                                   const float* __restrict__ dg1part,
                                                   const int* __restrict__ q_i1,
                                                   const Counters* __restrict__ ctr) {
-  const int spans = (sh.S2 + kSgdSpan - 1) / kSgdSpan;
-  const int jobs3 = (int)sh.n3, jobs2 = (int)sh.n2 * spans, jobs1 = (int)sh.n1;
+  __shared__ float red[kSgdParts][kSgdCols];
+  const int col = threadIdx.x % kSgdCols, part = threadIdx.x / kSgdCols;
+  const int sp3 = (sh.S3 + kSgdCols - 1) / kSgdCols, sp2 = (sh.S2 + kSgdCols - 1) / kSgdCols,
+            sp1 = (sh.S1 + kSgdCols - 1) / kSgdCols;
+  const int64_t jobs3 = (int64_t)sh.n3 * sp3, jobs2 = (int64_t)sh.n2 * sp2,
+                jobs1 = (int64_t)sh.n1 * sp1;
   const int Q = ctr->Q;
-  for (int job = blockIdx.x; job < jobs3 + jobs2 + jobs1; job += gridDim.x) {
+  for (int64_t job = blockIdx.x; job < jobs3 + jobs2 + jobs1; job += gridDim.x) {
+    const float* src;  // partial k of the list lives at src + k*stride
+    float* G;
+    int l0, l1, stride, o, S;
     if (job < jobs3) {
-      const int c0 = c3_start[job], c1 = c3_start[job + 1];
-      if (c1 == c0) continue;
-      float* G = g3 + (size_t)job * sh.S3;
-      for (int o = threadIdx.x; o < sh.S3; o += kThreads) {
-        float acc = 0.f;
-        for (int c = c0; c < c1; ++c) acc += part3[(size_t)c * sh.S3 + o];
-        G[o] = fmaf(-lr, acc, G[o]);
-      }
+      const int bin = (int)(job / sp3);
+      o = (int)(job % sp3) * kSgdCols + col;
+      l0 = c3_start[bin];
+      l1 = c3_start[bin + 1];
+      src = part3;
+      stride = S = sh.S3;
+      G = g3 + (size_t)bin * sh.S3;
     } else if (job < jobs3 + jobs2) {
-      const int bin = (job - jobs3) / spans, span = (job - jobs3) % spans;
-      const int c0 = c2_start[bin], c1 = c2_start[bin + 1];
-      if (c1 == c0) continue;
-      float* G = g2 + (size_t)bin * sh.S2;
-      const int o1 = min((span + 1) * kSgdSpan, sh.S2);
-      for (int o = span * kSgdSpan + threadIdx.x; o < o1; o += kThreads) {
-        float acc = 0.f;
-        for (int c = c0; c < c1; ++c) acc += part2[(size_t)c * sh.S2 + o];
-        G[o] = fmaf(-lr, acc, G[o]);
-      }
+      const int64_t j = job - jobs3;
+      const int bin = (int)(j / sp2);
+      o = (int)(j % sp2) * kSgdCols + col;
+      l0 = c2_start[bin];
+      l1 = c2_start[bin + 1];
+      src = part2;
+      stride = S = sh.S2;
+      G = g2 + (size_t)bin * sh.S2;
     } else {
-      const int i1 = job - jobs3 - jobs2;
-      const int q0 = lower_bound_i(q_i1, Q, i1), q1 = lower_bound_i(q_i1, Q, i1 + 1);
-      if (q1 == q0) continue;
-      float* G = g1 + (size_t)i1 * sh.S1;
-      for (int o = threadIdx.x; o < sh.S1; o += kThreads) {
-        float acc = 0.f;
-        for (int q = q0; q < q1; ++q) acc += dg1part[(size_t)q * sh.S1 + o];
-        G[o] = fmaf(-lr, acc, G[o]);
-      }
+      const int64_t j = job - jobs3 - jobs2;
+      const int i1 = (int)(j / sp1);
+      o = (int)(j % sp1) * kSgdCols + col;
+      l0 = lower_bound_i(q_i1, Q, i1);
+      l1 = lower_bound_i(q_i1, Q, i1 + 1);
+      src = dg1part;
+      stride = S = sh.S1;
+      G = g1 + (size_t)i1 * sh.S1;
     }
+    if (l1 == l0) continue;  // slice not touched by this batch (uniform for the block)
+    float acc = 0.f;
+    if (o < S) {
+      const float* p = src + o;
+      int k = l0 + part;
+      for (; k + 3 * kSgdParts < l1; k += 4 * kSgdParts) {
+        const float a0 = p[(size_t)k * stride], a1 = p[(size_t)(k + kSgdParts) * stride],
+                    a2 = p[(size_t)(k + 2 * kSgdParts) * stride],
+                    a3 = p[(size_t)(k + 3 * kSgdParts) * stride];
+        acc += a0;
+        acc += a1;
+        acc += a2;
+        acc += a3;
+      }
+      for (; k < l1; k += kSgdParts) acc += p[(size_t)k * stride];
+    }
+    red[part][col] = acc;
+    __syncthreads();
+    if (part == 0 && o < S) {
+      float t = red[0][col];
+#pragma unroll
+      for (int k = 1; k < kSgdParts; ++k) t += red[k][col];
+      G[o] = fmaf(-lr, t, G[o]);
+    }
+    __syncthreads();
   }
 }
 
@@ -408,11 +440,12 @@ void launch_prefix_bwd(const Plan& pl, const Workspace& ws, const float* g1, con
 
 void launch_sgd(const Plan& pl, const Workspace& ws, float* g1, float* g2, float* g3, float lr,
                 hipStream_t st) {
-  const int spans = cdiv(pl.sh.S2, kSgdSpan);
-  const int64_t jobs = (int64_t)pl.sh.n3 + (int64_t)pl.sh.n2 * spans + pl.sh.n1;
-  k_sgd<<<grid_for(jobs, kGridCap), kThreads, 0, st>>>(pl.sh, lr, g1, g2, g3, ws.part3, ws.c3_start,
-                                                      ws.part2, ws.c2_start, ws.dg1part, ws.q_i1,
-                                                      ws.ctr);
+  const Shape& s = pl.sh;
+  const int64_t jobs = (int64_t)s.n3 * cdiv(s.S3, kSgdCols) + (int64_t)s.n2 * cdiv(s.S2, kSgdCols) +
+                       (int64_t)s.n1 * cdiv(s.S1, kSgdCols);
+  k_sgd<<<grid_for(jobs, kGridCap * 2), kThreads, 0, st>>>(pl.sh, lr, g1, g2, g3, ws.part3,
+                                                          ws.c3_start, ws.part2, ws.c2_start,
+                                                          ws.dg1part, ws.q_i1, ws.ctr);
 }
 
 }  // namespace ttemb

@@ -54,14 +54,15 @@ struct ScatterLds {
 };
 
 // One block's share of a stable counting-sort pass over n_items items (block blk owns items
-// [blk*kSortItems, +kSortItems)).  cnt[b][bin] holds every block's bucket counts; the block sums
-// the table itself (buckets before, blocks before) instead of waiting for a separate scan launch.
+// [blk*kSortItems, +kSortItems)).  cnt[b][bin] holds, per bucket, the items of blocks before b and
+// tot[bin] the bucket totals (both written by a column-scan kernel over the blocks' histograms).
 // ItemOps: Item load(int idx); int digit(Item); void emit(uint32_t pos, Item).
 // When starts != nullptr block 0 also writes the bins+1 bucket offsets, and with chunk > 0 the
 // offsets of the buckets' chunk lists (ceil(count/chunk) chunks per bucket) plus their total.
 template <class ItemOps>
 __device__ void stable_scatter_block(ScatterLds& L, int blk, int n_items, int bins, int nbits,
-                                     const uint32_t* __restrict__ cnt, ItemOps ops, int* starts,
+                                     const uint32_t* __restrict__ cnt,
+                                     const uint32_t* __restrict__ tot, ItemOps ops, int* starts,
                                      int chunk, int* chunk_starts, int* n_chunks) {
   const int tid = threadIdx.x;
   const int nblk = (n_items + kSortItems - 1) / kSortItems;
@@ -69,16 +70,9 @@ __device__ void stable_scatter_block(ScatterLds& L, int blk, int n_items, int bi
   if (blk >= nblk && !writes_starts) return;  // uniform for the whole block
 
   for (int bin = tid; bin < bins; bin += kSortThreads) {
-    uint32_t before = 0, total = 0;
-    const uint32_t* col = cnt + bin;
-#pragma unroll 8
-    for (int b2 = 0; b2 < nblk; ++b2) {
-      const uint32_t c = col[(size_t)b2 * bins];
-      total += c;
-      before += (b2 < blk) ? c : 0u;
-    }
+    const uint32_t total = tot[bin];
     L.tot[bin] = total;
-    L.wh[0][bin] = before;
+    L.wh[0][bin] = cnt[(size_t)blk * bins + bin];  // items of this bucket in earlier blocks
     if (chunk > 0) L.wh[1][bin] = (total + chunk - 1) / chunk;
   }
   __syncthreads();
@@ -219,10 +213,60 @@ __global__ __launch_bounds__(kSortThreads) void k_sort_hist(const int64_t* __res
 template <bool FROM_IDS>
 __global__ __launch_bounds__(kSortThreads) void k_sort_scatter(SortOps<FROM_IDS> ops, int B,
                                                                int bits,
-                                                               const uint32_t* __restrict__ cnt) {
+                                                               const uint32_t* __restrict__ cnt,
+                                                               const uint32_t* __restrict__ tot) {
   __shared__ ScatterLds L;
-  stable_scatter_block(L, (int)blockIdx.x, B, 1 << bits, bits, cnt, ops, nullptr, 0, nullptr,
+  stable_scatter_block(L, (int)blockIdx.x, B, 1 << bits, bits, cnt, tot, ops, nullptr, 0, nullptr,
                        nullptr);
+}
+
+// Turns the blocks' bucket counts cnt[b][bin] into counts of earlier blocks (exclusive scan down
+// each column) and leaves the column totals in tot[bin].  One thread per bucket.
+__device__ __forceinline__ void column_scan(uint32_t* __restrict__ cnt, uint32_t* __restrict__ tot,
+                                            int nblk, int bins, int bin) {
+  uint32_t run = 0;
+  uint32_t* col = cnt + bin;
+  int b2 = 0;
+  for (; b2 + 8 <= nblk; b2 += 8) {
+    uint32_t c[8];
+#pragma unroll
+    for (int k = 0; k < 8; ++k) c[k] = col[(size_t)(b2 + k) * bins];
+#pragma unroll
+    for (int k = 0; k < 8; ++k) {
+      col[(size_t)(b2 + k) * bins] = run;
+      run += c[k];
+    }
+  }
+  for (; b2 < nblk; ++b2) {
+    const uint32_t c = col[(size_t)b2 * bins];
+    col[(size_t)b2 * bins] = run;
+    run += c;
+  }
+  tot[bin] = run;
+}
+
+constexpr int kScanThreads = 64;
+
+__global__ __launch_bounds__(kScanThreads) void k_sort_colscan(uint32_t* __restrict__ cnt,
+                                                               uint32_t* __restrict__ tot, int nblk,
+                                                               int bins) {
+  const int bin = blockIdx.x * kScanThreads + threadIdx.x;
+  if (bin < bins) column_scan(cnt, tot, nblk, bins, bin);
+}
+
+__global__ __launch_bounds__(kScanThreads) void k_group_colscan(uint32_t* __restrict__ cnt3,
+                                                                uint32_t* __restrict__ tot3, int n3,
+                                                                uint32_t* __restrict__ cnt2,
+                                                                uint32_t* __restrict__ tot2, int n2,
+                                                                int blocks3,
+                                                                const Counters* __restrict__ ctr) {
+  if ((int)blockIdx.x < blocks3) {
+    const int bin = blockIdx.x * kScanThreads + threadIdx.x;
+    if (bin < n3) column_scan(cnt3, tot3, (ctr->U + kSortItems - 1) / kSortItems, n3, bin);
+  } else {
+    const int bin = (blockIdx.x - blocks3) * kScanThreads + threadIdx.x;
+    if (bin < n2) column_scan(cnt2, tot2, (ctr->Q + kSortItems - 1) / kSortItems, n2, bin);
+  }
 }
 
 // ---------------------------------------------------------------------------------------------
@@ -389,7 +433,9 @@ struct GroupOps {
 
 __global__ __launch_bounds__(kSortThreads) void k_group(Shape sh, int u_blocks, int bits3, int bits2,
                                                         const uint32_t* __restrict__ cnt3,
+                                                        const uint32_t* __restrict__ tot3,
                                                         const uint32_t* __restrict__ cnt2,
+                                                        const uint32_t* __restrict__ tot2,
                                                         const int* __restrict__ u_i3,
                                                         const int* __restrict__ q_i2,
                                                         int* g3_list, int* g3_start, int* c3_start,
@@ -398,11 +444,11 @@ __global__ __launch_bounds__(kSortThreads) void k_group(Shape sh, int u_blocks, 
   __shared__ ScatterLds L;
   if ((int)blockIdx.x < u_blocks) {
     GroupOps ops{u_i3, g3_list};
-    stable_scatter_block(L, (int)blockIdx.x, ctr->U, (int)sh.n3, bits3, cnt3, ops, g3_start,
+    stable_scatter_block(L, (int)blockIdx.x, ctr->U, (int)sh.n3, bits3, cnt3, tot3, ops, g3_start,
                          kChunk3, c3_start, &ctr->nchunk3);
   } else {
     GroupOps ops{q_i2, g2_list};
-    stable_scatter_block(L, (int)blockIdx.x - u_blocks, ctr->Q, (int)sh.n2, bits2, cnt2, ops,
+    stable_scatter_block(L, (int)blockIdx.x - u_blocks, ctr->Q, (int)sh.n2, bits2, cnt2, tot2, ops,
                          g2_start, kChunk2, c2_start, &ctr->nchunk2);
   }
 }
@@ -413,11 +459,16 @@ __global__ __launch_bounds__(kSortThreads) void k_group(Shape sh, int u_blocks, 
 static inline int cdiv(int64_t a, int64_t b) { return (int)((a + b - 1) / b); }
 
 void launch_sort_pass(const Plan& pl, const Workspace& ws, const int64_t* ids, int B, int pass,
-                      hipStream_t st, int which /*0 = histogram, 1 = scatter*/) {
+                      hipStream_t st, int which /*0 = histogram, 1 = scatter, 2 = column scan*/) {
   const int blocks = cdiv(B, kSortItems);
   const int shift = pass * pl.bitsPerPass;
   const int bits = std::min(pl.bitsPerPass, pl.keyBits - shift);
   const uint32_t N = pl.sh.N;
+  if (which == 2) {
+    k_sort_colscan<<<cdiv(1 << bits, kScanThreads), kScanThreads, 0, st>>>(ws.cnt, ws.tot, blocks,
+                                                                         1 << bits);
+    return;
+  }
   if (pass == 0) {
     if (which == 0) {
       k_sort_hist<true><<<blocks, kSortThreads, 0, st>>>(
@@ -425,7 +476,7 @@ void launch_sort_pass(const Plan& pl, const Workspace& ws, const int64_t* ids, i
           pl.qBlocksMax * (int)pl.sh.n2, ws.ctr);
     } else {
       SortOps<true> ops{ids, nullptr, nullptr, ws.key[0], ws.val[0], N, shift, (1u << bits) - 1u};
-      k_sort_scatter<true><<<blocks, kSortThreads, 0, st>>>(ops, B, bits, ws.cnt);
+      k_sort_scatter<true><<<blocks, kSortThreads, 0, st>>>(ops, B, bits, ws.cnt, ws.tot);
     }
   } else {
     const int src = (pass - 1) & 1, dst = pass & 1;
@@ -435,7 +486,7 @@ void launch_sort_pass(const Plan& pl, const Workspace& ws, const int64_t* ids, i
     } else {
       SortOps<false> ops{nullptr, ws.key[src], ws.val[src], ws.key[dst], ws.val[dst], N, shift,
                          (1u << bits) - 1u};
-      k_sort_scatter<false><<<blocks, kSortThreads, 0, st>>>(ops, B, bits, ws.cnt);
+      k_sort_scatter<false><<<blocks, kSortThreads, 0, st>>>(ops, B, bits, ws.cnt, ws.tot);
     }
   }
 }
@@ -453,11 +504,18 @@ void launch_seg_write(const Plan& pl, const Workspace& ws, int B, hipStream_t st
                                                          ws.q_i1, ws.q_i2, ws.cnt3, ws.cnt2, ws.ctr);
 }
 
+void launch_group_scan(const Plan& pl, const Workspace& ws, hipStream_t st) {
+  const int b3 = cdiv(pl.sh.n3, kScanThreads), b2 = cdiv(pl.sh.n2, kScanThreads);
+  k_group_colscan<<<b3 + b2, kScanThreads, 0, st>>>(ws.cnt3, ws.tot3, (int)pl.sh.n3, ws.cnt2, ws.tot2,
+                                                   (int)pl.sh.n2, b3, ws.ctr);
+}
+
 void launch_group(const Plan& pl, const Workspace& ws, int B, hipStream_t st) {
   // blocks are sized from upper bounds (U <= B, Q <= min(B, n1*n2)); surplus blocks return at once
   const int ub = cdiv(B, kSortItems);
   const int qb = cdiv(std::min((int64_t)B, pl.maxQ), kSortItems);
-  k_group<<<ub + qb, kSortThreads, 0, st>>>(pl.sh, ub, pl.bits3, pl.bits2, ws.cnt3, ws.cnt2, ws.u_i3,
+  k_group<<<ub + qb, kSortThreads, 0, st>>>(pl.sh, ub, pl.bits3, pl.bits2, ws.cnt3, ws.tot3, ws.cnt2,
+                                           ws.tot2, ws.u_i3,
                                            ws.q_i2, ws.g3_list, ws.g3_start, ws.c3_start,
                                            ws.g2_list, ws.g2_start, ws.c2_start, ws.ctr);
 }

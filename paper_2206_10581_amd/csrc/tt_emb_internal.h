@@ -55,6 +55,7 @@ struct Workspace {
   uint32_t* key[2];   // radix-sort ping-pong keys      [maxB]
   uint32_t* val[2];   // radix-sort ping-pong positions [maxB]
   uint32_t* cnt;      // per-block digit histograms     [sortBlocks * kMaxBins]
+  uint32_t* tot;      // digit totals of the current pass  [kMaxBins]
   uint32_t* seg_nu;   // new-id flags per segment block     [segBlocks]
   uint32_t* seg_nq;   // new-prefix flags per segment block [segBlocks]
   int* s_u;           // sorted slot -> unique-id index (-1 for out-of-range ids) [maxB]
@@ -66,6 +67,8 @@ struct Workspace {
   int* q_i2;          // prefix -> i2                    [maxQ]
   uint32_t* cnt3;     // per-block histograms of i3 over unique ids   [uBlocks * n3]
   uint32_t* cnt2;     // per-block histograms of i2 over prefixes     [qBlocks * n2]
+  uint32_t* tot3;     // unique ids per i3  [n3]
+  uint32_t* tot2;     // prefixes per i2    [n2]
   int* g3_list;       // unique ids grouped by i3 (stable)  [maxB]
   int* g3_start;      // [n3+1]
   int* c3_start;      // first chunk of each i3 group [n3+1]
@@ -92,9 +95,11 @@ struct Plan {
 
 enum KernelSlot {
   kSlotSortHist = 0,
+  kSlotSortScan,
   kSlotSortScatter,
   kSlotSegCount,
   kSlotSegWrite,
+  kSlotGroupScan,
   kSlotGroup,
   kSlotPrefixFwd,
   kSlotRowFwd,

@@ -385,6 +385,187 @@ __global__ __launch_bounds__(kMThreads) void k_row_fwd_mfma(
 }
 
 // ---------------------------------------------------------------------------------------------
+// Sums grad_out over runs of equal ids (rows of D = 64*VPL floats, VPL floats per lane).
+// A block takes 256 consecutive sorted slots, 64 per wavefront.  Each wavefront loads the rows of
+// its slots (32 at a time, all loads in flight together), adds them up run by run in slot order,
+// and finishes the runs that lie inside its 64 slots; ids that occur once are skipped, later
+// kernels read their row from grad_out directly.  Pieces of runs that cross wavefronts are joined
+// in LDS, pieces that cross blocks leave one partial per block in carry[block][h] (h = 0: the run
+// began in an earlier block, h = 1: it begins here and continues).
+constexpr int kGsumBlockSlots = kMWaves * kWave;  // 256
+
+template <int VPL>
+struct LaneVec {
+  float v[VPL];
+};
+
+template <int VPL>
+__global__ __launch_bounds__(kMThreads) void k_gsum_block(int B, const float* __restrict__ grad,
+                                                          const int* __restrict__ s_u,
+                                                          const uint32_t* __restrict__ perm,
+                                                          float* __restrict__ gsum,
+                                                          float* __restrict__ carry, Counters* ctr) {
+  constexpr int D = kWave * VPL;
+  __shared__ float part[kMWaves][2][D];  // [wave][0 = head piece, 1 = tail piece]
+  __shared__ int head_state[kMWaves];    // 0 none, 1 head piece ends in this wave, 2 it runs through
+  __shared__ int tail_u[kMWaves];        // id whose run starts in this wave and continues, or -1
+  const int w = threadIdx.x / kWave, lane = threadIdx.x % kWave;
+  const int nbt = (B + kGsumBlockSlots - 1) / kGsumBlockSlots;
+  for (int bt = blockIdx.x; bt < nbt; bt += gridDim.x) {
+    const int wt0 = bt * kGsumBlockSlots + w * kWave;
+    const int s = wt0 + lane;
+    const int mysu = s < B ? s_u[s] : -1;
+    const uint32_t myb = s < B ? perm[s] : 0u;
+    if (s < B && myb >= (uint32_t)B) atomicOr(&ctr->err, 8);
+    const int prev_su = (wt0 > 0 && wt0 - 1 < B) ? s_u[wt0 - 1] : -2;
+    const int next_su = (wt0 + kWave < B) ? s_u[wt0 + kWave] : -2;
+    const int nv = __popcll(__ballot(mysu >= 0));
+    // a slot needs its row loaded unless its id occurs exactly once in the whole batch
+    int su_before = __shfl_up(mysu, 1), su_after = __shfl_down(mysu, 1);
+    if (lane == 0) su_before = prev_su;
+    if (lane == kWave - 1) su_after = next_su;
+    const bool need = mysu >= 0 && myb < (uint32_t)B && (su_before == mysu || su_after == mysu);
+    const unsigned long long need_mask = __ballot(need);
+
+    if (lane == 0) {
+      head_state[w] = 0;
+      tail_u[w] = -1;
+    }
+    LaneVec<VPL> acc;
+    int cur = -2, cur_first = 0;
+    auto flush = [&](int end_slot) {  // the run of cur covers tile slots [cur_first, end_slot)
+      if (cur < 0) return;
+      const bool starts_here = cur_first > 0 || prev_su != cur;
+      const bool ends_here = end_slot < kWave || next_su != cur;
+      if (starts_here && ends_here) {
+        if (end_slot - cur_first > 1) {
+          float* o = gsum + (size_t)cur * D + lane * VPL;
+#pragma unroll
+          for (int x = 0; x < VPL; ++x) o[x] = acc.v[x];
+        }
+      } else {
+        const int h = starts_here ? 1 : 0;
+#pragma unroll
+        for (int x = 0; x < VPL; ++x) part[w][h][lane * VPL + x] = acc.v[x];
+        if (lane == 0) {
+          if (h == 0) head_state[w] = ends_here ? 1 : 2;
+          else tail_u[w] = cur;
+        }
+      }
+    };
+    for (int half = 0; half < 2; ++half) {
+      if (half * 32 >= nv) break;
+      LaneVec<VPL> r[32];
+#pragma unroll
+      for (int k = 0; k < 32; ++k) {
+        const int slot = half * 32 + k;
+        const uint32_t b_row = __shfl(myb, slot);
+        if ((need_mask >> slot) & 1ull) {
+          const float* g = grad + (size_t)b_row * D + lane * VPL;
+#pragma unroll
+          for (int x = 0; x < VPL; ++x) r[k].v[x] = g[x];
+        } else {
+#pragma unroll
+          for (int x = 0; x < VPL; ++x) r[k].v[x] = 0.f;
+        }
+      }
+#pragma unroll
+      for (int k = 0; k < 32; ++k) {
+        const int slot = half * 32 + k;
+        if (slot < nv) {
+          const int u = __shfl(mysu, slot);
+          if (u != cur) {
+            flush(slot);
+            cur = u;
+            cur_first = slot;
+#pragma unroll
+            for (int x = 0; x < VPL; ++x) acc.v[x] = 0.f;
+          }
+#pragma unroll
+          for (int x = 0; x < VPL; ++x) acc.v[x] += r[k].v[x];
+        }
+      }
+    }
+    flush(nv);
+    __syncthreads();
+    // join the pieces inside the block, in wave order
+    // (a) the run that begins in this wave's tail
+    if (tail_u[w] >= 0) {
+      LaneVec<VPL> t;
+#pragma unroll
+      for (int x = 0; x < VPL; ++x) t.v[x] = part[w][1][lane * VPL + x];
+      bool open = true;
+      for (int k = w + 1; k < kMWaves && open; ++k) {
+        if (head_state[k] == 0) {  // cannot happen for a run that continues; keeps the loop safe
+          open = false;
+          break;
+        }
+#pragma unroll
+        for (int x = 0; x < VPL; ++x) t.v[x] += part[k][0][lane * VPL + x];
+        if (head_state[k] == 1) open = false;
+      }
+      float* o = open ? carry + ((size_t)bt * 2 + 1) * D : gsum + (size_t)tail_u[w] * D;
+#pragma unroll
+      for (int x = 0; x < VPL; ++x) o[lane * VPL + x] = t.v[x];
+    }
+    // (b) the run that came in from an earlier block
+    if (w == 0 && head_state[0] != 0) {
+      LaneVec<VPL> t;
+#pragma unroll
+      for (int x = 0; x < VPL; ++x) t.v[x] = part[0][0][lane * VPL + x];
+      for (int k = 1; k < kMWaves && head_state[k - 1] == 2; ++k) {
+        if (head_state[k] == 0) break;
+#pragma unroll
+        for (int x = 0; x < VPL; ++x) t.v[x] += part[k][0][lane * VPL + x];
+      }
+      float* o = carry + ((size_t)bt * 2) * D;
+#pragma unroll
+      for (int x = 0; x < VPL; ++x) o[lane * VPL + x] = t.v[x];
+    }
+    __syncthreads();
+  }
+}
+
+// The block in which a block-crossing run begins adds up that run's per-block partials in order.
+template <int VPL>
+__global__ __launch_bounds__(kWave) void k_gsum_block_fix(const int* __restrict__ s_u,
+                                                          const int* __restrict__ u_rs,
+                                                          const float* __restrict__ carry,
+                                                          float* __restrict__ gsum,
+                                                          const Counters* __restrict__ ctr) {
+  constexpr int D = kWave * VPL;
+  const int nvalid = ctr->nvalid, lane = threadIdx.x;
+  const int nbt = (nvalid + kGsumBlockSlots - 1) / kGsumBlockSlots;
+  for (int bt = blockIdx.x; bt < nbt; bt += gridDim.x) {
+    const int t0 = bt * kGsumBlockSlots, t1 = t0 + kGsumBlockSlots;
+    const int u = s_u[min(t1, nvalid) - 1];
+    const int rs = u_rs[u], re = u_rs[u + 1];
+    if (rs < t0 || re <= t1) continue;
+    const int last = (re - 1) / kGsumBlockSlots;
+    LaneVec<VPL> t;
+#pragma unroll
+    for (int x = 0; x < VPL; ++x) t.v[x] = carry[((size_t)bt * 2 + 1) * D + lane * VPL + x];
+    int k = bt + 1;
+    for (; k + 4 <= last + 1; k += 4) {
+      LaneVec<VPL> c[4];
+#pragma unroll
+      for (int j = 0; j < 4; ++j)
+#pragma unroll
+        for (int x = 0; x < VPL; ++x) c[j].v[x] = carry[((size_t)(k + j) * 2) * D + lane * VPL + x];
+#pragma unroll
+      for (int j = 0; j < 4; ++j)
+#pragma unroll
+        for (int x = 0; x < VPL; ++x) t.v[x] += c[j].v[x];
+    }
+    for (; k <= last; ++k)
+#pragma unroll
+      for (int x = 0; x < VPL; ++x) t.v[x] += carry[((size_t)k * 2) * D + lane * VPL + x];
+#pragma unroll
+    for (int x = 0; x < VPL; ++x) gsum[(size_t)u * D + lane * VPL + x] = t.v[x];
+  }
+}
+
+// ---------------------------------------------------------------------------------------------
 // dispatch
 
 bool mfma_shape(const Shape& s) {
@@ -456,6 +637,24 @@ void launch_row_fwd_mfma(const Plan& pl, const Workspace& ws, const float* g3, i
   const uint32_t* perm = ws.val[(pl.passes - 1) & 1];
   TT_DISPATCH_RD(pl.sh.r1, pl.sh.d3, (k_row_fwd_mfma<R, D3><<<grid, kMThreads, 0, st>>>(
                                          B, g3, ws.P, ws.s_u, perm, ws.u_i3, ws.u_q, out, ws.ctr)));
+}
+
+void launch_gsum_block(const Plan& pl, const Workspace& ws, const float* grad, int B,
+                       hipStream_t st) {
+  const int grid = grid_cap(cdivi(B, kGsumBlockSlots), kMGridCap);
+  const uint32_t* perm = ws.val[(pl.passes - 1) & 1];
+  if (pl.sh.D == 64)
+    k_gsum_block<1><<<grid, kMThreads, 0, st>>>(B, grad, ws.s_u, perm, ws.gsum, ws.carry, ws.ctr);
+  else
+    k_gsum_block<2><<<grid, kMThreads, 0, st>>>(B, grad, ws.s_u, perm, ws.gsum, ws.carry, ws.ctr);
+}
+
+void launch_gsum_block_fix(const Plan& pl, const Workspace& ws, int B, hipStream_t st) {
+  const int grid = grid_cap(cdivi(B, kGsumBlockSlots), kMGridCap);
+  if (pl.sh.D == 64)
+    k_gsum_block_fix<1><<<grid, kWave, 0, st>>>(ws.s_u, ws.u_rs, ws.carry, ws.gsum, ws.ctr);
+  else
+    k_gsum_block_fix<2><<<grid, kWave, 0, st>>>(ws.s_u, ws.u_rs, ws.carry, ws.gsum, ws.ctr);
 }
 
 }  // namespace ttemb
