@@ -133,6 +133,7 @@ static size_t carve(const Plan& pl, char* base, Workspace* ws) {
   w.u_rs = (int*)take((mB + 1) * 4);
   w.u_i3 = (int*)take(mB * 4);
   w.u_q = (int*)take(mB * 4);
+  w.u_code = (int*)take(mB * 4);
   w.q_us = (int*)take((mQ + 1) * 4);
   w.q_i1 = (int*)take(mQ * 4);
   w.q_i2 = (int*)take(mQ * 4);
@@ -143,9 +144,13 @@ static size_t carve(const Plan& pl, char* base, Workspace* ws) {
   w.g3_list = (int*)take(mB * 4);
   w.g3_start = (int*)take(((size_t)s.n3 + 1) * 4);
   w.c3_start = (int*)take(((size_t)s.n3 + 1) * 4);
+  w.c3_desc = (int4*)take((size_t)pl.maxChunk3 * 16);
   w.g2_list = (int*)take(mQ * 4);
   w.g2_start = (int*)take(((size_t)s.n2 + 1) * 4);
   w.c2_start = (int*)take(((size_t)s.n2 + 1) * 4);
+  w.c2_desc = (int4*)take((size_t)pl.maxChunk2 * 16);
+  w.g1_first = (int*)take((size_t)s.n1 * 8);  // g1_first[n1] followed by g1_end[n1]
+  w.g1_end = w.g1_first + s.n1;
   w.P = (float*)take(mQ * s.PN * 4);
   w.gsum = (float*)take(mB * s.D * 4);
   w.carry = (float*)take((size_t)pl.tilesMax * 2 * s.D * 4);

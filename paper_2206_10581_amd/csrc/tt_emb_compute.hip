@@ -25,12 +25,11 @@ constexpr int kWavesPerBlock = kThreads / kWave;
 __device__ __forceinline__ void flag_error(Counters* ctr, int bit) { atomicOr(&ctr->err, bit); }
 
 // Gradient row of unique id u: the batch row itself when the id occurs once, else its sum.
-__device__ __forceinline__ const float* grad_of_unique(int u, const int* __restrict__ u_rs,
-                                                       const uint32_t* __restrict__ perm,
+__device__ __forceinline__ const float* grad_of_unique(int u, const int* __restrict__ u_code,
                                                        const float* __restrict__ grad,
                                                        const float* __restrict__ gsum, int D) {
-  const int rs = u_rs[u];
-  return (u_rs[u + 1] - rs == 1) ? grad + (size_t)perm[rs] * D : gsum + (size_t)u * D;
+  const int code = u_code[u];
+  return code >= 0 ? grad + (size_t)code * D : gsum + (size_t)(-code - 1) * D;
 }
 
 // ---------------------------------------------------------------------------------------------
@@ -182,8 +181,7 @@ __global__ __launch_bounds__(kThreads) void k_gsum_fix(Shape sh, const int* __re
 __global__ __launch_bounds__(kThreads) void k_u_bwd(Shape sh, const float* __restrict__ g3,
                                                     const float* __restrict__ grad,
                                                     const float* __restrict__ gsum,
-                                                    const uint32_t* __restrict__ perm,
-                                                    const int* __restrict__ u_rs,
+                                                    const int* __restrict__ u_code,
                                                     const int* __restrict__ u_i3,
                                                     const int* __restrict__ q_us,
                                                     float* __restrict__ dPsum,
@@ -195,7 +193,7 @@ __global__ __launch_bounds__(kThreads) void k_u_bwd(Shape sh, const float* __res
       const int m = o / sh.r2, c = o % sh.r2;
       float acc = 0.f;
       for (int u = u0; u < u1; ++u) {
-        const float* g = grad_of_unique(u, u_rs, perm, grad, gsum, sh.D) + m * sh.d3;
+        const float* g = grad_of_unique(u, u_code, grad, gsum, sh.D) + m * sh.d3;
         const float* C = g3 + (size_t)u_i3[u] * sh.S3 + c * sh.d3;
         for (int j3 = 0; j3 < sh.d3; ++j3) acc = fmaf(g[j3], C[j3], acc);
       }
@@ -204,40 +202,27 @@ __global__ __launch_bounds__(kThreads) void k_u_bwd(Shape sh, const float* __res
   }
 }
 
-// Index of the group that owns chunk c: the last bin with chunk_start[bin] <= c.
-__device__ __forceinline__ int bin_of_chunk(const int* __restrict__ chunk_start, int bins, int c) {
-  int lo = 0, hi = bins;  // invariant: chunk_start[lo] <= c < chunk_start[hi]
-  while (hi - lo > 1) {
-    const int mid = (lo + hi) >> 1;
-    if (chunk_start[mid] <= c) lo = mid; else hi = mid;
-  }
-  return lo;
-}
-
 // part3[c] = sum over the unique ids u of chunk c (all with one i3) of P_q(u)^T g_u   (r2 x d3)
 __global__ __launch_bounds__(kThreads) void k_dg3(Shape sh, const float* __restrict__ P,
                                                   const float* __restrict__ grad,
                                                   const float* __restrict__ gsum,
-                                                  const uint32_t* __restrict__ perm,
-                                                  const int* __restrict__ u_rs,
+                                                  const int* __restrict__ u_code,
                                                   const int* __restrict__ u_q,
                                                   const int* __restrict__ g3_list,
-                                                  const int* __restrict__ g3_start,
-                                                  const int* __restrict__ c3_start,
+                                                  const int4* __restrict__ c3_desc,
                                                   float* __restrict__ part3,
                                                   const Counters* __restrict__ ctr) {
   const int nchunk = ctr->nchunk3;
   for (int c = blockIdx.x; c < nchunk; c += gridDim.x) {
-    const int bin = bin_of_chunk(c3_start, (int)sh.n3, c);
-    const int k0 = g3_start[bin] + (c - c3_start[bin]) * kChunk3;
-    const int k1 = min(k0 + kChunk3, g3_start[bin + 1]);
+    const int4 desc = c3_desc[c];
+    const int k0 = desc.y, k1 = desc.y + desc.z;
     for (int o = threadIdx.x; o < sh.S3; o += kThreads) {
       const int cc = o / sh.d3, j3 = o % sh.d3;
       float acc = 0.f;
       for (int k = k0; k < k1; ++k) {
         const int u = g3_list[k];
         const float* Pq = P + (size_t)u_q[u] * sh.PN + cc;
-        const float* g = grad_of_unique(u, u_rs, perm, grad, gsum, sh.D) + j3;
+        const float* g = grad_of_unique(u, u_code, grad, gsum, sh.D) + j3;
         for (int m = 0; m < sh.M; ++m) acc = fmaf(Pq[m * sh.r2], g[m * sh.d3], acc);
       }
       part3[(size_t)c * sh.S3 + o] = acc;
@@ -253,16 +238,14 @@ __global__ __launch_bounds__(kThreads) void k_prefix_bwd(Shape sh, const float* 
                                                          const float* __restrict__ dPsum,
                                                          const int* __restrict__ q_i1,
                                                          const int* __restrict__ g2_list,
-                                                         const int* __restrict__ g2_start,
-                                                         const int* __restrict__ c2_start,
+                                                         const int4* __restrict__ c2_desc,
                                                          float* __restrict__ dg1part,
                                                          float* __restrict__ part2,
                                                          const Counters* __restrict__ ctr) {
   const int nchunk = ctr->nchunk2;
   for (int c = blockIdx.x; c < nchunk; c += gridDim.x) {
-    const int bin = bin_of_chunk(c2_start, (int)sh.n2, c);
-    const int k0 = g2_start[bin] + (c - c2_start[bin]) * kChunk2;
-    const int k1 = min(k0 + kChunk2, g2_start[bin + 1]);
+    const int4 desc = c2_desc[c];
+    const int bin = desc.x, k0 = desc.y, k1 = desc.y + desc.z;
     const float* Bm = g2 + (size_t)bin * sh.S2;
     for (int k = k0; k < k1; ++k) {
       const int q = g2_list[k];
@@ -289,23 +272,16 @@ __global__ __launch_bounds__(kThreads) void k_prefix_bwd(Shape sh, const float* 
   }
 }
 
-__device__ __forceinline__ int lower_bound_i(const int* __restrict__ a, int n, int v) {
-  int lo = 0, hi = n;
-  while (lo < hi) {
-    const int mid = (lo + hi) >> 1;
-    if (a[mid] < v) lo = mid + 1; else hi = mid;
-  }
-  return lo;
-}
-
-constexpr int kSgdCols = 32;                    // slice entries handled by one job
-constexpr int kSgdParts = kThreads / kSgdCols;  // the job's list of partials is split 8 ways
+constexpr int kSgdLanes = 32;                     // threads side by side on one partial
+constexpr int kSgdParts = kThreads / kSgdLanes;   // the job's list of partials is split 8 ways
+constexpr int kSgdPer = 4;                        // slice entries per thread
+constexpr int kSgdSpan = kSgdLanes * kSgdPer;     // 128 slice entries per job
 
 // Adds up the partial gradients of every touched slice and applies the SGD step.  A job owns
-// kSgdCols consecutive entries of one slice; its list of partials (chunks for G3 and G2, prefixes
+// kSgdSpan consecutive entries of one slice; its list of partials (chunks for G3 and G2, prefixes
 // for G1) is dealt round-robin to kSgdParts groups of threads whose sums are then added in group
 // order, so the order of every sum depends on the list length only.
-// Jobs: n3*cdiv(S3) for G3, then n2*cdiv(S2) for G2, then n1*cdiv(S1) for G1.
+// Jobs: n3*cdiv(S3, span) for G3, then n2*cdiv(S2, span) for G2, then n1*cdiv(S1, span) for G1.
 __global__ __launch_bounds__(kThreads) void k_sgd(Shape sh, float lr, float* __restrict__ g1,
                                                   float* __restrict__ g2, float* __restrict__ g3,
                                                   const float* __restrict__ part3,
@@ -313,69 +289,63 @@ __global__ __launch_bounds__(kThreads) void k_sgd(Shape sh, float lr, float* __r
                                                   const float* __restrict__ part2,
                                                   const int* __restrict__ c2_start,
                                                   const float* __restrict__ dg1part,
-                                                  const int* __restrict__ q_i1,
-                                                  const Counters* __restrict__ ctr) {
-  __shared__ float red[kSgdParts][kSgdCols];
-  const int col = threadIdx.x % kSgdCols, part = threadIdx.x / kSgdCols;
-  const int sp3 = (sh.S3 + kSgdCols - 1) / kSgdCols, sp2 = (sh.S2 + kSgdCols - 1) / kSgdCols,
-            sp1 = (sh.S1 + kSgdCols - 1) / kSgdCols;
+                                                  const int* __restrict__ g1_first,
+                                                  const int* __restrict__ g1_end) {
+  __shared__ float red[kSgdParts][kSgdSpan];
+  const int lane = threadIdx.x % kSgdLanes, part = threadIdx.x / kSgdLanes;
+  const int sp3 = (sh.S3 + kSgdSpan - 1) / kSgdSpan, sp2 = (sh.S2 + kSgdSpan - 1) / kSgdSpan,
+            sp1 = (sh.S1 + kSgdSpan - 1) / kSgdSpan;
   const int64_t jobs3 = (int64_t)sh.n3 * sp3, jobs2 = (int64_t)sh.n2 * sp2,
                 jobs1 = (int64_t)sh.n1 * sp1;
-  const int Q = ctr->Q;
   for (int64_t job = blockIdx.x; job < jobs3 + jobs2 + jobs1; job += gridDim.x) {
-    const float* src;  // partial k of the list lives at src + k*stride
+    const float* src;  // partial k of the list lives at src + k*S
     float* G;
-    int l0, l1, stride, o, S;
+    int l0, l1, o0, S;
     if (job < jobs3) {
       const int bin = (int)(job / sp3);
-      o = (int)(job % sp3) * kSgdCols + col;
+      o0 = (int)(job % sp3) * kSgdSpan;
       l0 = c3_start[bin];
       l1 = c3_start[bin + 1];
       src = part3;
-      stride = S = sh.S3;
+      S = sh.S3;
       G = g3 + (size_t)bin * sh.S3;
     } else if (job < jobs3 + jobs2) {
       const int64_t j = job - jobs3;
       const int bin = (int)(j / sp2);
-      o = (int)(j % sp2) * kSgdCols + col;
+      o0 = (int)(j % sp2) * kSgdSpan;
       l0 = c2_start[bin];
       l1 = c2_start[bin + 1];
       src = part2;
-      stride = S = sh.S2;
+      S = sh.S2;
       G = g2 + (size_t)bin * sh.S2;
     } else {
       const int64_t j = job - jobs3 - jobs2;
       const int i1 = (int)(j / sp1);
-      o = (int)(j % sp1) * kSgdCols + col;
-      l0 = lower_bound_i(q_i1, Q, i1);
-      l1 = lower_bound_i(q_i1, Q, i1 + 1);
+      o0 = (int)(j % sp1) * kSgdSpan;
+      l0 = g1_first[i1];
+      l1 = g1_end[i1];
       src = dg1part;
-      stride = S = sh.S1;
+      S = sh.S1;
       G = g1 + (size_t)i1 * sh.S1;
     }
     if (l1 == l0) continue;  // slice not touched by this batch (uniform for the block)
-    float acc = 0.f;
-    if (o < S) {
-      const float* p = src + o;
-      int k = l0 + part;
-      for (; k + 3 * kSgdParts < l1; k += 4 * kSgdParts) {
-        const float a0 = p[(size_t)k * stride], a1 = p[(size_t)(k + kSgdParts) * stride],
-                    a2 = p[(size_t)(k + 2 * kSgdParts) * stride],
-                    a3 = p[(size_t)(k + 3 * kSgdParts) * stride];
-        acc += a0;
-        acc += a1;
-        acc += a2;
-        acc += a3;
-      }
-      for (; k < l1; k += kSgdParts) acc += p[(size_t)k * stride];
-    }
-    red[part][col] = acc;
-    __syncthreads();
-    if (part == 0 && o < S) {
-      float t = red[0][col];
+    float acc[kSgdPer];
 #pragma unroll
-      for (int k = 1; k < kSgdParts; ++k) t += red[k][col];
-      G[o] = fmaf(-lr, t, G[o]);
+    for (int x = 0; x < kSgdPer; ++x) acc[x] = 0.f;
+    for (int k = l0 + part; k < l1; k += kSgdParts) {
+      const float* p = src + (size_t)k * S + o0 + lane;
+#pragma unroll
+      for (int x = 0; x < kSgdPer; ++x)
+        if (o0 + lane + x * kSgdLanes < S) acc[x] += p[x * kSgdLanes];
+    }
+#pragma unroll
+    for (int x = 0; x < kSgdPer; ++x) red[part][lane + x * kSgdLanes] = acc[x];
+    __syncthreads();
+    if (threadIdx.x < kSgdSpan && o0 + (int)threadIdx.x < S) {
+      float t = red[0][threadIdx.x];
+#pragma unroll
+      for (int k = 1; k < kSgdParts; ++k) t += red[k][threadIdx.x];
+      G[o0 + threadIdx.x] = fmaf(-lr, t, G[o0 + threadIdx.x]);
     }
     __syncthreads();
   }
@@ -421,31 +391,31 @@ void launch_gsum_fix(const Plan& pl, const Workspace& ws, int B, hipStream_t st)
 void launch_u_bwd(const Plan& pl, const Workspace& ws, const float* g3, const float* grad, int B,
                   hipStream_t st) {
   const int grid = grid_for(std::min<int64_t>(B, pl.maxQ), kGridCap);
-  k_u_bwd<<<grid, kThreads, 0, st>>>(pl.sh, g3, grad, ws.gsum, ws.val[(pl.passes - 1) & 1], ws.u_rs,
-                                     ws.u_i3, ws.q_us, ws.dPsum, ws.ctr);
+  k_u_bwd<<<grid, kThreads, 0, st>>>(pl.sh, g3, grad, ws.gsum, ws.u_code, ws.u_i3, ws.q_us, ws.dPsum,
+                                     ws.ctr);
 }
 
 void launch_dg3(const Plan& pl, const Workspace& ws, const float* grad, int B, hipStream_t st) {
   const int grid = grid_for(cdiv(B, kChunk3) + pl.sh.n3, kGridCap);
-  k_dg3<<<grid, kThreads, 0, st>>>(pl.sh, ws.P, grad, ws.gsum, ws.val[(pl.passes - 1) & 1], ws.u_rs,
-                                   ws.u_q, ws.g3_list, ws.g3_start, ws.c3_start, ws.part3, ws.ctr);
+  k_dg3<<<grid, kThreads, 0, st>>>(pl.sh, ws.P, grad, ws.gsum, ws.u_code, ws.u_q, ws.g3_list,
+                                   ws.c3_desc, ws.part3, ws.ctr);
 }
 
 void launch_prefix_bwd(const Plan& pl, const Workspace& ws, const float* g1, const float* g2, int B,
                        hipStream_t st) {
   const int grid = grid_for(cdiv(std::min<int64_t>(B, pl.maxQ), kChunk2) + pl.sh.n2, kGridCap);
-  k_prefix_bwd<<<grid, kThreads, 0, st>>>(pl.sh, g1, g2, ws.dPsum, ws.q_i1, ws.g2_list, ws.g2_start,
-                                          ws.c2_start, ws.dg1part, ws.part2, ws.ctr);
+  k_prefix_bwd<<<grid, kThreads, 0, st>>>(pl.sh, g1, g2, ws.dPsum, ws.q_i1, ws.g2_list, ws.c2_desc,
+                                          ws.dg1part, ws.part2, ws.ctr);
 }
 
 void launch_sgd(const Plan& pl, const Workspace& ws, float* g1, float* g2, float* g3, float lr,
                 hipStream_t st) {
   const Shape& s = pl.sh;
-  const int64_t jobs = (int64_t)s.n3 * cdiv(s.S3, kSgdCols) + (int64_t)s.n2 * cdiv(s.S2, kSgdCols) +
-                       (int64_t)s.n1 * cdiv(s.S1, kSgdCols);
-  k_sgd<<<grid_for(jobs, kGridCap * 2), kThreads, 0, st>>>(pl.sh, lr, g1, g2, g3, ws.part3,
-                                                          ws.c3_start, ws.part2, ws.c2_start,
-                                                          ws.dg1part, ws.q_i1, ws.ctr);
+  const int64_t jobs = (int64_t)s.n3 * cdiv(s.S3, kSgdSpan) + (int64_t)s.n2 * cdiv(s.S2, kSgdSpan) +
+                       (int64_t)s.n1 * cdiv(s.S1, kSgdSpan);
+  k_sgd<<<grid_for(jobs, 1 << 16), kThreads, 0, st>>>(pl.sh, lr, g1, g2, g3, ws.part3, ws.c3_start,
+                                                     ws.part2, ws.c2_start, ws.dg1part,
+                                                     ws.g1_first, ws.g1_end);
 }
 
 }  // namespace ttemb

@@ -20,26 +20,48 @@ __device__ __forceinline__ uint32_t key_of_id(int64_t id, uint32_t N) {
   return ((uint64_t)id < (uint64_t)N) ? (uint32_t)id : N;
 }
 
-// In-place exclusive scan of arr[0..n) by one block of kSortThreads threads; returns the total.
-// scratch holds kSortThreads words.  Ends with a barrier.
-__device__ uint32_t block_exclusive_scan(uint32_t* arr, int n, uint32_t* scratch) {
+// ---------------------------------------------------------------------------------------------
+// block-wide helpers for 256 threads (4 wavefronts); lds4 holds at least 4 words
+
+__device__ __forceinline__ uint32_t wave_inclusive_scan(uint32_t v, int lane) {
+#pragma unroll
+  for (int off = 1; off < kWave; off <<= 1) {
+    const uint32_t t = __shfl_up(v, off);
+    if (lane >= off) v += t;
+  }
+  return v;
+}
+
+// Exclusive prefix of v over the block's threads; *total receives the block sum.
+__device__ __forceinline__ uint32_t block_exclusive_scan_value(uint32_t v, uint32_t* lds4,
+                                                               uint32_t* total) {
+  const int lane = threadIdx.x % kWave, w = threadIdx.x / kWave;
+  const uint32_t incl = wave_inclusive_scan(v, lane);
+  if (lane == kWave - 1) lds4[w] = incl;
+  __syncthreads();
+  uint32_t base = 0, tot = 0;
+#pragma unroll
+  for (int k = 0; k < kSortWaves; ++k) {
+    const uint32_t t = lds4[k];
+    base += (k < w) ? t : 0u;
+    tot += t;
+  }
+  __syncthreads();
+  *total = tot;
+  return base + incl - v;
+}
+
+// In-place exclusive scan of an LDS array arr[0..n), n <= kMaxBins; returns the total.
+__device__ uint32_t block_exclusive_scan(uint32_t* arr, int n, uint32_t* lds4) {
   const int tid = threadIdx.x;
   const int per = (n + kSortThreads - 1) / kSortThreads;
   const int lo = min(tid * per, n), hi = min(lo + per, n);
   uint32_t s = 0;
   for (int i = lo; i < hi; ++i) s += arr[i];
-  scratch[tid] = s;
-  __syncthreads();
-  for (int off = 1; off < kSortThreads; off <<= 1) {
-    uint32_t v = tid >= off ? scratch[tid - off] : 0u;
-    __syncthreads();
-    scratch[tid] += v;
-    __syncthreads();
-  }
-  uint32_t run = scratch[tid] - s;
-  const uint32_t total = scratch[kSortThreads - 1];
+  uint32_t total;
+  uint32_t run = block_exclusive_scan_value(s, lds4, &total);
   for (int i = lo; i < hi; ++i) {
-    uint32_t t = arr[i];
+    const uint32_t t = arr[i];
     arr[i] = run;
     run += t;
   }
@@ -47,56 +69,47 @@ __device__ uint32_t block_exclusive_scan(uint32_t* arr, int n, uint32_t* scratch
   return total;
 }
 
+// Lanes of a wavefront that hold the same digit (among lanes with valid set); one ballot per bit.
+__device__ __forceinline__ unsigned long long match_digit(int digit, bool valid, int nbits) {
+  unsigned long long peers = __ballot(valid);
+  for (int bit = 0; bit < nbits; ++bit) {
+    const bool one = valid && ((digit >> bit) & 1);
+    const unsigned long long vote = __ballot(one);
+    peers &= one ? vote : ~vote;
+  }
+  return peers;
+}
+
 struct ScatterLds {
-  uint32_t wh[kSortWaves][kMaxBins];  // per-wavefront histograms, then running output cursors
+  uint32_t wh[kSortWaves][kMaxBins];  // per-wavefront bucket counts, then first output positions
   uint32_t tot[kMaxBins];             // bucket totals, then this block's first output per bucket
-  uint32_t scratch[kSortThreads];
+  uint32_t aux[kMaxBins];             // chunks per bucket, then first chunk per bucket
+  uint32_t lds4[8];
 };
 
+constexpr int kSteps = kSortWaveItems / kWave;  // 16 items per lane
+
 // One block's share of a stable counting-sort pass over n_items items (block blk owns items
-// [blk*kSortItems, +kSortItems)).  cnt[b][bin] holds, per bucket, the items of blocks before b and
-// tot[bin] the bucket totals (both written by a column-scan kernel over the blocks' histograms).
+// [blk*kSortItems, +kSortItems), wavefront w of it the w-th quarter).  cnt[b][bin] holds, per
+// bucket, the items of blocks before b and tot[bin] the bucket totals (both from a column-scan
+// kernel over the blocks' histograms).
 // ItemOps: Item load(int idx); int digit(Item); void emit(uint32_t pos, Item).
-// When starts != nullptr block 0 also writes the bins+1 bucket offsets, and with chunk > 0 the
-// offsets of the buckets' chunk lists (ceil(count/chunk) chunks per bucket) plus their total.
+// With starts != nullptr the pass also publishes the bucket offsets (bins+1 entries, by block 0)
+// and, for chunk > 0, cuts every bucket into chunks of at most `chunk` items: chunk_desc[c] =
+// {bucket, first item, item count, 0} for all chunks c in bucket order, chunk_starts[bucket] the
+// first chunk of each bucket (bins+1 entries), *n_chunks the number of chunks.
 template <class ItemOps>
 __device__ void stable_scatter_block(ScatterLds& L, int blk, int n_items, int bins, int nbits,
                                      const uint32_t* __restrict__ cnt,
                                      const uint32_t* __restrict__ tot, ItemOps ops, int* starts,
-                                     int chunk, int* chunk_starts, int* n_chunks) {
+                                     int chunk, int* chunk_starts, int4* chunk_desc,
+                                     int* n_chunks) {
   const int tid = threadIdx.x;
   const int nblk = (n_items + kSortItems - 1) / kSortItems;
-  const bool writes_starts = (starts != nullptr && blk == 0);
-  if (blk >= nblk && !writes_starts) return;  // uniform for the whole block
+  const bool publishes = (starts != nullptr && blk == 0);
+  if (blk >= nblk && !publishes) return;  // uniform for the whole block
 
-  for (int bin = tid; bin < bins; bin += kSortThreads) {
-    const uint32_t total = tot[bin];
-    L.tot[bin] = total;
-    L.wh[0][bin] = cnt[(size_t)blk * bins + bin];  // items of this bucket in earlier blocks
-    if (chunk > 0) L.wh[1][bin] = (total + chunk - 1) / chunk;
-  }
-  __syncthreads();
-  const uint32_t total_items = block_exclusive_scan(L.tot, bins, L.scratch);
-  if (writes_starts) {
-    for (int bin = tid; bin < bins; bin += kSortThreads) starts[bin] = (int)L.tot[bin];
-    if (tid == 0) starts[bins] = (int)total_items;
-    if (chunk > 0) {
-      const uint32_t total_chunks = block_exclusive_scan(L.wh[1], bins, L.scratch);
-      for (int bin = tid; bin < bins; bin += kSortThreads) chunk_starts[bin] = (int)L.wh[1][bin];
-      if (tid == 0) {
-        chunk_starts[bins] = (int)total_chunks;
-        *n_chunks = (int)total_chunks;
-      }
-    }
-  }
-  if (blk >= nblk) return;
-  for (int bin = tid; bin < bins; bin += kSortThreads) L.tot[bin] += L.wh[0][bin];
-  __syncthreads();
-  for (int i = tid; i < kSortWaves * bins; i += kSortThreads) L.wh[i / bins][i % bins] = 0u;
-  __syncthreads();
-
-  // every lane keeps its 16 items (and their digits) in registers for both walks below
-  constexpr int kSteps = kSortWaveItems / kWave;
+  // items first: their loads overlap the table work below
   const int w = tid / kWave, lane = tid % kWave;
   const int wbase = blk * kSortItems + w * kSortWaveItems;
   typename ItemOps::Item items[kSteps];
@@ -106,46 +119,90 @@ __device__ void stable_scatter_block(ScatterLds& L, int blk, int n_items, int bi
     const int idx = wbase + step * kWave + lane;
     items[step] = ops.load(idx < n_items ? idx : 0);
   }
+  __builtin_amdgcn_sched_barrier(0);  // keep the loads together: their latencies overlap
 #pragma unroll
-  for (int step = 0; step < kSteps; ++step) {
-    const int idx = wbase + step * kWave + lane;
-    digits[step] = (idx < n_items) ? ops.digit(items[step]) : -1;
-  }
+  for (int step = 0; step < kSteps; ++step) digits[step] = ops.digit(items[step]);
+  __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
   for (int step = 0; step < kSteps; ++step)
-    if (digits[step] >= 0) atomicAdd(&L.wh[w][digits[step]], 1u);
+    if (wbase + step * kWave + lane >= n_items) digits[step] = -1;
+
+  for (int bin = tid; bin < bins; bin += kSortThreads) {
+    const uint32_t total = tot[bin];
+    L.tot[bin] = total;
+    L.wh[0][bin] = cnt[(size_t)blk * bins + bin];  // items of this bucket in earlier blocks
+    if (chunk > 0) L.aux[bin] = (total + chunk - 1) / chunk;
+  }
+  __syncthreads();
+  const uint32_t total_items = block_exclusive_scan(L.tot, bins, L.lds4);
+  if (starts != nullptr) {
+    if (publishes) {
+      for (int bin = tid; bin < bins; bin += kSortThreads) starts[bin] = (int)L.tot[bin];
+      if (tid == 0) starts[bins] = (int)total_items;
+    }
+    if (chunk > 0) {
+      // every participating block takes a share of the chunk descriptors
+      const uint32_t total_chunks = block_exclusive_scan(L.aux, bins, L.lds4);
+      if (publishes) {
+        for (int bin = tid; bin < bins; bin += kSortThreads) chunk_starts[bin] = (int)L.aux[bin];
+        if (tid == 0) {
+          chunk_starts[bins] = (int)total_chunks;
+          *n_chunks = (int)total_chunks;
+        }
+      }
+      const int nshare = max(nblk, 1);
+      for (uint32_t c = (uint32_t)blk * kSortThreads + tid; c < total_chunks;
+           c += (uint32_t)nshare * kSortThreads) {
+        int lo = 0, hi = bins;  // last bucket whose first chunk is <= c
+        while (hi - lo > 1) {
+          const int mid = (lo + hi) >> 1;
+          if (L.aux[mid] <= c) lo = mid; else hi = mid;
+        }
+        const uint32_t first = L.tot[lo];
+        const uint32_t end = (lo + 1 < bins) ? L.tot[lo + 1] : total_items;
+        const uint32_t k0 = first + (c - L.aux[lo]) * (uint32_t)chunk;
+        chunk_desc[c] = make_int4(lo, (int)k0, (int)min((uint32_t)chunk, end - k0), 0);
+      }
+    }
+  }
+  if (blk >= nblk) return;
+  __syncthreads();
+  for (int bin = tid; bin < bins; bin += kSortThreads) L.tot[bin] += L.wh[0][bin];
+  __syncthreads();
+  for (int i = tid; i < kSortWaves * bins; i += kSortThreads) L.wh[i / bins][i % bins] = 0u;
+  __syncthreads();
+
+  // Each wavefront walks its items in order, 64 at a time.  Lanes holding the same digit find each
+  // other by ballots; the lowest of them advances the wavefront's bucket counter for all, which
+  // gives every item its rank among the wavefront's items of that bucket.
+  const unsigned long long lt_mask = (1ull << lane) - 1ull;
+  uint32_t rank[kSteps];
+#pragma unroll
+  for (int step = 0; step < kSteps; ++step) {
+    const int digit = digits[step];
+    const bool valid = digit >= 0;
+    rank[step] = 0;
+    if (__ballot(valid) == 0ull) continue;  // wave-uniform
+    const unsigned long long peers = match_digit(digit, valid, nbits);
+    const int leader = valid ? (__ffsll((long long)peers) - 1) : lane;
+    uint32_t base = 0;
+    if (valid && lane == leader) base = atomicAdd(&L.wh[w][digit], (uint32_t)__popcll(peers));
+    rank[step] = __shfl(base, leader) + (uint32_t)__popcll(peers & lt_mask);
+  }
   __syncthreads();
   for (int bin = tid; bin < bins; bin += kSortThreads) {
     uint32_t run = L.tot[bin];
 #pragma unroll
     for (int k = 0; k < kSortWaves; ++k) {
-      uint32_t c = L.wh[k][bin];
+      const uint32_t c = L.wh[k][bin];
       L.wh[k][bin] = run;
       run += c;
     }
   }
   __syncthreads();
-
-  // Each wavefront walks its items in order, 64 at a time.  Lanes holding the same digit find each
-  // other with one ballot per digit bit; the lowest of them advances the bucket cursor for all.
-  const unsigned long long lt_mask = (1ull << lane) - 1ull;
 #pragma unroll
-  for (int step = 0; step < kSteps; ++step) {
-    const int digit = digits[step];
-    const bool valid = digit >= 0;
-    unsigned long long peers = __ballot(valid);
-    if (peers == 0ull) break;  // wave-uniform: the rest of this wavefront's range is empty
-    for (int bit = 0; bit < nbits; ++bit) {
-      const bool one = valid && ((digit >> bit) & 1);
-      const unsigned long long vote = __ballot(one);
-      peers &= one ? vote : ~vote;
-    }
-    const int leader = valid ? (__ffsll((long long)peers) - 1) : lane;
-    uint32_t base = 0;
-    if (valid && lane == leader) base = atomicAdd(&L.wh[w][digit], (uint32_t)__popcll(peers));
-    base = __shfl(base, leader);
-    if (valid) ops.emit(base + (uint32_t)__popcll(peers & lt_mask), items[step]);
-  }
+  for (int step = 0; step < kSteps; ++step)
+    if (digits[step] >= 0) ops.emit(L.wh[w][digits[step]] + rank[step], items[step]);
 }
 
 // ---------------------------------------------------------------------------------------------
@@ -177,34 +234,45 @@ struct SortOps {
   }
 };
 
-// Bucket counts of one radix digit per block.  The first pass also clears the tables that later
-// kernels of the same forward add into.
+// Bucket counts of one radix digit per block of kSortItems items.  Equal digits inside a
+// wavefront step are counted with one LDS atomic (a hot id would otherwise serialise thousands of
+// them).  The first pass also clears the tables that later kernels of the same forward add into.
 template <bool FROM_IDS>
-__global__ __launch_bounds__(kSortThreads) void k_sort_hist(const int64_t* __restrict__ ids,
-                                                            const uint32_t* __restrict__ kin, int B,
-                                                            uint32_t N, int shift, int bits,
-                                                            uint32_t* __restrict__ cnt,
-                                                            uint32_t* zero_a, int zero_a_n,
-                                                            uint32_t* zero_b, int zero_b_n,
-                                                            Counters* ctr) {
+__global__ __launch_bounds__(kSortThreads) void k_sort_hist(
+    const int64_t* __restrict__ ids, const uint32_t* __restrict__ kin, int B, uint32_t N, int shift,
+    int bits, uint32_t* __restrict__ cnt, uint32_t* zero_a, int zero_a_n, uint32_t* zero_b,
+    int zero_b_n, uint32_t* zero_c, int zero_c_n, Counters* ctr) {
   __shared__ uint32_t h[kMaxBins];
   const int tid = threadIdx.x, bins = 1 << bits;
   const uint32_t mask = (uint32_t)bins - 1u;
+  const int w = tid / kWave, lane = tid % kWave;
+  const int wbase = blockIdx.x * kSortItems + w * kSortWaveItems;
+  uint32_t keys[kSteps];
+#pragma unroll
+  for (int step = 0; step < kSteps; ++step) {
+    const int idx = wbase + step * kWave + lane;
+    const int ic = min(idx, B - 1);
+    keys[step] = FROM_IDS ? key_of_id(ids[ic], N) : kin[ic];
+  }
+  __builtin_amdgcn_sched_barrier(0);  // keep the loads together: their latencies overlap
   if (FROM_IDS) {
     const int gtid = blockIdx.x * kSortThreads + tid, gn = gridDim.x * kSortThreads;
     for (int i = gtid; i < zero_a_n; i += gn) zero_a[i] = 0u;
     for (int i = gtid; i < zero_b_n; i += gn) zero_b[i] = 0u;
+    for (int i = gtid; i < zero_c_n; i += gn) zero_c[i] = 0u;
     if (gtid == 0) ctr->err = 0;
   }
   for (int i = tid; i < bins; i += kSortThreads) h[i] = 0u;
   __syncthreads();
-  const int base = blockIdx.x * kSortItems;
-  for (int i = tid; i < kSortItems; i += kSortThreads) {
-    const int idx = base + i;
-    if (idx < B) {
-      const uint32_t key = FROM_IDS ? key_of_id(ids[idx], N) : kin[idx];
-      atomicAdd(&h[(key >> shift) & mask], 1u);
-    }
+#pragma unroll
+  for (int step = 0; step < kSteps; ++step) {
+    const int idx = wbase + step * kWave + lane;
+    const bool valid = idx < B;
+    if (__ballot(valid) == 0ull) continue;
+    const int digit = (int)((keys[step] >> shift) & mask);
+    const unsigned long long peers = match_digit(digit, valid, bits);
+    if (valid && lane == __ffsll((long long)peers) - 1)
+      atomicAdd(&h[digit], (uint32_t)__popcll(peers));
   }
   __syncthreads();
   for (int i = tid; i < bins; i += kSortThreads) cnt[(size_t)blockIdx.x * bins + i] = h[i];
@@ -217,7 +285,7 @@ __global__ __launch_bounds__(kSortThreads) void k_sort_scatter(SortOps<FROM_IDS>
                                                                const uint32_t* __restrict__ tot) {
   __shared__ ScatterLds L;
   stable_scatter_block(L, (int)blockIdx.x, B, 1 << bits, bits, cnt, tot, ops, nullptr, 0, nullptr,
-                       nullptr);
+                       nullptr, nullptr);
 }
 
 // Turns the blocks' bucket counts cnt[b][bin] into counts of earlier blocks (exclusive scan down
@@ -227,12 +295,12 @@ __device__ __forceinline__ void column_scan(uint32_t* __restrict__ cnt, uint32_t
   uint32_t run = 0;
   uint32_t* col = cnt + bin;
   int b2 = 0;
-  for (; b2 + 8 <= nblk; b2 += 8) {
-    uint32_t c[8];
+  for (; b2 + 16 <= nblk; b2 += 16) {
+    uint32_t c[16];
 #pragma unroll
-    for (int k = 0; k < 8; ++k) c[k] = col[(size_t)(b2 + k) * bins];
+    for (int k = 0; k < 16; ++k) c[k] = col[(size_t)(b2 + k) * bins];
 #pragma unroll
-    for (int k = 0; k < 8; ++k) {
+    for (int k = 0; k < 16; ++k) {
       col[(size_t)(b2 + k) * bins] = run;
       run += c[k];
     }
@@ -273,25 +341,31 @@ __global__ __launch_bounds__(kScanThreads) void k_group_colscan(uint32_t* __rest
 // Segment discovery over the sorted keys
 
 struct SegFlags {
-  uint32_t key[4];
-  bool valid[4], newu[4], newq[4], last_valid[4];
+  uint32_t key[4], prev[4];
+  bool valid[4], newu[4], newq[4], last_valid[4], single[4];
 };
 
 __device__ __forceinline__ SegFlags seg_flags(const uint32_t* __restrict__ skey, int B, uint32_t N,
                                               uint32_t n3, int s0) {
   SegFlags f;
-  uint32_t prev = (s0 > 0 && s0 - 1 < B) ? skey[s0 - 1] : 0xffffffffu;
+  uint32_t k[6];  // keys of slots s0-1 .. s0+4
+#pragma unroll
+  for (int j = 0; j < 6; ++j) {
+    const int s = s0 - 1 + j;
+    k[j] = (s >= 0 && s < B) ? skey[s] : 0xffffffffu;
+  }
+#pragma unroll
   for (int j = 0; j < 4; ++j) {
     const int s = s0 + j;
-    const uint32_t k = s < B ? skey[s] : 0xffffffffu;
-    const uint32_t next = (s + 1 < B) ? skey[s + 1] : 0xffffffffu;
-    f.key[j] = k;
-    f.valid[j] = (s < B) && (k < N);
+    const uint32_t key = k[j + 1], prev = k[j], next = k[j + 2];
+    f.key[j] = key;
+    f.prev[j] = prev;
+    f.valid[j] = (s < B) && (key < N);
     const bool first = (s == 0);
-    f.newu[j] = f.valid[j] && (first || k != prev);
-    f.newq[j] = f.valid[j] && (first || (k / n3) != (prev / n3));
+    f.newu[j] = f.valid[j] && (first || key != prev);
+    f.newq[j] = f.valid[j] && (first || (key / n3) != (prev / n3));
     f.last_valid[j] = f.valid[j] && !(next < N);
-    prev = k;
+    f.single[j] = f.newu[j] && next != key;  // the id occurs exactly once in the batch
   }
   return f;
 }
@@ -300,80 +374,58 @@ __global__ __launch_bounds__(kSegThreads) void k_seg_count(const uint32_t* __res
                                                            uint32_t N, uint32_t n3,
                                                            uint32_t* __restrict__ seg_nu,
                                                            uint32_t* __restrict__ seg_nq) {
-  __shared__ uint32_t su, sq;
-  if (threadIdx.x == 0) su = sq = 0u;
-  __syncthreads();
+  __shared__ uint32_t lds4[8];
   const SegFlags f = seg_flags(skey, B, N, n3, (int)blockIdx.x * kSegItems + (int)threadIdx.x * 4);
   uint32_t cu = 0, cq = 0;
+#pragma unroll
   for (int j = 0; j < 4; ++j) {
     cu += f.newu[j];
     cq += f.newq[j];
   }
-  if (cu) atomicAdd(&su, cu);
-  if (cq) atomicAdd(&sq, cq);
-  __syncthreads();
+  uint32_t tu, tq;
+  block_exclusive_scan_value(cu, lds4, &tu);
+  block_exclusive_scan_value(cq, lds4, &tq);
   if (threadIdx.x == 0) {
-    seg_nu[blockIdx.x] = su;
-    seg_nq[blockIdx.x] = sq;
+    seg_nu[blockIdx.x] = tu;
+    seg_nq[blockIdx.x] = tq;
   }
-}
-
-// Exclusive scan of one value per thread across a block of kSegThreads threads.
-__device__ uint32_t seg_block_scan(uint32_t v, uint32_t* lds) {
-  const int tid = threadIdx.x;
-  lds[tid] = v;
-  __syncthreads();
-  for (int off = 1; off < kSegThreads; off <<= 1) {
-    uint32_t t = tid >= off ? lds[tid - off] : 0u;
-    __syncthreads();
-    lds[tid] += t;
-    __syncthreads();
-  }
-  const uint32_t r = lds[tid] - v;
-  __syncthreads();
-  return r;
-}
-
-__device__ uint32_t seg_block_sum(uint32_t v, uint32_t* lds) {
-  const int tid = threadIdx.x;
-  lds[tid] = v;
-  __syncthreads();
-  for (int off = kSegThreads / 2; off > 0; off >>= 1) {
-    if (tid < off) lds[tid] += lds[tid + off];
-    __syncthreads();
-  }
-  const uint32_t r = lds[0];
-  __syncthreads();
-  return r;
 }
 
 // Numbers the unique ids and prefixes in sorted order, records their extents and coordinates, and
-// counts them per (block of 4096, i3) resp. (block of 4096, i2) for the grouping pass.
+// counts them per (block of 4096, i3) resp. (block of 4096, i2) for the grouping pass and per i1.
+// u_code[u] says where the gradient row of unique id u will be found: >= 0 is the batch position
+// of its only occurrence, -(u+1) means "row u of the per-id sums".
 __global__ __launch_bounds__(kSegThreads) void k_seg_write(
-    const uint32_t* __restrict__ skey, int B, Shape sh, const uint32_t* __restrict__ seg_nu,
-    const uint32_t* __restrict__ seg_nq, int* __restrict__ s_u, int* __restrict__ u_rs,
-    int* __restrict__ u_i3, int* __restrict__ u_q, int* __restrict__ q_us, int* __restrict__ q_i1,
-    int* __restrict__ q_i2, uint32_t* __restrict__ cnt3, uint32_t* __restrict__ cnt2,
-    Counters* __restrict__ ctr) {
-  __shared__ uint32_t lds[kSegThreads];
+    const uint32_t* __restrict__ skey, const uint32_t* __restrict__ perm, int B, Shape sh,
+    const uint32_t* __restrict__ seg_nu, const uint32_t* __restrict__ seg_nq, int* __restrict__ s_u,
+    int* __restrict__ u_rs, int* __restrict__ u_i3, int* __restrict__ u_q, int* __restrict__ u_code,
+    int* __restrict__ q_us, int* __restrict__ q_i1, int* __restrict__ q_i2,
+    uint32_t* __restrict__ cnt3, uint32_t* __restrict__ cnt2, int* __restrict__ g1_first,
+    int* __restrict__ g1_end, Counters* __restrict__ ctr) {
+  __shared__ uint32_t lds4[8];
   const int tid = threadIdx.x, blk = blockIdx.x;
+  const int s0 = blk * kSegItems + tid * 4;
+  const SegFlags f = seg_flags(skey, B, sh.N, sh.n3, s0);
+  uint32_t bpos[4];
+#pragma unroll
+  for (int j = 0; j < 4; ++j) bpos[j] = (s0 + j < B) ? perm[s0 + j] : 0u;
   uint32_t pu = 0, pq = 0;
   for (int b2 = tid; b2 < blk; b2 += kSegThreads) {
     pu += seg_nu[b2];
     pq += seg_nq[b2];
   }
-  const uint32_t offu = seg_block_sum(pu, lds);
-  const uint32_t offq = seg_block_sum(pq, lds);
+  uint32_t offu, offq, dummy;
+  block_exclusive_scan_value(pu, lds4, &offu);
+  block_exclusive_scan_value(pq, lds4, &offq);
 
-  const int s0 = blk * kSegItems + tid * 4;
-  const SegFlags f = seg_flags(skey, B, sh.N, sh.n3, s0);
   uint32_t cu = 0, cq = 0;
+#pragma unroll
   for (int j = 0; j < 4; ++j) {
     cu += f.newu[j];
     cq += f.newq[j];
   }
-  uint32_t ru = offu + seg_block_scan(cu, lds);  // unique ids before this thread's slots
-  uint32_t rq = offq + seg_block_scan(cq, lds);
+  uint32_t ru = offu + block_exclusive_scan_value(cu, lds4, &dummy);  // unique ids before my slots
+  uint32_t rq = offq + block_exclusive_scan_value(cq, lds4, &dummy);
 
   if (blk == 0 && tid == 0 && !f.valid[0]) {  // no in-range id at all
     ctr->U = 0;
@@ -382,6 +434,7 @@ __global__ __launch_bounds__(kSegThreads) void k_seg_write(
     u_rs[0] = 0;
     q_us[0] = 0;
   }
+#pragma unroll
   for (int j = 0; j < 4; ++j) {
     const int s = s0 + j;
     if (s >= B) break;
@@ -399,15 +452,22 @@ __global__ __launch_bounds__(kSegThreads) void k_seg_write(
       u_rs[u] = s;
       u_i3[u] = (int)i3;
       u_q[u] = q;
+      u_code[u] = f.single[j] ? (int)bpos[j] : -(u + 1);
       atomicAdd(&cnt3[(size_t)(u / kSortItems) * sh.n3 + i3], 1u);
     }
     if (f.newq[j]) {
       const uint32_t p = k / sh.n3;  // prefix number i1*n2 + i2
-      const uint32_t i2 = p % sh.n2;
+      const uint32_t i1 = p / sh.n2, i2 = p % sh.n2;
       q_us[q] = u;
-      q_i1[q] = (int)(p / sh.n2);
+      q_i1[q] = (int)i1;
       q_i2[q] = (int)i2;
       atomicAdd(&cnt2[(size_t)(q / kSortItems) * sh.n2 + i2], 1u);
+      // prefixes are numbered in (i1,i2) order: an i1 owns prefixes [g1_first, g1_end)
+      const uint32_t i1_before = (s == 0) ? 0xffffffffu : f.prev[j] / sh.n3 / sh.n2;
+      if (i1_before != i1) {
+        g1_first[i1] = q;
+        if (s != 0) g1_end[i1_before] = q;
+      }
     }
     if (f.last_valid[j]) {
       ctr->U = u + 1;
@@ -415,6 +475,7 @@ __global__ __launch_bounds__(kSegThreads) void k_seg_write(
       ctr->nvalid = s + 1;
       u_rs[u + 1] = s + 1;
       q_us[q + 1] = u + 1;
+      g1_end[k / sh.n3 / sh.n2] = q + 1;
     }
   }
 }
@@ -431,25 +492,21 @@ struct GroupOps {
   __device__ void emit(uint32_t pos, Item it) const { list[pos] = it; }
 };
 
-__global__ __launch_bounds__(kSortThreads) void k_group(Shape sh, int u_blocks, int bits3, int bits2,
-                                                        const uint32_t* __restrict__ cnt3,
-                                                        const uint32_t* __restrict__ tot3,
-                                                        const uint32_t* __restrict__ cnt2,
-                                                        const uint32_t* __restrict__ tot2,
-                                                        const int* __restrict__ u_i3,
-                                                        const int* __restrict__ q_i2,
-                                                        int* g3_list, int* g3_start, int* c3_start,
-                                                        int* g2_list, int* g2_start, int* c2_start,
-                                                        Counters* ctr) {
+__global__ __launch_bounds__(kSortThreads) void k_group(
+    Shape sh, int u_blocks, int bits3, int bits2, const uint32_t* __restrict__ cnt3,
+    const uint32_t* __restrict__ tot3, const uint32_t* __restrict__ cnt2,
+    const uint32_t* __restrict__ tot2, const int* __restrict__ u_i3, const int* __restrict__ q_i2,
+    int* g3_list, int* g3_start, int* c3_start, int4* c3_desc, int* g2_list, int* g2_start,
+    int* c2_start, int4* c2_desc, Counters* ctr) {
   __shared__ ScatterLds L;
   if ((int)blockIdx.x < u_blocks) {
     GroupOps ops{u_i3, g3_list};
     stable_scatter_block(L, (int)blockIdx.x, ctr->U, (int)sh.n3, bits3, cnt3, tot3, ops, g3_start,
-                         kChunk3, c3_start, &ctr->nchunk3);
+                         kChunk3, c3_start, c3_desc, &ctr->nchunk3);
   } else {
     GroupOps ops{q_i2, g2_list};
     stable_scatter_block(L, (int)blockIdx.x - u_blocks, ctr->Q, (int)sh.n2, bits2, cnt2, tot2, ops,
-                         g2_start, kChunk2, c2_start, &ctr->nchunk2);
+                         g2_start, kChunk2, c2_start, c2_desc, &ctr->nchunk2);
   }
 }
 
@@ -473,7 +530,7 @@ void launch_sort_pass(const Plan& pl, const Workspace& ws, const int64_t* ids, i
     if (which == 0) {
       k_sort_hist<true><<<blocks, kSortThreads, 0, st>>>(
           ids, nullptr, B, N, shift, bits, ws.cnt, ws.cnt3, pl.uBlocksMax * (int)pl.sh.n3, ws.cnt2,
-          pl.qBlocksMax * (int)pl.sh.n2, ws.ctr);
+          pl.qBlocksMax * (int)pl.sh.n2, (uint32_t*)ws.g1_first, 2 * (int)pl.sh.n1, ws.ctr);
     } else {
       SortOps<true> ops{ids, nullptr, nullptr, ws.key[0], ws.val[0], N, shift, (1u << bits) - 1u};
       k_sort_scatter<true><<<blocks, kSortThreads, 0, st>>>(ops, B, bits, ws.cnt, ws.tot);
@@ -482,7 +539,8 @@ void launch_sort_pass(const Plan& pl, const Workspace& ws, const int64_t* ids, i
     const int src = (pass - 1) & 1, dst = pass & 1;
     if (which == 0) {
       k_sort_hist<false><<<blocks, kSortThreads, 0, st>>>(nullptr, ws.key[src], B, N, shift, bits,
-                                                          ws.cnt, nullptr, 0, nullptr, 0, ws.ctr);
+                                                          ws.cnt, nullptr, 0, nullptr, 0, nullptr, 0,
+                                                          ws.ctr);
     } else {
       SortOps<false> ops{nullptr, ws.key[src], ws.val[src], ws.key[dst], ws.val[dst], N, shift,
                          (1u << bits) - 1u};
@@ -498,10 +556,10 @@ void launch_seg_count(const Plan& pl, const Workspace& ws, int B, hipStream_t st
 }
 
 void launch_seg_write(const Plan& pl, const Workspace& ws, int B, hipStream_t st) {
-  const uint32_t* skey = ws.key[(pl.passes - 1) & 1];
-  k_seg_write<<<cdiv(B, kSegItems), kSegThreads, 0, st>>>(skey, B, pl.sh, ws.seg_nu, ws.seg_nq,
-                                                         ws.s_u, ws.u_rs, ws.u_i3, ws.u_q, ws.q_us,
-                                                         ws.q_i1, ws.q_i2, ws.cnt3, ws.cnt2, ws.ctr);
+  const int f = (pl.passes - 1) & 1;
+  k_seg_write<<<cdiv(B, kSegItems), kSegThreads, 0, st>>>(
+      ws.key[f], ws.val[f], B, pl.sh, ws.seg_nu, ws.seg_nq, ws.s_u, ws.u_rs, ws.u_i3, ws.u_q,
+      ws.u_code, ws.q_us, ws.q_i1, ws.q_i2, ws.cnt3, ws.cnt2, ws.g1_first, ws.g1_end, ws.ctr);
 }
 
 void launch_group_scan(const Plan& pl, const Workspace& ws, hipStream_t st) {
@@ -515,9 +573,9 @@ void launch_group(const Plan& pl, const Workspace& ws, int B, hipStream_t st) {
   const int ub = cdiv(B, kSortItems);
   const int qb = cdiv(std::min((int64_t)B, pl.maxQ), kSortItems);
   k_group<<<ub + qb, kSortThreads, 0, st>>>(pl.sh, ub, pl.bits3, pl.bits2, ws.cnt3, ws.tot3, ws.cnt2,
-                                           ws.tot2, ws.u_i3,
-                                           ws.q_i2, ws.g3_list, ws.g3_start, ws.c3_start,
-                                           ws.g2_list, ws.g2_start, ws.c2_start, ws.ctr);
+                                           ws.tot2, ws.u_i3, ws.q_i2, ws.g3_list, ws.g3_start,
+                                           ws.c3_start, ws.c3_desc, ws.g2_list, ws.g2_start,
+                                           ws.c2_start, ws.c2_desc, ws.ctr);
 }
 
 }  // namespace ttemb

@@ -62,6 +62,7 @@ struct Workspace {
   int* u_rs;          // unique id -> first sorted slot  [maxB+1]
   int* u_i3;          // unique id -> i3                 [maxB]
   int* u_q;           // unique id -> prefix index       [maxB]
+  int* u_code;        // unique id -> where its gradient row is: batch position, or -(u+1) [maxB]
   int* q_us;          // prefix -> first unique id       [maxQ+1]
   int* q_i1;          // prefix -> i1                    [maxQ]
   int* q_i2;          // prefix -> i2                    [maxQ]
@@ -72,9 +73,13 @@ struct Workspace {
   int* g3_list;       // unique ids grouped by i3 (stable)  [maxB]
   int* g3_start;      // [n3+1]
   int* c3_start;      // first chunk of each i3 group [n3+1]
+  int4* c3_desc;      // chunk -> {i3, first list item, items, 0}  [maxChunk3]
   int* g2_list;       // prefixes grouped by i2 (stable) [maxQ]
   int* g2_start;      // [n2+1]
   int* c2_start;      // [n2+1]
+  int4* c2_desc;      // chunk -> {i2, first list item, items, 0}  [maxChunk2]
+  int* g1_first;      // i1 -> first prefix with that i1 (prefixes are sorted by i1) [n1]
+  int* g1_end;        // i1 -> one past its last prefix; directly follows g1_first  [n1]
   float* P;           // prefix products G1[i1] G2[i2]   [maxQ][PN]
   float* gsum;        // per unique id, sum of its rows' gradients [maxB][D]
   float* carry;       // per tile: head and tail partial sums [tiles][2][D]

@@ -29,48 +29,72 @@ __device__ __forceinline__ f4 mfma16(float a, float b, f4 c) {
   return __builtin_amdgcn_mfma_f32_16x16x4f32(a, b, c, 0, 0, 0);
 }
 
-__device__ __forceinline__ int chunk_bin(const int* __restrict__ chunk_start, int bins, int c) {
-  int lo = 0, hi = bins;  // chunk_start[lo] <= c < chunk_start[hi]
-  while (hi - lo > 1) {
-    const int mid = (lo + hi) >> 1;
-    if (chunk_start[mid] <= c) lo = mid; else hi = mid;
-  }
-  return lo;
-}
-
-// Where the gradient row of unique id u lives: >= 0 is a batch row of grad_out (the id occurs
-// once), < 0 encodes row -(x+1) of the per-id sums.
-__device__ __forceinline__ int grad_row_code(int u, const int* __restrict__ u_rs,
-                                             const uint32_t* __restrict__ perm) {
-  const int rs = u_rs[u];
-  return (u_rs[u + 1] - rs == 1) ? (int)perm[rs] : -(u + 1);
-}
 __device__ __forceinline__ const float* grad_row_ptr(int code, const float* __restrict__ grad,
                                                      const float* __restrict__ gsum, int D) {
+  // code >= 0: batch position of the id's only occurrence; else row -(code+1) of the per-id sums
   return code >= 0 ? grad + (size_t)code * D : gsum + (size_t)(-code - 1) * D;
 }
+
+typedef float f2 __attribute__((ext_vector_type(2)));
+
+// Value of v in lane `src`, where src is the same for the whole wavefront (a scalar read, no LDS).
+__device__ __forceinline__ int lane_value(int v, int src) {
+  return __builtin_amdgcn_readlane(v, __builtin_amdgcn_readfirstlane(src));
+}
+
+// One lane's share (VPL consecutive floats, VPL = 1 or 2) of a row, moved with a single
+// non-temporal access: rows of out and grad_out are streamed once and should not displace the
+// intermediates that the path does re-read.
+template <int VPL>
+__device__ __forceinline__ void stream_store(float* dst, const float* v) {
+  if constexpr (VPL == 2) __builtin_nontemporal_store(f2{v[0], v[1]}, (f2*)dst);
+  else __builtin_nontemporal_store(v[0], dst);
+}
+template <int VPL>
+__device__ __forceinline__ void stream_load(const float* src, float* v) {
+  if constexpr (VPL == 2) {
+    const f2 t = __builtin_nontemporal_load((const f2*)src);
+    v[0] = t.x;
+    v[1] = t.y;
+  } else {
+    v[0] = __builtin_nontemporal_load(src);
+  }
+}
+
+#define TT_ZERO16 {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f}
+
+// All kernels below are written as "issue every load of a work item, then compute": the loads of a
+// phase sit in one straight-line block that ends in sched_barrier(0), so the compiler cannot sink
+// them next to their uses (which would serialise their latencies); out-of-range lanes read a
+// clamped, valid address and their values are discarded by a select.
+#define TT_LOADS_DONE() __builtin_amdgcn_sched_barrier(0)
 
 // ---------------------------------------------------------------------------------------------
 // P_q = G1[i1] G2[i2] for the <= 16 prefixes of one by-i2 chunk: rows of up to eight G1 slices
 // stacked (32 x R) times the chunk's G2 slice (R x 4R).  One wavefront per chunk.
 template <int R>
 __global__ __launch_bounds__(kMThreads) void k_prefix_fwd_mfma(
-    Shape sh, const float* __restrict__ g1, const float* __restrict__ g2,
-    const int* __restrict__ g2_list, const int* __restrict__ g2_start,
-    const int* __restrict__ c2_start, const int* __restrict__ q_i1, float* __restrict__ P,
+    const float* __restrict__ g1, const float* __restrict__ g2, const int* __restrict__ g2_list,
+    const int4* __restrict__ c2_desc, const int* __restrict__ q_i1, float* __restrict__ P,
     const Counters* __restrict__ ctr) {
   constexpr int W = 4 * R, PN = 16 * R, S1 = 4 * R, S2 = R * W, KH = R / 2, NT = W / 32;
+  constexpr int NTG = (R == 64) ? 2 : NT;  // column tiles whose G2 operands are in flight together
+  constexpr int NG = NT / NTG;
   const int w = threadIdx.x / kWave, lane = threadIdx.x % kWave;
   const int half = lane / 32, l32 = lane % 32;
   const int nchunk = ctr->nchunk2;
   for (int c = blockIdx.x * kMWaves + w; c < nchunk; c += gridDim.x * kMWaves) {
-    const int bin = chunk_bin(c2_start, (int)sh.n2, c);
-    const int k0 = g2_start[bin] + (c - c2_start[bin]) * kChunk2;
-    const int cnt = min(kChunk2, g2_start[bin + 1] - k0);
-    const int myq = lane < cnt ? g2_list[k0 + lane] : -1;
-    const int myi1 = myq >= 0 ? q_i1[myq] : 0;
-    const float* Bm = g2 + (size_t)bin * S2;
-
+    const int4 desc = c2_desc[c];
+    const int bin = desc.x, cnt = desc.z;
+    const float* Bm = g2 + (size_t)bin * S2 + (size_t)(KH * half) * W + l32;
+    float b[2][NTG][KH];
+#pragma unroll
+    for (int t = 0; t < NTG; ++t)
+#pragma unroll
+      for (int j = 0; j < KH; ++j) b[0][t][j] = Bm[(size_t)j * W + t * 32];
+    int myq = g2_list[desc.y + min(lane, cnt - 1)];
+    const int myi1 = q_i1[myq];
+    if (lane >= cnt) myq = -1;
     float a[2][KH];
 #pragma unroll
     for (int mt = 0; mt < 2; ++mt) {
@@ -79,27 +103,42 @@ __global__ __launch_bounds__(kMThreads) void k_prefix_fwd_mfma(
       const f4* src = (const f4*)(g1 + (size_t)i1 * S1 + j1 * R + KH * half);
 #pragma unroll
       for (int j = 0; j < KH / 4; ++j) {
-        f4 v = q >= 0 ? src[j] : f4{0.f, 0.f, 0.f, 0.f};
-        a[mt][4 * j + 0] = v.x;
-        a[mt][4 * j + 1] = v.y;
-        a[mt][4 * j + 2] = v.z;
-        a[mt][4 * j + 3] = v.w;
+        f4 v = src[j];
+        a[mt][4 * j + 0] = q >= 0 ? v.x : 0.f;
+        a[mt][4 * j + 1] = q >= 0 ? v.y : 0.f;
+        a[mt][4 * j + 2] = q >= 0 ? v.z : 0.f;
+        a[mt][4 * j + 3] = q >= 0 ? v.w : 0.f;
       }
     }
-    for (int nt = 0; nt < NT; ++nt) {
-      float b[KH];
+    int qrow[2][4];  // prefix of accumulator rows v/4 of each row tile
 #pragma unroll
-      for (int j = 0; j < KH; ++j) b[j] = Bm[(size_t)(KH * half + j) * W + nt * 32 + l32];
+    for (int mt = 0; mt < 2; ++mt)
 #pragma unroll
-      for (int mt = 0; mt < 2; ++mt) {
-        if (mt * 8 >= cnt) break;
-        f16v acc = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
+      for (int x = 0; x < 4; ++x) qrow[mt][x] = __shfl(myq, mt * 8 + 2 * x + half);
+    TT_LOADS_DONE();
 #pragma unroll
-        for (int j = 0; j < KH; ++j) acc = mfma32(a[mt][j], b[j], acc);
+    for (int ng = 0; ng < NG; ++ng) {
+      if (ng + 1 < NG) {
 #pragma unroll
-        for (int v = 0; v < 16; ++v) {
-          const int q = __shfl(myq, mt * 8 + 2 * (v / 4) + half);
-          if (q >= 0) P[(size_t)q * PN + (v % 4) * W + nt * 32 + l32] = acc[v];
+        for (int t = 0; t < NTG; ++t)
+#pragma unroll
+          for (int j = 0; j < KH; ++j)
+            b[(ng + 1) & 1][t][j] = Bm[(size_t)j * W + ((ng + 1) * NTG + t) * 32];
+        TT_LOADS_DONE();
+      }
+#pragma unroll
+      for (int t = 0; t < NTG; ++t) {
+        const int nt = ng * NTG + t;
+#pragma unroll
+        for (int mt = 0; mt < 2; ++mt) {
+          f16v acc = TT_ZERO16;
+#pragma unroll
+          for (int j = 0; j < KH; ++j) acc = mfma32(a[mt][j], b[ng & 1][t][j], acc);
+#pragma unroll
+          for (int v = 0; v < 16; ++v) {
+            const int q = qrow[mt][v / 4];
+            if (q >= 0) P[(size_t)q * PN + (v % 4) * W + nt * 32 + l32] = acc[v];
+          }
         }
       }
     }
@@ -109,62 +148,73 @@ __global__ __launch_bounds__(kMThreads) void k_prefix_fwd_mfma(
 // ---------------------------------------------------------------------------------------------
 // Gradients at prefix level for one by-i2 chunk (<= 16 prefixes q, Bm = G2[i2]); work items are
 // (chunk, part), one wavefront each:
-//   part 0   dg1part[q] = dPsum_q Bm^T     rows of up to eight dPsum_q stacked (32 x 4R) times
-//                                          Bm^T (4R x R)
-//   part 1   part2[c] = sum_q G1[i1(q)]^T dPsum_q    (R x 4 cnt) times (4 cnt x 4R)
+//   part 0,1 dg1part[q] = dPsum_q Bm^T for the first / second eight prefixes: their dPsum rows
+//            stacked (32 x 4R) times Bm^T (4R x R)
+//   part 2   part2[c] = sum_q G1[i1(q)]^T dPsum_q    (R x 4 cnt) times (4 cnt x 4R)
 template <int R>
 __global__ __launch_bounds__(kMThreads) void k_prefix_bwd_mfma(
-    Shape sh, const float* __restrict__ g1, const float* __restrict__ g2,
-    const float* __restrict__ dPsum, const int* __restrict__ g2_list,
-    const int* __restrict__ g2_start, const int* __restrict__ c2_start,
-    const int* __restrict__ q_i1, float* __restrict__ dg1part, float* __restrict__ part2,
-    const Counters* __restrict__ ctr) {
+    const float* __restrict__ g1, const float* __restrict__ g2, const float* __restrict__ dPsum,
+    const int* __restrict__ g2_list, const int4* __restrict__ c2_desc, const int* __restrict__ q_i1,
+    float* __restrict__ dg1part, float* __restrict__ part2, const Counters* __restrict__ ctr) {
   constexpr int W = 4 * R, PN = 16 * R, S1 = 4 * R, S2 = R * W;
   const int w = threadIdx.x / kWave, lane = threadIdx.x % kWave;
   const int half = lane / 32, l32 = lane % 32;
-  const int nitems = ctr->nchunk2 * 2;
+  const int nitems = ctr->nchunk2 * 3;
   for (int item = blockIdx.x * kMWaves + w; item < nitems; item += gridDim.x * kMWaves) {
-    const int c = item >> 1, part = item & 1;
-    const int bin = chunk_bin(c2_start, (int)sh.n2, c);
-    const int k0 = g2_start[bin] + (c - c2_start[bin]) * kChunk2;
-    const int cnt = min(kChunk2, g2_start[bin + 1] - k0);
-    const int myq = lane < cnt ? g2_list[k0 + lane] : -1;
-    const int myi1 = myq >= 0 ? q_i1[myq] : 0;
+    const int c = item / 3, part = item % 3;
+    const int4 desc = c2_desc[c];
+    const int bin = desc.x, cnt = desc.z;
+    if (part == 1 && cnt <= 8) continue;
+    int myq = g2_list[desc.y + min(lane, cnt - 1)];
+    const int myi1 = q_i1[myq];
+    if (lane >= cnt) myq = -1;
     const float* Bm = g2 + (size_t)bin * S2;
 
-    if (part == 0) {
-      constexpr int NT = (R + 31) / 32;
-      for (int mt = 0; mt < 2; ++mt) {
-        if (mt * 8 >= cnt) break;
-        const int q = __shfl(myq, mt * 8 + l32 / 4), j1 = l32 % 4;
-        const float* arow = dPsum + (size_t)(q >= 0 ? q : 0) * PN + j1 * W;
-        for (int nt = 0; nt < NT; ++nt) {
-          const int n = nt * 32 + l32;
-          const float* brow = Bm + (size_t)(n < R ? n : 0) * W;
-          f16v acc = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
-          for (int kb = 0; kb < W / 64; ++kb) {
-            const int kbase = kb * 64 + 32 * half;
-            f4 av[8], bv[8];
+    if (part < 2) {
+      constexpr int NT = (R + 31) / 32, KB = W / 64;
+      const int mt = part;
+      const int q = __shfl(myq, mt * 8 + l32 / 4), j1 = l32 % 4;
+      const f4* arow = (const f4*)(dPsum + (size_t)(q >= 0 ? q : 0) * PN + j1 * W + 32 * half);
+      int qrow[4];
+#pragma unroll
+      for (int x = 0; x < 4; ++x) qrow[x] = __shfl(myq, mt * 8 + 2 * x + half);
+#pragma unroll
+      for (int nt = 0; nt < NT; ++nt) {
+        const int n = nt * 32 + l32;
+        const f4* brow = (const f4*)(Bm + (size_t)(n < R ? n : 0) * W + 32 * half);
+        f4 av[2][8], bv[2][8];
+#pragma unroll
+        for (int j = 0; j < 8; ++j) {
+          av[0][j] = arow[j];
+          bv[0][j] = brow[j];
+        }
+        TT_LOADS_DONE();
+        f16v acc = TT_ZERO16;
+#pragma unroll
+        for (int kb = 0; kb < KB; ++kb) {
+          if (kb + 1 < KB) {
 #pragma unroll
             for (int j = 0; j < 8; ++j) {
-              av[j] = ((const f4*)(arow + kbase))[j];
-              bv[j] = ((const f4*)(brow + kbase))[j];
+              av[(kb + 1) & 1][j] = arow[(kb + 1) * 16 + j];
+              bv[(kb + 1) & 1][j] = brow[(kb + 1) * 16 + j];
             }
-#pragma unroll
-            for (int j = 0; j < 8; ++j) {
-              if (q < 0) av[j] = f4{0.f, 0.f, 0.f, 0.f};
-              if (n >= R) bv[j] = f4{0.f, 0.f, 0.f, 0.f};
-              acc = mfma32(av[j].x, bv[j].x, acc);
-              acc = mfma32(av[j].y, bv[j].y, acc);
-              acc = mfma32(av[j].z, bv[j].z, acc);
-              acc = mfma32(av[j].w, bv[j].w, acc);
-            }
+            TT_LOADS_DONE();
           }
 #pragma unroll
-          for (int v = 0; v < 16; ++v) {
-            const int qv = __shfl(myq, mt * 8 + 2 * (v / 4) + half);
-            if (qv >= 0 && n < R) dg1part[(size_t)qv * S1 + (v % 4) * R + n] = acc[v];
+          for (int j = 0; j < 8; ++j) {
+            f4 x = av[kb & 1][j], y = bv[kb & 1][j];
+            if (q < 0) x = f4{0.f, 0.f, 0.f, 0.f};
+            if (n >= R) y = f4{0.f, 0.f, 0.f, 0.f};
+            acc = mfma32(x.x, y.x, acc);
+            acc = mfma32(x.y, y.y, acc);
+            acc = mfma32(x.z, y.z, acc);
+            acc = mfma32(x.w, y.w, acc);
           }
+        }
+#pragma unroll
+        for (int v = 0; v < 16; ++v) {
+          const int qv = qrow[v / 4];
+          if (qv >= 0 && n < R) dg1part[(size_t)qv * S1 + (v % 4) * R + n] = acc[v];
         }
       }
     } else {
@@ -175,21 +225,39 @@ __global__ __launch_bounds__(kMThreads) void k_prefix_bwd_mfma(
         qh[jq] = __shfl(myq, 8 * half + jq);
         ih[jq] = __shfl(myi1, 8 * half + jq);
       }
+      float a[MT][32];
+#pragma unroll
       for (int mt = 0; mt < MT; ++mt) {
         const int m = mt * 32 + l32;
-        float a[32];
 #pragma unroll
-        for (int j = 0; j < 32; ++j)
-          a[j] = (qh[j / 4] >= 0 && m < R) ? g1[(size_t)ih[j / 4] * S1 + (j % 4) * R + m] : 0.f;
-        for (int nt = 0; nt < NT; ++nt) {
-          const int n = nt * 32 + l32;
-          float b[32];
+        for (int j = 0; j < 32; ++j) a[mt][j] = g1[(size_t)ih[j / 4] * S1 + (j % 4) * R + (m < R ? m : 0)];
+      }
+      float b[2][32];
+#pragma unroll
+      for (int j = 0; j < 32; ++j)
+        b[0][j] = dPsum[(size_t)(qh[j / 4] >= 0 ? qh[j / 4] : 0) * PN + (j % 4) * W + l32];
+      TT_LOADS_DONE();
+#pragma unroll
+      for (int mt = 0; mt < MT; ++mt) {
+        const int m = mt * 32 + l32;
+#pragma unroll
+        for (int j = 0; j < 32; ++j) a[mt][j] = (qh[j / 4] >= 0 && m < R) ? a[mt][j] : 0.f;
+      }
+#pragma unroll
+      for (int nt = 0; nt < NT; ++nt) {
+        const int n = nt * 32 + l32;
+        if (nt + 1 < NT) {
 #pragma unroll
           for (int j = 0; j < 32; ++j)
-            b[j] = qh[j / 4] >= 0 ? dPsum[(size_t)qh[j / 4] * PN + (j % 4) * W + n] : 0.f;
-          f16v acc = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
+            b[(nt + 1) & 1][j] =
+                dPsum[(size_t)(qh[j / 4] >= 0 ? qh[j / 4] : 0) * PN + (j % 4) * W + n + 32];
+          TT_LOADS_DONE();
+        }
 #pragma unroll
-          for (int j = 0; j < 32; ++j) acc = mfma32(a[j], b[j], acc);
+        for (int mt = 0; mt < MT; ++mt) {
+          f16v acc = TT_ZERO16;
+#pragma unroll
+          for (int j = 0; j < 32; ++j) acc = mfma32(a[mt][j], b[nt & 1][j], acc);
 #pragma unroll
           for (int v = 0; v < 16; ++v) {
             const int mrow = mt * 32 + 8 * (v / 4) + 4 * half + (v % 4);
@@ -203,13 +271,13 @@ __global__ __launch_bounds__(kMThreads) void k_prefix_bwd_mfma(
 
 // ---------------------------------------------------------------------------------------------
 // dPsum_q = sum over the unique ids u of prefix q of g_u G3[i3(u)]^T  (16 x D3 times D3 x R).
-// One wavefront per prefix; the ids of a prefix extend the contraction index.
+// One wavefront per prefix; the ids of a prefix extend the contraction index, UB at a time.
 template <int R, int D3>
 __global__ __launch_bounds__(kMThreads) void k_u_bwd_mfma(
     const float* __restrict__ g3, const float* __restrict__ grad, const float* __restrict__ gsum,
-    const uint32_t* __restrict__ perm, const int* __restrict__ u_rs, const int* __restrict__ u_i3,
-    const int* __restrict__ q_us, float* __restrict__ dPsum, const Counters* __restrict__ ctr) {
-  constexpr int PN = 16 * R, S3 = R * D3, D = 16 * D3, NT = R / 16, KS = D3 / 4;
+    const int* __restrict__ u_code, const int* __restrict__ u_i3, const int* __restrict__ q_us,
+    float* __restrict__ dPsum, const Counters* __restrict__ ctr) {
+  constexpr int PN = 16 * R, S3 = R * D3, D = 16 * D3, NT = R / 16, KS = D3 / 4, UB = 4;
   const int w = threadIdx.x / kWave, lane = threadIdx.x % kWave;
   const int l16 = lane % 16, kg = lane / 16;
   const int Q = ctr->Q;
@@ -220,22 +288,31 @@ __global__ __launch_bounds__(kMThreads) void k_u_bwd_mfma(
     for (int nt = 0; nt < NT; ++nt) acc[nt] = f4{0.f, 0.f, 0.f, 0.f};
     for (int ub = u0; ub < u1; ub += kWave) {
       const int n = min(kWave, u1 - ub);
-      const int myi3 = lane < n ? u_i3[ub + lane] : 0;
-      const int mycode = lane < n ? grad_row_code(ub + lane, u_rs, perm) : 0;
-      for (int i = 0; i < n; ++i) {
-        const float* gp = grad_row_ptr(__shfl(mycode, i), grad, gsum, D) + l16 * D3 + KS * kg;
-        const float* cp = g3 + (size_t)__shfl(myi3, i) * S3 + l16 * D3 + KS * kg;
-        float a[KS], b[NT][KS];
+      const int myi3 = u_i3[ub + min(lane, n - 1)];
+      const int mycode = u_code[ub + min(lane, n - 1)];
+      for (int i0 = 0; i0 < n; i0 += UB) {
+        float a[UB][KS], b[UB][NT][KS];
 #pragma unroll
-        for (int s = 0; s < KS; ++s) a[s] = gp[s];
+        for (int x = 0; x < UB; ++x) {
+          const int i = min(i0 + x, n - 1);
+          const float* gp = grad_row_ptr(lane_value(mycode, i), grad, gsum, D) + l16 * D3 + KS * kg;
+          const float* cp = g3 + (size_t)lane_value(myi3, i) * S3 + l16 * D3 + KS * kg;
 #pragma unroll
-        for (int nt = 0; nt < NT; ++nt)
+          for (int s = 0; s < KS; ++s) a[x][s] = gp[s];
 #pragma unroll
-          for (int s = 0; s < KS; ++s) b[nt][s] = cp[nt * 16 * D3 + s];
+          for (int nt = 0; nt < NT; ++nt)
 #pragma unroll
-        for (int nt = 0; nt < NT; ++nt)
+            for (int s = 0; s < KS; ++s) b[x][nt][s] = cp[nt * 16 * D3 + s];
+        }
+        TT_LOADS_DONE();
 #pragma unroll
-          for (int s = 0; s < KS; ++s) acc[nt] = mfma16(a[s], b[nt][s], acc[nt]);
+        for (int x = 0; x < UB; ++x) {
+          const bool on = i0 + x < n;
+#pragma unroll
+          for (int nt = 0; nt < NT; ++nt)
+#pragma unroll
+            for (int s = 0; s < KS; ++s) acc[nt] = mfma16(on ? a[x][s] : 0.f, b[x][nt][s], acc[nt]);
+        }
       }
     }
     float* dst = dPsum + (size_t)q * PN;
@@ -248,42 +325,49 @@ __global__ __launch_bounds__(kMThreads) void k_u_bwd_mfma(
 
 // ---------------------------------------------------------------------------------------------
 // part3[c]^T = sum over the <= 16 unique ids u of one by-i3 chunk of g_u^T P_q(u)
-// (D3 x 16 times 16 x R; the D3 rows occupy the first rows of a 16-row tile).
+// (D3 x 16 times 16 x R; the D3 rows occupy the first rows of a 16-row tile), UB ids at a time.
 template <int R, int D3>
 __global__ __launch_bounds__(kMThreads) void k_dg3_mfma(
-    Shape sh, const float* __restrict__ P, const float* __restrict__ grad,
-    const float* __restrict__ gsum, const uint32_t* __restrict__ perm,
-    const int* __restrict__ u_rs, const int* __restrict__ u_q, const int* __restrict__ g3_list,
-    const int* __restrict__ g3_start, const int* __restrict__ c3_start, float* __restrict__ part3,
-    const Counters* __restrict__ ctr) {
-  constexpr int PN = 16 * R, S3 = R * D3, D = 16 * D3, NT = R / 16;
+    const float* __restrict__ P, const float* __restrict__ grad, const float* __restrict__ gsum,
+    const int* __restrict__ u_code, const int* __restrict__ u_q, const int* __restrict__ g3_list,
+    const int4* __restrict__ c3_desc, float* __restrict__ part3, const Counters* __restrict__ ctr) {
+  constexpr int PN = 16 * R, S3 = R * D3, D = 16 * D3, NT = R / 16, UB = (R == 64) ? 4 : 8;
   const int w = threadIdx.x / kWave, lane = threadIdx.x % kWave;
   const int l16 = lane % 16, kg = lane / 16;
   const int nchunk = ctr->nchunk3;
   for (int c = blockIdx.x * kMWaves + w; c < nchunk; c += gridDim.x * kMWaves) {
-    const int bin = chunk_bin(c3_start, (int)sh.n3, c);
-    const int k0 = g3_start[bin] + (c - c3_start[bin]) * kChunk3;
-    const int cnt = min(kChunk3, g3_start[bin + 1] - k0);
-    const int myu = lane < cnt ? g3_list[k0 + lane] : 0;
-    const int myq = lane < cnt ? u_q[myu] : 0;
-    const int mycode = lane < cnt ? grad_row_code(myu, u_rs, perm) : 0;
+    const int4 desc = c3_desc[c];
+    const int cnt = desc.z;
+    const int myu = g3_list[desc.y + min(lane, cnt - 1)];
+    const int myq = u_q[myu];
+    const int mycode = u_code[myu];
     f4 acc[NT];
 #pragma unroll
     for (int nt = 0; nt < NT; ++nt) acc[nt] = f4{0.f, 0.f, 0.f, 0.f};
-    for (int i = 0; i < cnt; ++i) {
-      const float* gp = grad_row_ptr(__shfl(mycode, i), grad, gsum, D) + (4 * kg) * D3;
-      const float* pp = P + (size_t)__shfl(myq, i) * PN + (4 * kg) * R + l16;
-      float a[4], b[NT][4];
+    for (int i0 = 0; i0 < cnt; i0 += UB) {
+      float a[UB][4], b[UB][NT][4];
 #pragma unroll
-      for (int s = 0; s < 4; ++s) a[s] = l16 < D3 ? gp[s * D3 + l16] : 0.f;
+      for (int x = 0; x < UB; ++x) {
+        const int i = min(i0 + x, cnt - 1);
+        const float* gp = grad_row_ptr(lane_value(mycode, i), grad, gsum, D) + (4 * kg) * D3 +
+                          (l16 < D3 ? l16 : 0);
+        const float* pp = P + (size_t)lane_value(myq, i) * PN + (4 * kg) * R + l16;
 #pragma unroll
-      for (int nt = 0; nt < NT; ++nt)
+        for (int s = 0; s < 4; ++s) a[x][s] = gp[s * D3];
 #pragma unroll
-        for (int s = 0; s < 4; ++s) b[nt][s] = pp[s * R + nt * 16];
+        for (int nt = 0; nt < NT; ++nt)
 #pragma unroll
-      for (int nt = 0; nt < NT; ++nt)
+          for (int s = 0; s < 4; ++s) b[x][nt][s] = pp[s * R + nt * 16];
+      }
+      TT_LOADS_DONE();
 #pragma unroll
-        for (int s = 0; s < 4; ++s) acc[nt] = mfma16(a[s], b[nt][s], acc[nt]);
+      for (int x = 0; x < UB; ++x) {
+        const bool on = (i0 + x < cnt) && (l16 < D3);
+#pragma unroll
+        for (int nt = 0; nt < NT; ++nt)
+#pragma unroll
+          for (int s = 0; s < 4; ++s) acc[nt] = mfma16(on ? a[x][s] : 0.f, b[x][nt][s], acc[nt]);
+      }
     }
     float* dst = part3 + (size_t)c * S3;
 #pragma unroll
@@ -298,88 +382,118 @@ __global__ __launch_bounds__(kMThreads) void k_dg3_mfma(
 
 // ---------------------------------------------------------------------------------------------
 // Rows: one wavefront per tile of 64 sorted slots.  The distinct ids of a tile are taken in groups
-// of up to 16/D3 that share a prefix: E = P_q (16 x R) times their G3 slices side by side
-// (R x 16).  Each finished row goes through LDS so that one store instruction writes a whole row
-// to every batch position that holds the id.
+// of up to 16/D3 consecutive ids that share a prefix: E = P_q (16 x R) times their G3 slices side
+// by side (R x 16).  Up to NB groups are worked on together (operand loads in flight together);
+// their rows go through LDS so that one store instruction writes a whole row to every batch
+// position that holds the id.  Rows are written with non-temporal stores: nothing on this path
+// reads them back.
 template <int R, int D3>
 __global__ __launch_bounds__(kMThreads) void k_row_fwd_mfma(
     int B, const float* __restrict__ g3, const float* __restrict__ P, const int* __restrict__ s_u,
     const uint32_t* __restrict__ perm, const int* __restrict__ u_i3, const int* __restrict__ u_q,
     float* __restrict__ out, Counters* ctr) {
   constexpr int PN = 16 * R, S3 = R * D3, D = 16 * D3, UPT = 16 / D3, KQ = R / 4, VPL = D / kWave;
-  __shared__ float ebuf[kMWaves][UPT * D];
+  constexpr int NB = 4;
+  __shared__ float ebuf[kMWaves][NB * UPT * D];
   const int w = threadIdx.x / kWave, lane = threadIdx.x % kWave;
   const int l16 = lane % 16, kg = lane / 16;
+  const int ul = l16 / D3, j3 = l16 % D3;
   float* E = ebuf[w];
   const int ntiles = (B + kWave - 1) / kWave;
   for (int tile = blockIdx.x * kMWaves + w; tile < ntiles; tile += gridDim.x * kMWaves) {
     const int s = tile * kWave + lane;
-    const int mysu = s < B ? s_u[s] : -1;
-    const uint32_t myb = s < B ? perm[s] : 0u;
+    int mysu = s_u[min(s, B - 1)];
+    uint32_t myb = perm[min(s, B - 1)];
+    if (s >= B) mysu = -2;  // lanes past the batch: neither an id nor an out-of-range slot
     if (s < B && myb >= (uint32_t)B) atomicOr(&ctr->err, 4);
     // out-of-range ids (the tail of the sorted order) get zero rows
-    unsigned long long zero_slots = __ballot(s < B && mysu < 0 && myb < (uint32_t)B);
+    unsigned long long zero_slots = __ballot(mysu == -1 && myb < (uint32_t)B);
     while (zero_slots) {
       const int sl = __ffsll((long long)zero_slots) - 1;
       zero_slots &= zero_slots - 1;
-      float* o = out + (size_t)__shfl(myb, sl) * D + lane * VPL;
+      float* o = out + (size_t)(uint32_t)lane_value((int)myb, sl) * D + lane * VPL;
 #pragma unroll
       for (int e = 0; e < VPL; ++e) o[e] = 0.f;
     }
     const int nv = __popcll(__ballot(mysu >= 0));
     if (nv == 0) continue;
-    const int u_lo = __shfl(mysu, 0), nu = __shfl(mysu, nv - 1) - u_lo + 1;
-    const int myq = lane < nu ? u_q[u_lo + lane] : -1;
-    const int myi3 = lane < nu ? u_i3[u_lo + lane] : 0;
-    int i = 0;
-    while (i < nu) {
-      const int q = __shfl(myq, i);
-      int g = 1;
-      while (g < UPT && i + g < nu && __shfl(myq, i + g) == q) ++g;
-      // A = P_q: row l16, k = KQ*kg .. KQ*kg + KQ-1
-      float a[KQ], b[KQ];
-      const f4* pa = (const f4*)(P + (size_t)q * PN + l16 * R + KQ * kg);
+    const int u_lo = lane_value(mysu, 0), nu = lane_value(mysu, nv - 1) - u_lo + 1;
+    int myq = u_q[u_lo + min(lane, nu - 1)];
+    const int myi3 = u_i3[u_lo + min(lane, nu - 1)];
+    if (lane >= nu) myq = -1;
+    // group starts: every UPT-th id of a run of ids with one prefix
+    const int q_before = __shfl_up(myq, 1);
+    const unsigned long long run_starts = __ballot(lane < nu && (lane == 0 || myq != q_before));
+    const unsigned long long upto = run_starts & (lane == 63 ? ~0ull : ((2ull << lane) - 1ull));
+    const int run_first = 63 - __clzll((long long)upto);
+    unsigned long long groups = __ballot(lane < nu && ((lane - run_first) % UPT) == 0);
+    const int rel = mysu - u_lo;
+    while (groups) {
+      int st[NB], gsz[NB];
 #pragma unroll
-      for (int j = 0; j < KQ / 4; ++j) {
-        const f4 v = pa[j];
-        a[4 * j + 0] = v.x;
-        a[4 * j + 1] = v.y;
-        a[4 * j + 2] = v.z;
-        a[4 * j + 3] = v.w;
+      for (int x = 0; x < NB; ++x) {
+        if (groups) {
+          st[x] = __ffsll((long long)groups) - 1;
+          groups &= groups - 1;
+          gsz[x] = (groups ? __ffsll((long long)groups) - 1 : nu) - st[x];
+        } else {
+          st[x] = -1;
+          gsz[x] = 0;
+        }
       }
-      // B = the group's G3 slices side by side: column l16 -> id l16/D3 of the group, j3 = l16%D3
-      const int ul = l16 / D3, j3 = l16 % D3;
-      const int i3 = __shfl(myi3, min(i + ul, nu - 1));
-      const float* pc = g3 + (size_t)i3 * S3 + (KQ * kg) * D3 + j3;
+      float a[NB][KQ], b[NB][KQ];
 #pragma unroll
-      for (int j = 0; j < KQ; ++j) b[j] = ul < g ? pc[j * D3] : 0.f;
-      f4 acc = {0.f, 0.f, 0.f, 0.f};
+      for (int x = 0; x < NB; ++x) {
+        const int first = st[x] >= 0 ? st[x] : 0;
+        const int q = lane_value(myq, first);
+        const int i3 = __shfl(myi3, min(first + ul, nu - 1));
+        const f4* pa = (const f4*)(P + (size_t)(q >= 0 ? q : 0) * PN + l16 * R + KQ * kg);
+        const float* pc = g3 + (size_t)i3 * S3 + (KQ * kg) * D3 + j3;
 #pragma unroll
-      for (int j = 0; j < KQ; ++j) acc = mfma16(a[j], b[j], acc);
-      __builtin_amdgcn_wave_barrier();
+        for (int j = 0; j < KQ / 4; ++j) {
+          const f4 v = pa[j];
+          a[x][4 * j + 0] = v.x;
+          a[x][4 * j + 1] = v.y;
+          a[x][4 * j + 2] = v.z;
+          a[x][4 * j + 3] = v.w;
+        }
 #pragma unroll
-      for (int v = 0; v < 4; ++v) E[ul * D + (4 * kg + v) * D3 + j3] = acc[v];
+        for (int j = 0; j < KQ; ++j) b[x][j] = pc[j * D3];
+      }
+      TT_LOADS_DONE();
+#pragma unroll
+      for (int x = 0; x < NB; ++x) {
+        f4 acc = {0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+        for (int j = 0; j < KQ; ++j) acc = mfma16(a[x][j], b[x][j], acc);
+        if (ul < gsz[x]) {
+          float* e = E + (st[x] + ul - st[0]) * D + (4 * kg) * D3 + j3;
+#pragma unroll
+          for (int v = 0; v < 4; ++v) e[v * D3] = acc[v];
+        }
+      }
       __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
       __builtin_amdgcn_wave_barrier();
       __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
-      for (int k = 0; k < g; ++k) {
+      // rows of the ids st[0] .. last of this batch, to every slot that holds them
+      int last = st[0] + gsz[0];
+#pragma unroll
+      for (int x = 1; x < NB; ++x)
+        if (st[x] >= 0) last = st[x] + gsz[x];
+      for (int k = st[0]; k < last; ++k) {
         float e[VPL];
 #pragma unroll
-        for (int x = 0; x < VPL; ++x) e[x] = E[k * D + lane * VPL + x];
-        unsigned long long slots = __ballot(mysu == u_lo + i + k);
+        for (int y = 0; y < VPL; ++y) e[y] = E[(k - st[0]) * D + lane * VPL + y];
+        unsigned long long slots = __ballot(rel == k && mysu >= 0);
         while (slots) {
           const int sl = __ffsll((long long)slots) - 1;
           slots &= slots - 1;
-          const uint32_t b_row = __shfl(myb, sl);
-          if (b_row < (uint32_t)B) {
-            float* o = out + (size_t)b_row * D + lane * VPL;
-#pragma unroll
-            for (int x = 0; x < VPL; ++x) o[x] = e[x];
-          }
+          const uint32_t b_row = (uint32_t)lane_value((int)myb, sl);
+          if (b_row < (uint32_t)B) stream_store<VPL>(out + (size_t)b_row * D + lane * VPL, e);
         }
       }
+      __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
       __builtin_amdgcn_wave_barrier();
-      i += g;
     }
   }
 }
@@ -459,11 +573,9 @@ __global__ __launch_bounds__(kMThreads) void k_gsum_block(int B, const float* __
 #pragma unroll
       for (int k = 0; k < 32; ++k) {
         const int slot = half * 32 + k;
-        const uint32_t b_row = __shfl(myb, slot);
+        const uint32_t b_row = (uint32_t)lane_value((int)myb, slot);
         if ((need_mask >> slot) & 1ull) {
-          const float* g = grad + (size_t)b_row * D + lane * VPL;
-#pragma unroll
-          for (int x = 0; x < VPL; ++x) r[k].v[x] = g[x];
+          stream_load<VPL>(grad + (size_t)b_row * D + lane * VPL, r[k].v);
         } else {
 #pragma unroll
           for (int x = 0; x < VPL; ++x) r[k].v[x] = 0.f;
@@ -473,7 +585,7 @@ __global__ __launch_bounds__(kMThreads) void k_gsum_block(int B, const float* __
       for (int k = 0; k < 32; ++k) {
         const int slot = half * 32 + k;
         if (slot < nv) {
-          const int u = __shfl(mysu, slot);
+          const int u = lane_value(mysu, slot);
           if (u != cur) {
             flush(slot);
             cur = u;
@@ -599,36 +711,33 @@ void launch_prefix_fwd_mfma(const Plan& pl, const Workspace& ws, const float* g1
   const int64_t chunks = cdivi(std::min<int64_t>(B, pl.maxQ), kChunk2) + pl.sh.n2;
   const int grid = grid_cap(cdivi(chunks, kMWaves), kMGridCap);
   TT_DISPATCH_R(pl.sh.r1, (k_prefix_fwd_mfma<R><<<grid, kMThreads, 0, st>>>(
-                              pl.sh, g1, g2, ws.g2_list, ws.g2_start, ws.c2_start, ws.q_i1, ws.P,
-                              ws.ctr)));
+                              g1, g2, ws.g2_list, ws.c2_desc, ws.q_i1, ws.P, ws.ctr)));
 }
 
 void launch_prefix_bwd_mfma(const Plan& pl, const Workspace& ws, const float* g1, const float* g2,
                             int B, hipStream_t st) {
-  const int64_t items = 2 * (cdivi(std::min<int64_t>(B, pl.maxQ), kChunk2) + (int64_t)pl.sh.n2);
+  const int64_t items = 3 * (cdivi(std::min<int64_t>(B, pl.maxQ), kChunk2) + (int64_t)pl.sh.n2);
   const int grid = grid_cap(cdivi(items, kMWaves), kMGridCap);
   TT_DISPATCH_R(pl.sh.r1, (k_prefix_bwd_mfma<R><<<grid, kMThreads, 0, st>>>(
-                              pl.sh, g1, g2, ws.dPsum, ws.g2_list, ws.g2_start, ws.c2_start,
-                              ws.q_i1, ws.dg1part, ws.part2, ws.ctr)));
+                              g1, g2, ws.dPsum, ws.g2_list, ws.c2_desc, ws.q_i1, ws.dg1part,
+                              ws.part2, ws.ctr)));
 }
 
 void launch_u_bwd_mfma(const Plan& pl, const Workspace& ws, const float* g3, const float* grad,
                        int B, hipStream_t st) {
   const int grid = grid_cap(cdivi(std::min<int64_t>(B, pl.maxQ), kMWaves), kMGridCap);
-  const uint32_t* perm = ws.val[(pl.passes - 1) & 1];
   TT_DISPATCH_RD(pl.sh.r1, pl.sh.d3, (k_u_bwd_mfma<R, D3><<<grid, kMThreads, 0, st>>>(
-                                         g3, grad, ws.gsum, perm, ws.u_rs, ws.u_i3, ws.q_us,
-                                         ws.dPsum, ws.ctr)));
+                                         g3, grad, ws.gsum, ws.u_code, ws.u_i3, ws.q_us, ws.dPsum,
+                                         ws.ctr)));
 }
 
 void launch_dg3_mfma(const Plan& pl, const Workspace& ws, const float* grad, int B,
                      hipStream_t st) {
   const int64_t chunks = cdivi(B, kChunk3) + (int64_t)pl.sh.n3;
   const int grid = grid_cap(cdivi(chunks, kMWaves), kMGridCap);
-  const uint32_t* perm = ws.val[(pl.passes - 1) & 1];
   TT_DISPATCH_RD(pl.sh.r1, pl.sh.d3, (k_dg3_mfma<R, D3><<<grid, kMThreads, 0, st>>>(
-                                         pl.sh, ws.P, grad, ws.gsum, perm, ws.u_rs, ws.u_q,
-                                         ws.g3_list, ws.g3_start, ws.c3_start, ws.part3, ws.ctr)));
+                                         ws.P, grad, ws.gsum, ws.u_code, ws.u_q, ws.g3_list,
+                                         ws.c3_desc, ws.part3, ws.ctr)));
 }
 
 void launch_row_fwd_mfma(const Plan& pl, const Workspace& ws, const float* g3, int B, float* out,
