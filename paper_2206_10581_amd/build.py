@@ -15,9 +15,9 @@ def lib_path() -> str:
     return LIB
 
 
-def build(verbose: bool = False) -> str:
+def build(verbose: bool = False, extra_flags=()) -> str:
     """Compile every HIP source into one shared library, in-tree."""
-    cmd = ["hipcc", "-O3", "-std=c++17", "--offload-arch=gfx950", "-fPIC", "-shared",
+    cmd = ["hipcc", *extra_flags, "-O3", "-std=c++17", "--offload-arch=gfx950", "-fPIC", "-shared",
            "-I" + os.path.join(ROOT, "include"), "-I" + CSRC,
            # packed fp32 instructions are kept out of the generated code
            "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
@@ -33,4 +33,5 @@ def build(verbose: bool = False) -> str:
 
 
 if __name__ == "__main__":
-    print(build(verbose=True))
+    import sys
+    print(build(verbose=True, extra_flags=tuple(sys.argv[1:])))

@@ -35,9 +35,8 @@ void launch_prefix_fwd_mfma(const Plan&, const Workspace&, const float* g1, cons
                             hipStream_t);
 void launch_row_fwd_mfma(const Plan&, const Workspace&, const float* g3, int B, float* out,
                          hipStream_t);
-void launch_u_bwd_mfma(const Plan&, const Workspace&, const float* g3, const float* grad, int B,
-                       hipStream_t);
-void launch_dg3_mfma(const Plan&, const Workspace&, const float* grad, int B, hipStream_t);
+void launch_id_bwd_mfma(const Plan&, const Workspace&, const float* g3, const float* grad, int B,
+                        hipStream_t);
 void launch_prefix_bwd_mfma(const Plan&, const Workspace&, const float* g1, const float* g2, int B,
                             hipStream_t);
 void launch_gsum_block(const Plan&, const Workspace&, const float* grad, int B, hipStream_t);
@@ -158,6 +157,11 @@ static size_t carve(const Plan& pl, char* base, Workspace* ws) {
   w.dg1part = (float*)take(mQ * s.S1 * 4);
   w.part3 = (float*)take((size_t)pl.maxChunk3 * s.S3 * 4);
   w.part2 = (float*)take((size_t)pl.maxChunk2 * s.S2 * 4);
+#ifdef TT_EMB_TRACE
+  w.trace = (unsigned long long*)take((size_t)(1u << 17) * 8 * 8);
+#else
+  w.trace = nullptr;
+#endif
   if (ws) *ws = w;
   return off;
 }
@@ -271,6 +275,10 @@ int tt_emb_create(tt_emb_t* out, const tt_emb_config* cfg, float* g1, float* g2,
   h->mfma = mfma_shape(pl.sh) && !(cfg->flags & TT_EMB_FLAG_GENERIC_KERNELS);
   std::memset(h->prof_launches, 0, sizeof(h->prof_launches));
   std::memset(h->prof_ms, 0, sizeof(h->prof_ms));
+#ifdef TT_EMB_TRACE
+  (void)hipMemset(h->ws.trace, 0, (size_t)(1u << 17) * 64);
+  (void)hipMemcpy(&h->ws.ctr->trace, &h->ws.trace, sizeof(void*), hipMemcpyHostToDevice);
+#endif
   *out = h;
   return TT_EMB_OK;
 }
@@ -345,16 +353,15 @@ int tt_emb_backward_update(tt_emb_t h, const float* grad_out, float lr, void* hi
     else launch_gsum_fix(pl, ws, B, st);
   });
   if (rc) return rc;
-  rc = run_slot(h, kSlotUBwd, st, [&] {
-    if (h->mfma) launch_u_bwd_mfma(pl, ws, h->g3, grad_out, B, st);
-    else launch_u_bwd(pl, ws, h->g3, grad_out, B, st);
-  });
-  if (rc) return rc;
-  rc = run_slot(h, kSlotDg3, st, [&] {
-    if (h->mfma) launch_dg3_mfma(pl, ws, grad_out, B, st);
-    else launch_dg3(pl, ws, grad_out, B, st);
-  });
-  if (rc) return rc;
+  if (h->mfma) {
+    rc = run_slot(h, kSlotUBwd, st, [&] { launch_id_bwd_mfma(pl, ws, h->g3, grad_out, B, st); });
+    if (rc) return rc;
+  } else {
+    rc = run_slot(h, kSlotUBwd, st, [&] { launch_u_bwd(pl, ws, h->g3, grad_out, B, st); });
+    if (rc) return rc;
+    rc = run_slot(h, kSlotDg3, st, [&] { launch_dg3(pl, ws, grad_out, B, st); });
+    if (rc) return rc;
+  }
   rc = run_slot(h, kSlotPrefixBwd, st, [&] {
     if (h->mfma) launch_prefix_bwd_mfma(pl, ws, h->g1, h->g2, B, st);
     else launch_prefix_bwd(pl, ws, h->g1, h->g2, B, st);
@@ -405,6 +412,15 @@ int tt_emb_profile_read(tt_emb_t h, int slot, const char** name, int64_t* launch
   h->prof_ms[slot] = 0.0;
   return rc;
 }
+
+#ifdef TT_EMB_TRACE
+int tt_emb_debug_trace(tt_emb_t h, unsigned long long* dst, size_t n) {
+  (void)hipDeviceSynchronize();
+  int rc = (int)hipMemcpy(dst, h->ws.trace, n * 8, hipMemcpyDeviceToHost);
+  (void)hipMemset(h->ws.trace, 0, (size_t)(1u << 17) * 64);
+  return rc;
+}
+#endif
 
 int tt_emb_destroy(tt_emb_t h) {
   if (h == nullptr) return TT_EMB_EINVAL;

@@ -272,16 +272,14 @@ __global__ __launch_bounds__(kThreads) void k_prefix_bwd(Shape sh, const float* 
   }
 }
 
-constexpr int kSgdLanes = 32;                     // threads side by side on one partial
-constexpr int kSgdParts = kThreads / kSgdLanes;   // the job's list of partials is split 8 ways
-constexpr int kSgdPer = 4;                        // slice entries per thread
-constexpr int kSgdSpan = kSgdLanes * kSgdPer;     // 128 slice entries per job
-
-// Adds up the partial gradients of every touched slice and applies the SGD step.  A job owns
-// kSgdSpan consecutive entries of one slice; its list of partials (chunks for G3 and G2, prefixes
-// for G1) is dealt round-robin to kSgdParts groups of threads whose sums are then added in group
-// order, so the order of every sum depends on the list length only.
+// Adds up the partial gradients of every touched slice and applies the SGD step.
+// A job owns up to 256*VEC consecutive entries of one slice (VEC = 4 when slice sizes allow 16-byte
+// accesses, else 1).  Its threads are arranged as `parts` groups side by side on the entries; the
+// job's list of partials (chunks for G3 and G2, prefixes for G1) is dealt round-robin to the
+// groups, whose sums are then added in group order.  parts depends on the slice size only and
+// every group walks its share in list order, so the order of each sum is fixed by the list length.
 // Jobs: n3*cdiv(S3, span) for G3, then n2*cdiv(S2, span) for G2, then n1*cdiv(S1, span) for G1.
+template <int VEC>
 __global__ __launch_bounds__(kThreads) void k_sgd(Shape sh, float lr, float* __restrict__ g1,
                                                   float* __restrict__ g2, float* __restrict__ g3,
                                                   const float* __restrict__ part3,
@@ -290,11 +288,12 @@ __global__ __launch_bounds__(kThreads) void k_sgd(Shape sh, float lr, float* __r
                                                   const int* __restrict__ c2_start,
                                                   const float* __restrict__ dg1part,
                                                   const int* __restrict__ g1_first,
-                                                  const int* __restrict__ g1_end) {
-  __shared__ float red[kSgdParts][kSgdSpan];
-  const int lane = threadIdx.x % kSgdLanes, part = threadIdx.x / kSgdLanes;
-  const int sp3 = (sh.S3 + kSgdSpan - 1) / kSgdSpan, sp2 = (sh.S2 + kSgdSpan - 1) / kSgdSpan,
-            sp1 = (sh.S1 + kSgdSpan - 1) / kSgdSpan;
+                                                  const int* __restrict__ g1_end,
+                                                  Counters* __restrict__ ctr) {
+  constexpr int kSpan = kThreads * VEC, kUnroll = 8;
+  __shared__ float red[kThreads][VEC];
+  const int sp3 = (sh.S3 + kSpan - 1) / kSpan, sp2 = (sh.S2 + kSpan - 1) / kSpan,
+            sp1 = (sh.S1 + kSpan - 1) / kSpan;
   const int64_t jobs3 = (int64_t)sh.n3 * sp3, jobs2 = (int64_t)sh.n2 * sp2,
                 jobs1 = (int64_t)sh.n1 * sp1;
   for (int64_t job = blockIdx.x; job < jobs3 + jobs2 + jobs1; job += gridDim.x) {
@@ -303,7 +302,7 @@ __global__ __launch_bounds__(kThreads) void k_sgd(Shape sh, float lr, float* __r
     int l0, l1, o0, S;
     if (job < jobs3) {
       const int bin = (int)(job / sp3);
-      o0 = (int)(job % sp3) * kSgdSpan;
+      o0 = (int)(job % sp3) * kSpan;
       l0 = c3_start[bin];
       l1 = c3_start[bin + 1];
       src = part3;
@@ -312,7 +311,7 @@ __global__ __launch_bounds__(kThreads) void k_sgd(Shape sh, float lr, float* __r
     } else if (job < jobs3 + jobs2) {
       const int64_t j = job - jobs3;
       const int bin = (int)(j / sp2);
-      o0 = (int)(j % sp2) * kSgdSpan;
+      o0 = (int)(j % sp2) * kSpan;
       l0 = c2_start[bin];
       l1 = c2_start[bin + 1];
       src = part2;
@@ -321,7 +320,7 @@ __global__ __launch_bounds__(kThreads) void k_sgd(Shape sh, float lr, float* __r
     } else {
       const int64_t j = job - jobs3 - jobs2;
       const int i1 = (int)(j / sp1);
-      o0 = (int)(j % sp1) * kSgdSpan;
+      o0 = (int)(j % sp1) * kSpan;
       l0 = g1_first[i1];
       l1 = g1_end[i1];
       src = dg1part;
@@ -329,25 +328,52 @@ __global__ __launch_bounds__(kThreads) void k_sgd(Shape sh, float lr, float* __r
       G = g1 + (size_t)i1 * sh.S1;
     }
     if (l1 == l0) continue;  // slice not touched by this batch (uniform for the block)
-    float acc[kSgdPer];
+    // thread layout: `lanes` threads side by side cover the job's entries, `parts` such groups
+    const int cols = min(kSpan, S - o0);
+    int lanes = 1;
+    while (lanes * VEC < cols) lanes <<= 1;  // power of two, at most kThreads
+    const int parts = kThreads / lanes;
+    const int lane = threadIdx.x % lanes, part = threadIdx.x / lanes;
+    const bool active = lane * VEC < cols;
+    const int o = o0 + (active ? lane * VEC : 0);
+    float g_old[VEC], acc[VEC];
 #pragma unroll
-    for (int x = 0; x < kSgdPer; ++x) acc[x] = 0.f;
-    for (int k = l0 + part; k < l1; k += kSgdParts) {
-      const float* p = src + (size_t)k * S + o0 + lane;
-#pragma unroll
-      for (int x = 0; x < kSgdPer; ++x)
-        if (o0 + lane + x * kSgdLanes < S) acc[x] += p[x * kSgdLanes];
+    for (int x = 0; x < VEC; ++x) {
+      g_old[x] = G[o + x];
+      acc[x] = 0.f;
     }
+    const float* p = src + o;
+    int k = l0 + part;
+    for (; k + (kUnroll - 1) * parts < l1; k += kUnroll * parts) {
+      float v[kUnroll][VEC];
 #pragma unroll
-    for (int x = 0; x < kSgdPer; ++x) red[part][lane + x * kSgdLanes] = acc[x];
-    __syncthreads();
-    if (threadIdx.x < kSgdSpan && o0 + (int)threadIdx.x < S) {
-      float t = red[0][threadIdx.x];
+      for (int j = 0; j < kUnroll; ++j)
 #pragma unroll
-      for (int k = 1; k < kSgdParts; ++k) t += red[k][threadIdx.x];
-      G[o0 + threadIdx.x] = fmaf(-lr, t, G[o0 + threadIdx.x]);
+        for (int x = 0; x < VEC; ++x) v[j][x] = p[(size_t)(k + j * parts) * S + x];
+      __builtin_amdgcn_sched_barrier(0);  // all loads of the round are in flight together
+#pragma unroll
+      for (int j = 0; j < kUnroll; ++j)
+#pragma unroll
+        for (int x = 0; x < VEC; ++x) acc[x] += v[j][x];
     }
-    __syncthreads();
+    for (; k < l1; k += parts)
+#pragma unroll
+      for (int x = 0; x < VEC; ++x) acc[x] += p[(size_t)k * S + x];
+    if (parts > 1) {
+#pragma unroll
+      for (int x = 0; x < VEC; ++x) red[threadIdx.x][x] = acc[x];
+      __syncthreads();
+      if (part == 0) {
+        for (int q = 1; q < parts; ++q)
+#pragma unroll
+          for (int x = 0; x < VEC; ++x) acc[x] += red[q * lanes + lane][x];
+      }
+    }
+    if (part == 0 && active) {
+#pragma unroll
+      for (int x = 0; x < VEC; ++x) G[o + x] = fmaf(-lr, acc[x], g_old[x]);
+    }
+    if (parts > 1) __syncthreads();
   }
 }
 
@@ -411,11 +437,17 @@ void launch_prefix_bwd(const Plan& pl, const Workspace& ws, const float* g1, con
 void launch_sgd(const Plan& pl, const Workspace& ws, float* g1, float* g2, float* g3, float lr,
                 hipStream_t st) {
   const Shape& s = pl.sh;
-  const int64_t jobs = (int64_t)s.n3 * cdiv(s.S3, kSgdSpan) + (int64_t)s.n2 * cdiv(s.S2, kSgdSpan) +
-                       (int64_t)s.n1 * cdiv(s.S1, kSgdSpan);
-  k_sgd<<<grid_for(jobs, 1 << 16), kThreads, 0, st>>>(pl.sh, lr, g1, g2, g3, ws.part3, ws.c3_start,
-                                                     ws.part2, ws.c2_start, ws.dg1part,
-                                                     ws.g1_first, ws.g1_end);
+  const bool vec = (s.S1 % 4 == 0) && (s.S2 % 4 == 0) && (s.S3 % 4 == 0);
+  const int span = kThreads * (vec ? 4 : 1);
+  const int64_t jobs = (int64_t)s.n3 * cdiv(s.S3, span) + (int64_t)s.n2 * cdiv(s.S2, span) +
+                       (int64_t)s.n1 * cdiv(s.S1, span);
+  const int grid = grid_for(jobs, 1 << 16);
+  if (vec)
+    k_sgd<4><<<grid, kThreads, 0, st>>>(pl.sh, lr, g1, g2, g3, ws.part3, ws.c3_start, ws.part2,
+                                        ws.c2_start, ws.dg1part, ws.g1_first, ws.g1_end, ws.ctr);
+  else
+    k_sgd<1><<<grid, kThreads, 0, st>>>(pl.sh, lr, g1, g2, g3, ws.part3, ws.c3_start, ws.part2,
+                                        ws.c2_start, ws.dg1part, ws.g1_first, ws.g1_end, ws.ctr);
 }
 
 }  // namespace ttemb

@@ -21,7 +21,7 @@ __device__ __forceinline__ uint32_t key_of_id(int64_t id, uint32_t N) {
 }
 
 // ---------------------------------------------------------------------------------------------
-// block-wide helpers for 256 threads (4 wavefronts); lds4 holds at least 4 words
+// block-wide helpers; ldsw holds at least one word per wavefront of the block
 
 __device__ __forceinline__ uint32_t wave_inclusive_scan(uint32_t v, int lane) {
 #pragma unroll
@@ -33,16 +33,15 @@ __device__ __forceinline__ uint32_t wave_inclusive_scan(uint32_t v, int lane) {
 }
 
 // Exclusive prefix of v over the block's threads; *total receives the block sum.
-__device__ __forceinline__ uint32_t block_exclusive_scan_value(uint32_t v, uint32_t* lds4,
+__device__ __forceinline__ uint32_t block_exclusive_scan_value(uint32_t v, uint32_t* ldsw,
                                                                uint32_t* total) {
-  const int lane = threadIdx.x % kWave, w = threadIdx.x / kWave;
+  const int lane = threadIdx.x % kWave, w = threadIdx.x / kWave, nw = blockDim.x / kWave;
   const uint32_t incl = wave_inclusive_scan(v, lane);
-  if (lane == kWave - 1) lds4[w] = incl;
+  if (lane == kWave - 1) ldsw[w] = incl;
   __syncthreads();
   uint32_t base = 0, tot = 0;
-#pragma unroll
-  for (int k = 0; k < kSortWaves; ++k) {
-    const uint32_t t = lds4[k];
+  for (int k = 0; k < nw; ++k) {
+    const uint32_t t = ldsw[k];
     base += (k < w) ? t : 0u;
     tot += t;
   }
@@ -52,14 +51,14 @@ __device__ __forceinline__ uint32_t block_exclusive_scan_value(uint32_t v, uint3
 }
 
 // In-place exclusive scan of an LDS array arr[0..n), n <= kMaxBins; returns the total.
-__device__ uint32_t block_exclusive_scan(uint32_t* arr, int n, uint32_t* lds4) {
-  const int tid = threadIdx.x;
-  const int per = (n + kSortThreads - 1) / kSortThreads;
+__device__ uint32_t block_exclusive_scan(uint32_t* arr, int n, uint32_t* ldsw) {
+  const int tid = threadIdx.x, nt = blockDim.x;
+  const int per = (n + nt - 1) / nt;
   const int lo = min(tid * per, n), hi = min(lo + per, n);
   uint32_t s = 0;
   for (int i = lo; i < hi; ++i) s += arr[i];
   uint32_t total;
-  uint32_t run = block_exclusive_scan_value(s, lds4, &total);
+  uint32_t run = block_exclusive_scan_value(s, ldsw, &total);
   for (int i = lo; i < hi; ++i) {
     const uint32_t t = arr[i];
     arr[i] = run;
@@ -81,16 +80,18 @@ __device__ __forceinline__ unsigned long long match_digit(int digit, bool valid,
 }
 
 struct ScatterLds {
-  uint32_t wh[kSortWaves][kMaxBins];  // per-wavefront bucket counts, then first output positions
-  uint32_t tot[kMaxBins];             // bucket totals, then this block's first output per bucket
-  uint32_t aux[kMaxBins];             // chunks per bucket, then first chunk per bucket
-  uint32_t lds4[8];
+  // per-wavefront bucket counts, later block-local output offsets; two 16-bit buckets per word
+  // (a wavefront owns 256 items and a block 4096, so both fit)
+  uint32_t wh[kSortWaves][kMaxBins / 2];
+  uint32_t tot[kMaxBins];  // bucket totals, then this block's first output per bucket
+  uint32_t aux[kMaxBins];  // chunks per bucket, then first chunk per bucket
+  uint32_t ldsw[kSortWaves];
 };
 
-constexpr int kSteps = kSortWaveItems / kWave;  // 16 items per lane
+constexpr int kSteps = kSortWaveItems / kWave;  // items per lane
 
 // One block's share of a stable counting-sort pass over n_items items (block blk owns items
-// [blk*kSortItems, +kSortItems), wavefront w of it the w-th quarter).  cnt[b][bin] holds, per
+// [blk*kSortItems, +kSortItems), wavefront w of it the w-th sixteenth).  cnt[b][bin] holds, per
 // bucket, the items of blocks before b and tot[bin] the bucket totals (both from a column-scan
 // kernel over the blocks' histograms).
 // ItemOps: Item load(int idx); int digit(Item); void emit(uint32_t pos, Item).
@@ -119,6 +120,18 @@ __device__ void stable_scatter_block(ScatterLds& L, int blk, int n_items, int bi
     const int idx = wbase + step * kWave + lane;
     items[step] = ops.load(idx < n_items ? idx : 0);
   }
+  uint32_t before[kMaxBins / kSortThreads];  // items of my buckets in earlier blocks
+#pragma unroll
+  for (int k = 0; k < kMaxBins / kSortThreads; ++k) {
+    const int bin = tid + k * kSortThreads;
+    const int bc = min(bin, bins - 1);
+    const uint32_t total = tot[bc];
+    before[k] = cnt[(size_t)blk * bins + bc];
+    if (bin < bins) {
+      L.tot[bin] = total;
+      if (chunk > 0) L.aux[bin] = (total + chunk - 1) / chunk;
+    }
+  }
   __builtin_amdgcn_sched_barrier(0);  // keep the loads together: their latencies overlap
 #pragma unroll
   for (int step = 0; step < kSteps; ++step) digits[step] = ops.digit(items[step]);
@@ -126,15 +139,8 @@ __device__ void stable_scatter_block(ScatterLds& L, int blk, int n_items, int bi
 #pragma unroll
   for (int step = 0; step < kSteps; ++step)
     if (wbase + step * kWave + lane >= n_items) digits[step] = -1;
-
-  for (int bin = tid; bin < bins; bin += kSortThreads) {
-    const uint32_t total = tot[bin];
-    L.tot[bin] = total;
-    L.wh[0][bin] = cnt[(size_t)blk * bins + bin];  // items of this bucket in earlier blocks
-    if (chunk > 0) L.aux[bin] = (total + chunk - 1) / chunk;
-  }
   __syncthreads();
-  const uint32_t total_items = block_exclusive_scan(L.tot, bins, L.lds4);
+  const uint32_t total_items = block_exclusive_scan(L.tot, bins, L.ldsw);
   if (starts != nullptr) {
     if (publishes) {
       for (int bin = tid; bin < bins; bin += kSortThreads) starts[bin] = (int)L.tot[bin];
@@ -142,7 +148,7 @@ __device__ void stable_scatter_block(ScatterLds& L, int blk, int n_items, int bi
     }
     if (chunk > 0) {
       // every participating block takes a share of the chunk descriptors
-      const uint32_t total_chunks = block_exclusive_scan(L.aux, bins, L.lds4);
+      const uint32_t total_chunks = block_exclusive_scan(L.aux, bins, L.ldsw);
       if (publishes) {
         for (int bin = tid; bin < bins; bin += kSortThreads) chunk_starts[bin] = (int)L.aux[bin];
         if (tid == 0) {
@@ -167,9 +173,13 @@ __device__ void stable_scatter_block(ScatterLds& L, int blk, int n_items, int bi
   }
   if (blk >= nblk) return;
   __syncthreads();
-  for (int bin = tid; bin < bins; bin += kSortThreads) L.tot[bin] += L.wh[0][bin];
-  __syncthreads();
-  for (int i = tid; i < kSortWaves * bins; i += kSortThreads) L.wh[i / bins][i % bins] = 0u;
+#pragma unroll
+  for (int k = 0; k < kMaxBins / kSortThreads; ++k) {
+    const int bin = tid + k * kSortThreads;
+    if (bin < bins) L.tot[bin] += before[k];
+  }
+  const int words = (bins + 1) / 2;
+  for (int i = tid; i < kSortWaves * words; i += kSortThreads) L.wh[i / words][i % words] = 0u;
   __syncthreads();
 
   // Each wavefront walks its items in order, 64 at a time.  Lanes holding the same digit find each
@@ -185,24 +195,33 @@ __device__ void stable_scatter_block(ScatterLds& L, int blk, int n_items, int bi
     if (__ballot(valid) == 0ull) continue;  // wave-uniform
     const unsigned long long peers = match_digit(digit, valid, nbits);
     const int leader = valid ? (__ffsll((long long)peers) - 1) : lane;
-    uint32_t base = 0;
-    if (valid && lane == leader) base = atomicAdd(&L.wh[w][digit], (uint32_t)__popcll(peers));
-    rank[step] = __shfl(base, leader) + (uint32_t)__popcll(peers & lt_mask);
+    const int sh = 16 * (digit & 1);
+    uint32_t old = 0;
+    if (valid && lane == leader)
+      old = atomicAdd(&L.wh[w][digit >> 1], (uint32_t)__popcll(peers) << sh);
+    rank[step] = ((__shfl(old, leader) >> sh) & 0xffffu) + (uint32_t)__popcll(peers & lt_mask);
   }
   __syncthreads();
-  for (int bin = tid; bin < bins; bin += kSortThreads) {
-    uint32_t run = L.tot[bin];
+  // per bucket: counts of the wavefronts -> offsets inside the block (one thread per word)
+  for (int word = tid; word < words; word += kSortThreads) {
+    uint32_t lo = 0, hi = 0;
 #pragma unroll
     for (int k = 0; k < kSortWaves; ++k) {
-      const uint32_t c = L.wh[k][bin];
-      L.wh[k][bin] = run;
-      run += c;
+      const uint32_t c = L.wh[k][word];
+      L.wh[k][word] = lo | (hi << 16);
+      lo += c & 0xffffu;
+      hi += c >> 16;
     }
   }
   __syncthreads();
 #pragma unroll
-  for (int step = 0; step < kSteps; ++step)
-    if (digits[step] >= 0) ops.emit(L.wh[w][digits[step]] + rank[step], items[step]);
+  for (int step = 0; step < kSteps; ++step) {
+    const int digit = digits[step];
+    if (digit >= 0) {
+      const uint32_t off = (L.wh[w][digit >> 1] >> (16 * (digit & 1))) & 0xffffu;
+      ops.emit(L.tot[digit] + off + rank[step], items[step]);
+    }
+  }
 }
 
 // ---------------------------------------------------------------------------------------------
@@ -374,7 +393,7 @@ __global__ __launch_bounds__(kSegThreads) void k_seg_count(const uint32_t* __res
                                                            uint32_t N, uint32_t n3,
                                                            uint32_t* __restrict__ seg_nu,
                                                            uint32_t* __restrict__ seg_nq) {
-  __shared__ uint32_t lds4[8];
+  __shared__ uint32_t lds4[kSegThreads / kWave];
   const SegFlags f = seg_flags(skey, B, N, n3, (int)blockIdx.x * kSegItems + (int)threadIdx.x * 4);
   uint32_t cu = 0, cq = 0;
 #pragma unroll
@@ -402,7 +421,7 @@ __global__ __launch_bounds__(kSegThreads) void k_seg_write(
     int* __restrict__ q_us, int* __restrict__ q_i1, int* __restrict__ q_i2,
     uint32_t* __restrict__ cnt3, uint32_t* __restrict__ cnt2, int* __restrict__ g1_first,
     int* __restrict__ g1_end, Counters* __restrict__ ctr) {
-  __shared__ uint32_t lds4[8];
+  __shared__ uint32_t lds4[kSegThreads / kWave];
   const int tid = threadIdx.x, blk = blockIdx.x;
   const int s0 = blk * kSegItems + tid * 4;
   const SegFlags f = seg_flags(skey, B, sh.N, sh.n3, s0);

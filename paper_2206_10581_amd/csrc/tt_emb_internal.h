@@ -11,10 +11,10 @@ namespace ttemb {
 
 constexpr int kWave = 64;
 
-// stable counting-sort blocks: 4 wavefronts, each owning 1024 consecutive items of the block
-constexpr int kSortThreads = 256;
-constexpr int kSortWaves = 4;
-constexpr int kSortWaveItems = 1024;
+// stable counting-sort blocks: 16 wavefronts, each owning 256 consecutive items of the block
+constexpr int kSortThreads = 1024;
+constexpr int kSortWaves = 16;
+constexpr int kSortWaveItems = 256;
 constexpr int kSortItems = kSortWaves * kSortWaveItems;  // 4096 items per block
 constexpr int kMaxBins = 2048;                            // digit / bucket count limit per pass
 
@@ -46,8 +46,20 @@ struct Counters {
   int nchunk3;  // partial-sum chunks over the by-i3 grouping of unique ids
   int nchunk2;  // partial-sum chunks over the by-i2 grouping of unique prefixes
   int err;      // nonzero: a kernel met an impossible index (bit mask of sites)
-  int pad[2];
+  unsigned long long* trace;  // debugging builds (TT_EMB_TRACE): per-wavefront time stamps
 };
+
+// Debugging aid, compiled in only with -DTT_EMB_TRACE: wavefront `gw` stores the 100 MHz wall clock
+// in slot 0..7 of its record.  tt_emb_debug_trace() copies the records to the host.
+#ifdef TT_EMB_TRACE
+#define TT_TRACE(ctr, gw, slot)                                                        \
+  do {                                                                                 \
+    if ((threadIdx.x % 64) == 0 && (size_t)(gw) < (1u << 17))                          \
+      (ctr)->trace[(size_t)(gw) * 8 + (slot)] = wall_clock64();                        \
+  } while (0)
+#else
+#define TT_TRACE(ctr, gw, slot) do { } while (0)
+#endif
 
 // All device arrays carved out of the caller's workspace.
 struct Workspace {
@@ -87,6 +99,7 @@ struct Workspace {
   float* dg1part;     // per prefix: its term of dG1[i1]      [maxQ][S1]
   float* part3;       // per chunk: partial dG3 slice         [maxChunk3][S3]
   float* part2;       // per chunk: partial dG2 slice         [maxChunk2][S2]
+  unsigned long long* trace;  // TT_EMB_TRACE builds only: 2^17 records of 8 stamps
 };
 
 struct Plan {

@@ -273,15 +273,15 @@ __global__ __launch_bounds__(kMThreads) void k_prefix_bwd_mfma(
 // dPsum_q = sum over the unique ids u of prefix q of g_u G3[i3(u)]^T  (16 x D3 times D3 x R).
 // One wavefront per prefix; the ids of a prefix extend the contraction index, UB at a time.
 template <int R, int D3>
-__global__ __launch_bounds__(kMThreads) void k_u_bwd_mfma(
-    const float* __restrict__ g3, const float* __restrict__ grad, const float* __restrict__ gsum,
-    const int* __restrict__ u_code, const int* __restrict__ u_i3, const int* __restrict__ q_us,
-    float* __restrict__ dPsum, const Counters* __restrict__ ctr) {
+__device__ __forceinline__ void u_bwd_role(
+    int block, int nblocks, const float* __restrict__ g3, const float* __restrict__ grad,
+    const float* __restrict__ gsum, const int* __restrict__ u_code, const int* __restrict__ u_i3,
+    const int* __restrict__ q_us, float* __restrict__ dPsum, const Counters* __restrict__ ctr) {
   constexpr int PN = 16 * R, S3 = R * D3, D = 16 * D3, NT = R / 16, KS = D3 / 4, UB = 4;
   const int w = threadIdx.x / kWave, lane = threadIdx.x % kWave;
   const int l16 = lane % 16, kg = lane / 16;
   const int Q = ctr->Q;
-  for (int q = blockIdx.x * kMWaves + w; q < Q; q += gridDim.x * kMWaves) {
+  for (int q = block * kMWaves + w; q < Q; q += nblocks * kMWaves) {
     const int u0 = q_us[q], u1 = q_us[q + 1];
     f4 acc[NT];
 #pragma unroll
@@ -327,15 +327,16 @@ __global__ __launch_bounds__(kMThreads) void k_u_bwd_mfma(
 // part3[c]^T = sum over the <= 16 unique ids u of one by-i3 chunk of g_u^T P_q(u)
 // (D3 x 16 times 16 x R; the D3 rows occupy the first rows of a 16-row tile), UB ids at a time.
 template <int R, int D3>
-__global__ __launch_bounds__(kMThreads) void k_dg3_mfma(
-    const float* __restrict__ P, const float* __restrict__ grad, const float* __restrict__ gsum,
-    const int* __restrict__ u_code, const int* __restrict__ u_q, const int* __restrict__ g3_list,
-    const int4* __restrict__ c3_desc, float* __restrict__ part3, const Counters* __restrict__ ctr) {
+__device__ __forceinline__ void dg3_role(
+    int block, int nblocks, const float* __restrict__ P, const float* __restrict__ grad,
+    const float* __restrict__ gsum, const int* __restrict__ u_code, const int* __restrict__ u_q,
+    const int* __restrict__ g3_list, const int4* __restrict__ c3_desc, float* __restrict__ part3,
+    const Counters* __restrict__ ctr) {
   constexpr int PN = 16 * R, S3 = R * D3, D = 16 * D3, NT = R / 16, UB = (R == 64) ? 4 : 8;
   const int w = threadIdx.x / kWave, lane = threadIdx.x % kWave;
   const int l16 = lane % 16, kg = lane / 16;
   const int nchunk = ctr->nchunk3;
-  for (int c = blockIdx.x * kMWaves + w; c < nchunk; c += gridDim.x * kMWaves) {
+  for (int c = block * kMWaves + w; c < nchunk; c += nblocks * kMWaves) {
     const int4 desc = c3_desc[c];
     const int cnt = desc.z;
     const int myu = g3_list[desc.y + min(lane, cnt - 1)];
@@ -378,6 +379,23 @@ __global__ __launch_bounds__(kMThreads) void k_dg3_mfma(
         if (j3 < D3) dst[(nt * 16 + l16) * D3 + j3] = acc[nt][v];
       }
   }
+}
+
+// ---------------------------------------------------------------------------------------------
+// The two gradient steps that only need the per-id gradient sums run side by side in one launch:
+// even blocks form dPsum per prefix, odd blocks the partial G3 gradients per by-i3 chunk.
+template <int R, int D3>
+__global__ __launch_bounds__(kMThreads) void k_id_bwd_mfma(
+    const float* __restrict__ g3, const float* __restrict__ P, const float* __restrict__ grad,
+    const float* __restrict__ gsum, const int* __restrict__ u_code, const int* __restrict__ u_i3,
+    const int* __restrict__ u_q, const int* __restrict__ q_us, const int* __restrict__ g3_list,
+    const int4* __restrict__ c3_desc, float* __restrict__ dPsum, float* __restrict__ part3,
+    const Counters* __restrict__ ctr) {
+  const int role = blockIdx.x & 1, block = blockIdx.x >> 1, nblocks = gridDim.x >> 1;
+  if (role == 0)
+    u_bwd_role<R, D3>(block, nblocks, g3, grad, gsum, u_code, u_i3, q_us, dPsum, ctr);
+  else
+    dg3_role<R, D3>(block, nblocks, P, grad, gsum, u_code, u_q, g3_list, c3_desc, part3, ctr);
 }
 
 // ---------------------------------------------------------------------------------------------
@@ -500,13 +518,15 @@ __global__ __launch_bounds__(kMThreads) void k_row_fwd_mfma(
 
 // ---------------------------------------------------------------------------------------------
 // Sums grad_out over runs of equal ids (rows of D = 64*VPL floats, VPL floats per lane).
-// A block takes 256 consecutive sorted slots, 64 per wavefront.  Each wavefront loads the rows of
+// A block takes 1024 consecutive sorted slots, 64 per wavefront.  Each wavefront loads the rows of
 // its slots (32 at a time, all loads in flight together), adds them up run by run in slot order,
 // and finishes the runs that lie inside its 64 slots; ids that occur once are skipped, later
 // kernels read their row from grad_out directly.  Pieces of runs that cross wavefronts are joined
 // in LDS, pieces that cross blocks leave one partial per block in carry[block][h] (h = 0: the run
 // began in an earlier block, h = 1: it begins here and continues).
-constexpr int kGsumBlockSlots = kMWaves * kWave;  // 256
+constexpr int kGsumWaves = 16;
+constexpr int kGsumThreads = kGsumWaves * kWave;
+constexpr int kGsumBlockSlots = kGsumWaves * kWave;  // 1024
 
 template <int VPL>
 struct LaneVec {
@@ -514,15 +534,15 @@ struct LaneVec {
 };
 
 template <int VPL>
-__global__ __launch_bounds__(kMThreads) void k_gsum_block(int B, const float* __restrict__ grad,
+__global__ __launch_bounds__(kGsumThreads) void k_gsum_block(int B, const float* __restrict__ grad,
                                                           const int* __restrict__ s_u,
                                                           const uint32_t* __restrict__ perm,
                                                           float* __restrict__ gsum,
                                                           float* __restrict__ carry, Counters* ctr) {
   constexpr int D = kWave * VPL;
-  __shared__ float part[kMWaves][2][D];  // [wave][0 = head piece, 1 = tail piece]
-  __shared__ int head_state[kMWaves];    // 0 none, 1 head piece ends in this wave, 2 it runs through
-  __shared__ int tail_u[kMWaves];        // id whose run starts in this wave and continues, or -1
+  __shared__ float part[kGsumWaves][2][D];  // [wave][0 = head piece, 1 = tail piece]
+  __shared__ int head_state[kGsumWaves];    // 0 none, 1 head piece ends in this wave, 2 it runs through
+  __shared__ int tail_u[kGsumWaves];        // id whose run starts in this wave and continues, or -1
   const int w = threadIdx.x / kWave, lane = threadIdx.x % kWave;
   const int nbt = (B + kGsumBlockSlots - 1) / kGsumBlockSlots;
   for (int bt = blockIdx.x; bt < nbt; bt += gridDim.x) {
@@ -607,7 +627,7 @@ __global__ __launch_bounds__(kMThreads) void k_gsum_block(int B, const float* __
 #pragma unroll
       for (int x = 0; x < VPL; ++x) t.v[x] = part[w][1][lane * VPL + x];
       bool open = true;
-      for (int k = w + 1; k < kMWaves && open; ++k) {
+      for (int k = w + 1; k < kGsumWaves && open; ++k) {
         if (head_state[k] == 0) {  // cannot happen for a run that continues; keeps the loop safe
           open = false;
           break;
@@ -625,7 +645,7 @@ __global__ __launch_bounds__(kMThreads) void k_gsum_block(int B, const float* __
       LaneVec<VPL> t;
 #pragma unroll
       for (int x = 0; x < VPL; ++x) t.v[x] = part[0][0][lane * VPL + x];
-      for (int k = 1; k < kMWaves && head_state[k - 1] == 2; ++k) {
+      for (int k = 1; k < kGsumWaves && head_state[k - 1] == 2; ++k) {
         if (head_state[k] == 0) break;
 #pragma unroll
         for (int x = 0; x < VPL; ++x) t.v[x] += part[k][0][lane * VPL + x];
@@ -658,14 +678,15 @@ __global__ __launch_bounds__(kWave) void k_gsum_block_fix(const int* __restrict_
 #pragma unroll
     for (int x = 0; x < VPL; ++x) t.v[x] = carry[((size_t)bt * 2 + 1) * D + lane * VPL + x];
     int k = bt + 1;
-    for (; k + 4 <= last + 1; k += 4) {
-      LaneVec<VPL> c[4];
+    for (; k + 8 <= last + 1; k += 8) {
+      LaneVec<VPL> c[8];
 #pragma unroll
-      for (int j = 0; j < 4; ++j)
+      for (int j = 0; j < 8; ++j)
 #pragma unroll
         for (int x = 0; x < VPL; ++x) c[j].v[x] = carry[((size_t)(k + j) * 2) * D + lane * VPL + x];
+      __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
-      for (int j = 0; j < 4; ++j)
+      for (int j = 0; j < 8; ++j)
 #pragma unroll
         for (int x = 0; x < VPL; ++x) t.v[x] += c[j].v[x];
     }
@@ -723,21 +744,15 @@ void launch_prefix_bwd_mfma(const Plan& pl, const Workspace& ws, const float* g1
                               ws.part2, ws.ctr)));
 }
 
-void launch_u_bwd_mfma(const Plan& pl, const Workspace& ws, const float* g3, const float* grad,
-                       int B, hipStream_t st) {
-  const int grid = grid_cap(cdivi(std::min<int64_t>(B, pl.maxQ), kMWaves), kMGridCap);
-  TT_DISPATCH_RD(pl.sh.r1, pl.sh.d3, (k_u_bwd_mfma<R, D3><<<grid, kMThreads, 0, st>>>(
-                                         g3, grad, ws.gsum, ws.u_code, ws.u_i3, ws.q_us, ws.dPsum,
+void launch_id_bwd_mfma(const Plan& pl, const Workspace& ws, const float* g3, const float* grad,
+                        int B, hipStream_t st) {
+  // both roles loop over their work with a stride of half the grid (which must be even)
+  const int64_t waves_q = std::min<int64_t>(B, pl.maxQ), waves_c = cdivi(B, kChunk3) + (int64_t)pl.sh.n3;
+  const int per_role = grid_cap(cdivi(std::max(waves_q, waves_c), kMWaves), kMGridCap);
+  TT_DISPATCH_RD(pl.sh.r1, pl.sh.d3, (k_id_bwd_mfma<R, D3><<<2 * per_role, kMThreads, 0, st>>>(
+                                         g3, ws.P, grad, ws.gsum, ws.u_code, ws.u_i3, ws.u_q,
+                                         ws.q_us, ws.g3_list, ws.c3_desc, ws.dPsum, ws.part3,
                                          ws.ctr)));
-}
-
-void launch_dg3_mfma(const Plan& pl, const Workspace& ws, const float* grad, int B,
-                     hipStream_t st) {
-  const int64_t chunks = cdivi(B, kChunk3) + (int64_t)pl.sh.n3;
-  const int grid = grid_cap(cdivi(chunks, kMWaves), kMGridCap);
-  TT_DISPATCH_RD(pl.sh.r1, pl.sh.d3, (k_dg3_mfma<R, D3><<<grid, kMThreads, 0, st>>>(
-                                         ws.P, grad, ws.gsum, ws.u_code, ws.u_q, ws.g3_list,
-                                         ws.c3_desc, ws.part3, ws.ctr)));
 }
 
 void launch_row_fwd_mfma(const Plan& pl, const Workspace& ws, const float* g3, int B, float* out,
@@ -753,9 +768,9 @@ void launch_gsum_block(const Plan& pl, const Workspace& ws, const float* grad, i
   const int grid = grid_cap(cdivi(B, kGsumBlockSlots), kMGridCap);
   const uint32_t* perm = ws.val[(pl.passes - 1) & 1];
   if (pl.sh.D == 64)
-    k_gsum_block<1><<<grid, kMThreads, 0, st>>>(B, grad, ws.s_u, perm, ws.gsum, ws.carry, ws.ctr);
+    k_gsum_block<1><<<grid, kGsumThreads, 0, st>>>(B, grad, ws.s_u, perm, ws.gsum, ws.carry, ws.ctr);
   else
-    k_gsum_block<2><<<grid, kMThreads, 0, st>>>(B, grad, ws.s_u, perm, ws.gsum, ws.carry, ws.ctr);
+    k_gsum_block<2><<<grid, kGsumThreads, 0, st>>>(B, grad, ws.s_u, perm, ws.gsum, ws.carry, ws.ctr);
 }
 
 void launch_gsum_block_fix(const Plan& pl, const Workspace& ws, int B, hipStream_t st) {
