@@ -148,6 +148,8 @@ def main() -> int:
         per_step_us = rec["ms"] * 1e3 / max(args.profile_steps, 1)
         launches = rec["launches"] / max(args.profile_steps, 1)
         by, fl = kernel_work(name, w, B, U, Q, touched_bytes, 0)
+        if name == "u_bwd" and prof.get("dg3", {}).get("launches", 0) == 0:
+            fl *= 2          # matrix-core shapes: dPsum and the dG3 partials share one launch
         kernels[name] = {"us_per_step": round(per_step_us, 2), "launches_per_step": launches,
                          "alg_bytes": int(by), "alg_flops": int(fl)}
     if not kernels:          # --profile-steps 0: no per-kernel leg (used under an external profiler)

@@ -71,198 +71,198 @@ __device__ __forceinline__ void stream_load(const float* src, float* v) {
 
 // ---------------------------------------------------------------------------------------------
 // P_q = G1[i1] G2[i2] for the <= 16 prefixes of one by-i2 chunk: rows of up to eight G1 slices
-// stacked (32 x R) times the chunk's G2 slice (R x 4R).  One wavefront per chunk.
+// stacked (32 x R) times the chunk's G2 slice (R x 4R).  A work unit is (chunk, half of the 4R
+// output columns); one single-wavefront block per unit, so that the units spread evenly over all
+// SIMDs.
+constexpr int kPfUnits = 2;  // units per chunk in the forward prefix kernel
+
 template <int R>
-__global__ __launch_bounds__(kMThreads) void k_prefix_fwd_mfma(
+__global__ __launch_bounds__(kWave) void k_prefix_fwd_mfma(
     const float* __restrict__ g1, const float* __restrict__ g2, const int* __restrict__ g2_list,
     const int4* __restrict__ c2_desc, const int* __restrict__ q_i1, float* __restrict__ P,
     const Counters* __restrict__ ctr) {
   constexpr int W = 4 * R, PN = 16 * R, S1 = 4 * R, S2 = R * W, KH = R / 2, NT = W / 32;
-  constexpr int NTG = (R == 64) ? 2 : NT;  // column tiles whose G2 operands are in flight together
-  constexpr int NG = NT / NTG;
-  const int w = threadIdx.x / kWave, lane = threadIdx.x % kWave;
-  const int half = lane / 32, l32 = lane % 32;
-  const int nchunk = ctr->nchunk2;
-  for (int c = blockIdx.x * kMWaves + w; c < nchunk; c += gridDim.x * kMWaves) {
-    const int4 desc = c2_desc[c];
-    const int bin = desc.x, cnt = desc.z;
-    const float* Bm = g2 + (size_t)bin * S2 + (size_t)(KH * half) * W + l32;
-    float b[2][NTG][KH];
+  constexpr int NTH = NT / kPfUnits;  // column tiles of one unit
+  const int lane = threadIdx.x, half = lane / 32, l32 = lane % 32;
+  const int unit = blockIdx.x;
+  TT_TRACE(ctr, unit, 0);
+  if (unit >= ctr->nchunk2 * kPfUnits) return;
+  TT_TRACE(ctr, unit, 1);
+  const int c = unit / kPfUnits, nt0 = (unit % kPfUnits) * NTH;
+  const int4 desc = c2_desc[c];
+  const int bin = desc.x, cnt = desc.z;
+  const float* Bm = g2 + (size_t)bin * S2 + (size_t)(KH * half) * W + nt0 * 32 + l32;
+  float b[NTH][KH];
 #pragma unroll
-    for (int t = 0; t < NTG; ++t)
+  for (int t = 0; t < NTH; ++t)
 #pragma unroll
-      for (int j = 0; j < KH; ++j) b[0][t][j] = Bm[(size_t)j * W + t * 32];
-    int myq = g2_list[desc.y + min(lane, cnt - 1)];
-    const int myi1 = q_i1[myq];
-    if (lane >= cnt) myq = -1;
-    float a[2][KH];
+    for (int j = 0; j < KH; ++j) b[t][j] = Bm[(size_t)j * W + t * 32];
+  int myq = g2_list[desc.y + min(lane, cnt - 1)];
+  const int myi1 = q_i1[myq];
+  if (lane >= cnt) myq = -1;
+  float a[2][KH];
+#pragma unroll
+  for (int mt = 0; mt < 2; ++mt) {
+    const int ql = mt * 8 + l32 / 4, j1 = l32 % 4;
+    const int q = __shfl(myq, ql), i1 = __shfl(myi1, ql);
+    const f4* src = (const f4*)(g1 + (size_t)i1 * S1 + j1 * R + KH * half);
+#pragma unroll
+    for (int j = 0; j < KH / 4; ++j) {
+      f4 v = src[j];
+      a[mt][4 * j + 0] = q >= 0 ? v.x : 0.f;
+      a[mt][4 * j + 1] = q >= 0 ? v.y : 0.f;
+      a[mt][4 * j + 2] = q >= 0 ? v.z : 0.f;
+      a[mt][4 * j + 3] = q >= 0 ? v.w : 0.f;
+    }
+  }
+  int qrow[2][4];  // prefix of accumulator rows v/4 of each row tile
+#pragma unroll
+  for (int mt = 0; mt < 2; ++mt)
+#pragma unroll
+    for (int x = 0; x < 4; ++x) qrow[mt][x] = __shfl(myq, mt * 8 + 2 * x + half);
+  TT_LOADS_DONE();
+#ifdef TT_EMB_TRACE
+  if (a[0][0] + a[1][1] + b[0][0] + b[NTH - 1][KH - 1] == 1.2345f) P[0] = 0.f;
+#endif
+  TT_TRACE(ctr, unit, 2);
+#pragma unroll
+  for (int t = 0; t < NTH; ++t) {
 #pragma unroll
     for (int mt = 0; mt < 2; ++mt) {
-      const int ql = mt * 8 + l32 / 4, j1 = l32 % 4;
-      const int q = __shfl(myq, ql), i1 = __shfl(myi1, ql);
-      const f4* src = (const f4*)(g1 + (size_t)i1 * S1 + j1 * R + KH * half);
+      if (mt * 8 >= cnt) break;
+      f16v acc = TT_ZERO16;
 #pragma unroll
-      for (int j = 0; j < KH / 4; ++j) {
-        f4 v = src[j];
-        a[mt][4 * j + 0] = q >= 0 ? v.x : 0.f;
-        a[mt][4 * j + 1] = q >= 0 ? v.y : 0.f;
-        a[mt][4 * j + 2] = q >= 0 ? v.z : 0.f;
-        a[mt][4 * j + 3] = q >= 0 ? v.w : 0.f;
-      }
-    }
-    int qrow[2][4];  // prefix of accumulator rows v/4 of each row tile
+      for (int j = 0; j < KH; ++j) acc = mfma32(a[mt][j], b[t][j], acc);
 #pragma unroll
-    for (int mt = 0; mt < 2; ++mt)
-#pragma unroll
-      for (int x = 0; x < 4; ++x) qrow[mt][x] = __shfl(myq, mt * 8 + 2 * x + half);
-    TT_LOADS_DONE();
-#pragma unroll
-    for (int ng = 0; ng < NG; ++ng) {
-      if (ng + 1 < NG) {
-#pragma unroll
-        for (int t = 0; t < NTG; ++t)
-#pragma unroll
-          for (int j = 0; j < KH; ++j)
-            b[(ng + 1) & 1][t][j] = Bm[(size_t)j * W + ((ng + 1) * NTG + t) * 32];
-        TT_LOADS_DONE();
-      }
-#pragma unroll
-      for (int t = 0; t < NTG; ++t) {
-        const int nt = ng * NTG + t;
-#pragma unroll
-        for (int mt = 0; mt < 2; ++mt) {
-          f16v acc = TT_ZERO16;
-#pragma unroll
-          for (int j = 0; j < KH; ++j) acc = mfma32(a[mt][j], b[ng & 1][t][j], acc);
-#pragma unroll
-          for (int v = 0; v < 16; ++v) {
-            const int q = qrow[mt][v / 4];
-            if (q >= 0) P[(size_t)q * PN + (v % 4) * W + nt * 32 + l32] = acc[v];
-          }
-        }
+      for (int v = 0; v < 16; ++v) {
+        const int q = qrow[mt][v / 4];
+        if (q >= 0) P[(size_t)q * PN + (v % 4) * W + (nt0 + t) * 32 + l32] = acc[v];
       }
     }
   }
+  TT_TRACE(ctr, unit, 3);
 }
 
 // ---------------------------------------------------------------------------------------------
-// Gradients at prefix level for one by-i2 chunk (<= 16 prefixes q, Bm = G2[i2]); work items are
-// (chunk, part), one wavefront each:
-//   part 0,1 dg1part[q] = dPsum_q Bm^T for the first / second eight prefixes: their dPsum rows
-//            stacked (32 x 4R) times Bm^T (4R x R)
-//   part 2   part2[c] = sum_q G1[i1(q)]^T dPsum_q    (R x 4 cnt) times (4 cnt x 4R)
+// Gradients at prefix level for one by-i2 chunk (<= 16 prefixes q, Bm = G2[i2]).  Four work units
+// per chunk, one single-wavefront block each:
+//   unit 0,1  dg1part[q] = dPsum_q Bm^T for the first / second eight prefixes: their dPsum rows
+//             stacked (32 x 4R) times Bm^T (4R x R)
+//   unit 2,3  one half of the columns of part2[c] = sum_q G1[i1(q)]^T dPsum_q
+//             ((R x 4 cnt) times (4 cnt x 4R))
+constexpr int kPbUnits = 4;
+
 template <int R>
-__global__ __launch_bounds__(kMThreads) void k_prefix_bwd_mfma(
+__global__ __launch_bounds__(kWave) void k_prefix_bwd_mfma(
     const float* __restrict__ g1, const float* __restrict__ g2, const float* __restrict__ dPsum,
     const int* __restrict__ g2_list, const int4* __restrict__ c2_desc, const int* __restrict__ q_i1,
     float* __restrict__ dg1part, float* __restrict__ part2, const Counters* __restrict__ ctr) {
   constexpr int W = 4 * R, PN = 16 * R, S1 = 4 * R, S2 = R * W;
-  const int w = threadIdx.x / kWave, lane = threadIdx.x % kWave;
-  const int half = lane / 32, l32 = lane % 32;
-  const int nitems = ctr->nchunk2 * 3;
-  for (int item = blockIdx.x * kMWaves + w; item < nitems; item += gridDim.x * kMWaves) {
-    const int c = item / 3, part = item % 3;
-    const int4 desc = c2_desc[c];
-    const int bin = desc.x, cnt = desc.z;
-    if (part == 1 && cnt <= 8) continue;
-    int myq = g2_list[desc.y + min(lane, cnt - 1)];
-    const int myi1 = q_i1[myq];
-    if (lane >= cnt) myq = -1;
-    const float* Bm = g2 + (size_t)bin * S2;
+  const int lane = threadIdx.x, half = lane / 32, l32 = lane % 32;
+  const int unit = blockIdx.x;
+  if (unit >= ctr->nchunk2 * kPbUnits) return;
+  const int c = unit / kPbUnits, part = unit % kPbUnits;
+  const int4 desc = c2_desc[c];
+  const int bin = desc.x, cnt = desc.z;
+  if (part == 1 && cnt <= 8) return;
+  int myq = g2_list[desc.y + min(lane, cnt - 1)];
+  const int myi1 = q_i1[myq];
+  if (lane >= cnt) myq = -1;
+  const float* Bm = g2 + (size_t)bin * S2;
 
-    if (part < 2) {
-      constexpr int NT = (R + 31) / 32, KB = W / 64;
-      const int mt = part;
-      const int q = __shfl(myq, mt * 8 + l32 / 4), j1 = l32 % 4;
-      const f4* arow = (const f4*)(dPsum + (size_t)(q >= 0 ? q : 0) * PN + j1 * W + 32 * half);
-      int qrow[4];
+  if (part < 2) {
+    constexpr int NT = (R + 31) / 32, KB = W / 64;
+    const int mt = part;
+    const int q = __shfl(myq, mt * 8 + l32 / 4), j1 = l32 % 4;
+    const f4* arow = (const f4*)(dPsum + (size_t)(q >= 0 ? q : 0) * PN + j1 * W + 32 * half);
+    int qrow[4];
 #pragma unroll
-      for (int x = 0; x < 4; ++x) qrow[x] = __shfl(myq, mt * 8 + 2 * x + half);
+    for (int x = 0; x < 4; ++x) qrow[x] = __shfl(myq, mt * 8 + 2 * x + half);
 #pragma unroll
-      for (int nt = 0; nt < NT; ++nt) {
-        const int n = nt * 32 + l32;
-        const f4* brow = (const f4*)(Bm + (size_t)(n < R ? n : 0) * W + 32 * half);
-        f4 av[2][8], bv[2][8];
+    for (int nt = 0; nt < NT; ++nt) {
+      const int n = nt * 32 + l32;
+      const f4* brow = (const f4*)(Bm + (size_t)(n < R ? n : 0) * W + 32 * half);
+      f4 av[2][8], bv[2][8];
 #pragma unroll
-        for (int j = 0; j < 8; ++j) {
-          av[0][j] = arow[j];
-          bv[0][j] = brow[j];
-        }
-        TT_LOADS_DONE();
-        f16v acc = TT_ZERO16;
+      for (int j = 0; j < 8; ++j) {
+        av[0][j] = arow[j];
+        bv[0][j] = brow[j];
+      }
+      TT_LOADS_DONE();
+      f16v acc = TT_ZERO16;
 #pragma unroll
-        for (int kb = 0; kb < KB; ++kb) {
-          if (kb + 1 < KB) {
-#pragma unroll
-            for (int j = 0; j < 8; ++j) {
-              av[(kb + 1) & 1][j] = arow[(kb + 1) * 16 + j];
-              bv[(kb + 1) & 1][j] = brow[(kb + 1) * 16 + j];
-            }
-            TT_LOADS_DONE();
-          }
+      for (int kb = 0; kb < KB; ++kb) {
+        if (kb + 1 < KB) {
 #pragma unroll
           for (int j = 0; j < 8; ++j) {
-            f4 x = av[kb & 1][j], y = bv[kb & 1][j];
-            if (q < 0) x = f4{0.f, 0.f, 0.f, 0.f};
-            if (n >= R) y = f4{0.f, 0.f, 0.f, 0.f};
-            acc = mfma32(x.x, y.x, acc);
-            acc = mfma32(x.y, y.y, acc);
-            acc = mfma32(x.z, y.z, acc);
-            acc = mfma32(x.w, y.w, acc);
+            av[(kb + 1) & 1][j] = arow[(kb + 1) * 16 + j];
+            bv[(kb + 1) & 1][j] = brow[(kb + 1) * 16 + j];
           }
-        }
-#pragma unroll
-        for (int v = 0; v < 16; ++v) {
-          const int qv = qrow[v / 4];
-          if (qv >= 0 && n < R) dg1part[(size_t)qv * S1 + (v % 4) * R + n] = acc[v];
-        }
-      }
-    } else {
-      constexpr int MT = (R + 31) / 32, NT = W / 32;
-      int qh[8], ih[8];  // the eight prefixes whose rows this half of the wavefront feeds as k
-#pragma unroll
-      for (int jq = 0; jq < 8; ++jq) {
-        qh[jq] = __shfl(myq, 8 * half + jq);
-        ih[jq] = __shfl(myi1, 8 * half + jq);
-      }
-      float a[MT][32];
-#pragma unroll
-      for (int mt = 0; mt < MT; ++mt) {
-        const int m = mt * 32 + l32;
-#pragma unroll
-        for (int j = 0; j < 32; ++j) a[mt][j] = g1[(size_t)ih[j / 4] * S1 + (j % 4) * R + (m < R ? m : 0)];
-      }
-      float b[2][32];
-#pragma unroll
-      for (int j = 0; j < 32; ++j)
-        b[0][j] = dPsum[(size_t)(qh[j / 4] >= 0 ? qh[j / 4] : 0) * PN + (j % 4) * W + l32];
-      TT_LOADS_DONE();
-#pragma unroll
-      for (int mt = 0; mt < MT; ++mt) {
-        const int m = mt * 32 + l32;
-#pragma unroll
-        for (int j = 0; j < 32; ++j) a[mt][j] = (qh[j / 4] >= 0 && m < R) ? a[mt][j] : 0.f;
-      }
-#pragma unroll
-      for (int nt = 0; nt < NT; ++nt) {
-        const int n = nt * 32 + l32;
-        if (nt + 1 < NT) {
-#pragma unroll
-          for (int j = 0; j < 32; ++j)
-            b[(nt + 1) & 1][j] =
-                dPsum[(size_t)(qh[j / 4] >= 0 ? qh[j / 4] : 0) * PN + (j % 4) * W + n + 32];
           TT_LOADS_DONE();
         }
 #pragma unroll
-        for (int mt = 0; mt < MT; ++mt) {
-          f16v acc = TT_ZERO16;
+        for (int j = 0; j < 8; ++j) {
+          f4 x = av[kb & 1][j], y = bv[kb & 1][j];
+          if (q < 0) x = f4{0.f, 0.f, 0.f, 0.f};
+          if (n >= R) y = f4{0.f, 0.f, 0.f, 0.f};
+          acc = mfma32(x.x, y.x, acc);
+          acc = mfma32(x.y, y.y, acc);
+          acc = mfma32(x.z, y.z, acc);
+          acc = mfma32(x.w, y.w, acc);
+        }
+      }
 #pragma unroll
-          for (int j = 0; j < 32; ++j) acc = mfma32(a[mt][j], b[nt & 1][j], acc);
+      for (int v = 0; v < 16; ++v) {
+        const int qv = qrow[v / 4];
+        if (qv >= 0 && n < R) dg1part[(size_t)qv * S1 + (v % 4) * R + n] = acc[v];
+      }
+    }
+  } else {
+    constexpr int MT = (R + 31) / 32, NT = W / 32, NTH = NT / 2;
+    const int nt0 = (part - 2) * NTH;
+    int qh[8], ih[8];  // the eight prefixes whose rows this half of the wavefront feeds as k
 #pragma unroll
-          for (int v = 0; v < 16; ++v) {
-            const int mrow = mt * 32 + 8 * (v / 4) + 4 * half + (v % 4);
-            if (mrow < R) part2[(size_t)c * S2 + (size_t)mrow * W + n] = acc[v];
-          }
+    for (int jq = 0; jq < 8; ++jq) {
+      qh[jq] = __shfl(myq, 8 * half + jq);
+      ih[jq] = __shfl(myi1, 8 * half + jq);
+    }
+    float a[MT][32];
+#pragma unroll
+    for (int mt = 0; mt < MT; ++mt) {
+      const int m = mt * 32 + l32;
+#pragma unroll
+      for (int j = 0; j < 32; ++j) a[mt][j] = g1[(size_t)ih[j / 4] * S1 + (j % 4) * R + (m < R ? m : 0)];
+    }
+    float b[2][32];
+#pragma unroll
+    for (int j = 0; j < 32; ++j)
+      b[0][j] = dPsum[(size_t)(qh[j / 4] >= 0 ? qh[j / 4] : 0) * PN + (j % 4) * W + nt0 * 32 + l32];
+    TT_LOADS_DONE();
+#pragma unroll
+    for (int mt = 0; mt < MT; ++mt) {
+      const int m = mt * 32 + l32;
+#pragma unroll
+      for (int j = 0; j < 32; ++j) a[mt][j] = (qh[j / 4] >= 0 && m < R) ? a[mt][j] : 0.f;
+    }
+#pragma unroll
+    for (int t = 0; t < NTH; ++t) {
+      const int n = (nt0 + t) * 32 + l32;
+      if (t + 1 < NTH) {
+#pragma unroll
+        for (int j = 0; j < 32; ++j)
+          b[(t + 1) & 1][j] =
+              dPsum[(size_t)(qh[j / 4] >= 0 ? qh[j / 4] : 0) * PN + (j % 4) * W + n + 32];
+        TT_LOADS_DONE();
+      }
+#pragma unroll
+      for (int mt = 0; mt < MT; ++mt) {
+        f16v acc = TT_ZERO16;
+#pragma unroll
+        for (int j = 0; j < 32; ++j) acc = mfma32(a[mt][j], b[t & 1][j], acc);
+#pragma unroll
+        for (int v = 0; v < 16; ++v) {
+          const int mrow = mt * 32 + 8 * (v / 4) + 4 * half + (v % 4);
+          if (mrow < R) part2[(size_t)c * S2 + (size_t)mrow * W + n] = acc[v];
         }
       }
     }
@@ -729,17 +729,18 @@ constexpr int kMGridCap = 256 * 8;
 
 void launch_prefix_fwd_mfma(const Plan& pl, const Workspace& ws, const float* g1, const float* g2,
                             int B, hipStream_t st) {
+  // one block per possible work unit (upper bound from B); blocks past the real count return at once
   const int64_t chunks = cdivi(std::min<int64_t>(B, pl.maxQ), kChunk2) + pl.sh.n2;
-  const int grid = grid_cap(cdivi(chunks, kMWaves), kMGridCap);
-  TT_DISPATCH_R(pl.sh.r1, (k_prefix_fwd_mfma<R><<<grid, kMThreads, 0, st>>>(
+  const int grid = (int)(chunks * kPfUnits);
+  TT_DISPATCH_R(pl.sh.r1, (k_prefix_fwd_mfma<R><<<grid, kWave, 0, st>>>(
                               g1, g2, ws.g2_list, ws.c2_desc, ws.q_i1, ws.P, ws.ctr)));
 }
 
 void launch_prefix_bwd_mfma(const Plan& pl, const Workspace& ws, const float* g1, const float* g2,
                             int B, hipStream_t st) {
-  const int64_t items = 3 * (cdivi(std::min<int64_t>(B, pl.maxQ), kChunk2) + (int64_t)pl.sh.n2);
-  const int grid = grid_cap(cdivi(items, kMWaves), kMGridCap);
-  TT_DISPATCH_R(pl.sh.r1, (k_prefix_bwd_mfma<R><<<grid, kMThreads, 0, st>>>(
+  const int64_t chunks = cdivi(std::min<int64_t>(B, pl.maxQ), kChunk2) + pl.sh.n2;
+  const int grid = (int)(chunks * kPbUnits);
+  TT_DISPATCH_R(pl.sh.r1, (k_prefix_bwd_mfma<R><<<grid, kWave, 0, st>>>(
                               g1, g2, ws.dPsum, ws.g2_list, ws.c2_desc, ws.q_i1, ws.dg1part,
                               ws.part2, ws.ctr)));
 }

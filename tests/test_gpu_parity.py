@@ -178,6 +178,41 @@ def test_config2_in_full():
     assert stats["Q"] == 56 * 56
 
 
+# ----------------------------------------------------------------------------- full benchmark sizes
+
+def _check_full(cfg, seed=None, ids=None):
+    # the benchmark's launch configuration: max_batch = batch, default flags
+    w, cores, gen_ids, grad = _workload(cfg, seed)
+    ids = gen_ids if ids is None else ids
+    out, new, stats = check_against_oracle(w.n, w.d, w.r, cores, ids, grad, w.lr)
+    print(f"config {cfg}: B={ids.size} U={stats['U']} Q={stats['Q']}")
+    return w, ids, stats
+
+
+def test_config3_full_size_zipf_batch():
+    w, ids, stats = _check_full(3)
+    # the skew this workload is about: one id holds more than a tenth of the batch
+    assert np.bincount(np.unique(ids, return_inverse=True)[1]).max() > 20_000
+
+
+def test_config3_full_size_second_seed():
+    _check_full(3, seed=103)
+
+
+def test_config4_full_size_permuted_and_rank_order():
+    w, ids, stats = _check_full(4)
+    # secondary reading of the workload: Zipf rank = id (hot ids contiguous, fewer prefixes)
+    rng = np.random.default_rng(4)
+    ranks = wl.bounded_zipf_ranks(rng, w.N, w.zipf_s, w.batch)
+    _, _, stats2 = _check_full(4, ids=ranks)
+    assert stats2["Q"] < stats["Q"]
+
+
+def test_config5_full_size_clustered_rank64():
+    w, ids, stats = _check_full(5)
+    assert stats["Q"] < 4000 and stats["U"] > 250_000     # few prefixes, mostly distinct ids
+
+
 # ----------------------------------------------------------------------------- properties
 
 def test_bit_reproducible_and_lr_zero():
