@@ -30,6 +30,14 @@ if ROOT not in sys.path:
 HBM_PEAK = 8.0e12        # bytes/s, MI355X HBM3E
 FP32_PEAK = 157.3e12     # flop/s, MI355X fp32 (vector with packed ops, or fp32 MFMA)
 
+# Bytes beyond L2 per launch (fetched + written), from two `rocprofv3 --pmc` runs (FETCH_SIZE,
+# WRITE_SIZE) scaled by the readings for the 2,380 KiB core-restore copy of the same process; the
+# table and the commands are in profiles/step_config3_hbm_traffic.md.  Only the default workload was
+# measured; for anything else `traffic` is null.
+MEASURED_TRAFFIC = {3: {"row_fwd": 39.8e6 + 102.4e6, "gsum": 84.6e6 + 4.8e6, "u_bwd": 139.5e6 + 37.8e6,
+                        "prefix_bwd": 79.4e6 + 26.8e6, "prefix_fwd": 10.7e6 + 34.8e6,
+                        "sgd": 32.0e6 + 2.4e6}}
+
 
 def kernel_work(slot: str, w, B: int, U: int, Q: int, touched_bytes: int, passes: int):
     """Algorithmic (HBM bytes, fp32 flops) one step asks of a kernel slot.  Bytes are the slot's
@@ -175,6 +183,8 @@ def main() -> int:
                     "peak": FP32_PEAK / 1e12, "unit": "TFLOP/s", "frac": fl / launch_s / FP32_PEAK,
                     "traffic": None}
     roofline["avg_launch_us"] = round(launch_s * 1e6, 2)
+    if args.seed is None:
+        roofline["traffic"] = MEASURED_TRAFFIC.get(args.config, {}).get(dom)
 
     # the path as a whole against its binding bound
     F1, F2 = 2 * d1 * r1 * d2 * r2, 2 * d1 * d2 * r2 * d3

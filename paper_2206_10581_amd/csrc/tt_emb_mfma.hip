@@ -85,9 +85,7 @@ __global__ __launch_bounds__(kWave) void k_prefix_fwd_mfma(
   constexpr int NTH = NT / kPfUnits;  // column tiles of one unit
   const int lane = threadIdx.x, half = lane / 32, l32 = lane % 32;
   const int unit = blockIdx.x;
-  TT_TRACE(ctr, unit, 0);
   if (unit >= ctr->nchunk2 * kPfUnits) return;
-  TT_TRACE(ctr, unit, 1);
   const int c = unit / kPfUnits, nt0 = (unit % kPfUnits) * NTH;
   const int4 desc = c2_desc[c];
   const int bin = desc.x, cnt = desc.z;
@@ -121,10 +119,6 @@ __global__ __launch_bounds__(kWave) void k_prefix_fwd_mfma(
 #pragma unroll
     for (int x = 0; x < 4; ++x) qrow[mt][x] = __shfl(myq, mt * 8 + 2 * x + half);
   TT_LOADS_DONE();
-#ifdef TT_EMB_TRACE
-  if (a[0][0] + a[1][1] + b[0][0] + b[NTH - 1][KH - 1] == 1.2345f) P[0] = 0.f;
-#endif
-  TT_TRACE(ctr, unit, 2);
 #pragma unroll
   for (int t = 0; t < NTH; ++t) {
 #pragma unroll
@@ -140,7 +134,6 @@ __global__ __launch_bounds__(kWave) void k_prefix_fwd_mfma(
       }
     }
   }
-  TT_TRACE(ctr, unit, 3);
 }
 
 // ---------------------------------------------------------------------------------------------
@@ -418,6 +411,8 @@ __global__ __launch_bounds__(kMThreads) void k_row_fwd_mfma(
   const int ul = l16 / D3, j3 = l16 % D3;
   float* E = ebuf[w];
   const int ntiles = (B + kWave - 1) / kWave;
+  const int gw = blockIdx.x * kMWaves + w;
+  TT_TRACE(ctr, gw, 0);
   for (int tile = blockIdx.x * kMWaves + w; tile < ntiles; tile += gridDim.x * kMWaves) {
     const int s = tile * kWave + lane;
     int mysu = s_u[min(s, B - 1)];
@@ -446,7 +441,15 @@ __global__ __launch_bounds__(kMThreads) void k_row_fwd_mfma(
     const int run_first = 63 - __clzll((long long)upto);
     unsigned long long groups = __ballot(lane < nu && ((lane - run_first) % UPT) == 0);
     const int rel = mysu - u_lo;
+#ifdef TT_EMB_TRACE
+    if (myq + myi3 == -12345) out[0] = 0.f;
+    int nbatch = 0;
+#endif
+    if (tile == gw) TT_TRACE(ctr, gw, 1);
     while (groups) {
+#ifdef TT_EMB_TRACE
+      ++nbatch;
+#endif
       int st[NB], gsz[NB];
 #pragma unroll
       for (int x = 0; x < NB; ++x) {
@@ -479,6 +482,10 @@ __global__ __launch_bounds__(kMThreads) void k_row_fwd_mfma(
         for (int j = 0; j < KQ; ++j) b[x][j] = pc[j * D3];
       }
       TT_LOADS_DONE();
+#ifdef TT_EMB_TRACE
+      if (a[0][0] + b[NB - 1][KQ - 1] == 1.2345f) out[0] = 0.f;
+      if (tile == gw && nbatch == 1) TT_TRACE(ctr, gw, 2);
+#endif
 #pragma unroll
       for (int x = 0; x < NB; ++x) {
         f4 acc = {0.f, 0.f, 0.f, 0.f};
@@ -498,6 +505,9 @@ __global__ __launch_bounds__(kMThreads) void k_row_fwd_mfma(
 #pragma unroll
       for (int x = 1; x < NB; ++x)
         if (st[x] >= 0) last = st[x] + gsz[x];
+#ifdef TT_EMB_TRACE
+      if (tile == gw && nbatch == 1) TT_TRACE(ctr, gw, 3);
+#endif
       for (int k = st[0]; k < last; ++k) {
         float e[VPL];
 #pragma unroll
@@ -512,8 +522,13 @@ __global__ __launch_bounds__(kMThreads) void k_row_fwd_mfma(
       }
       __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
       __builtin_amdgcn_wave_barrier();
+#ifdef TT_EMB_TRACE
+      if (tile == gw && nbatch == 1) TT_TRACE(ctr, gw, 4);
+#endif
     }
+    if (tile == gw) TT_TRACE(ctr, gw, 5);
   }
+  TT_TRACE(ctr, gw, 6);
 }
 
 // ---------------------------------------------------------------------------------------------
