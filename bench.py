@@ -75,6 +75,8 @@ def main() -> int:
     ap.add_argument("--seed", type=int, default=None)
     ap.add_argument("--profile-steps", type=int, default=20)
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-prepare", action="store_true",
+                    help="do not overlap the next step's index work with this step's backward")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on ONE GPU (replicated-core data parallelism is described "
@@ -115,9 +117,13 @@ def main() -> int:
 
     def step():
         flat.copy_(snapshot)
+        if not args.no_prepare:
+            emb.prepare(ids)        # index pipeline of the NEXT step, overlapped with this step
         emb.forward(ids, out)
         emb.backward_update(grad, w.lr)
 
+    if not args.no_prepare:
+        emb.prepare(ids)            # the first step's own index work
     for _ in range(args.warmup):
         step()
     torch.cuda.synchronize()
@@ -219,6 +225,7 @@ def main() -> int:
         "data": "synthetic",
         "config": {"workload": w.name, "N": w.N, "n": list(w.n), "d": list(w.d), "ranks": list(w.r),
                    "batch": B, "ids": w.ids, "zipf_s": w.zipf_s, "seed": seed, "lr": w.lr,
+                   "next_batch_index_overlap": not args.no_prepare,
                    "U": U, "Q": Q, "max_multiplicity": struct["max_multiplicity"]},
         "roofline": roofline, "cpu_baseline": cpu, "path_roofline": path, "kernels": kernels,
     }

@@ -24,7 +24,8 @@
  * Memory.  Every pointer named "device" is HIP device memory owned by the caller; the library
  * borrows it and never allocates or frees device memory.  Cores, out and grad_out must be 16-byte
  * aligned, ids 8-byte aligned (TT_EMB_EINVAL otherwise).  The handle owns host bookkeeping only.
- * All calls are asynchronous on the given HIP stream unless stated otherwise.  A handle must not
+ * All calls are asynchronous on the given HIP stream unless stated otherwise (tt_emb_prepare also
+ * uses one internal stream of default priority, created on its first call).  A handle must not
  * be used from two threads or two streams at once.
  *
  * Errors.  Every function returns TT_EMB_OK (0) or a negative code and never aborts.
@@ -88,6 +89,23 @@ int tt_emb_create(tt_emb_t* out, const tt_emb_config* cfg, float* g1, float* g2,
  * stream has passed this call.  hip_stream is a hipStream_t (0 = the null stream).
  */
 int tt_emb_forward(tt_emb_t h, const int64_t* ids, int64_t B, float* out, void* hip_stream);
+
+/*
+ * Optional: builds the index structures (split, sort, unique ids and prefixes: the part of
+ * Section 4.2's sharing that depends on the ids only) of a COMING batch ahead of time, on a stream
+ * of the library's own that starts once everything enqueued so far on hip_stream has run.  A later
+ * tt_emb_forward with the same ids pointer and the same B finds them ready, waits for them on its
+ * own stream and skips that work (the oldest such batch if two match); a prepared batch that no
+ * forward asks for is eventually overwritten.  The workspace holds two index sets: one may be in
+ * use by a forward/backward pair while the other is filled, so at most two batches can be ahead
+ * (one while a backward_update is still outstanding).  Typical use, once per step and before the
+ * forward of the current batch: prepare(next ids); forward(ids); ...; backward_update(...) - the
+ * next batch's index work then overlaps this batch's arithmetic (minibatch samplers know the next
+ * ids early).  The ids buffer must keep its contents until that forward has been enqueued.
+ * Results are identical with or without it.  tt_emb_get_stats refers to the latest forward only
+ * until the next tt_emb_prepare.
+ */
+int tt_emb_prepare(tt_emb_t h, const int64_t* ids, int64_t B, void* hip_stream);
 
 /*
  * Backward and update (Section 5, phases "bwd" and "upd").  grad_out: device fp32[B][D] for the

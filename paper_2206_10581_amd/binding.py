@@ -50,6 +50,7 @@ def load_library():
                                   c_size_t]
     lib.tt_emb_forward.argtypes = [c_void_p, c_void_p, c_int64, c_void_p, c_void_p]
     lib.tt_emb_backward_update.argtypes = [c_void_p, c_void_p, c_float, c_void_p]
+    lib.tt_emb_prepare.argtypes = [c_void_p, c_void_p, c_int64, c_void_p]
     lib.tt_emb_get_stats.argtypes = [c_void_p, POINTER(c_int64), POINTER(c_int64), POINTER(c_int64)]
     lib.tt_emb_profile_enable.argtypes = [c_void_p, c_int]
     lib.tt_emb_profile_slots.argtypes = []
@@ -58,7 +59,7 @@ def load_library():
     lib.tt_emb_destroy.argtypes = [c_void_p]
     lib.tt_emb_strerror.argtypes = [c_int]
     lib.tt_emb_strerror.restype = c_char_p
-    for name in ("tt_emb_workspace_bytes", "tt_emb_create", "tt_emb_forward",
+    for name in ("tt_emb_workspace_bytes", "tt_emb_create", "tt_emb_forward", "tt_emb_prepare",
                  "tt_emb_backward_update", "tt_emb_get_stats", "tt_emb_profile_enable",
                  "tt_emb_profile_slots", "tt_emb_profile_read", "tt_emb_destroy"):
         getattr(lib, name).restype = c_int
@@ -98,6 +99,10 @@ def tt_emb_create(cfg: TTEmbConfig, g1_ptr: int, g2_ptr: int, g3_ptr: int, ws_pt
 def tt_emb_forward(h, ids_ptr: int, B: int, out_ptr: int, stream: int) -> int:
     return load_library().tt_emb_forward(h, c_void_p(ids_ptr), c_int64(B), c_void_p(out_ptr),
                                          c_void_p(stream))
+
+
+def tt_emb_prepare(h, ids_ptr: int, B: int, stream: int) -> int:
+    return load_library().tt_emb_prepare(h, c_void_p(ids_ptr), c_int64(B), c_void_p(stream))
 
 
 def tt_emb_backward_update(h, grad_ptr: int, lr: float, stream: int) -> int:
@@ -179,6 +184,15 @@ class TTEmbedding:
         if rc:
             raise TTEmbError(rc, "tt_emb_forward")
         return out
+
+    def prepare(self, ids):
+        """Index work of the next batch, overlapped with whatever follows on the current stream."""
+        torch = self.torch
+        assert ids.dtype == torch.int64 and ids.is_contiguous() and ids.device == self.device
+        rc = tt_emb_prepare(self.handle, ids.data_ptr() if ids.numel() else 0, ids.numel(),
+                            self._stream())
+        if rc:
+            raise TTEmbError(rc, "tt_emb_prepare")
 
     def backward_update(self, grad_out, lr: float):
         torch = self.torch

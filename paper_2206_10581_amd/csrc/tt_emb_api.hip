@@ -110,8 +110,10 @@ static int make_plan(const tt_emb_config* c, Plan* pl) {
   return TT_EMB_OK;
 }
 
-// Walks the workspace layout; with base == nullptr only the size is computed.
-static size_t carve(const Plan& pl, char* base, Workspace* ws) {
+// Walks the workspace layout; with base == nullptr only the size is computed.  The index arrays
+// exist twice (ws[0], ws[1]): one set serves the forward/backward pair in flight while
+// tt_emb_prepare fills the other for the next batch; the arithmetic buffers are shared.
+static size_t carve(const Plan& pl, char* base, Workspace* ws /* [2] or nullptr */) {
   size_t off = 0;
   auto take = [&](size_t bytes) -> char* {
     char* p = base ? base + off : nullptr;
@@ -120,36 +122,40 @@ static size_t carve(const Plan& pl, char* base, Workspace* ws) {
   };
   const Shape& s = pl.sh;
   const size_t mB = (size_t)pl.maxB, mQ = (size_t)pl.maxQ;
-  Workspace w;
-  w.ctr = (Counters*)take(sizeof(Counters));
-  for (int k = 0; k < 2; ++k) w.key[k] = (uint32_t*)take(mB * 4);
-  for (int k = 0; k < 2; ++k) w.val[k] = (uint32_t*)take(mB * 4);
-  w.cnt = (uint32_t*)take((size_t)pl.sortBlocksMax * kMaxBins * 4);
-  w.tot = (uint32_t*)take((size_t)kMaxBins * 4);
-  w.seg_nu = (uint32_t*)take((size_t)pl.segBlocksMax * 4);
-  w.seg_nq = (uint32_t*)take((size_t)pl.segBlocksMax * 4);
-  w.s_u = (int*)take(mB * 4);
-  w.u_rs = (int*)take((mB + 1) * 4);
-  w.u_i3 = (int*)take(mB * 4);
-  w.u_q = (int*)take(mB * 4);
-  w.u_code = (int*)take(mB * 4);
-  w.q_us = (int*)take((mQ + 1) * 4);
-  w.q_i1 = (int*)take(mQ * 4);
-  w.q_i2 = (int*)take(mQ * 4);
-  w.cnt3 = (uint32_t*)take((size_t)pl.uBlocksMax * s.n3 * 4);
-  w.cnt2 = (uint32_t*)take((size_t)pl.qBlocksMax * s.n2 * 4);
-  w.tot3 = (uint32_t*)take((size_t)s.n3 * 4);
-  w.tot2 = (uint32_t*)take((size_t)s.n2 * 4);
-  w.g3_list = (int*)take(mB * 4);
-  w.g3_start = (int*)take(((size_t)s.n3 + 1) * 4);
-  w.c3_start = (int*)take(((size_t)s.n3 + 1) * 4);
-  w.c3_desc = (int4*)take((size_t)pl.maxChunk3 * 16);
-  w.g2_list = (int*)take(mQ * 4);
-  w.g2_start = (int*)take(((size_t)s.n2 + 1) * 4);
-  w.c2_start = (int*)take(((size_t)s.n2 + 1) * 4);
-  w.c2_desc = (int4*)take((size_t)pl.maxChunk2 * 16);
-  w.g1_first = (int*)take((size_t)s.n1 * 8);  // g1_first[n1] followed by g1_end[n1]
-  w.g1_end = w.g1_first + s.n1;
+  Workspace set[2];
+  for (int i = 0; i < 2; ++i) {
+    Workspace& w = set[i];
+    w.ctr = (Counters*)take(sizeof(Counters));
+    for (int k = 0; k < 2; ++k) w.key[k] = (uint32_t*)take(mB * 4);
+    for (int k = 0; k < 2; ++k) w.val[k] = (uint32_t*)take(mB * 4);
+    w.cnt = (uint32_t*)take((size_t)pl.sortBlocksMax * kMaxBins * 4);
+    w.tot = (uint32_t*)take((size_t)kMaxBins * 4);
+    w.seg_nu = (uint32_t*)take((size_t)pl.segBlocksMax * 4);
+    w.seg_nq = (uint32_t*)take((size_t)pl.segBlocksMax * 4);
+    w.s_u = (int*)take(mB * 4);
+    w.u_rs = (int*)take((mB + 1) * 4);
+    w.u_i3 = (int*)take(mB * 4);
+    w.u_q = (int*)take(mB * 4);
+    w.u_code = (int*)take(mB * 4);
+    w.q_us = (int*)take((mQ + 1) * 4);
+    w.q_i1 = (int*)take(mQ * 4);
+    w.q_i2 = (int*)take(mQ * 4);
+    w.cnt3 = (uint32_t*)take((size_t)pl.uBlocksMax * s.n3 * 4);
+    w.cnt2 = (uint32_t*)take((size_t)pl.qBlocksMax * s.n2 * 4);
+    w.tot3 = (uint32_t*)take((size_t)s.n3 * 4);
+    w.tot2 = (uint32_t*)take((size_t)s.n2 * 4);
+    w.g3_list = (int*)take(mB * 4);
+    w.g3_start = (int*)take(((size_t)s.n3 + 1) * 4);
+    w.c3_start = (int*)take(((size_t)s.n3 + 1) * 4);
+    w.c3_desc = (int4*)take((size_t)pl.maxChunk3 * 16);
+    w.g2_list = (int*)take(mQ * 4);
+    w.g2_start = (int*)take(((size_t)s.n2 + 1) * 4);
+    w.c2_start = (int*)take(((size_t)s.n2 + 1) * 4);
+    w.c2_desc = (int4*)take((size_t)pl.maxChunk2 * 16);
+    w.g1_first = (int*)take((size_t)s.n1 * 8);  // g1_first[n1] followed by g1_end[n1]
+    w.g1_end = w.g1_first + s.n1;
+  }
+  Workspace& w = set[0];
   w.P = (float*)take(mQ * s.PN * 4);
   w.gsum = (float*)take(mB * s.D * 4);
   w.carry = (float*)take((size_t)pl.tilesMax * 2 * s.D * 4);
@@ -162,7 +168,18 @@ static size_t carve(const Plan& pl, char* base, Workspace* ws) {
 #else
   w.trace = nullptr;
 #endif
-  if (ws) *ws = w;
+  set[1].P = w.P;
+  set[1].gsum = w.gsum;
+  set[1].carry = w.carry;
+  set[1].dPsum = w.dPsum;
+  set[1].dg1part = w.dg1part;
+  set[1].part3 = w.part3;
+  set[1].part2 = w.part2;
+  set[1].trace = w.trace;
+  if (ws) {
+    ws[0] = set[0];
+    ws[1] = set[1];
+  }
   return off;
 }
 
@@ -178,12 +195,24 @@ using namespace ttemb;
 struct tt_emb {
   tt_emb_config cfg;
   Plan plan;
-  Workspace ws;
+  Workspace ws[2];    // two index sets over shared arithmetic buffers
+  int cur;            // set of the latest forward (and of the backward that follows it)
   float *g1, *g2, *g3;
   int64_t pending_B;  // -1: no forward pending
   int64_t last_B;     // batch size of the latest forward
   bool have_forward;
   hipStream_t last_stream;
+  // tt_emb_prepare: index pipelines of coming batches on a stream of the library's own
+  hipStream_t side;     // created on first use, default priority
+  hipEvent_t ev_fork;   // recorded on the caller's stream, awaited by side
+  struct Prepared {
+    bool valid;         // this index set holds a batch that no forward has consumed yet
+    const int64_t* ids;
+    int64_t B;
+    uint64_t seq;       // order of the prepare calls
+    hipEvent_t ready;   // recorded on side when the set is complete
+  } prep[2];
+  uint64_t prep_seq;
   bool profiling;
   bool mfma;  // matrix-core kernels apply to this shape and are not switched off
   std::vector<EventPair> events;
@@ -263,7 +292,12 @@ int tt_emb_create(tt_emb_t* out, const tt_emb_config* cfg, float* g1, float* g2,
   if (h == nullptr) return TT_EMB_EINVAL;
   h->cfg = *cfg;
   h->plan = pl;
-  carve(pl, (char*)workspace, &h->ws);
+  carve(pl, (char*)workspace, h->ws);
+  h->cur = 0;
+  h->side = nullptr;
+  h->ev_fork = nullptr;
+  h->prep_seq = 0;
+  for (int i = 0; i < 2; ++i) h->prep[i] = tt_emb::Prepared{false, nullptr, 0, 0, nullptr};
   h->g1 = g1;
   h->g2 = g2;
   h->g3 = g3;
@@ -276,10 +310,79 @@ int tt_emb_create(tt_emb_t* out, const tt_emb_config* cfg, float* g1, float* g2,
   std::memset(h->prof_launches, 0, sizeof(h->prof_launches));
   std::memset(h->prof_ms, 0, sizeof(h->prof_ms));
 #ifdef TT_EMB_TRACE
-  (void)hipMemset(h->ws.trace, 0, (size_t)(1u << 17) * 64);
-  (void)hipMemcpy(&h->ws.ctr->trace, &h->ws.trace, sizeof(void*), hipMemcpyHostToDevice);
+  (void)hipMemset(h->ws[0].trace, 0, (size_t)(1u << 17) * 64);
+  for (int i = 0; i < 2; ++i)
+    (void)hipMemcpy(&h->ws[i].ctr->trace, &h->ws[i].trace, sizeof(void*), hipMemcpyHostToDevice);
 #endif
   *out = h;
+  return TT_EMB_OK;
+}
+
+// Index pipeline of one batch into index set `set`, on stream st.
+static int run_index(tt_emb* h, int set, const int64_t* ids, int B, hipStream_t st) {
+  const Plan& pl = h->plan;
+  const Workspace& ws = h->ws[set];
+  int rc;
+  for (int pass = 0; pass < pl.passes; ++pass) {
+    rc = run_slot(h, kSlotSortHist, st, [&] { launch_sort_pass(pl, ws, ids, B, pass, st, 0); });
+    if (rc) return rc;
+    rc = run_slot(h, kSlotSortScan, st, [&] { launch_sort_pass(pl, ws, ids, B, pass, st, 2); });
+    if (rc) return rc;
+    rc = run_slot(h, kSlotSortScatter, st, [&] { launch_sort_pass(pl, ws, ids, B, pass, st, 1); });
+    if (rc) return rc;
+  }
+  rc = run_slot(h, kSlotSegCount, st, [&] { launch_seg_count(pl, ws, B, st); });
+  if (rc) return rc;
+  rc = run_slot(h, kSlotSegWrite, st, [&] { launch_seg_write(pl, ws, B, st); });
+  if (rc) return rc;
+  rc = run_slot(h, kSlotGroupScan, st, [&] { launch_group_scan(pl, ws, st); });
+  if (rc) return rc;
+  return run_slot(h, kSlotGroup, st, [&] { launch_group(pl, ws, B, st); });
+}
+
+int tt_emb_prepare(tt_emb_t h, const int64_t* ids, int64_t B64, void* hip_stream) {
+  if (h == nullptr || B64 < 0) return TT_EMB_EINVAL;
+  if (B64 > h->plan.maxB) return TT_EMB_ENOSPC;
+  if (B64 == 0) return TT_EMB_OK;  // nothing to prepare; forward handles the empty batch itself
+  if (ids == nullptr || ((uintptr_t)ids & 7u) != 0) return TT_EMB_EINVAL;
+  hipStream_t st = (hipStream_t)hip_stream;
+  hipError_t e;
+  if (h->side == nullptr) {
+    e = hipStreamCreateWithFlags(&h->side, hipStreamNonBlocking);
+    if (e != hipSuccess) return hip_fail(e);
+    e = hipEventCreateWithFlags(&h->ev_fork, hipEventDisableTiming);
+    if (e != hipSuccess) return hip_fail(e);
+    for (int i = 0; i < 2; ++i) {
+      e = hipEventCreateWithFlags(&h->prep[i].ready, hipEventDisableTiming);
+      if (e != hipSuccess) return hip_fail(e);
+    }
+  }
+  // Pick the index set to fill.  A set is free when no backward_update still has to be enqueued for
+  // it (that is only `cur`, between a forward and its backward) and no prepared batch waits in it.
+  // With both taken, the prepared batch that is not the newest is overwritten.
+  const bool cur_busy = h->pending_B >= 0;
+  int target = -1;
+  for (int s : {h->cur ^ 1, h->cur})
+    if (target < 0 && !h->prep[s].valid && !(s == h->cur && cur_busy)) target = s;
+  if (target < 0) {
+    if (cur_busy || !h->prep[h->cur].valid) target = h->cur ^ 1;
+    else target = h->prep[0].seq < h->prep[1].seq ? 0 : 1;
+  }
+  h->prep[target].valid = false;
+  // everything that used this set earlier (its backward_update, or an index pipeline on side that
+  // is now dropped) is ordered before: side is in order, and the fork event covers hip_stream
+  e = hipEventRecord(h->ev_fork, st);
+  if (e != hipSuccess) return hip_fail(e);
+  e = hipStreamWaitEvent(h->side, h->ev_fork, 0);
+  if (e != hipSuccess) return hip_fail(e);
+  int rc = run_index(h, target, ids, (int)B64, h->side);
+  if (rc) return rc;
+  e = hipEventRecord(h->prep[target].ready, h->side);
+  if (e != hipSuccess) return hip_fail(e);
+  h->prep[target].valid = true;
+  h->prep[target].ids = ids;
+  h->prep[target].B = B64;
+  h->prep[target].seq = ++h->prep_seq;
   return TT_EMB_OK;
 }
 
@@ -297,25 +400,38 @@ int tt_emb_forward(tt_emb_t h, const int64_t* ids, int64_t B64, float* out, void
   if (((uintptr_t)out & 15u) != 0 || ((uintptr_t)ids & 7u) != 0) return TT_EMB_EINVAL;
   const int B = (int)B64;
   const Plan& pl = h->plan;
-  const Workspace& ws = h->ws;
   h->pending_B = -1;
   int rc;
-  for (int pass = 0; pass < pl.passes; ++pass) {
-    rc = run_slot(h, kSlotSortHist, st, [&] { launch_sort_pass(pl, ws, ids, B, pass, st, 0); });
-    if (rc) return rc;
-    rc = run_slot(h, kSlotSortScan, st, [&] { launch_sort_pass(pl, ws, ids, B, pass, st, 2); });
-    if (rc) return rc;
-    rc = run_slot(h, kSlotSortScatter, st, [&] { launch_sort_pass(pl, ws, ids, B, pass, st, 1); });
+  // oldest prepared batch with these ids and this size, if any
+  int found = -1;
+  for (int s = 0; s < 2; ++s)
+    if (h->prep[s].valid && h->prep[s].ids == ids && h->prep[s].B == B64 &&
+        (found < 0 || h->prep[s].seq < h->prep[found].seq))
+      found = s;
+  if (found >= 0) {
+    hipError_t e = hipStreamWaitEvent(st, h->prep[found].ready, 0);
+    if (e != hipSuccess) return hip_fail(e);
+    h->prep[found].valid = false;
+    h->cur = found;
+  } else {
+    // build the index structures here; take a set no prepared batch waits in, else drop one
+    int target = !h->prep[h->cur].valid ? h->cur : (!h->prep[h->cur ^ 1].valid ? (h->cur ^ 1) : h->cur);
+    if (h->prep[target].valid) {
+      hipError_t e = hipStreamWaitEvent(st, h->prep[target].ready, 0);
+      if (e != hipSuccess) return hip_fail(e);
+      h->prep[target].valid = false;
+    } else if (h->side != nullptr) {
+      // an index pipeline that was dropped earlier may still be writing this set on side
+      hipError_t e = hipEventRecord(h->ev_fork, h->side);
+      if (e != hipSuccess) return hip_fail(e);
+      e = hipStreamWaitEvent(st, h->ev_fork, 0);
+      if (e != hipSuccess) return hip_fail(e);
+    }
+    h->cur = target;
+    rc = run_index(h, h->cur, ids, B, st);
     if (rc) return rc;
   }
-  rc = run_slot(h, kSlotSegCount, st, [&] { launch_seg_count(pl, ws, B, st); });
-  if (rc) return rc;
-  rc = run_slot(h, kSlotSegWrite, st, [&] { launch_seg_write(pl, ws, B, st); });
-  if (rc) return rc;
-  rc = run_slot(h, kSlotGroupScan, st, [&] { launch_group_scan(pl, ws, st); });
-  if (rc) return rc;
-  rc = run_slot(h, kSlotGroup, st, [&] { launch_group(pl, ws, B, st); });
-  if (rc) return rc;
+  const Workspace& ws = h->ws[h->cur];
   rc = run_slot(h, kSlotPrefixFwd, st, [&] {
     if (h->mfma) launch_prefix_fwd_mfma(pl, ws, h->g1, h->g2, B, st);
     else launch_prefix_fwd(pl, ws, h->g1, h->g2, B, st);
@@ -341,7 +457,7 @@ int tt_emb_backward_update(tt_emb_t h, const float* grad_out, float lr, void* hi
   if (grad_out == nullptr || ((uintptr_t)grad_out & 15u) != 0) return TT_EMB_EINVAL;
   hipStream_t st = (hipStream_t)hip_stream;
   const Plan& pl = h->plan;
-  const Workspace& ws = h->ws;
+  const Workspace& ws = h->ws[h->cur];
   int rc;
   rc = run_slot(h, kSlotGsum, st, [&] {
     if (h->mfma) launch_gsum_block(pl, ws, grad_out, B, st);
@@ -379,7 +495,7 @@ int tt_emb_get_stats(tt_emb_t h, int64_t* U, int64_t* Q, int64_t* out_of_range) 
   if (h->have_forward) {
     hipError_t e = hipStreamSynchronize(h->last_stream);
     if (e != hipSuccess) return hip_fail(e);
-    e = hipMemcpy(&c, h->ws.ctr, sizeof(c), hipMemcpyDeviceToHost);
+    e = hipMemcpy(&c, h->ws[h->cur].ctr, sizeof(c), hipMemcpyDeviceToHost);
     if (e != hipSuccess) return hip_fail(e);
     oob = h->last_B - (int64_t)c.nvalid;
   }
@@ -416,8 +532,8 @@ int tt_emb_profile_read(tt_emb_t h, int slot, const char** name, int64_t* launch
 #ifdef TT_EMB_TRACE
 int tt_emb_debug_trace(tt_emb_t h, unsigned long long* dst, size_t n) {
   (void)hipDeviceSynchronize();
-  int rc = (int)hipMemcpy(dst, h->ws.trace, n * 8, hipMemcpyDeviceToHost);
-  (void)hipMemset(h->ws.trace, 0, (size_t)(1u << 17) * 64);
+  int rc = (int)hipMemcpy(dst, h->ws[0].trace, n * 8, hipMemcpyDeviceToHost);
+  (void)hipMemset(h->ws[0].trace, 0, (size_t)(1u << 17) * 64);
   return rc;
 }
 #endif
@@ -425,6 +541,12 @@ int tt_emb_debug_trace(tt_emb_t h, unsigned long long* dst, size_t n) {
 int tt_emb_destroy(tt_emb_t h) {
   if (h == nullptr) return TT_EMB_EINVAL;
   (void)drain_events(h);
+  if (h->side != nullptr) {
+    (void)hipStreamSynchronize(h->side);
+    (void)hipEventDestroy(h->ev_fork);
+    for (int i = 0; i < 2; ++i) (void)hipEventDestroy(h->prep[i].ready);
+    (void)hipStreamDestroy(h->side);
+  }
   delete h;
   return TT_EMB_OK;
 }

@@ -11,6 +11,7 @@
 // The summation index k may be enumerated in any order as long as A and B agree, so each lane
 // takes a contiguous run of k (vector loads) instead of the strided one the raw layout suggests.
 #include <algorithm>
+#include <type_traits>
 
 #include "tt_emb_internal.h"
 
@@ -149,10 +150,11 @@ template <int R>
 __global__ __launch_bounds__(kWave) void k_prefix_bwd_mfma(
     const float* __restrict__ g1, const float* __restrict__ g2, const float* __restrict__ dPsum,
     const int* __restrict__ g2_list, const int4* __restrict__ c2_desc, const int* __restrict__ q_i1,
-    float* __restrict__ dg1part, float* __restrict__ part2, const Counters* __restrict__ ctr) {
+    float* __restrict__ dg1part, float* __restrict__ part2, Counters* __restrict__ ctr) {
   constexpr int W = 4 * R, PN = 16 * R, S1 = 4 * R, S2 = R * W;
   const int lane = threadIdx.x, half = lane / 32, l32 = lane % 32;
   const int unit = blockIdx.x;
+  TT_TRACE(ctr, unit, 0);
   if (unit >= ctr->nchunk2 * kPbUnits) return;
   const int c = unit / kPbUnits, part = unit % kPbUnits;
   const int4 desc = c2_desc[c];
@@ -161,6 +163,11 @@ __global__ __launch_bounds__(kWave) void k_prefix_bwd_mfma(
   int myq = g2_list[desc.y + min(lane, cnt - 1)];
   const int myi1 = q_i1[myq];
   if (lane >= cnt) myq = -1;
+#ifdef TT_EMB_TRACE
+  if (myq + myi1 == -12345) dg1part[0] = 0.f;
+  TT_TRACE(ctr, unit, 1);
+  if (lane == 0) ctr->trace[(size_t)unit * 8 + 6] = part + 1;
+#endif
   const float* Bm = g2 + (size_t)bin * S2;
 
   if (part < 2) {
@@ -182,6 +189,10 @@ __global__ __launch_bounds__(kWave) void k_prefix_bwd_mfma(
         bv[0][j] = brow[j];
       }
       TT_LOADS_DONE();
+#ifdef TT_EMB_TRACE
+      if (av[0][0].x + bv[0][7].w == 1.2345f) dg1part[0] = 0.f;
+      if (nt == 0) TT_TRACE(ctr, unit, 2);
+#endif
       f16v acc = TT_ZERO16;
 #pragma unroll
       for (int kb = 0; kb < KB; ++kb) {
@@ -231,6 +242,10 @@ __global__ __launch_bounds__(kWave) void k_prefix_bwd_mfma(
     for (int j = 0; j < 32; ++j)
       b[0][j] = dPsum[(size_t)(qh[j / 4] >= 0 ? qh[j / 4] : 0) * PN + (j % 4) * W + nt0 * 32 + l32];
     TT_LOADS_DONE();
+#ifdef TT_EMB_TRACE
+    if (a[0][0] + b[0][31] == 1.2345f) dg1part[0] = 0.f;
+    TT_TRACE(ctr, unit, 2);
+#endif
 #pragma unroll
     for (int mt = 0; mt < MT; ++mt) {
       const int m = mt * 32 + l32;
@@ -260,6 +275,7 @@ __global__ __launch_bounds__(kWave) void k_prefix_bwd_mfma(
       }
     }
   }
+  TT_TRACE(ctr, unit, 5);
 }
 
 // ---------------------------------------------------------------------------------------------
@@ -283,10 +299,12 @@ __device__ __forceinline__ void u_bwd_role(
       const int n = min(kWave, u1 - ub);
       const int myi3 = u_i3[ub + min(lane, n - 1)];
       const int mycode = u_code[ub + min(lane, n - 1)];
-      for (int i0 = 0; i0 < n; i0 += UB) {
-        float a[UB][KS], b[UB][NT][KS];
+      // UBX ids per round: their operand loads are in flight together
+      auto round = [&](auto ubx, int i0) {
+        constexpr int UBX = decltype(ubx)::value;
+        float a[UBX][KS], b[UBX][NT][KS];
 #pragma unroll
-        for (int x = 0; x < UB; ++x) {
+        for (int x = 0; x < UBX; ++x) {
           const int i = min(i0 + x, n - 1);
           const float* gp = grad_row_ptr(lane_value(mycode, i), grad, gsum, D) + l16 * D3 + KS * kg;
           const float* cp = g3 + (size_t)lane_value(myi3, i) * S3 + l16 * D3 + KS * kg;
@@ -299,14 +317,17 @@ __device__ __forceinline__ void u_bwd_role(
         }
         TT_LOADS_DONE();
 #pragma unroll
-        for (int x = 0; x < UB; ++x) {
+        for (int x = 0; x < UBX; ++x) {
           const bool on = i0 + x < n;
 #pragma unroll
           for (int nt = 0; nt < NT; ++nt)
 #pragma unroll
             for (int s = 0; s < KS; ++s) acc[nt] = mfma16(on ? a[x][s] : 0.f, b[x][nt][s], acc[nt]);
         }
-      }
+      };
+      int i0 = 0;
+      for (; i0 + 16 <= n; i0 += 16) round(std::integral_constant<int, 16>{}, i0);
+      for (; i0 < n; i0 += UB) round(std::integral_constant<int, UB>{}, i0);
     }
     float* dst = dPsum + (size_t)q * PN;
 #pragma unroll
@@ -411,8 +432,6 @@ __global__ __launch_bounds__(kMThreads) void k_row_fwd_mfma(
   const int ul = l16 / D3, j3 = l16 % D3;
   float* E = ebuf[w];
   const int ntiles = (B + kWave - 1) / kWave;
-  const int gw = blockIdx.x * kMWaves + w;
-  TT_TRACE(ctr, gw, 0);
   for (int tile = blockIdx.x * kMWaves + w; tile < ntiles; tile += gridDim.x * kMWaves) {
     const int s = tile * kWave + lane;
     int mysu = s_u[min(s, B - 1)];
@@ -441,15 +460,7 @@ __global__ __launch_bounds__(kMThreads) void k_row_fwd_mfma(
     const int run_first = 63 - __clzll((long long)upto);
     unsigned long long groups = __ballot(lane < nu && ((lane - run_first) % UPT) == 0);
     const int rel = mysu - u_lo;
-#ifdef TT_EMB_TRACE
-    if (myq + myi3 == -12345) out[0] = 0.f;
-    int nbatch = 0;
-#endif
-    if (tile == gw) TT_TRACE(ctr, gw, 1);
     while (groups) {
-#ifdef TT_EMB_TRACE
-      ++nbatch;
-#endif
       int st[NB], gsz[NB];
 #pragma unroll
       for (int x = 0; x < NB; ++x) {
@@ -482,10 +493,6 @@ __global__ __launch_bounds__(kMThreads) void k_row_fwd_mfma(
         for (int j = 0; j < KQ; ++j) b[x][j] = pc[j * D3];
       }
       TT_LOADS_DONE();
-#ifdef TT_EMB_TRACE
-      if (a[0][0] + b[NB - 1][KQ - 1] == 1.2345f) out[0] = 0.f;
-      if (tile == gw && nbatch == 1) TT_TRACE(ctr, gw, 2);
-#endif
 #pragma unroll
       for (int x = 0; x < NB; ++x) {
         f4 acc = {0.f, 0.f, 0.f, 0.f};
@@ -505,9 +512,6 @@ __global__ __launch_bounds__(kMThreads) void k_row_fwd_mfma(
 #pragma unroll
       for (int x = 1; x < NB; ++x)
         if (st[x] >= 0) last = st[x] + gsz[x];
-#ifdef TT_EMB_TRACE
-      if (tile == gw && nbatch == 1) TT_TRACE(ctr, gw, 3);
-#endif
       for (int k = st[0]; k < last; ++k) {
         float e[VPL];
 #pragma unroll
@@ -522,13 +526,8 @@ __global__ __launch_bounds__(kMThreads) void k_row_fwd_mfma(
       }
       __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
       __builtin_amdgcn_wave_barrier();
-#ifdef TT_EMB_TRACE
-      if (tile == gw && nbatch == 1) TT_TRACE(ctr, gw, 4);
-#endif
     }
-    if (tile == gw) TT_TRACE(ctr, gw, 5);
   }
-  TT_TRACE(ctr, gw, 6);
 }
 
 // ---------------------------------------------------------------------------------------------

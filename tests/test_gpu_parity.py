@@ -227,6 +227,68 @@ def test_bit_reproducible_and_lr_zero():
         np.testing.assert_array_equal(x, y)
 
 
+def test_prepare_pipeline_matches_oracle_over_three_steps():
+    # the next batch's index work is enqueued between forward and backward of the current one;
+    # three different batches, cores carried from step to step on both sides
+    torch = _torch()
+    from paper_2206_10581_amd import TTEmbedding
+    w, cores, _, _ = _workload(2)
+    s = Shape(w.n, w.d, w.r)
+    sizes = [7000, 2500, 9000]
+    batches = [(wl.make_ids(w, 40 + k, B), wl.make_grads(w, 40 + k, B)) for k, B in enumerate(sizes)]
+    batches[1][0][:400] = batches[1][0][0]                       # a hot id in the middle batch
+    emb = TTEmbedding(w.n, w.d, w.r, 10_000, cores)
+    t_ids = [torch.from_numpy(b[0]).cuda() for b in batches]
+    t_grad = [torch.from_numpy(b[1]).cuda() for b in batches]
+    outs = []
+    for k in range(3):
+        outs.append(emb.forward(t_ids[k]))
+        if k + 1 < 3:
+            emb.prepare(t_ids[k + 1])
+        else:
+            emb.prepare(t_ids[0])          # prepared but never used: must be harmless
+        emb.backward_update(t_grad[k], w.lr)
+    torch.cuda.synchronize()
+    emb.stats()
+    ref = [c.copy() for c in cores]
+    for k in range(3):
+        ids, grad = batches[k]
+        assert row_error(outs[k].cpu().numpy(), ora.forward(s, *ref, ids)) <= ROW_TOL, f"step {k}"
+        ref = list(ora.backward_update(s, *ref, ids, grad, w.lr))
+    for k in range(3):
+        assert core_error(emb.cores[k].cpu().numpy(), ref[k]) <= CORE_TOL
+    # two batches ahead: prepare(next) is called before the forward of the current batch
+    emb2 = TTEmbedding(w.n, w.d, w.r, 10_000, cores)
+    outs2 = []
+    emb2.prepare(t_ids[0])
+    for k in range(3):
+        if k + 1 < 3:
+            emb2.prepare(t_ids[k + 1])
+        outs2.append(emb2.forward(t_ids[k]))
+        emb2.backward_update(t_grad[k], w.lr)
+    torch.cuda.synchronize()
+    emb2.stats()
+    for k in range(3):
+        assert torch.equal(outs2[k], outs[k]), f"step {k}"
+        assert torch.equal(emb2.cores[k], emb.cores[k])
+    emb2.close()
+    # a prepared batch that does not match the next forward is dropped, results unchanged
+    base = [c.clone() for c in emb.cores]
+    emb.prepare(t_ids[1])
+    out_a = emb.forward(t_ids[2]).clone()
+    emb.backward_update(t_grad[2], w.lr)
+    after_a = [c.clone() for c in emb.cores]
+    for c, b in zip(emb.cores, base):
+        c.copy_(b)
+    out_b = emb.forward(t_ids[2]).clone()
+    emb.backward_update(t_grad[2], w.lr)
+    torch.cuda.synchronize()
+    assert torch.equal(out_a, out_b)
+    for x, y in zip(after_a, emb.cores):
+        assert torch.equal(x, y)
+    emb.close()
+
+
 def test_abi_error_codes():
     torch = _torch()
     import paper_2206_10581_amd as lib
