@@ -178,6 +178,44 @@ def test_config2_in_full():
     assert stats["Q"] == 56 * 56
 
 
+# ----------------------------------------------------------------------------- the paper's own shapes
+
+@pytest.mark.parametrize("name,n,d,R,B", [
+    ("ogbn-arxiv", (55, 55, 56), (8, 4, 4), 16, 20_000),
+    ("ogbn-products", (125, 140, 140), (4, 5, 5), 8, 20_000),       # D = 100, rows of 400 bytes
+    ("ogbn-papers100M", (480, 500, 500), (8, 4, 4), 8, 30_000),
+    ("unequal ranks", (40, 60, 50), (4, 4, 8), (16, 32), 10_000),
+])
+def test_paper_table_shapes(name, n, d, R, B):
+    # Table "ogb-dim-tt": the factorisations and dimension orderings the paper itself uses; they
+    # run on the any-shape kernels
+    rng = np.random.default_rng(len(name))
+    r = R if isinstance(R, tuple) else (R, R)
+    s = Shape(n, d, r)
+    cores = tuple((rng.standard_normal(cs) / np.sqrt(r[0])).astype(np.float32) for cs in s.core_shapes())
+    ids = rng.integers(0, s.N, size=B, dtype=np.int64)
+    ids[: B // 20] = ids[0]
+    ids[B // 20: B // 10] = ids[0] + rng.integers(0, 30, size=B // 10 - B // 20)   # shared prefixes
+    ids = np.minimum(ids, s.N - 1)
+    grad = rng.standard_normal((B, s.D)).astype(np.float32)
+    check_against_oracle(n, d, r, cores, ids, grad, 0.01)
+
+
+def test_orthogonal_initialisation_on_the_gpu():
+    # Claim 1 of the paper, checked on the GPU forward over every id of a small table: no oracle
+    torch = _torch()
+    from paper_2206_10581_amd import TTEmbedding
+    for n, d, r in [((4, 8, 128), (4, 4, 8), (16, 16)), ((6, 5, 7), (2, 2, 3), (3, 2))]:
+        s = Shape(n, d, r)
+        cores = wl.make_orthogonal_cores(n, d, r, seed=3)
+        emb = TTEmbedding(n, d, r, s.N, cores)
+        W = emb.forward(torch.arange(s.N, dtype=torch.int64, device="cuda")).double().cpu().numpy()
+        emb.close()
+        gram = W.T @ W
+        alpha = np.trace(gram) / s.D
+        np.testing.assert_allclose(gram, alpha * np.eye(s.D), atol=2e-5 * alpha)
+
+
 # ----------------------------------------------------------------------------- full benchmark sizes
 
 def _check_full(cfg, seed=None, ids=None):

@@ -181,6 +181,22 @@ def test_duplicate_and_out_of_range_ids():
     assert not out[3].any() and not out[4].any() and out[2].any()
 
 
+def test_orthogonal_core_initialisation_gives_orthogonal_table():
+    # Algorithm 2 and Claim 1: cores with semi-orthogonal unfoldings make W^T W a multiple of I.
+    # This pins the forward over ALL ids of a table without any reference implementation.
+    import workloads as wl
+    for n, d, r in [((6, 5, 7), (2, 2, 3), (3, 2)), ((4, 8, 12), (2, 2, 2), (4, 4))]:
+        s = Shape(n, d, r)
+        g = wl.make_orthogonal_cores(n, d, r, seed=12)
+        W = ora.forward_f64(s, *g, np.arange(s.N))
+        gram = W.T @ W
+        alpha = np.trace(gram) / s.D
+        assert alpha > 0.5
+        np.testing.assert_allclose(gram, alpha * np.eye(s.D), atol=1e-5 * alpha)
+    with pytest.raises(ValueError):
+        wl.make_orthogonal_cores((10, 10, 4), (2, 2, 5), (4, 4), seed=1)   # 5*4 > 4*1 vectors
+
+
 # ----------------------------------------------------------------------------- sizes
 
 def test_parameter_counts_and_memory_reduction_table():

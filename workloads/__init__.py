@@ -123,3 +123,28 @@ def batch_structure(w: Workload, ids: np.ndarray) -> dict:
             "max_multiplicity": int(cnt.max()) if cnt.size else 0,
             "i1": int(np.unique(q // w.n[1]).size), "i2": int(np.unique(q % w.n[1]).size),
             "i3": int(np.unique(u % w.n[2]).size)}
+
+
+def make_orthogonal_cores(n, d, r, seed: int):
+    """Cores initialised as in the paper's Algorithm 2 ("Orthogonal Initialization of TT-cores"):
+    for core i, n_i*R_{i-1} orthonormal vectors of length m_i*R_i (paper letters: m = node factor,
+    n = dimension factor) fill the core so that its unfolding is semi-orthogonal; Claim 1 then
+    makes the columns of the full table orthogonal.  Needs d_i*R_{i-1} <= n_i*R_i for every core
+    (the paper's feasibility condition, Section 4.1).  Returns fp32 cores in slice-contiguous
+    layout g1[n1,d1,r1], g2[n2,r1,d2,r2], g3[n3,r2,d3].  This is input generation for tests; it is
+    not on the lookup path."""
+    rng = np.random.default_rng(seed)
+    ranks = (1, int(r[0]), int(r[1]), 1)
+    cores = []
+    for i in range(3):
+        rows, cols = int(n[i]) * ranks[i + 1], int(d[i]) * ranks[i]
+        if cols > rows:
+            raise ValueError(f"core {i + 1}: {cols} orthogonal vectors of length {rows} do not exist")
+        q, _ = np.linalg.qr(rng.standard_normal((rows, cols)))     # columns: orthonormal vectors v
+        v = q.T.reshape(ranks[i], int(d[i]), int(n[i]), ranks[i + 1])  # v[r, j, i_k, s]
+        # paper: G_i(r, :, j, :) = reshape(v_{n_i r + j}, [m_i, R_i]);  ours: g[i_k][r][j][s]
+        cores.append(np.ascontiguousarray(np.transpose(v, (2, 0, 1, 3))).astype(np.float32))
+    g1 = cores[0].reshape(int(n[0]), int(d[0]), ranks[1])
+    g2 = cores[1]
+    g3 = cores[2].reshape(int(n[2]), ranks[2], int(d[2]))
+    return g1, g2, g3
