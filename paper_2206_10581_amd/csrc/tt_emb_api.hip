@@ -39,6 +39,9 @@ void launch_id_bwd_mfma(const Plan&, const Workspace&, const float* g3, const fl
                         hipStream_t);
 void launch_prefix_bwd_mfma(const Plan&, const Workspace&, const float* g1, const float* g2, int B,
                             hipStream_t);
+bool mfma_fused_mid(const Shape&);
+void launch_bwd_mid_mfma(const Plan&, const Workspace&, const float* g1, const float* g2,
+                         const float* g3, const float* grad, int B, hipStream_t);
 void launch_gsum_block(const Plan&, const Workspace&, const float* grad, int B, hipStream_t);
 void launch_gsum_block_fix(const Plan&, const Workspace&, int B, hipStream_t);
 
@@ -469,20 +472,27 @@ int tt_emb_backward_update(tt_emb_t h, const float* grad_out, float lr, void* hi
     else launch_gsum_fix(pl, ws, B, st);
   });
   if (rc) return rc;
-  if (h->mfma) {
-    rc = run_slot(h, kSlotUBwd, st, [&] { launch_id_bwd_mfma(pl, ws, h->g3, grad_out, B, st); });
+  if (h->mfma && mfma_fused_mid(pl.sh)) {
+    // ranks up to 32: per-id and per-prefix gradient steps in one launch
+    rc = run_slot(h, kSlotUBwd, st,
+                  [&] { launch_bwd_mid_mfma(pl, ws, h->g1, h->g2, h->g3, grad_out, B, st); });
     if (rc) return rc;
   } else {
-    rc = run_slot(h, kSlotUBwd, st, [&] { launch_u_bwd(pl, ws, h->g3, grad_out, B, st); });
-    if (rc) return rc;
-    rc = run_slot(h, kSlotDg3, st, [&] { launch_dg3(pl, ws, grad_out, B, st); });
+    if (h->mfma) {
+      rc = run_slot(h, kSlotUBwd, st, [&] { launch_id_bwd_mfma(pl, ws, h->g3, grad_out, B, st); });
+      if (rc) return rc;
+    } else {
+      rc = run_slot(h, kSlotUBwd, st, [&] { launch_u_bwd(pl, ws, h->g3, grad_out, B, st); });
+      if (rc) return rc;
+      rc = run_slot(h, kSlotDg3, st, [&] { launch_dg3(pl, ws, grad_out, B, st); });
+      if (rc) return rc;
+    }
+    rc = run_slot(h, kSlotPrefixBwd, st, [&] {
+      if (h->mfma) launch_prefix_bwd_mfma(pl, ws, h->g1, h->g2, B, st);
+      else launch_prefix_bwd(pl, ws, h->g1, h->g2, B, st);
+    });
     if (rc) return rc;
   }
-  rc = run_slot(h, kSlotPrefixBwd, st, [&] {
-    if (h->mfma) launch_prefix_bwd_mfma(pl, ws, h->g1, h->g2, B, st);
-    else launch_prefix_bwd(pl, ws, h->g1, h->g2, B, st);
-  });
-  if (rc) return rc;
   rc = run_slot(h, kSlotSgd, st, [&] { launch_sgd(pl, ws, h->g1, h->g2, h->g3, lr, st); });
   return rc;
 }

@@ -340,17 +340,17 @@ __device__ __forceinline__ void u_bwd_role(
 // ---------------------------------------------------------------------------------------------
 // part3[c]^T = sum over the <= 16 unique ids u of one by-i3 chunk of g_u^T P_q(u)
 // (D3 x 16 times 16 x R; the D3 rows occupy the first rows of a 16-row tile), UB ids at a time.
-template <int R, int D3>
+template <int R, int D3, int UB>
 __device__ __forceinline__ void dg3_role(
-    int block, int nblocks, const float* __restrict__ P, const float* __restrict__ grad,
+    int wave, int nwaves, const float* __restrict__ P, const float* __restrict__ grad,
     const float* __restrict__ gsum, const int* __restrict__ u_code, const int* __restrict__ u_q,
     const int* __restrict__ g3_list, const int4* __restrict__ c3_desc, float* __restrict__ part3,
     const Counters* __restrict__ ctr) {
-  constexpr int PN = 16 * R, S3 = R * D3, D = 16 * D3, NT = R / 16, UB = (R == 64) ? 4 : 8;
-  const int w = threadIdx.x / kWave, lane = threadIdx.x % kWave;
+  constexpr int PN = 16 * R, S3 = R * D3, D = 16 * D3, NT = R / 16;
+  const int lane = threadIdx.x % kWave;
   const int l16 = lane % 16, kg = lane / 16;
   const int nchunk = ctr->nchunk3;
-  for (int c = block * kMWaves + w; c < nchunk; c += nblocks * kMWaves) {
+  for (int c = wave; c < nchunk; c += nwaves) {
     const int4 desc = c3_desc[c];
     const int cnt = desc.z;
     const int myu = g3_list[desc.y + min(lane, cnt - 1)];
@@ -409,7 +409,179 @@ __global__ __launch_bounds__(kMThreads) void k_id_bwd_mfma(
   if (role == 0)
     u_bwd_role<R, D3>(block, nblocks, g3, grad, gsum, u_code, u_i3, q_us, dPsum, ctr);
   else
-    dg3_role<R, D3>(block, nblocks, P, grad, gsum, u_code, u_q, g3_list, c3_desc, part3, ctr);
+    dg3_role<R, D3, (R == 64) ? 4 : 8>(block * kMWaves + (int)threadIdx.x / kWave, nblocks * kMWaves,
+                                       P, grad, gsum, u_code, u_q, g3_list, c3_desc, part3, ctr);
+}
+
+// ---------------------------------------------------------------------------------------------
+// Ranks up to 32: the whole middle of the backward pass in one launch, without dPsum ever leaving
+// the chip.  A block of eight wavefronts owns one by-i2 chunk (<= 16 prefixes q, Bm = G2[i2]):
+//   (i)   dPsum_q = sum over the ids u of q of g_u G3[i3(u)]^T, each wavefront two prefixes, four
+//         ids of each in flight together; results go to an LDS tile of 64 rows
+//         (row = 4*prefix + j1) by 4R columns, Bm sits in LDS beside it
+//   (ii)  wavefronts 0..3: dg1part[q] = dPsum_q Bm^T for four prefixes each (operands from LDS)
+//   (iii) wavefronts 4..7: 32 columns each of part2[c] = sum_q G1[i1(q)]^T dPsum_q
+// Blocks past the chunk range take the by-i3 chunks of the G3 gradient (dg3_role), one per
+// wavefront; that step only needs the per-id gradient sums and the cached prefix products, so
+// both run side by side.
+constexpr int kMidThreads = 512;
+constexpr int kMidWaves = kMidThreads / kWave;
+
+template <int R, int D3>
+__global__ __launch_bounds__(kMidThreads, 6) void k_bwd_mid_mfma(
+    const float* __restrict__ g1, const float* __restrict__ g2, const float* __restrict__ g3,
+    const float* __restrict__ P, const float* __restrict__ grad, const float* __restrict__ gsum,
+    const int* __restrict__ u_code, const int* __restrict__ u_i3, const int* __restrict__ u_q,
+    const int* __restrict__ q_us, const int* __restrict__ q_i1, const int* __restrict__ g2_list,
+    const int4* __restrict__ c2_desc, const int* __restrict__ g3_list,
+    const int4* __restrict__ c3_desc, float* __restrict__ dg1part, float* __restrict__ part2,
+    float* __restrict__ part3, int chunk_blocks, const Counters* __restrict__ ctr) {
+  static_assert(R == 16 || R == 32, "the LDS tiles are sized for ranks up to 32");
+  constexpr int W = 4 * R, S1 = 4 * R, S2 = R * W, S3 = R * D3, D = 16 * D3;
+  constexpr int TS = W + 4;  // padded row stride of the LDS tiles (keeps 16-byte alignment)
+  constexpr int NT16 = R / 16, KS = D3 / 4, UB = 4;
+  __shared__ __align__(16) float T[64 * TS];
+  __shared__ __align__(16) float Bl[R * TS];
+  __shared__ int q_of[16], i1_of[16], u0_of[16], u1_of[16];
+  const int tid = threadIdx.x, w = tid / kWave, lane = tid % kWave;
+  const int trace_id = blockIdx.x * kMidWaves + w;
+  (void)trace_id;
+  TT_TRACE(ctr, trace_id, 0);
+  if ((int)blockIdx.x >= chunk_blocks) {
+    dg3_role<R, D3, 4>(((int)blockIdx.x - chunk_blocks) * kMidWaves + w,
+                       ((int)gridDim.x - chunk_blocks) * kMidWaves, P, grad, gsum, u_code, u_q,
+                       g3_list, c3_desc, part3, ctr);
+    TT_TRACE(ctr, trace_id, 4);
+    return;
+  }
+  const int c = blockIdx.x;
+  if (c >= ctr->nchunk2) return;
+  const int4 desc = c2_desc[c];
+  const int bin = desc.x, cnt = desc.z;
+  const float* Bm = g2 + (size_t)bin * S2;
+  if (tid < 16) {
+    const int q = g2_list[desc.y + min(tid, cnt - 1)];
+    const bool on = tid < cnt;
+    q_of[tid] = on ? q : -1;
+    i1_of[tid] = q_i1[q];
+    u0_of[tid] = on ? q_us[q] : 0;
+    u1_of[tid] = on ? q_us[q + 1] : 0;
+  }
+  for (int i = tid; i < R * W / 4; i += kMidThreads) {
+    const f4 v = ((const f4*)Bm)[i];
+    *(f4*)&Bl[((i * 4) / W) * TS + (i * 4) % W] = v;
+  }
+  __syncthreads();
+  TT_TRACE(ctr, trace_id, 1);
+
+  const int l16 = lane % 16, kg = lane / 16;
+  // (i) this wavefront's two prefixes (local numbers 2w, 2w+1)
+  {
+    f4 acc[2][NT16];
+#pragma unroll
+    for (int x = 0; x < 2; ++x)
+#pragma unroll
+      for (int nt = 0; nt < NT16; ++nt) acc[x][nt] = f4{0.f, 0.f, 0.f, 0.f};
+    const int u0a = u0_of[2 * w], u0b = u0_of[2 * w + 1];
+    const int na = u1_of[2 * w] - u0a, nb = u1_of[2 * w + 1] - u0b;
+    const int rounds = (max(na, nb) + UB - 1) / UB;
+    for (int r = 0; r < rounds; ++r) {
+      // lanes 0..7 hold the round's slots: prefix x = lane/4, id r*UB + lane%4 of its list
+      const int si = r * UB + lane % UB;
+      const bool second = (lane / UB) & 1;
+      const bool slot_on = lane < 2 * UB && si < (second ? nb : na);
+      const int uu = slot_on ? (second ? u0b : u0a) + si : 0;
+      const int mycode = u_code[uu], myi3 = u_i3[uu];
+      float a[2 * UB][KS], b[2 * UB][NT16][KS];
+#pragma unroll
+      for (int sl = 0; sl < 2 * UB; ++sl) {
+        const float* gp = grad_row_ptr(lane_value(mycode, sl), grad, gsum, D) + l16 * D3 + KS * kg;
+        const float* cp = g3 + (size_t)lane_value(myi3, sl) * S3 + l16 * D3 + KS * kg;
+#pragma unroll
+        for (int k = 0; k < KS; ++k) a[sl][k] = gp[k];
+#pragma unroll
+        for (int nt = 0; nt < NT16; ++nt)
+#pragma unroll
+          for (int k = 0; k < KS; ++k) b[sl][nt][k] = cp[nt * 16 * D3 + k];
+      }
+      TT_LOADS_DONE();
+      const unsigned long long on_mask = __ballot(slot_on);
+#pragma unroll
+      for (int sl = 0; sl < 2 * UB; ++sl) {
+        const bool on = (on_mask >> sl) & 1ull;
+#pragma unroll
+        for (int nt = 0; nt < NT16; ++nt)
+#pragma unroll
+          for (int k = 0; k < KS; ++k)
+            acc[sl / UB][nt] = mfma16(on ? a[sl][k] : 0.f, b[sl][nt][k], acc[sl / UB][nt]);
+      }
+    }
+    // accumulator element v of lane (kg, l16) is dPsum_q[m = 4*kg + v][n = nt*16 + l16], i.e. row
+    // j1 = kg of the prefix and column j2*R + n with j2 = v
+#pragma unroll
+    for (int x = 0; x < 2; ++x)
+#pragma unroll
+      for (int nt = 0; nt < NT16; ++nt)
+#pragma unroll
+        for (int v = 0; v < 4; ++v)
+          T[((2 * w + x) * 4 + kg) * TS + v * R + nt * 16 + l16] = acc[x][nt][v];
+  }
+  TT_TRACE(ctr, trace_id, 2);
+  __syncthreads();
+  TT_TRACE(ctr, trace_id, 3);
+
+  if (w < 4) {
+    // (ii) tile rows 16w .. 16w+15 (prefixes 4w .. 4w+3) times Bm^T, 16 x 16 output tiles; lane
+    // group kg contracts over columns [KQ*kg, KQ*kg + KQ)
+    constexpr int KQ = W / 4;
+    const f4* arow = (const f4*)&T[(16 * w + l16) * TS + KQ * kg];
+    f4 acc[NT16];
+#pragma unroll
+    for (int nt = 0; nt < NT16; ++nt) acc[nt] = f4{0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+    for (int j = 0; j < KQ / 4; ++j) {
+      const f4 x = arow[j];
+#pragma unroll
+      for (int nt = 0; nt < NT16; ++nt) {
+        const f4 y = *(const f4*)&Bl[(16 * nt + l16) * TS + KQ * kg + 4 * j];
+        acc[nt] = mfma16(x.x, y.x, acc[nt]);
+        acc[nt] = mfma16(x.y, y.y, acc[nt]);
+        acc[nt] = mfma16(x.z, y.z, acc[nt]);
+        acc[nt] = mfma16(x.w, y.w, acc[nt]);
+      }
+    }
+    // accumulator element v: tile row 4*kg + v = prefix 4w + kg, j1 = v; column n = 16*nt + l16
+    const int qv = q_of[4 * w + kg];
+    if (qv >= 0) {
+#pragma unroll
+      for (int nt = 0; nt < NT16; ++nt)
+#pragma unroll
+        for (int v = 0; v < 4; ++v) dg1part[(size_t)qv * S1 + v * R + 16 * nt + l16] = acc[nt][v];
+    }
+  } else if (w - 4 < W / 32) {
+    // (iii) G1 rows of the sixteen prefixes (as the contraction index) times 32 columns of the tile
+    const int half = lane / 32, l32 = lane % 32;
+    float a[32];
+#pragma unroll
+    for (int j = 0; j < 32; ++j) {
+      const int ql = 8 * half + j / 4;
+      a[j] = g1[(size_t)i1_of[ql] * S1 + (j % 4) * R + (l32 < R ? l32 : 0)];
+    }
+    TT_LOADS_DONE();
+#pragma unroll
+    for (int j = 0; j < 32; ++j)
+      if (q_of[8 * half + j / 4] < 0 || l32 >= R) a[j] = 0.f;
+    const int n = (w - 4) * 32 + l32;
+    f16v acc = TT_ZERO16;
+#pragma unroll
+    for (int j = 0; j < 32; ++j) acc = mfma32(a[j], T[(32 * half + j) * TS + n], acc);
+#pragma unroll
+    for (int v = 0; v < 16; ++v) {
+      const int mrow = 8 * (v / 4) + 4 * half + (v % 4);
+      if (mrow < R) part2[(size_t)c * S2 + (size_t)mrow * W + n] = acc[v];
+    }
+  }
+  TT_TRACE(ctr, trace_id, 4);
 }
 
 // ---------------------------------------------------------------------------------------------
@@ -768,6 +940,25 @@ void launch_id_bwd_mfma(const Plan& pl, const Workspace& ws, const float* g3, co
                                          g3, ws.P, grad, ws.gsum, ws.u_code, ws.u_i3, ws.u_q,
                                          ws.q_us, ws.g3_list, ws.c3_desc, ws.dPsum, ws.part3,
                                          ws.ctr)));
+}
+
+// true when k_bwd_mid_mfma covers the shape (else: k_id_bwd_mfma followed by k_prefix_bwd_mfma)
+bool mfma_fused_mid(const Shape& s) { return mfma_shape(s) && s.r1 <= 32; }
+
+void launch_bwd_mid_mfma(const Plan& pl, const Workspace& ws, const float* g1, const float* g2,
+                         const float* g3, const float* grad, int B, hipStream_t st) {
+  const int chunk_blocks = cdivi(std::min<int64_t>(B, pl.maxQ), kChunk2) + (int)pl.sh.n2;
+  const int dg3_blocks = cdivi(cdivi(B, kChunk3) + (int64_t)pl.sh.n3, kMidWaves);
+#define TT_MID(RR, DD)                                                                            \
+  k_bwd_mid_mfma<RR, DD><<<chunk_blocks + dg3_blocks, kMidThreads, 0, st>>>(                        \
+      g1, g2, g3, ws.P, grad, ws.gsum, ws.u_code, ws.u_i3, ws.u_q, ws.q_us, ws.q_i1, ws.g2_list,  \
+      ws.c2_desc, ws.g3_list, ws.c3_desc, ws.dg1part, ws.part2, ws.part3, chunk_blocks, ws.ctr)
+  if (pl.sh.r1 == 16) {
+    if (pl.sh.d3 == 4) TT_MID(16, 4); else TT_MID(16, 8);
+  } else {
+    if (pl.sh.d3 == 4) TT_MID(32, 4); else TT_MID(32, 8);
+  }
+#undef TT_MID
 }
 
 void launch_row_fwd_mfma(const Plan& pl, const Workspace& ws, const float* g3, int B, float* out,
