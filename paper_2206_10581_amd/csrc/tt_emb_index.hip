@@ -85,6 +85,7 @@ struct ScatterLds {
   uint32_t wh[kSortWaves][kMaxBins / 2];
   uint32_t tot[kMaxBins];  // bucket totals, then this block's first output per bucket
   uint32_t aux[kMaxBins];  // chunks per bucket, then first chunk per bucket
+  uint32_t base[kMaxBins]; // first output of every bucket (all blocks), for chunked passes
   uint32_t ldsw[kSortWaves];
 };
 
@@ -94,7 +95,9 @@ constexpr int kSteps = kSortWaveItems / kWave;  // items per lane
 // [blk*kSortItems, +kSortItems), wavefront w of it the w-th sixteenth).  cnt[b][bin] holds, per
 // bucket, the items of blocks before b and tot[bin] the bucket totals (both from a column-scan
 // kernel over the blocks' histograms).
-// ItemOps: Item load(int idx); int digit(Item); void emit(uint32_t pos, Item).
+// ItemOps: Item load(int idx); int digit(Item); void emit(uint32_t pos, Item); and, for chunked
+// passes, void emit_chunked(uint32_t pos, uint32_t chunk, uint32_t t, Item): item is the t-th of
+// chunk `chunk` (its record goes to chunk*chunk_size + t of a per-chunk table).
 // With starts != nullptr the pass also publishes the bucket offsets (bins+1 entries, by block 0)
 // and, for chunk > 0, cuts every bucket into chunks of at most `chunk` items: chunk_desc[c] =
 // {bucket, first item, item count, 0} for all chunks c in bucket order, chunk_starts[bucket] the
@@ -141,6 +144,9 @@ __device__ void stable_scatter_block(ScatterLds& L, int blk, int n_items, int bi
     if (wbase + step * kWave + lane >= n_items) digits[step] = -1;
   __syncthreads();
   const uint32_t total_items = block_exclusive_scan(L.tot, bins, L.ldsw);
+  if (chunk > 0) {
+    for (int bin = tid; bin < bins; bin += kSortThreads) L.base[bin] = L.tot[bin];
+  }
   if (starts != nullptr) {
     if (publishes) {
       for (int bin = tid; bin < bins; bin += kSortThreads) starts[bin] = (int)L.tot[bin];
@@ -219,7 +225,14 @@ __device__ void stable_scatter_block(ScatterLds& L, int blk, int n_items, int bi
     const int digit = digits[step];
     if (digit >= 0) {
       const uint32_t off = (L.wh[w][digit >> 1] >> (16 * (digit & 1))) & 0xffffu;
-      ops.emit(L.tot[digit] + off + rank[step], items[step]);
+      const uint32_t pos = L.tot[digit] + off + rank[step];
+      if constexpr (ItemOps::kChunked) {
+        const uint32_t in_bucket = pos - L.base[digit];
+        ops.emit_chunked(pos, L.aux[digit] + in_bucket / (uint32_t)chunk, in_bucket % (uint32_t)chunk,
+                         items[step]);
+      } else {
+        ops.emit(pos, items[step]);
+      }
     }
   }
 }
@@ -234,6 +247,7 @@ struct KV {
 template <bool FROM_IDS>
 struct SortOps {
   using Item = KV;
+  static constexpr bool kChunked = false;
   const int64_t* ids;
   const uint32_t* kin;
   const uint32_t* vin;
@@ -502,28 +516,62 @@ __global__ __launch_bounds__(kSegThreads) void k_seg_write(
 // ---------------------------------------------------------------------------------------------
 // Grouping: unique ids by i3 (for the G3 gradient), prefixes by i2 (for G2 and the prefix product)
 
-struct GroupOps {
-  using Item = int;
-  const int* digit_of;
+// Unique ids by i3.  Besides the list, every chunk gets a table of its ids' records
+// {gradient-row code, prefix}, so that the gradient kernels need no further look-ups.
+struct GroupOps3 {
+  struct Item {
+    int u, i3, code, q;
+  };
+  static constexpr bool kChunked = true;
+  const int* u_i3;
+  const int* u_code;
+  const int* u_q;
   int* list;
-  __device__ Item load(int idx) const { return idx; }
-  __device__ int digit(Item it) const { return digit_of[it]; }
-  __device__ void emit(uint32_t pos, Item it) const { list[pos] = it; }
+  int2* item;
+  __device__ Item load(int idx) const { return Item{idx, u_i3[idx], u_code[idx], u_q[idx]}; }
+  __device__ int digit(Item it) const { return it.i3; }
+  __device__ void emit_chunked(uint32_t pos, uint32_t chunk, uint32_t t, Item it) const {
+    list[pos] = it.u;
+    item[(size_t)chunk * kChunk3 + t] = make_int2(it.code, it.q);
+  }
+};
+
+// Prefixes by i2; chunk records are {prefix, i1, first unique id, one past its last unique id}.
+struct GroupOps2 {
+  struct Item {
+    int q, i2, i1, u0, u1;
+  };
+  static constexpr bool kChunked = true;
+  const int* q_i2;
+  const int* q_i1;
+  const int* q_us;
+  int* list;
+  int4* item;
+  __device__ Item load(int idx) const {
+    return Item{idx, q_i2[idx], q_i1[idx], q_us[idx], q_us[idx + 1]};
+  }
+  __device__ int digit(Item it) const { return it.i2; }
+  __device__ void emit_chunked(uint32_t pos, uint32_t chunk, uint32_t t, Item it) const {
+    list[pos] = it.q;
+    item[(size_t)chunk * kChunk2 + t] = make_int4(it.q, it.i1, it.u0, it.u1);
+  }
 };
 
 __global__ __launch_bounds__(kSortThreads) void k_group(
     Shape sh, int u_blocks, int bits3, int bits2, const uint32_t* __restrict__ cnt3,
     const uint32_t* __restrict__ tot3, const uint32_t* __restrict__ cnt2,
-    const uint32_t* __restrict__ tot2, const int* __restrict__ u_i3, const int* __restrict__ q_i2,
-    int* g3_list, int* g3_start, int* c3_start, int4* c3_desc, int* g2_list, int* g2_start,
-    int* c2_start, int4* c2_desc, Counters* ctr) {
+    const uint32_t* __restrict__ tot2, const int* __restrict__ u_i3, const int* __restrict__ u_code,
+    const int* __restrict__ u_q, const int* __restrict__ q_i2, const int* __restrict__ q_i1,
+    const int* __restrict__ q_us, int* g3_list, int* g3_start, int* c3_start, int4* c3_desc,
+    int2* c3_item, int* g2_list, int* g2_start, int* c2_start, int4* c2_desc, int4* c2_item,
+    Counters* ctr) {
   __shared__ ScatterLds L;
   if ((int)blockIdx.x < u_blocks) {
-    GroupOps ops{u_i3, g3_list};
+    GroupOps3 ops{u_i3, u_code, u_q, g3_list, c3_item};
     stable_scatter_block(L, (int)blockIdx.x, ctr->U, (int)sh.n3, bits3, cnt3, tot3, ops, g3_start,
                          kChunk3, c3_start, c3_desc, &ctr->nchunk3);
   } else {
-    GroupOps ops{q_i2, g2_list};
+    GroupOps2 ops{q_i2, q_i1, q_us, g2_list, c2_item};
     stable_scatter_block(L, (int)blockIdx.x - u_blocks, ctr->Q, (int)sh.n2, bits2, cnt2, tot2, ops,
                          g2_start, kChunk2, c2_start, c2_desc, &ctr->nchunk2);
   }
@@ -592,9 +640,10 @@ void launch_group(const Plan& pl, const Workspace& ws, int B, hipStream_t st) {
   const int ub = cdiv(B, kSortItems);
   const int qb = cdiv(std::min((int64_t)B, pl.maxQ), kSortItems);
   k_group<<<ub + qb, kSortThreads, 0, st>>>(pl.sh, ub, pl.bits3, pl.bits2, ws.cnt3, ws.tot3, ws.cnt2,
-                                           ws.tot2, ws.u_i3, ws.q_i2, ws.g3_list, ws.g3_start,
-                                           ws.c3_start, ws.c3_desc, ws.g2_list, ws.g2_start,
-                                           ws.c2_start, ws.c2_desc, ws.ctr);
+                                           ws.tot2, ws.u_i3, ws.u_code, ws.u_q, ws.q_i2, ws.q_i1,
+                                           ws.q_us, ws.g3_list, ws.g3_start, ws.c3_start, ws.c3_desc,
+                                           ws.c3_item, ws.g2_list, ws.g2_start, ws.c2_start,
+                                           ws.c2_desc, ws.c2_item, ws.ctr);
 }
 
 }  // namespace ttemb

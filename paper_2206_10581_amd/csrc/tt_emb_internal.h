@@ -22,7 +22,10 @@ constexpr int kSegThreads = 256;
 constexpr int kSegItems = 1024;  // sorted slots per block in the segment kernels (4 per thread)
 
 constexpr int kTileSlots = 32;   // sorted slots per wavefront tile in the row kernels
-constexpr int kChunk3 = 16;      // unique ids per partial sum of a G3 slice gradient
+#ifndef TT_CHUNK3
+#define TT_CHUNK3 16
+#endif
+constexpr int kChunk3 = TT_CHUNK3;  // unique ids per partial sum of a G3 slice gradient
 constexpr int kChunk2 = 16;      // unique prefixes per partial sum of a G2 slice gradient
 
 // Table and slice geometry, passed to kernels by value.
@@ -86,10 +89,12 @@ struct Workspace {
   int* g3_start;      // [n3+1]
   int* c3_start;      // first chunk of each i3 group [n3+1]
   int4* c3_desc;      // chunk -> {i3, first list item, items, 0}  [maxChunk3]
+  int2* c3_item;      // chunk, t -> {gradient-row code, prefix} of its t-th id [maxChunk3][kChunk3]
   int* g2_list;       // prefixes grouped by i2 (stable) [maxQ]
   int* g2_start;      // [n2+1]
   int* c2_start;      // [n2+1]
   int4* c2_desc;      // chunk -> {i2, first list item, items, 0}  [maxChunk2]
+  int4* c2_item;      // chunk, t -> {q, i1, first unique id, end} of its t-th prefix [maxChunk2][kChunk2]
   int* g1_first;      // i1 -> first prefix with that i1 (prefixes are sorted by i1) [n1]
   int* g1_end;        // i1 -> one past its last prefix; directly follows g1_first  [n1]
   float* P;           // prefix products G1[i1] G2[i2]   [maxQ][PN]

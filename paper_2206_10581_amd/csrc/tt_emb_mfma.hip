@@ -22,6 +22,9 @@ typedef float f16v __attribute__((ext_vector_type(16)));
 
 constexpr int kMThreads = 256;
 constexpr int kMWaves = kMThreads / kWave;
+// sorted slots per wavefront in the row kernel (lanes past it idle in the index steps): half a
+// wavefront's worth keeps twice as many wavefronts in flight, which hides the store latency better
+constexpr int kRowTile = 32;
 
 __device__ __forceinline__ f16v mfma32(float a, float b, f16v c) {
   return __builtin_amdgcn_mfma_f32_32x32x2f32(a, b, c, 0, 0, 0);
@@ -79,16 +82,17 @@ constexpr int kPfUnits = 2;  // units per chunk in the forward prefix kernel
 
 template <int R>
 __global__ __launch_bounds__(kWave) void k_prefix_fwd_mfma(
-    const float* __restrict__ g1, const float* __restrict__ g2, const int* __restrict__ g2_list,
-    const int4* __restrict__ c2_desc, const int* __restrict__ q_i1, float* __restrict__ P,
-    const Counters* __restrict__ ctr) {
+    const float* __restrict__ g1, const float* __restrict__ g2, const int4* __restrict__ c2_item,
+    const int4* __restrict__ c2_desc, float* __restrict__ P, const Counters* __restrict__ ctr) {
   constexpr int W = 4 * R, PN = 16 * R, S1 = 4 * R, S2 = R * W, KH = R / 2, NT = W / 32;
   constexpr int NTH = NT / kPfUnits;  // column tiles of one unit
   const int lane = threadIdx.x, half = lane / 32, l32 = lane % 32;
   const int unit = blockIdx.x;
-  if (unit >= ctr->nchunk2 * kPfUnits) return;
   const int c = unit / kPfUnits, nt0 = (unit % kPfUnits) * NTH;
+  // the chunk's records and descriptor are read together (the grid never exceeds the tables)
+  const int4 item = c2_item[(size_t)c * kChunk2 + lane % kChunk2];
   const int4 desc = c2_desc[c];
+  if (c >= ctr->nchunk2) return;
   const int bin = desc.x, cnt = desc.z;
   const float* Bm = g2 + (size_t)bin * S2 + (size_t)(KH * half) * W + nt0 * 32 + l32;
   float b[NTH][KH];
@@ -96,9 +100,9 @@ __global__ __launch_bounds__(kWave) void k_prefix_fwd_mfma(
   for (int t = 0; t < NTH; ++t)
 #pragma unroll
     for (int j = 0; j < KH; ++j) b[t][j] = Bm[(size_t)j * W + t * 32];
-  int myq = g2_list[desc.y + min(lane, cnt - 1)];
-  const int myi1 = q_i1[myq];
-  if (lane >= cnt) myq = -1;
+  const bool mine = lane < cnt;  // records past the chunk's count are unwritten
+  const int myq = mine ? item.x : -1;
+  const int myi1 = mine ? item.y : 0;
   float a[2][KH];
 #pragma unroll
   for (int mt = 0; mt < 2; ++mt) {
@@ -149,20 +153,21 @@ constexpr int kPbUnits = 4;
 template <int R>
 __global__ __launch_bounds__(kWave) void k_prefix_bwd_mfma(
     const float* __restrict__ g1, const float* __restrict__ g2, const float* __restrict__ dPsum,
-    const int* __restrict__ g2_list, const int4* __restrict__ c2_desc, const int* __restrict__ q_i1,
-    float* __restrict__ dg1part, float* __restrict__ part2, Counters* __restrict__ ctr) {
+    const int4* __restrict__ c2_item, const int4* __restrict__ c2_desc, float* __restrict__ dg1part,
+    float* __restrict__ part2, Counters* __restrict__ ctr) {
   constexpr int W = 4 * R, PN = 16 * R, S1 = 4 * R, S2 = R * W;
   const int lane = threadIdx.x, half = lane / 32, l32 = lane % 32;
   const int unit = blockIdx.x;
   TT_TRACE(ctr, unit, 0);
-  if (unit >= ctr->nchunk2 * kPbUnits) return;
   const int c = unit / kPbUnits, part = unit % kPbUnits;
+  const int4 item = c2_item[(size_t)c * kChunk2 + lane % kChunk2];
   const int4 desc = c2_desc[c];
+  if (c >= ctr->nchunk2) return;
   const int bin = desc.x, cnt = desc.z;
   if (part == 1 && cnt <= 8) return;
-  int myq = g2_list[desc.y + min(lane, cnt - 1)];
-  const int myi1 = q_i1[myq];
-  if (lane >= cnt) myq = -1;
+  const bool mine = lane < cnt;  // records past the chunk's count are unwritten
+  const int myq = mine ? item.x : -1;
+  const int myi1 = mine ? item.y : 0;
 #ifdef TT_EMB_TRACE
   if (myq + myi1 == -12345) dg1part[0] = 0.f;
   TT_TRACE(ctr, unit, 1);
@@ -343,19 +348,17 @@ __device__ __forceinline__ void u_bwd_role(
 template <int R, int D3, int UB>
 __device__ __forceinline__ void dg3_role(
     int wave, int nwaves, const float* __restrict__ P, const float* __restrict__ grad,
-    const float* __restrict__ gsum, const int* __restrict__ u_code, const int* __restrict__ u_q,
-    const int* __restrict__ g3_list, const int4* __restrict__ c3_desc, float* __restrict__ part3,
-    const Counters* __restrict__ ctr) {
+    const float* __restrict__ gsum, const int2* __restrict__ c3_item,
+    const int4* __restrict__ c3_desc, float* __restrict__ part3, const Counters* __restrict__ ctr) {
   constexpr int PN = 16 * R, S3 = R * D3, D = 16 * D3, NT = R / 16;
   const int lane = threadIdx.x % kWave;
   const int l16 = lane % 16, kg = lane / 16;
   const int nchunk = ctr->nchunk3;
   for (int c = wave; c < nchunk; c += nwaves) {
-    const int4 desc = c3_desc[c];
-    const int cnt = desc.z;
-    const int myu = g3_list[desc.y + min(lane, cnt - 1)];
-    const int myq = u_q[myu];
-    const int mycode = u_code[myu];
+    const int2 item = c3_item[(size_t)c * kChunk3 + lane % kChunk3];
+    const int cnt = c3_desc[c].z;
+    // records past the chunk's count are unwritten; only lanes below cnt are ever read
+    const int mycode = item.x, myq = item.y;
     f4 acc[NT];
 #pragma unroll
     for (int nt = 0; nt < NT; ++nt) acc[nt] = f4{0.f, 0.f, 0.f, 0.f};
@@ -402,7 +405,7 @@ template <int R, int D3>
 __global__ __launch_bounds__(kMThreads) void k_id_bwd_mfma(
     const float* __restrict__ g3, const float* __restrict__ P, const float* __restrict__ grad,
     const float* __restrict__ gsum, const int* __restrict__ u_code, const int* __restrict__ u_i3,
-    const int* __restrict__ u_q, const int* __restrict__ q_us, const int* __restrict__ g3_list,
+    const int* __restrict__ q_us, const int2* __restrict__ c3_item,
     const int4* __restrict__ c3_desc, float* __restrict__ dPsum, float* __restrict__ part3,
     const Counters* __restrict__ ctr) {
   const int role = blockIdx.x & 1, block = blockIdx.x >> 1, nblocks = gridDim.x >> 1;
@@ -410,7 +413,7 @@ __global__ __launch_bounds__(kMThreads) void k_id_bwd_mfma(
     u_bwd_role<R, D3>(block, nblocks, g3, grad, gsum, u_code, u_i3, q_us, dPsum, ctr);
   else
     dg3_role<R, D3, (R == 64) ? 4 : 8>(block * kMWaves + (int)threadIdx.x / kWave, nblocks * kMWaves,
-                                       P, grad, gsum, u_code, u_q, g3_list, c3_desc, part3, ctr);
+                                       P, grad, gsum, c3_item, c3_desc, part3, ctr);
 }
 
 // ---------------------------------------------------------------------------------------------
@@ -431,9 +434,8 @@ template <int R, int D3>
 __global__ __launch_bounds__(kMidThreads, 6) void k_bwd_mid_mfma(
     const float* __restrict__ g1, const float* __restrict__ g2, const float* __restrict__ g3,
     const float* __restrict__ P, const float* __restrict__ grad, const float* __restrict__ gsum,
-    const int* __restrict__ u_code, const int* __restrict__ u_i3, const int* __restrict__ u_q,
-    const int* __restrict__ q_us, const int* __restrict__ q_i1, const int* __restrict__ g2_list,
-    const int4* __restrict__ c2_desc, const int* __restrict__ g3_list,
+    const int* __restrict__ u_code, const int* __restrict__ u_i3, const int4* __restrict__ c2_item,
+    const int4* __restrict__ c2_desc, const int2* __restrict__ c3_item,
     const int4* __restrict__ c3_desc, float* __restrict__ dg1part, float* __restrict__ part2,
     float* __restrict__ part3, int chunk_blocks, const Counters* __restrict__ ctr) {
   static_assert(R == 16 || R == 32, "the LDS tiles are sized for ranks up to 32");
@@ -447,25 +449,27 @@ __global__ __launch_bounds__(kMidThreads, 6) void k_bwd_mid_mfma(
   const int trace_id = blockIdx.x * kMidWaves + w;
   (void)trace_id;
   TT_TRACE(ctr, trace_id, 0);
+  // blocks past the by-i2 chunk range take the by-i3 chunks, one per wavefront
   if ((int)blockIdx.x >= chunk_blocks) {
     dg3_role<R, D3, 4>(((int)blockIdx.x - chunk_blocks) * kMidWaves + w,
-                       ((int)gridDim.x - chunk_blocks) * kMidWaves, P, grad, gsum, u_code, u_q,
-                       g3_list, c3_desc, part3, ctr);
+                       ((int)gridDim.x - chunk_blocks) * kMidWaves, P, grad, gsum, c3_item, c3_desc,
+                       part3, ctr);
     TT_TRACE(ctr, trace_id, 4);
     return;
   }
+  // records, descriptor and chunk count are read together (the grid never exceeds the tables)
   const int c = blockIdx.x;
-  if (c >= ctr->nchunk2) return;
+  const int4 item = c2_item[(size_t)c * kChunk2 + tid % kChunk2];
   const int4 desc = c2_desc[c];
+  if (c >= ctr->nchunk2) return;
   const int bin = desc.x, cnt = desc.z;
   const float* Bm = g2 + (size_t)bin * S2;
   if (tid < 16) {
-    const int q = g2_list[desc.y + min(tid, cnt - 1)];
-    const bool on = tid < cnt;
-    q_of[tid] = on ? q : -1;
-    i1_of[tid] = q_i1[q];
-    u0_of[tid] = on ? q_us[q] : 0;
-    u1_of[tid] = on ? q_us[q + 1] : 0;
+    const bool on = tid < cnt;  // records past the chunk's count are unwritten
+    q_of[tid] = on ? item.x : -1;
+    i1_of[tid] = on ? item.y : 0;
+    u0_of[tid] = on ? item.z : 0;
+    u1_of[tid] = on ? item.w : 0;
   }
   for (int i = tid; i < R * W / 4; i += kMidThreads) {
     const f4 v = ((const f4*)Bm)[i];
@@ -473,6 +477,14 @@ __global__ __launch_bounds__(kMidThreads, 6) void k_bwd_mid_mfma(
   }
   __syncthreads();
   TT_TRACE(ctr, trace_id, 1);
+#ifdef TT_EXP_P0ONLY
+  if (ctr->nchunk2 >= 0) return;
+#endif
+#ifdef TT_EXP_NOSTORE
+  const bool do_store = ctr->nchunk2 < 0;
+#else
+  const bool do_store = true;
+#endif
 
   const int l16 = lane % 16, kg = lane / 16;
   // (i) this wavefront's two prefixes (local numbers 2w, 2w+1)
@@ -491,7 +503,11 @@ __global__ __launch_bounds__(kMidThreads, 6) void k_bwd_mid_mfma(
       const bool second = (lane / UB) & 1;
       const bool slot_on = lane < 2 * UB && si < (second ? nb : na);
       const int uu = slot_on ? (second ? u0b : u0a) + si : 0;
+#ifdef TT_EXP_FIXGRAD
+      const int mycode = u_code[uu] & 0, myi3 = u_i3[uu];
+#else
       const int mycode = u_code[uu], myi3 = u_i3[uu];
+#endif
       float a[2 * UB][KS], b[2 * UB][NT16][KS];
 #pragma unroll
       for (int sl = 0; sl < 2 * UB; ++sl) {
@@ -508,12 +524,14 @@ __global__ __launch_bounds__(kMidThreads, 6) void k_bwd_mid_mfma(
       const unsigned long long on_mask = __ballot(slot_on);
 #pragma unroll
       for (int sl = 0; sl < 2 * UB; ++sl) {
-        const bool on = (on_mask >> sl) & 1ull;
+        // wavefront-uniform: empty slots cost no matrix-core time
+        if ((on_mask >> sl) & 1ull) {
 #pragma unroll
-        for (int nt = 0; nt < NT16; ++nt)
+          for (int nt = 0; nt < NT16; ++nt)
 #pragma unroll
-          for (int k = 0; k < KS; ++k)
-            acc[sl / UB][nt] = mfma16(on ? a[sl][k] : 0.f, b[sl][nt][k], acc[sl / UB][nt]);
+            for (int k = 0; k < KS; ++k)
+              acc[sl / UB][nt] = mfma16(a[sl][k], b[sl][nt][k], acc[sl / UB][nt]);
+        }
       }
     }
     // accumulator element v of lane (kg, l16) is dPsum_q[m = 4*kg + v][n = nt*16 + l16], i.e. row
@@ -552,7 +570,7 @@ __global__ __launch_bounds__(kMidThreads, 6) void k_bwd_mid_mfma(
     }
     // accumulator element v: tile row 4*kg + v = prefix 4w + kg, j1 = v; column n = 16*nt + l16
     const int qv = q_of[4 * w + kg];
-    if (qv >= 0) {
+    if (qv >= 0 && do_store) {
 #pragma unroll
       for (int nt = 0; nt < NT16; ++nt)
 #pragma unroll
@@ -578,14 +596,29 @@ __global__ __launch_bounds__(kMidThreads, 6) void k_bwd_mid_mfma(
 #pragma unroll
     for (int v = 0; v < 16; ++v) {
       const int mrow = 8 * (v / 4) + 4 * half + (v % 4);
-      if (mrow < R) part2[(size_t)c * S2 + (size_t)mrow * W + n] = acc[v];
+      if (mrow < R && do_store) part2[(size_t)c * S2 + (size_t)mrow * W + n] = acc[v];
     }
   }
   TT_TRACE(ctr, trace_id, 4);
 }
 
 // ---------------------------------------------------------------------------------------------
-// Rows: one wavefront per tile of 64 sorted slots.  The distinct ids of a tile are taken in groups
+// The by-i3 chunks alone, one per wavefront, for launches that run beside the by-i2 chunk blocks on
+// a second stream: without the LDS tiles of those blocks many more wavefronts are resident.
+#ifndef TT_DG3_UB
+#define TT_DG3_UB 8
+#endif
+template <int R, int D3>
+__global__ __launch_bounds__(kMThreads) void k_dg3_mfma(
+    const float* __restrict__ P, const float* __restrict__ grad, const float* __restrict__ gsum,
+    const int2* __restrict__ c3_item, const int4* __restrict__ c3_desc, float* __restrict__ part3,
+    const Counters* __restrict__ ctr) {
+  dg3_role<R, D3, TT_DG3_UB>((int)blockIdx.x * kMWaves + (int)threadIdx.x / kWave,
+                             (int)gridDim.x * kMWaves, P, grad, gsum, c3_item, c3_desc, part3, ctr);
+}
+
+// ---------------------------------------------------------------------------------------------
+// Rows: one wavefront per tile of kRowTile sorted slots.  The distinct ids of a tile are taken in groups
 // of up to 16/D3 consecutive ids that share a prefix: E = P_q (16 x R) times their G3 slices side
 // by side (R x 16).  Up to NB groups are worked on together (operand loads in flight together);
 // their rows go through LDS so that one store instruction writes a whole row to every batch
@@ -603,9 +636,10 @@ __global__ __launch_bounds__(kMThreads) void k_row_fwd_mfma(
   const int l16 = lane % 16, kg = lane / 16;
   const int ul = l16 / D3, j3 = l16 % D3;
   float* E = ebuf[w];
-  const int ntiles = (B + kWave - 1) / kWave;
+  constexpr int TSL = kRowTile;
+  const int ntiles = (B + TSL - 1) / TSL;
   for (int tile = blockIdx.x * kMWaves + w; tile < ntiles; tile += gridDim.x * kMWaves) {
-    const int s = tile * kWave + lane;
+    const int s = lane < TSL ? tile * TSL + lane : B;
     int mysu = s_u[min(s, B - 1)];
     uint32_t myb = perm[min(s, B - 1)];
     if (s >= B) mysu = -2;  // lanes past the batch: neither an id nor an out-of-range slot
@@ -710,7 +744,10 @@ __global__ __launch_bounds__(kMThreads) void k_row_fwd_mfma(
 // kernels read their row from grad_out directly.  Pieces of runs that cross wavefronts are joined
 // in LDS, pieces that cross blocks leave one partial per block in carry[block][h] (h = 0: the run
 // began in an earlier block, h = 1: it begins here and continues).
-constexpr int kGsumWaves = 16;
+#ifndef TT_GSUM_WAVES
+#define TT_GSUM_WAVES 16
+#endif
+constexpr int kGsumWaves = TT_GSUM_WAVES;
 constexpr int kGsumThreads = kGsumWaves * kWave;
 constexpr int kGsumBlockSlots = kGsumWaves * kWave;  // 1024
 
@@ -919,7 +956,7 @@ void launch_prefix_fwd_mfma(const Plan& pl, const Workspace& ws, const float* g1
   const int64_t chunks = cdivi(std::min<int64_t>(B, pl.maxQ), kChunk2) + pl.sh.n2;
   const int grid = (int)(chunks * kPfUnits);
   TT_DISPATCH_R(pl.sh.r1, (k_prefix_fwd_mfma<R><<<grid, kWave, 0, st>>>(
-                              g1, g2, ws.g2_list, ws.c2_desc, ws.q_i1, ws.P, ws.ctr)));
+                              g1, g2, ws.c2_item, ws.c2_desc, ws.P, ws.ctr)));
 }
 
 void launch_prefix_bwd_mfma(const Plan& pl, const Workspace& ws, const float* g1, const float* g2,
@@ -927,8 +964,8 @@ void launch_prefix_bwd_mfma(const Plan& pl, const Workspace& ws, const float* g1
   const int64_t chunks = cdivi(std::min<int64_t>(B, pl.maxQ), kChunk2) + pl.sh.n2;
   const int grid = (int)(chunks * kPbUnits);
   TT_DISPATCH_R(pl.sh.r1, (k_prefix_bwd_mfma<R><<<grid, kWave, 0, st>>>(
-                              g1, g2, ws.dPsum, ws.g2_list, ws.c2_desc, ws.q_i1, ws.dg1part,
-                              ws.part2, ws.ctr)));
+                              g1, g2, ws.dPsum, ws.c2_item, ws.c2_desc, ws.dg1part, ws.part2,
+                              ws.ctr)));
 }
 
 void launch_id_bwd_mfma(const Plan& pl, const Workspace& ws, const float* g3, const float* grad,
@@ -937,22 +974,28 @@ void launch_id_bwd_mfma(const Plan& pl, const Workspace& ws, const float* g3, co
   const int64_t waves_q = std::min<int64_t>(B, pl.maxQ), waves_c = cdivi(B, kChunk3) + (int64_t)pl.sh.n3;
   const int per_role = grid_cap(cdivi(std::max(waves_q, waves_c), kMWaves), kMGridCap);
   TT_DISPATCH_RD(pl.sh.r1, pl.sh.d3, (k_id_bwd_mfma<R, D3><<<2 * per_role, kMThreads, 0, st>>>(
-                                         g3, ws.P, grad, ws.gsum, ws.u_code, ws.u_i3, ws.u_q,
-                                         ws.q_us, ws.g3_list, ws.c3_desc, ws.dPsum, ws.part3,
-                                         ws.ctr)));
+                                         g3, ws.P, grad, ws.gsum, ws.u_code, ws.u_i3, ws.q_us,
+                                         ws.c3_item, ws.c3_desc, ws.dPsum, ws.part3, ws.ctr)));
 }
 
 // true when k_bwd_mid_mfma covers the shape (else: k_id_bwd_mfma followed by k_prefix_bwd_mfma)
 bool mfma_fused_mid(const Shape& s) { return mfma_shape(s) && s.r1 <= 32; }
 
+void launch_dg3_mfma(const Plan& pl, const Workspace& ws, const float* grad, int B, hipStream_t st) {
+  const int grid = cdivi(cdivi(B, kChunk3) + (int64_t)pl.sh.n3, kMWaves);
+  TT_DISPATCH_RD(pl.sh.r1, pl.sh.d3, (k_dg3_mfma<R, D3><<<grid, kMThreads, 0, st>>>(
+                                         ws.P, grad, ws.gsum, ws.c3_item, ws.c3_desc, ws.part3,
+                                         ws.ctr)));
+}
+
 void launch_bwd_mid_mfma(const Plan& pl, const Workspace& ws, const float* g1, const float* g2,
-                         const float* g3, const float* grad, int B, hipStream_t st) {
+                         const float* g3, const float* grad, int B, bool with_dg3, hipStream_t st) {
   const int chunk_blocks = cdivi(std::min<int64_t>(B, pl.maxQ), kChunk2) + (int)pl.sh.n2;
-  const int dg3_blocks = cdivi(cdivi(B, kChunk3) + (int64_t)pl.sh.n3, kMidWaves);
+  const int dg3_blocks = with_dg3 ? cdivi(cdivi(B, kChunk3) + (int64_t)pl.sh.n3, kMidWaves) : 0;
 #define TT_MID(RR, DD)                                                                            \
   k_bwd_mid_mfma<RR, DD><<<chunk_blocks + dg3_blocks, kMidThreads, 0, st>>>(                        \
-      g1, g2, g3, ws.P, grad, ws.gsum, ws.u_code, ws.u_i3, ws.u_q, ws.q_us, ws.q_i1, ws.g2_list,  \
-      ws.c2_desc, ws.g3_list, ws.c3_desc, ws.dg1part, ws.part2, ws.part3, chunk_blocks, ws.ctr)
+      g1, g2, g3, ws.P, grad, ws.gsum, ws.u_code, ws.u_i3, ws.c2_item, ws.c2_desc, ws.c3_item,    \
+      ws.c3_desc, ws.dg1part, ws.part2, ws.part3, chunk_blocks, ws.ctr)
   if (pl.sh.r1 == 16) {
     if (pl.sh.d3 == 4) TT_MID(16, 4); else TT_MID(16, 8);
   } else {
@@ -963,7 +1006,7 @@ void launch_bwd_mid_mfma(const Plan& pl, const Workspace& ws, const float* g1, c
 
 void launch_row_fwd_mfma(const Plan& pl, const Workspace& ws, const float* g3, int B, float* out,
                          hipStream_t st) {
-  const int grid = grid_cap(cdivi(cdivi(B, kWave), kMWaves), kMGridCap);
+  const int grid = grid_cap(cdivi(cdivi(B, kRowTile), kMWaves), 1 << 20);
   const uint32_t* perm = ws.val[(pl.passes - 1) & 1];
   TT_DISPATCH_RD(pl.sh.r1, pl.sh.d3, (k_row_fwd_mfma<R, D3><<<grid, kMThreads, 0, st>>>(
                                          B, g3, ws.P, ws.s_u, perm, ws.u_i3, ws.u_q, out, ws.ctr)));
