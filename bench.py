@@ -7,9 +7,12 @@ tt_emb_backward_update (gradient sums, core gradients, SGD).  The metric is rows
 duplicates counted.  The default workload is the 2.5M-node rank-32 table with a 200,000-row Zipf
 batch; `--config K` picks another of the five synthetic workloads.
 
-Inside the timed region every step also restores the cores from a snapshot with one device-side
-copy (a few MB): repeated SGD steps on the same random gradients would otherwise overflow within a
-few steps.  The copy is extra work that is counted against the measured rate.
+Repeated SGD steps on the same random gradients feed back through the three cores and overflow
+within a few steps at the workloads' learning rate (the hottest id occurs 24,000 times in the default
+batch), so the timed steps use a learning rate of 1e-8: the kernels execute exactly the same
+instructions, and the cores stay where they are for hundreds of steps.  `--restore` times the other
+protocol instead: the workload's own learning rate, with the cores put back from a snapshot by one
+device-side copy per step inside the timed region (extra work, counted against the rate).
 
 Prints ONE JSON line.  `roofline` describes the kernel with the largest share of the step, timed
 with HIP events on its own stream by the library's profiling hook in a separate, untimed leg;
@@ -34,9 +37,8 @@ FP32_PEAK = 157.3e12     # flop/s, MI355X fp32 (vector with packed ops, or fp32 
 # WRITE_SIZE) scaled by the readings for the 2,380 KiB core-restore copy of the same process; the
 # table and the commands are in profiles/step_config3_hbm_traffic.md.  Only the default workload was
 # measured; for anything else `traffic` is null.
-MEASURED_TRAFFIC = {3: {"row_fwd": 39.8e6 + 102.4e6, "gsum": 84.6e6 + 4.8e6, "u_bwd": 139.5e6 + 37.8e6,
-                        "prefix_bwd": 79.4e6 + 26.8e6, "prefix_fwd": 10.7e6 + 34.8e6,
-                        "sgd": 32.0e6 + 2.4e6}}
+MEASURED_TRAFFIC = {3: {"row_fwd": 41.0e6 + 102.4e6, "gsum": 84.5e6 + 4.8e6, "u_bwd": 153.4e6 + 29.8e6,
+                        "prefix_fwd": 10.3e6 + 34.8e6, "sgd": 32.0e6 + 2.4e6}}
 
 
 def kernel_work(slot: str, w, B: int, U: int, Q: int, touched_bytes: int, passes: int):
@@ -75,6 +77,10 @@ def main() -> int:
     ap.add_argument("--seed", type=int, default=None)
     ap.add_argument("--profile-steps", type=int, default=20)
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--restore", action="store_true",
+                    help="workload learning rate, cores restored from a snapshot every step")
+    ap.add_argument("--lr", type=float, default=1e-8,
+                    help="learning rate of the timed steps (ignored with --restore)")
     ap.add_argument("--no-prepare", action="store_true",
                     help="do not overlap the next step's index work with this step's backward")
     args = ap.parse_args()
@@ -115,12 +121,15 @@ def main() -> int:
     out = torch.empty((B, D), dtype=torch.float32, device=dev)
     emb = TTEmbedding(w.n, w.d, w.r, B, cores, device=dev)
 
+    lr = w.lr if args.restore else args.lr
+
     def step():
-        flat.copy_(snapshot)
+        if args.restore:
+            flat.copy_(snapshot)
         if not args.no_prepare:
             emb.prepare(ids)        # index pipeline of the NEXT step, overlapped with this step
         emb.forward(ids, out)
-        emb.backward_update(grad, w.lr)
+        emb.backward_update(grad, lr)
 
     if not args.no_prepare:
         emb.prepare(ids)            # the first step's own index work
@@ -133,10 +142,15 @@ def main() -> int:
     t0 = time.perf_counter()
     for _ in range(args.steps):
         step()
+    t_enq = time.perf_counter()     # host side done: every launch of the timed steps is enqueued
     torch.cuda.synchronize()
     t1 = time.perf_counter()
     ms_per_step = (t1 - t0) * 1e3 / args.steps
+    host_ms_per_step = (t_enq - t0) * 1e3 / args.steps
     rows_per_s = B / (ms_per_step * 1e-3)
+    if not bool(torch.isfinite(flat).all()) or not bool(torch.isfinite(out).all()):
+        print("bench.py: cores or rows overflowed during the timed steps", file=sys.stderr)
+        return 4
 
     # untimed leg: per-kernel durations from HIP events recorded on the launch stream
     prof = {}
@@ -164,6 +178,9 @@ def main() -> int:
         by, fl = kernel_work(name, w, B, U, Q, touched_bytes, 0)
         if name == "u_bwd" and prof.get("dg3", {}).get("launches", 0) == 0:
             fl *= 2          # matrix-core shapes: dPsum and the dG3 partials share one launch
+            if prof.get("prefix_bwd", {}).get("launches", 0) == 0:
+                # ranks up to 32: the prefix-level gradients are formed in that launch too
+                fl += kernel_work("prefix_bwd", w, B, U, Q, touched_bytes, 0)[1]
         kernels[name] = {"us_per_step": round(per_step_us, 2), "launches_per_step": launches,
                          "alg_bytes": int(by), "alg_flops": int(fl)}
     if not kernels:          # --profile-steps 0: no per-kernel leg (used under an external profiler)
@@ -185,7 +202,7 @@ def main() -> int:
                     "peak": HBM_PEAK / 1e9, "unit": "GB/s", "frac": by / launch_s / HBM_PEAK,
                     "traffic": None}
     else:
-        roofline = {"kernel": dom, "bound": "alu", "achieved": fl / launch_s / 1e12,
+        roofline = {"kernel": dom, "bound": "mfma", "achieved": fl / launch_s / 1e12,
                     "peak": FP32_PEAK / 1e12, "unit": "TFLOP/s", "frac": fl / launch_s / FP32_PEAK,
                     "traffic": None}
     roofline["avg_launch_us"] = round(launch_s * 1e6, 2)
@@ -221,10 +238,11 @@ def main() -> int:
     line = {
         "metric": "TT-embedding rows/s (fwd+bwd+update)", "value": rows_per_s, "unit": "rows/s",
         "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": ms_per_step,
-        "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "f32",
+        "host_enqueue_ms_per_step": host_ms_per_step, "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "f32",
         "data": "synthetic",
         "config": {"workload": w.name, "N": w.N, "n": list(w.n), "d": list(w.d), "ranks": list(w.r),
-                   "batch": B, "ids": w.ids, "zipf_s": w.zipf_s, "seed": seed, "lr": w.lr,
+                   "batch": B, "ids": w.ids, "zipf_s": w.zipf_s, "seed": seed, "lr": lr,
+                   "protocol": "restore_each_step" if args.restore else "small_lr_no_restore",
                    "next_batch_index_overlap": not args.no_prepare,
                    "U": U, "Q": Q, "max_multiplicity": struct["max_multiplicity"]},
         "roofline": roofline, "cpu_baseline": cpu, "path_roofline": path, "kernels": kernels,
