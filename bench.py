@@ -34,11 +34,11 @@ HBM_PEAK = 8.0e12        # bytes/s, MI355X HBM3E
 FP32_PEAK = 157.3e12     # flop/s, MI355X fp32 (vector with packed ops, or fp32 MFMA)
 
 # Bytes beyond L2 per launch (fetched + written), from two `rocprofv3 --pmc` runs (FETCH_SIZE,
-# WRITE_SIZE) scaled by the readings for the 2,380 KiB core-restore copy of the same process; the
-# table and the commands are in profiles/step_config3_hbm_traffic.md.  Only the default workload was
+# WRITE_SIZE) scaled by the readings for a plain 256 MiB device copy in the same process; the table
+# and the commands are in profiles/step_config3_hbm_traffic.md.  Only the default workload was
 # measured; for anything else `traffic` is null.
-MEASURED_TRAFFIC = {3: {"row_fwd": 41.0e6 + 102.4e6, "gsum": 84.5e6 + 4.8e6, "u_bwd": 153.4e6 + 29.8e6,
-                        "prefix_fwd": 10.3e6 + 34.8e6, "sgd": 32.0e6 + 2.4e6}}
+MEASURED_TRAFFIC = {3: {"row_fwd": 41.0e6 + 102.4e6, "gsum": 85.4e6 + 4.8e6, "u_bwd": 155.0e6 + 29.8e6,
+                        "prefix_fwd": 10.4e6 + 34.8e6, "sgd": 32.4e6 + 2.4e6}}
 
 
 def kernel_work(slot: str, w, B: int, U: int, Q: int, touched_bytes: int, passes: int):
@@ -81,6 +81,9 @@ def main() -> int:
                     help="workload learning rate, cores restored from a snapshot every step")
     ap.add_argument("--lr", type=float, default=1e-8,
                     help="learning rate of the timed steps (ignored with --restore)")
+    ap.add_argument("--calib-copy-mib", type=int, default=0,
+                    help="also run one plain device copy of this many MiB (known traffic, to scale "
+                         "a profiler's HBM counters)")
     ap.add_argument("--no-prepare", action="store_true",
                     help="do not overlap the next step's index work with this step's backward")
     args = ap.parse_args()
@@ -131,6 +134,13 @@ def main() -> int:
         emb.forward(ids, out)
         emb.backward_update(grad, lr)
 
+    if args.calib_copy_mib > 0:
+        src = torch.ones(args.calib_copy_mib << 18, dtype=torch.float32, device=dev)
+        dst = torch.empty_like(src)
+        torch.cuda.synchronize()
+        dst.copy_(src)              # one copy kernel that reads and writes calib_copy_mib MiB
+        torch.cuda.synchronize()
+        del src, dst
     if not args.no_prepare:
         emb.prepare(ids)            # the first step's own index work
     for _ in range(args.warmup):
@@ -170,11 +180,15 @@ def main() -> int:
                          + np.unique((ok // n3) % n2).size * r1 * d2 * r2
                          + np.unique(ok % n3).size * r2 * d3)
     kernels = {}
+    # what a HIP event pair adds by itself (measured with nothing between the two events) is taken
+    # off every launch, so that the durations are the kernels' own, as a profiler would report them
+    ep = prof.pop("event_pair", {"launches": 0, "ms": 0.0})
+    pair_us = ep["ms"] * 1e3 / ep["launches"] if ep["launches"] else 0.0
     for name, rec in prof.items():
         if rec["launches"] == 0:
             continue
-        per_step_us = rec["ms"] * 1e3 / max(args.profile_steps, 1)
         launches = rec["launches"] / max(args.profile_steps, 1)
+        per_step_us = max(rec["ms"] * 1e3 / max(args.profile_steps, 1) - pair_us * launches, 0.0)
         by, fl = kernel_work(name, w, B, U, Q, touched_bytes, 0)
         if name == "u_bwd" and prof.get("dg3", {}).get("launches", 0) == 0:
             fl *= 2          # matrix-core shapes: dPsum and the dG3 partials share one launch
@@ -206,6 +220,7 @@ def main() -> int:
                     "peak": FP32_PEAK / 1e12, "unit": "TFLOP/s", "frac": fl / launch_s / FP32_PEAK,
                     "traffic": None}
     roofline["avg_launch_us"] = round(launch_s * 1e6, 2)
+    roofline["event_pair_us"] = round(pair_us, 2)     # already subtracted from avg_launch_us
     if args.seed is None:
         roofline["traffic"] = MEASURED_TRAFFIC.get(args.config, {}).get(dom)
 
@@ -224,16 +239,28 @@ def main() -> int:
     if not args.no_cpu_baseline:
         from oracle import tt_oracle as ora
         s = ora.Shape(w.n, w.d, w.r)
-        sample = min(B, {1: 256, 2: 50_000, 3: 40_000, 4: 100_000, 5: 10_000}[args.config])
-        ora.forward(s, *cores_np, ids_np[:256], tag="f32")          # loads the library
+
+        def oracle_step(rows):
+            ora.forward(s, *cores_np, ids_np[:rows], tag="f32")
+            ora.backward_update(s, *cores_np, ids_np[:rows], grad_np[:rows], w.lr, tag="f32")
+
+        oracle_step(256)                                   # loads the library
+        probe = min(B, 20_000)
         c0 = time.perf_counter()
-        ora.forward(s, *cores_np, ids_np[:sample], tag="f32")
-        ora.backward_update(s, *cores_np, ids_np[:sample], grad_np[:sample], w.lr, tag="f32")
+        oracle_step(probe)
+        rate = probe / (time.perf_counter() - c0)          # rows/s, all host threads
+        # about one second of wall time on all host threads, i.e. 10-30 s of CPU work
+        want = max(int(rate * 1.2), probe)
+        reps, rows = (max(1, round(want / B)), B) if want >= B else (1, want)
+        c0 = time.perf_counter()
+        for _ in range(reps):
+            oracle_step(rows)
         c1 = time.perf_counter()
-        cpu = {"value": sample / (c1 - c0), "unit": "rows/s", "cores": ora.threads("f32"),
+        what = (f"the whole batch, {reps} time(s)" if rows == B else f"first {rows} rows of the batch")
+        cpu = {"value": reps * rows / (c1 - c0), "unit": "rows/s", "cores": ora.threads("f32"),
                "kind": "oracle",
-               "sample": f"first {sample} rows of the same batch, fp32 OpenMP build of the oracle, "
-                         f"forward + backward + update, {c1 - c0:.2f} s"}
+               "sample": f"{what}: fp32 OpenMP build of the oracle, forward + backward + update, "
+                         f"{c1 - c0:.2f} s wall on {ora.threads('f32')} threads"}
 
     line = {
         "metric": "TT-embedding rows/s (fwd+bwd+update)", "value": rows_per_s, "unit": "rows/s",

@@ -131,6 +131,8 @@ int tt_emb_get_stats(tt_emb_t h, int64_t* U, int64_t* Q, int64_t* out_of_range);
  * measurement).  tt_emb_profile_read synchronises, then reports for kernel slot k (0 <= k < n,
  * n = return value of tt_emb_profile_slots) its name, the number of launches and their summed
  * duration in milliseconds since profiling was enabled or last read; it then resets the sums.
+ * The last slot, "event_pair", is an event pair with no launch between, recorded once per
+ * backward_update: its average is what the bracketing itself adds to every other slot.
  */
 int tt_emb_profile_enable(tt_emb_t h, int enable);
 int tt_emb_profile_slots(void);

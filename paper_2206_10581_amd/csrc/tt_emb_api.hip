@@ -49,7 +49,7 @@ void launch_gsum_block_fix(const Plan&, const Workspace&, int B, hipStream_t);
 static const char* const kSlotNames[kSlotCount] = {
     "sort_hist", "sort_scan", "sort_scatter", "seg_count", "seg_write",  "group_scan", "group",
     "prefix_fwd", "row_fwd",  "gsum",         "gsum_fix",  "u_bwd",      "dg3",        "prefix_bwd",
-    "sgd"};
+    "sgd",        "event_pair"};
 
 static thread_local std::string g_hip_error = "HIP call failed";
 
@@ -529,6 +529,8 @@ int tt_emb_backward_update(tt_emb_t h, const float* grad_out, float lr, void* hi
     if (rc) return rc;
   }
   rc = run_slot(h, kSlotSgd, st, [&] { launch_sgd(pl, ws, h->g1, h->g2, h->g3, lr, st); });
+  if (rc) return rc;
+  if (h->profiling) rc = run_slot(h, kSlotEventPair, st, [] {});
   return rc;
 }
 

@@ -132,6 +132,7 @@ enum KernelSlot {
   kSlotDg3,
   kSlotPrefixBwd,
   kSlotSgd,
+  kSlotEventPair,  // an event pair with nothing between: the cost the timing itself adds to a slot
   kSlotCount
 };
 
