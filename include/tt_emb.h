@@ -91,6 +91,31 @@ int tt_emb_create(tt_emb_t* out, const tt_emb_config* cfg, float* g1, float* g2,
 int tt_emb_forward(tt_emb_t h, const int64_t* ids, int64_t B, float* out, void* hip_stream);
 
 /*
+ * Lookup only (evaluation, inference): as tt_emb_forward, but the batch does not stay pending, so no
+ * backward_update can follow it.  Returns TT_EMB_ESTATE while a forward is pending (its cached
+ * products share the workspace).
+ */
+int tt_emb_forward_eval(tt_emb_t h, const int64_t* ids, int64_t B, float* out, void* hip_stream);
+
+/*
+ * Writes the rows first_row .. first_row+count-1 of the table W itself (Section 3, Eq. "tt-matrix":
+ * the dense matrix the cores stand for) to out, device fp32[count][D]; count may exceed max_batch
+ * (the rows are produced max_batch at a time).  Row numbers are table rows: a re-indexing table is
+ * not applied.  0 <= first_row, first_row + count <= N.  TT_EMB_ESTATE while a forward is pending.
+ */
+int tt_emb_materialize(tt_emb_t h, int64_t first_row, int64_t count, float* out, void* hip_stream);
+
+/*
+ * Node re-indexing (Section 4.2: nodes are renumbered, e.g. by graph partition, so that nodes that
+ * are drawn together get neighbouring table rows and share (i1,i2) prefixes).  new_id_of: device
+ * int32[n_ids], borrowed until replaced or the handle is destroyed; every later prepare / forward /
+ * forward_eval looks up row new_id_of[id] for id in [0, n_ids) and treats any other id, and any
+ * entry outside [0, N), as out of range.  new_id_of = NULL (n_ids = 0) removes the table.  Host-only;
+ * prepared batches are dropped.  TT_EMB_ESTATE while a forward is pending.
+ */
+int tt_emb_set_reindex(tt_emb_t h, const int32_t* new_id_of, int64_t n_ids);
+
+/*
  * Optional: builds the index structures (split, sort, unique ids and prefixes: the part of
  * Section 4.2's sharing that depends on the ids only) of a COMING batch ahead of time, on a stream
  * of the library's own that starts once everything enqueued so far on hip_stream has run.  A later

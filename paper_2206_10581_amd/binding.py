@@ -50,6 +50,9 @@ def load_library():
                                   c_size_t]
     lib.tt_emb_forward.argtypes = [c_void_p, c_void_p, c_int64, c_void_p, c_void_p]
     lib.tt_emb_backward_update.argtypes = [c_void_p, c_void_p, c_float, c_void_p]
+    lib.tt_emb_forward_eval.argtypes = [c_void_p, c_void_p, c_int64, c_void_p, c_void_p]
+    lib.tt_emb_materialize.argtypes = [c_void_p, c_int64, c_int64, c_void_p, c_void_p]
+    lib.tt_emb_set_reindex.argtypes = [c_void_p, c_void_p, c_int64]
     lib.tt_emb_prepare.argtypes = [c_void_p, c_void_p, c_int64, c_void_p]
     lib.tt_emb_get_stats.argtypes = [c_void_p, POINTER(c_int64), POINTER(c_int64), POINTER(c_int64)]
     lib.tt_emb_profile_enable.argtypes = [c_void_p, c_int]
@@ -60,7 +63,8 @@ def load_library():
     lib.tt_emb_strerror.argtypes = [c_int]
     lib.tt_emb_strerror.restype = c_char_p
     for name in ("tt_emb_workspace_bytes", "tt_emb_create", "tt_emb_forward", "tt_emb_prepare",
-                 "tt_emb_backward_update", "tt_emb_get_stats", "tt_emb_profile_enable",
+                 "tt_emb_backward_update", "tt_emb_forward_eval", "tt_emb_materialize",
+                 "tt_emb_set_reindex", "tt_emb_get_stats", "tt_emb_profile_enable",
                  "tt_emb_profile_slots", "tt_emb_profile_read", "tt_emb_destroy"):
         getattr(lib, name).restype = c_int
     _lib = lib
@@ -99,6 +103,20 @@ def tt_emb_create(cfg: TTEmbConfig, g1_ptr: int, g2_ptr: int, g3_ptr: int, ws_pt
 def tt_emb_forward(h, ids_ptr: int, B: int, out_ptr: int, stream: int) -> int:
     return load_library().tt_emb_forward(h, c_void_p(ids_ptr), c_int64(B), c_void_p(out_ptr),
                                          c_void_p(stream))
+
+
+def tt_emb_forward_eval(h, ids_ptr: int, B: int, out_ptr: int, stream: int) -> int:
+    return load_library().tt_emb_forward_eval(h, c_void_p(ids_ptr), c_int64(B), c_void_p(out_ptr),
+                                              c_void_p(stream))
+
+
+def tt_emb_materialize(h, first_row: int, count: int, out_ptr: int, stream: int) -> int:
+    return load_library().tt_emb_materialize(h, c_int64(first_row), c_int64(count),
+                                             c_void_p(out_ptr), c_void_p(stream))
+
+
+def tt_emb_set_reindex(h, table_ptr: int, n_ids: int) -> int:
+    return load_library().tt_emb_set_reindex(h, c_void_p(table_ptr), c_int64(n_ids))
 
 
 def tt_emb_prepare(h, ids_ptr: int, B: int, stream: int) -> int:
@@ -184,6 +202,48 @@ class TTEmbedding:
         if rc:
             raise TTEmbError(rc, "tt_emb_forward")
         return out
+
+    def forward_eval(self, ids, out=None):
+        """Lookup without keeping anything for a backward pass."""
+        torch = self.torch
+        assert ids.dtype == torch.int64 and ids.is_contiguous() and ids.device == self.device
+        B = ids.numel()
+        if out is None:
+            out = torch.empty((B, self.D), dtype=torch.float32, device=self.device)
+        assert out.is_contiguous() and out.shape == (B, self.D) and out.dtype == torch.float32
+        rc = tt_emb_forward_eval(self.handle, ids.data_ptr() if B else 0, B,
+                                 out.data_ptr() if B else 0, self._stream())
+        if rc:
+            raise TTEmbError(rc, "tt_emb_forward_eval")
+        return out
+
+    def materialize(self, first_row: int = 0, count: int | None = None, out=None):
+        """Rows first_row .. first_row+count-1 of the dense table the cores define."""
+        torch = self.torch
+        N = self.n[0] * self.n[1] * self.n[2]
+        count = N - first_row if count is None else count
+        if out is None:
+            out = torch.empty((count, self.D), dtype=torch.float32, device=self.device)
+        assert out.is_contiguous() and out.shape == (count, self.D) and out.dtype == torch.float32
+        rc = tt_emb_materialize(self.handle, first_row, count, out.data_ptr() if count else 0,
+                                self._stream())
+        if rc:
+            raise TTEmbError(rc, "tt_emb_materialize")
+        return out
+
+    def set_reindex(self, new_id_of):
+        """Installs (or, with None, removes) an old-id -> table-row table: device int32 tensor."""
+        torch = self.torch
+        if new_id_of is None:
+            self._reindex = None
+            rc = tt_emb_set_reindex(self.handle, 0, 0)
+        else:
+            assert new_id_of.dtype == torch.int32 and new_id_of.is_contiguous()
+            assert new_id_of.device == self.device
+            self._reindex = new_id_of          # keeps the borrowed table alive
+            rc = tt_emb_set_reindex(self.handle, new_id_of.data_ptr(), new_id_of.numel())
+        if rc:
+            raise TTEmbError(rc, "tt_emb_set_reindex")
 
     def prepare(self, ids):
         """Index work of the next batch, overlapped with whatever follows on the current stream."""

@@ -11,7 +11,7 @@
 namespace ttemb {
 
 // launchers defined next to their kernels
-void launch_sort_pass(const Plan&, const Workspace&, const int64_t* ids, int B, int pass, hipStream_t,
+void launch_sort_pass(const Plan&, const Workspace&, const IdSource& src, int B, int pass, hipStream_t,
                       int which);
 void launch_seg_count(const Plan&, const Workspace&, int B, hipStream_t);
 void launch_seg_write(const Plan&, const Workspace&, int B, hipStream_t);
@@ -204,6 +204,8 @@ struct tt_emb {
   Workspace ws[2];    // two index sets over shared arithmetic buffers
   int cur;            // set of the latest forward (and of the backward that follows it)
   float *g1, *g2, *g3;
+  const int32_t* reindex;  // old id -> table row applied in front of the split, or nullptr
+  int64_t reindex_n;
   int64_t pending_B;  // -1: no forward pending
   int64_t last_B;     // batch size of the latest forward
   bool have_forward;
@@ -310,6 +312,8 @@ int tt_emb_create(tt_emb_t* out, const tt_emb_config* cfg, float* g1, float* g2,
   h->g1 = g1;
   h->g2 = g2;
   h->g3 = g3;
+  h->reindex = nullptr;
+  h->reindex_n = 0;
   h->pending_B = -1;
   h->last_B = 0;
   h->have_forward = false;
@@ -328,16 +332,16 @@ int tt_emb_create(tt_emb_t* out, const tt_emb_config* cfg, float* g1, float* g2,
 }
 
 // Index pipeline of one batch into index set `set`, on stream st.
-static int run_index(tt_emb* h, int set, const int64_t* ids, int B, hipStream_t st) {
+static int run_index(tt_emb* h, int set, const IdSource& src, int B, hipStream_t st) {
   const Plan& pl = h->plan;
   const Workspace& ws = h->ws[set];
   int rc;
   for (int pass = 0; pass < pl.passes; ++pass) {
-    rc = run_slot(h, kSlotSortHist, st, [&] { launch_sort_pass(pl, ws, ids, B, pass, st, 0); });
+    rc = run_slot(h, kSlotSortHist, st, [&] { launch_sort_pass(pl, ws, src, B, pass, st, 0); });
     if (rc) return rc;
-    rc = run_slot(h, kSlotSortScan, st, [&] { launch_sort_pass(pl, ws, ids, B, pass, st, 2); });
+    rc = run_slot(h, kSlotSortScan, st, [&] { launch_sort_pass(pl, ws, src, B, pass, st, 2); });
     if (rc) return rc;
-    rc = run_slot(h, kSlotSortScatter, st, [&] { launch_sort_pass(pl, ws, ids, B, pass, st, 1); });
+    rc = run_slot(h, kSlotSortScatter, st, [&] { launch_sort_pass(pl, ws, src, B, pass, st, 1); });
     if (rc) return rc;
   }
   rc = run_slot(h, kSlotSegCount, st, [&] { launch_seg_count(pl, ws, B, st); });
@@ -384,7 +388,7 @@ int tt_emb_prepare(tt_emb_t h, const int64_t* ids, int64_t B64, void* hip_stream
   if (e != hipSuccess) return hip_fail(e);
   e = hipStreamWaitEvent(h->side, h->ev_fork, 0);
   if (e != hipSuccess) return hip_fail(e);
-  int rc = run_index(h, target, ids, (int)B64, h->side);
+  int rc = run_index(h, target, IdSource{ids, 0, h->reindex, h->reindex_n}, (int)B64, h->side);
   if (rc) return rc;
   e = hipEventRecord(h->prep[target].ready, h->side);
   if (e != hipSuccess) return hip_fail(e);
@@ -395,18 +399,20 @@ int tt_emb_prepare(tt_emb_t h, const int64_t* ids, int64_t B64, void* hip_stream
   return TT_EMB_OK;
 }
 
-int tt_emb_forward(tt_emb_t h, const int64_t* ids, int64_t B64, float* out, void* hip_stream) {
-  if (h == nullptr || B64 < 0) return TT_EMB_EINVAL;
-  if (B64 > h->plan.maxB) return TT_EMB_ENOSPC;
-  hipStream_t st = (hipStream_t)hip_stream;
+}  // extern "C"
+
+// Forward of one batch whose ids come from src (a device array, or consecutive table rows).  With
+// arm set the batch stays pending for backward_update.
+static int forward_impl(tt_emb* h, const IdSource& src, int64_t B64, float* out, hipStream_t st,
+                        bool arm) {
+  const int64_t* ids = src.ids;
   h->last_stream = st;
   if (B64 == 0) {
-    h->pending_B = 0;
+    h->pending_B = arm ? 0 : -1;
     h->have_forward = false;
     return TT_EMB_OK;
   }
-  if (ids == nullptr || out == nullptr) return TT_EMB_EINVAL;
-  if (((uintptr_t)out & 15u) != 0 || ((uintptr_t)ids & 7u) != 0) return TT_EMB_EINVAL;
+  if (out == nullptr || ((uintptr_t)out & 15u) != 0) return TT_EMB_EINVAL;
   const int B = (int)B64;
   const Plan& pl = h->plan;
   h->pending_B = -1;
@@ -414,7 +420,7 @@ int tt_emb_forward(tt_emb_t h, const int64_t* ids, int64_t B64, float* out, void
   // oldest prepared batch with these ids and this size, if any
   int found = -1;
   for (int s = 0; s < 2; ++s)
-    if (h->prep[s].valid && h->prep[s].ids == ids && h->prep[s].B == B64 &&
+    if (ids != nullptr && h->prep[s].valid && h->prep[s].ids == ids && h->prep[s].B == B64 &&
         (found < 0 || h->prep[s].seq < h->prep[found].seq))
       found = s;
   if (found >= 0) {
@@ -437,7 +443,7 @@ int tt_emb_forward(tt_emb_t h, const int64_t* ids, int64_t B64, float* out, void
       if (e != hipSuccess) return hip_fail(e);
     }
     h->cur = target;
-    rc = run_index(h, h->cur, ids, B, st);
+    rc = run_index(h, h->cur, src, B, st);
     if (rc) return rc;
   }
   const Workspace& ws = h->ws[h->cur];
@@ -451,9 +457,53 @@ int tt_emb_forward(tt_emb_t h, const int64_t* ids, int64_t B64, float* out, void
     else launch_row_fwd(pl, ws, h->g3, B, out, st);
   });
   if (rc) return rc;
-  h->pending_B = B;
+  h->pending_B = arm ? B : -1;
   h->last_B = B;
   h->have_forward = true;
+  return TT_EMB_OK;
+}
+
+extern "C" {
+
+int tt_emb_forward(tt_emb_t h, const int64_t* ids, int64_t B64, float* out, void* hip_stream) {
+  if (h == nullptr || B64 < 0) return TT_EMB_EINVAL;
+  if (B64 > h->plan.maxB) return TT_EMB_ENOSPC;
+  if (B64 > 0 && (ids == nullptr || ((uintptr_t)ids & 7u) != 0)) return TT_EMB_EINVAL;
+  return forward_impl(h, IdSource{ids, 0, h->reindex, h->reindex_n}, B64, out,
+                      (hipStream_t)hip_stream, true);
+}
+
+int tt_emb_forward_eval(tt_emb_t h, const int64_t* ids, int64_t B64, float* out, void* hip_stream) {
+  if (h == nullptr || B64 < 0) return TT_EMB_EINVAL;
+  if (B64 > h->plan.maxB) return TT_EMB_ENOSPC;
+  if (B64 > 0 && (ids == nullptr || ((uintptr_t)ids & 7u) != 0)) return TT_EMB_EINVAL;
+  if (h->pending_B >= 0) return TT_EMB_ESTATE;  // would overwrite what the pending backward needs
+  return forward_impl(h, IdSource{ids, 0, h->reindex, h->reindex_n}, B64, out,
+                      (hipStream_t)hip_stream, false);
+}
+
+int tt_emb_materialize(tt_emb_t h, int64_t first_row, int64_t count, float* out, void* hip_stream) {
+  if (h == nullptr || first_row < 0 || count < 0) return TT_EMB_EINVAL;
+  if (first_row + count > (int64_t)h->plan.sh.N) return TT_EMB_EINVAL;
+  if (count > 0 && out == nullptr) return TT_EMB_EINVAL;
+  if (h->pending_B >= 0) return TT_EMB_ESTATE;  // would overwrite what the pending backward needs
+  const int64_t D = h->plan.sh.D;
+  for (int64_t off = 0; off < count; off += h->plan.maxB) {
+    const int64_t nb = std::min<int64_t>(h->plan.maxB, count - off);
+    int rc = forward_impl(h, IdSource{nullptr, first_row + off, nullptr, 0}, nb, out + off * D,
+                          (hipStream_t)hip_stream, false);
+    if (rc) return rc;
+  }
+  return TT_EMB_OK;
+}
+
+int tt_emb_set_reindex(tt_emb_t h, const int32_t* new_id_of, int64_t n_ids) {
+  if (h == nullptr || n_ids < 0 || (new_id_of == nullptr && n_ids != 0)) return TT_EMB_EINVAL;
+  if (new_id_of != nullptr && ((uintptr_t)new_id_of & 3u) != 0) return TT_EMB_EINVAL;
+  if (h->pending_B >= 0) return TT_EMB_ESTATE;  // between a forward and its backward_update
+  h->reindex = new_id_of;
+  h->reindex_n = new_id_of != nullptr ? n_ids : 0;
+  for (int i = 0; i < 2; ++i) h->prep[i].valid = false;  // prepared batches used the old table
   return TT_EMB_OK;
 }
 

@@ -15,7 +15,14 @@
 
 namespace ttemb {
 
-__device__ __forceinline__ uint32_t key_of_id(int64_t id, uint32_t N) {
+__device__ __forceinline__ uint32_t key_of_id(const IdSource& src, int idx, uint32_t N) {
+  int64_t id = src.ids != nullptr ? src.ids[idx] : src.base + idx;
+  if (src.reindex != nullptr) {
+    // node re-indexing (paper Section 4.2: ids renumbered so that a partition's nodes are
+    // consecutive): one gather in front of the split
+    if ((uint64_t)id >= (uint64_t)src.n_ids) return N;
+    id = src.reindex[id];
+  }
   // ids outside [0, N) (negative ones included) become the sentinel N and sort to the end
   return ((uint64_t)id < (uint64_t)N) ? (uint32_t)id : N;
 }
@@ -248,7 +255,7 @@ template <bool FROM_IDS>
 struct SortOps {
   using Item = KV;
   static constexpr bool kChunked = false;
-  const int64_t* ids;
+  IdSource src;
   const uint32_t* kin;
   const uint32_t* vin;
   uint32_t* kout;
@@ -257,7 +264,7 @@ struct SortOps {
   int shift;
   uint32_t mask;
   __device__ Item load(int idx) const {
-    if (FROM_IDS) return KV{key_of_id(ids[idx], N), (uint32_t)idx};
+    if (FROM_IDS) return KV{key_of_id(src, idx, N), (uint32_t)idx};
     return KV{kin[idx], vin[idx]};
   }
   __device__ int digit(Item it) const { return (int)((it.key >> shift) & mask); }
@@ -272,7 +279,7 @@ struct SortOps {
 // them).  The first pass also clears the tables that later kernels of the same forward add into.
 template <bool FROM_IDS>
 __global__ __launch_bounds__(kSortThreads) void k_sort_hist(
-    const int64_t* __restrict__ ids, const uint32_t* __restrict__ kin, int B, uint32_t N, int shift,
+    IdSource src, const uint32_t* __restrict__ kin, int B, uint32_t N, int shift,
     int bits, uint32_t* __restrict__ cnt, uint32_t* zero_a, int zero_a_n, uint32_t* zero_b,
     int zero_b_n, uint32_t* zero_c, int zero_c_n, Counters* ctr) {
   __shared__ uint32_t h[kMaxBins];
@@ -285,7 +292,7 @@ __global__ __launch_bounds__(kSortThreads) void k_sort_hist(
   for (int step = 0; step < kSteps; ++step) {
     const int idx = wbase + step * kWave + lane;
     const int ic = min(idx, B - 1);
-    keys[step] = FROM_IDS ? key_of_id(ids[ic], N) : kin[ic];
+    keys[step] = FROM_IDS ? key_of_id(src, ic, N) : kin[ic];
   }
   __builtin_amdgcn_sched_barrier(0);  // keep the loads together: their latencies overlap
   if (FROM_IDS) {
@@ -582,7 +589,7 @@ __global__ __launch_bounds__(kSortThreads) void k_group(
 
 static inline int cdiv(int64_t a, int64_t b) { return (int)((a + b - 1) / b); }
 
-void launch_sort_pass(const Plan& pl, const Workspace& ws, const int64_t* ids, int B, int pass,
+void launch_sort_pass(const Plan& pl, const Workspace& ws, const IdSource& src, int B, int pass,
                       hipStream_t st, int which /*0 = histogram, 1 = scatter, 2 = column scan*/) {
   const int blocks = cdiv(B, kSortItems);
   const int shift = pass * pl.bitsPerPass;
@@ -596,20 +603,20 @@ void launch_sort_pass(const Plan& pl, const Workspace& ws, const int64_t* ids, i
   if (pass == 0) {
     if (which == 0) {
       k_sort_hist<true><<<blocks, kSortThreads, 0, st>>>(
-          ids, nullptr, B, N, shift, bits, ws.cnt, ws.cnt3, pl.uBlocksMax * (int)pl.sh.n3, ws.cnt2,
+          src, nullptr, B, N, shift, bits, ws.cnt, ws.cnt3, pl.uBlocksMax * (int)pl.sh.n3, ws.cnt2,
           pl.qBlocksMax * (int)pl.sh.n2, (uint32_t*)ws.g1_first, 2 * (int)pl.sh.n1, ws.ctr);
     } else {
-      SortOps<true> ops{ids, nullptr, nullptr, ws.key[0], ws.val[0], N, shift, (1u << bits) - 1u};
+      SortOps<true> ops{src, nullptr, nullptr, ws.key[0], ws.val[0], N, shift, (1u << bits) - 1u};
       k_sort_scatter<true><<<blocks, kSortThreads, 0, st>>>(ops, B, bits, ws.cnt, ws.tot);
     }
   } else {
-    const int src = (pass - 1) & 1, dst = pass & 1;
+    const int from = (pass - 1) & 1, dst = pass & 1;
     if (which == 0) {
-      k_sort_hist<false><<<blocks, kSortThreads, 0, st>>>(nullptr, ws.key[src], B, N, shift, bits,
+      k_sort_hist<false><<<blocks, kSortThreads, 0, st>>>(IdSource{}, ws.key[from], B, N, shift, bits,
                                                           ws.cnt, nullptr, 0, nullptr, 0, nullptr, 0,
                                                           ws.ctr);
     } else {
-      SortOps<false> ops{nullptr, ws.key[src], ws.val[src], ws.key[dst], ws.val[dst], N, shift,
+      SortOps<false> ops{IdSource{}, ws.key[from], ws.val[from], ws.key[dst], ws.val[dst], N, shift,
                          (1u << bits) - 1u};
       k_sort_scatter<false><<<blocks, kSortThreads, 0, st>>>(ops, B, bits, ws.cnt, ws.tot);
     }

@@ -28,6 +28,14 @@ constexpr int kTileSlots = 32;   // sorted slots per wavefront tile in the row k
 constexpr int kChunk3 = TT_CHUNK3;  // unique ids per partial sum of a G3 slice gradient
 constexpr int kChunk2 = 16;      // unique prefixes per partial sum of a G2 slice gradient
 
+// Where the ids of a batch come from, passed to the first sort pass by value.
+struct IdSource {
+  const int64_t* ids;      // device [B]; nullptr: the consecutive ids base, base+1, ...
+  int64_t base;
+  const int32_t* reindex;  // device [n_ids] old id -> table row, or nullptr (ids are table rows)
+  int64_t n_ids;
+};
+
 // Table and slice geometry, passed to kernels by value.
 struct Shape {
   uint32_t n1, n2, n3, N;  // node factors and N = n1*n2*n3

@@ -69,6 +69,22 @@ def test_handle_state_machine_without_launches(lib):
     assert lib.tt_emb_get_stats(h) == (0, 0, 0, 0)
     assert lib.tt_emb_backward_update(h, 0, 0.01, 0) == 0         # consumes the empty forward
     assert lib.tt_emb_backward_update(h, 0, 0.01, 0) == TT_EMB_ESTATE
+    # lookup-only calls and the re-indexing table: argument checks and the pending-forward rule
+    assert lib.tt_emb_forward_eval(h, 256, 9, 256, 0) == TT_EMB_ENOSPC
+    assert lib.tt_emb_forward_eval(h, 0, 0, 0, 0) == 0
+    assert lib.tt_emb_backward_update(h, 0, 0.01, 0) == TT_EMB_ESTATE   # eval leaves nothing pending
+    assert lib.tt_emb_materialize(h, 0, 0, 0, 0) == 0
+    assert lib.tt_emb_materialize(h, -1, 1, 256, 0) == TT_EMB_EINVAL
+    assert lib.tt_emb_materialize(h, 999, 2, 256, 0) == TT_EMB_EINVAL   # past the 1000-row table
+    assert lib.tt_emb_set_reindex(h, 0, 5) == TT_EMB_EINVAL
+    assert lib.tt_emb_set_reindex(h, 258, 5) == TT_EMB_EINVAL           # misaligned int32 table
+    assert lib.tt_emb_set_reindex(h, 256, 5) == 0
+    assert lib.tt_emb_set_reindex(h, 0, 0) == 0
+    assert lib.tt_emb_forward(h, 0, 0, 0, 0) == 0
+    assert lib.tt_emb_forward_eval(h, 0, 0, 0, 0) == TT_EMB_ESTATE      # a forward is pending
+    assert lib.tt_emb_materialize(h, 0, 0, 0, 0) == TT_EMB_ESTATE
+    assert lib.tt_emb_set_reindex(h, 256, 5) == TT_EMB_ESTATE
+    assert lib.tt_emb_backward_update(h, 0, 0.01, 0) == 0
     assert lib.tt_emb_profile_slots() >= 10
     assert lib.tt_emb_profile_read(h, 0)[0] == 0 and lib.tt_emb_profile_read(h, 999)[0] == TT_EMB_EINVAL
     assert lib.tt_emb_destroy(h) == 0

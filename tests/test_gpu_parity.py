@@ -327,6 +327,82 @@ def test_prepare_pipeline_matches_oracle_over_three_steps():
     emb.close()
 
 
+def test_lookup_only_calls_and_dense_materialisation():
+    """forward_eval gives the rows of forward and arms no backward; materialize writes the dense
+    table the cores define (all of config 1's 1000 rows, and a window of a rank-32 table that is
+    longer than max_batch, so it is produced in several pieces)."""
+    torch = _torch()
+    from paper_2206_10581_amd import TTEmbedding
+    from paper_2206_10581_amd.binding import TTEmbError, TT_EMB_ESTATE
+    w, cores, ids, grad = _workload(1)
+    s = Shape(w.n, w.d, w.r)
+    emb = TTEmbedding(w.n, w.d, w.r, 256, cores)
+    t_ids = torch.from_numpy(ids).cuda()
+    out = emb.forward_eval(t_ids)
+    assert row_error(out.cpu().numpy(), ora.forward(s, *cores, ids)) <= ROW_TOL
+    with pytest.raises(TTEmbError) as e:
+        emb.backward_update(torch.from_numpy(grad).cuda(), w.lr)
+    assert e.value.code == TT_EMB_ESTATE
+    table = emb.materialize().cpu().numpy()                       # 1000 rows, four pieces of 256
+    ref = ora.forward(s, *cores, np.arange(s.N, dtype=np.int64))
+    assert table.shape == ref.shape and row_error(table, ref) <= ROW_TOL
+    for c_gpu, c in zip(emb.cores, cores):                        # lookups never write the cores
+        np.testing.assert_array_equal(c_gpu.cpu().numpy(), c)
+    emb.close()
+
+    w, cores, _, _ = _workload(3)
+    s = Shape(w.n, w.d, w.r)
+    emb = TTEmbedding(w.n, w.d, w.r, 3000, cores)
+    first, count = 136 * 136 * 5 - 4000, 10_001                   # crosses an i1 boundary
+    part = emb.materialize(first, count).cpu().numpy()
+    ref = ora.forward(s, *cores, np.arange(first, first + count, dtype=np.int64))
+    assert row_error(part, ref) <= ROW_TOL
+    emb.close()
+
+
+def test_node_reindexing_table():
+    """With a re-indexing table the row of id i is W[new_id_of[i]] in forward and in the gradients;
+    ids outside the table and entries outside [0, N) count as out of range."""
+    torch = _torch()
+    from paper_2206_10581_amd import TTEmbedding
+    w, cores, _, _ = _workload(2)
+    s = Shape(w.n, w.d, w.r)
+    rng = np.random.default_rng(77)
+    n_nodes = 150_000                                             # fewer nodes than table rows
+    table = rng.permutation(s.N)[:n_nodes].astype(np.int32)
+    table[:3] = [-1, s.N, s.N + 5]                                # entries that point outside
+    B = 20_000
+    ids = rng.integers(0, n_nodes, B).astype(np.int64)
+    ids[:40] = ids[40]                                            # a repeated node
+    ids[100:110] = [n_nodes, n_nodes + 7, -1, 0, 1, 2, -5, 1 << 40, n_nodes - 1, 3]
+    grad = rng.standard_normal((B, s.D)).astype(np.float32)
+    # what the table means, written out with NumPy: look the id up, out-of-table ids stay invalid
+    inside = (ids >= 0) & (ids < n_nodes)
+    rows = np.where(inside, table[np.clip(ids, 0, n_nodes - 1)].astype(np.int64), -1)
+    emb = TTEmbedding(w.n, w.d, w.r, B, cores)
+    emb.set_reindex(torch.from_numpy(table).cuda())
+    out = emb.forward(torch.from_numpy(ids).cuda())
+    stats = emb.stats(check=False)
+    emb.backward_update(torch.from_numpy(grad).cuda(), w.lr)
+    torch.cuda.synchronize()
+    ok = rows[(rows >= 0) & (rows < s.N)]
+    assert stats["U"] == np.unique(ok).size and stats["out_of_range"] == B - ok.size
+    assert row_error(out.cpu().numpy(), ora.forward(s, *cores, rows)) <= ROW_TOL
+    ref_new = ora.backward_update(s, *cores, rows, grad, w.lr)
+    for k in range(3):
+        assert core_error(emb.cores[k].cpu().numpy(), ref_new[k]) <= CORE_TOL
+        step_gpu = (cores[k].astype(np.float64) - emb.cores[k].cpu().numpy()) / w.lr
+        step_ref = (cores[k].astype(np.float64) - ref_new[k]) / w.lr
+        slack = 2 * np.finfo(np.float32).eps * np.abs(cores[k]).max() / w.lr
+        assert np.abs(step_gpu - step_ref).max() <= STEP_TOL * np.abs(step_ref).max() + slack
+    # without the table the same ids mean table rows again
+    emb.set_reindex(None)
+    out2 = emb.forward_eval(torch.from_numpy(ids).cuda()).cpu().numpy()
+    new_cores = [c.cpu().numpy() for c in emb.cores]
+    assert row_error(out2, ora.forward(s, *new_cores, ids)) <= ROW_TOL
+    emb.close()
+
+
 def test_abi_error_codes():
     torch = _torch()
     import paper_2206_10581_amd as lib
