@@ -41,8 +41,7 @@ void launch_prefix_bwd_mfma(const Plan&, const Workspace&, const float* g1, cons
                             hipStream_t);
 bool mfma_fused_mid(const Shape&);
 void launch_bwd_mid_mfma(const Plan&, const Workspace&, const float* g1, const float* g2,
-                         const float* g3, const float* grad, int B, bool with_dg3, hipStream_t);
-void launch_dg3_mfma(const Plan&, const Workspace&, const float* grad, int B, hipStream_t);
+                         const float* g3, const float* grad, int B, hipStream_t);
 void launch_gsum_block(const Plan&, const Workspace&, const float* grad, int B, hipStream_t);
 void launch_gsum_block_fix(const Plan&, const Workspace&, int B, hipStream_t);
 
@@ -213,8 +212,6 @@ struct tt_emb {
   // tt_emb_prepare: index pipelines of coming batches on a stream of the library's own
   hipStream_t side;     // created on first use, default priority
   hipEvent_t ev_fork;   // recorded on the caller's stream, awaited by side
-  hipStream_t side2;    // second gradient kernel of backward_update (created on first use)
-  hipEvent_t ev_fork2, ev_join2;
   struct Prepared {
     bool valid;         // this index set holds a batch that no forward has consumed yet
     const int64_t* ids;
@@ -305,7 +302,6 @@ int tt_emb_create(tt_emb_t* out, const tt_emb_config* cfg, float* g1, float* g2,
   carve(pl, (char*)workspace, h->ws);
   h->cur = 0;
   h->side = nullptr;
-  h->side2 = nullptr;
   h->ev_fork = nullptr;
   h->prep_seq = 0;
   for (int i = 0; i < 2; ++i) h->prep[i] = tt_emb::Prepared{false, nullptr, 0, 0, nullptr};
@@ -530,38 +526,9 @@ int tt_emb_backward_update(tt_emb_t h, const float* grad_out, float lr, void* hi
   if (rc) return rc;
   if (h->mfma && mfma_fused_mid(pl.sh)) {
     // ranks up to 32: per-id and per-prefix gradient steps in one launch
-#ifdef TT_SPLIT_DG3
-    // the G3 gradient partials run beside the by-i2 chunk blocks on a stream of the library's own
-    hipError_t e;
-    if (h->side2 == nullptr) {
-      e = hipStreamCreateWithFlags(&h->side2, hipStreamNonBlocking);
-      if (e != hipSuccess) return hip_fail(e);
-      e = hipEventCreateWithFlags(&h->ev_fork2, hipEventDisableTiming);
-      if (e != hipSuccess) return hip_fail(e);
-      e = hipEventCreateWithFlags(&h->ev_join2, hipEventDisableTiming);
-      if (e != hipSuccess) return hip_fail(e);
-    }
-    e = hipEventRecord(h->ev_fork2, st);
-    if (e != hipSuccess) return hip_fail(e);
-    e = hipStreamWaitEvent(h->side2, h->ev_fork2, 0);
-    if (e != hipSuccess) return hip_fail(e);
-    launch_dg3_mfma(pl, ws, grad_out, B, h->side2);
-    e = hipEventRecord(h->ev_join2, h->side2);
-    if (e != hipSuccess) return hip_fail(e);
     rc = run_slot(h, kSlotUBwd, st,
-                  [&] { launch_bwd_mid_mfma(pl, ws, h->g1, h->g2, h->g3, grad_out, B, false, st); });
+                  [&] { launch_bwd_mid_mfma(pl, ws, h->g1, h->g2, h->g3, grad_out, B, st); });
     if (rc) return rc;
-    e = hipStreamWaitEvent(st, h->ev_join2, 0);
-    if (e != hipSuccess) return hip_fail(e);
-#else
-    rc = run_slot(h, kSlotUBwd, st,
-#ifdef TT_EXP_NODG3K
-                  [&] { launch_bwd_mid_mfma(pl, ws, h->g1, h->g2, h->g3, grad_out, B, false, st); });
-#else
-                  [&] { launch_bwd_mid_mfma(pl, ws, h->g1, h->g2, h->g3, grad_out, B, true, st); });
-#endif
-    if (rc) return rc;
-#endif
   } else {
     if (h->mfma) {
       rc = run_slot(h, kSlotUBwd, st, [&] { launch_id_bwd_mfma(pl, ws, h->g3, grad_out, B, st); });
@@ -638,12 +605,6 @@ int tt_emb_debug_trace(tt_emb_t h, unsigned long long* dst, size_t n) {
 int tt_emb_destroy(tt_emb_t h) {
   if (h == nullptr) return TT_EMB_EINVAL;
   (void)drain_events(h);
-  if (h->side2 != nullptr) {
-    (void)hipStreamSynchronize(h->side2);
-    (void)hipEventDestroy(h->ev_fork2);
-    (void)hipEventDestroy(h->ev_join2);
-    (void)hipStreamDestroy(h->side2);
-  }
   if (h->side != nullptr) {
     (void)hipStreamSynchronize(h->side);
     (void)hipEventDestroy(h->ev_fork);

@@ -22,10 +22,7 @@ constexpr int kSegThreads = 256;
 constexpr int kSegItems = 1024;  // sorted slots per block in the segment kernels (4 per thread)
 
 constexpr int kTileSlots = 32;   // sorted slots per wavefront tile in the row kernels
-#ifndef TT_CHUNK3
-#define TT_CHUNK3 16
-#endif
-constexpr int kChunk3 = TT_CHUNK3;  // unique ids per partial sum of a G3 slice gradient
+constexpr int kChunk3 = 16;       // unique ids per partial sum of a G3 slice gradient
 constexpr int kChunk2 = 16;      // unique prefixes per partial sum of a G2 slice gradient
 
 // Where the ids of a batch come from, passed to the first sort pass by value.

@@ -477,14 +477,6 @@ __global__ __launch_bounds__(kMidThreads, 6) void k_bwd_mid_mfma(
   }
   __syncthreads();
   TT_TRACE(ctr, trace_id, 1);
-#ifdef TT_EXP_P0ONLY
-  if (ctr->nchunk2 >= 0) return;
-#endif
-#ifdef TT_EXP_NOSTORE
-  const bool do_store = ctr->nchunk2 < 0;
-#else
-  const bool do_store = true;
-#endif
 
   const int l16 = lane % 16, kg = lane / 16;
   // (i) this wavefront's two prefixes (local numbers 2w, 2w+1)
@@ -503,11 +495,7 @@ __global__ __launch_bounds__(kMidThreads, 6) void k_bwd_mid_mfma(
       const bool second = (lane / UB) & 1;
       const bool slot_on = lane < 2 * UB && si < (second ? nb : na);
       const int uu = slot_on ? (second ? u0b : u0a) + si : 0;
-#ifdef TT_EXP_FIXGRAD
-      const int mycode = u_code[uu] & 0, myi3 = u_i3[uu];
-#else
       const int mycode = u_code[uu], myi3 = u_i3[uu];
-#endif
       float a[2 * UB][KS], b[2 * UB][NT16][KS];
 #pragma unroll
       for (int sl = 0; sl < 2 * UB; ++sl) {
@@ -570,7 +558,7 @@ __global__ __launch_bounds__(kMidThreads, 6) void k_bwd_mid_mfma(
     }
     // accumulator element v: tile row 4*kg + v = prefix 4w + kg, j1 = v; column n = 16*nt + l16
     const int qv = q_of[4 * w + kg];
-    if (qv >= 0 && do_store) {
+    if (qv >= 0) {
 #pragma unroll
       for (int nt = 0; nt < NT16; ++nt)
 #pragma unroll
@@ -596,25 +584,10 @@ __global__ __launch_bounds__(kMidThreads, 6) void k_bwd_mid_mfma(
 #pragma unroll
     for (int v = 0; v < 16; ++v) {
       const int mrow = 8 * (v / 4) + 4 * half + (v % 4);
-      if (mrow < R && do_store) part2[(size_t)c * S2 + (size_t)mrow * W + n] = acc[v];
+      if (mrow < R) part2[(size_t)c * S2 + (size_t)mrow * W + n] = acc[v];
     }
   }
   TT_TRACE(ctr, trace_id, 4);
-}
-
-// ---------------------------------------------------------------------------------------------
-// The by-i3 chunks alone, one per wavefront, for launches that run beside the by-i2 chunk blocks on
-// a second stream: without the LDS tiles of those blocks many more wavefronts are resident.
-#ifndef TT_DG3_UB
-#define TT_DG3_UB 8
-#endif
-template <int R, int D3>
-__global__ __launch_bounds__(kMThreads) void k_dg3_mfma(
-    const float* __restrict__ P, const float* __restrict__ grad, const float* __restrict__ gsum,
-    const int2* __restrict__ c3_item, const int4* __restrict__ c3_desc, float* __restrict__ part3,
-    const Counters* __restrict__ ctr) {
-  dg3_role<R, D3, TT_DG3_UB>((int)blockIdx.x * kMWaves + (int)threadIdx.x / kWave,
-                             (int)gridDim.x * kMWaves, P, grad, gsum, c3_item, c3_desc, part3, ctr);
 }
 
 // ---------------------------------------------------------------------------------------------
@@ -744,10 +717,7 @@ __global__ __launch_bounds__(kMThreads) void k_row_fwd_mfma(
 // kernels read their row from grad_out directly.  Pieces of runs that cross wavefronts are joined
 // in LDS, pieces that cross blocks leave one partial per block in carry[block][h] (h = 0: the run
 // began in an earlier block, h = 1: it begins here and continues).
-#ifndef TT_GSUM_WAVES
-#define TT_GSUM_WAVES 16
-#endif
-constexpr int kGsumWaves = TT_GSUM_WAVES;
+constexpr int kGsumWaves = 16;
 constexpr int kGsumThreads = kGsumWaves * kWave;
 constexpr int kGsumBlockSlots = kGsumWaves * kWave;  // 1024
 
@@ -981,17 +951,10 @@ void launch_id_bwd_mfma(const Plan& pl, const Workspace& ws, const float* g3, co
 // true when k_bwd_mid_mfma covers the shape (else: k_id_bwd_mfma followed by k_prefix_bwd_mfma)
 bool mfma_fused_mid(const Shape& s) { return mfma_shape(s) && s.r1 <= 32; }
 
-void launch_dg3_mfma(const Plan& pl, const Workspace& ws, const float* grad, int B, hipStream_t st) {
-  const int grid = cdivi(cdivi(B, kChunk3) + (int64_t)pl.sh.n3, kMWaves);
-  TT_DISPATCH_RD(pl.sh.r1, pl.sh.d3, (k_dg3_mfma<R, D3><<<grid, kMThreads, 0, st>>>(
-                                         ws.P, grad, ws.gsum, ws.c3_item, ws.c3_desc, ws.part3,
-                                         ws.ctr)));
-}
-
 void launch_bwd_mid_mfma(const Plan& pl, const Workspace& ws, const float* g1, const float* g2,
-                         const float* g3, const float* grad, int B, bool with_dg3, hipStream_t st) {
+                         const float* g3, const float* grad, int B, hipStream_t st) {
   const int chunk_blocks = cdivi(std::min<int64_t>(B, pl.maxQ), kChunk2) + (int)pl.sh.n2;
-  const int dg3_blocks = with_dg3 ? cdivi(cdivi(B, kChunk3) + (int64_t)pl.sh.n3, kMidWaves) : 0;
+  const int dg3_blocks = cdivi(cdivi(B, kChunk3) + (int64_t)pl.sh.n3, kMidWaves);
 #define TT_MID(RR, DD)                                                                            \
   k_bwd_mid_mfma<RR, DD><<<chunk_blocks + dg3_blocks, kMidThreads, 0, st>>>(                        \
       g1, g2, g3, ws.P, grad, ws.gsum, ws.u_code, ws.u_i3, ws.c2_item, ws.c2_desc, ws.c3_item,    \
