@@ -593,7 +593,7 @@ __global__ __launch_bounds__(kMidThreads, 6) void k_bwd_mid_mfma(
 // ---------------------------------------------------------------------------------------------
 // Rows: one wavefront per tile of kRowTile sorted slots.  The distinct ids of a tile are taken in groups
 // of up to 16/D3 consecutive ids that share a prefix: E = P_q (16 x R) times their G3 slices side
-// by side (R x 16).  Up to NB groups are worked on together (operand loads in flight together);
+// by side (R x 16).  Up to NB = 3 groups are worked on together (operand loads in flight together);
 // their rows go through LDS so that one store instruction writes a whole row to every batch
 // position that holds the id.  Rows are written with non-temporal stores: nothing on this path
 // reads them back.
@@ -603,7 +603,7 @@ __global__ __launch_bounds__(kMThreads) void k_row_fwd_mfma(
     const uint32_t* __restrict__ perm, const int* __restrict__ u_i3, const int* __restrict__ u_q,
     float* __restrict__ out, Counters* ctr) {
   constexpr int PN = 16 * R, S3 = R * D3, D = 16 * D3, UPT = 16 / D3, KQ = R / 4, VPL = D / kWave;
-  constexpr int NB = 4;
+  constexpr int NB = 3;  // groups per batch: 4 cost two wavefronts per SIMD of occupancy
   __shared__ float ebuf[kMWaves][NB * UPT * D];
   const int w = threadIdx.x / kWave, lane = threadIdx.x % kWave;
   const int l16 = lane % 16, kg = lane / 16;
