@@ -15,7 +15,6 @@ void launch_sort_pass(const Plan&, const Workspace&, const IdSource& src, int B,
                       int which);
 void launch_seg_count(const Plan&, const Workspace&, int B, hipStream_t);
 void launch_seg_write(const Plan&, const Workspace&, int B, hipStream_t);
-void launch_group_scan(const Plan&, const Workspace&, hipStream_t);
 void launch_group(const Plan&, const Workspace&, int B, hipStream_t);
 void launch_prefix_fwd(const Plan&, const Workspace&, const float* g1, const float* g2, int B,
                        hipStream_t);
@@ -46,7 +45,7 @@ void launch_gsum_block(const Plan&, const Workspace&, const float* grad, int B, 
 void launch_gsum_block_fix(const Plan&, const Workspace&, int B, hipStream_t);
 
 static const char* const kSlotNames[kSlotCount] = {
-    "sort_hist", "sort_scan", "sort_scatter", "seg_count", "seg_write",  "group_scan", "group",
+    "sort_hist", "sort_scan", "sort_scatter", "seg_count", "seg_write",  "group",
     "prefix_fwd", "row_fwd",  "gsum",         "gsum_fix",  "u_bwd",      "dg3",        "prefix_bwd",
     "sgd",        "event_pair"};
 
@@ -145,8 +144,6 @@ static size_t carve(const Plan& pl, char* base, Workspace* ws /* [2] or nullptr 
     w.q_i2 = (int*)take(mQ * 4);
     w.cnt3 = (uint32_t*)take((size_t)pl.uBlocksMax * s.n3 * 4);
     w.cnt2 = (uint32_t*)take((size_t)pl.qBlocksMax * s.n2 * 4);
-    w.tot3 = (uint32_t*)take((size_t)s.n3 * 4);
-    w.tot2 = (uint32_t*)take((size_t)s.n2 * 4);
     w.g3_list = (int*)take(mB * 4);
     w.g3_start = (int*)take(((size_t)s.n3 + 1) * 4);
     w.c3_start = (int*)take(((size_t)s.n3 + 1) * 4);
@@ -335,16 +332,16 @@ static int run_index(tt_emb* h, int set, const IdSource& src, int B, hipStream_t
   for (int pass = 0; pass < pl.passes; ++pass) {
     rc = run_slot(h, kSlotSortHist, st, [&] { launch_sort_pass(pl, ws, src, B, pass, st, 0); });
     if (rc) return rc;
-    rc = run_slot(h, kSlotSortScan, st, [&] { launch_sort_pass(pl, ws, src, B, pass, st, 2); });
-    if (rc) return rc;
+    if (cdiv64(B, kSortItems) > kFoldScanBlocks) {
+      rc = run_slot(h, kSlotSortScan, st, [&] { launch_sort_pass(pl, ws, src, B, pass, st, 2); });
+      if (rc) return rc;
+    }
     rc = run_slot(h, kSlotSortScatter, st, [&] { launch_sort_pass(pl, ws, src, B, pass, st, 1); });
     if (rc) return rc;
   }
   rc = run_slot(h, kSlotSegCount, st, [&] { launch_seg_count(pl, ws, B, st); });
   if (rc) return rc;
   rc = run_slot(h, kSlotSegWrite, st, [&] { launch_seg_write(pl, ws, B, st); });
-  if (rc) return rc;
-  rc = run_slot(h, kSlotGroupScan, st, [&] { launch_group_scan(pl, ws, st); });
   if (rc) return rc;
   return run_slot(h, kSlotGroup, st, [&] { launch_group(pl, ws, B, st); });
 }

@@ -99,9 +99,11 @@ struct ScatterLds {
 constexpr int kSteps = kSortWaveItems / kWave;  // items per lane
 
 // One block's share of a stable counting-sort pass over n_items items (block blk owns items
-// [blk*kSortItems, +kSortItems), wavefront w of it the w-th sixteenth).  cnt[b][bin] holds, per
-// bucket, the items of blocks before b and tot[bin] the bucket totals (both from a column-scan
-// kernel over the blocks' histograms).
+// [blk*kSortItems, +kSortItems), wavefront w of it the w-th sixteenth).  With tot != nullptr,
+// cnt[b][bin] holds, per bucket, the items of blocks before b and tot[bin] the bucket totals (both
+// from a column-scan kernel over the blocks' histograms); with tot == nullptr, cnt holds the
+// blocks' own histograms and every block adds up its columns itself (cheaper than one more launch
+// when there are few blocks).
 // ItemOps: Item load(int idx); int digit(Item); void emit(uint32_t pos, Item); and, for chunked
 // passes, void emit_chunked(uint32_t pos, uint32_t chunk, uint32_t t, Item): item is the t-th of
 // chunk `chunk` (its record goes to chunk*chunk_size + t of a per-chunk table).
@@ -135,8 +137,28 @@ __device__ void stable_scatter_block(ScatterLds& L, int blk, int n_items, int bi
   for (int k = 0; k < kMaxBins / kSortThreads; ++k) {
     const int bin = tid + k * kSortThreads;
     const int bc = min(bin, bins - 1);
-    const uint32_t total = tot[bc];
-    before[k] = cnt[(size_t)blk * bins + bc];
+    uint32_t total;
+    if (tot != nullptr) {
+      total = tot[bc];
+      before[k] = cnt[(size_t)blk * bins + bc];
+    } else {
+      // column sums over the blocks' histograms, kFoldRows rows in flight
+      uint32_t bsum = 0, tsum = 0;
+      for (int b0 = 0; b0 < nblk; b0 += kFoldRows) {
+        uint32_t v[kFoldRows];
+#pragma unroll
+        for (int j = 0; j < kFoldRows; ++j) v[j] = cnt[(size_t)min(b0 + j, nblk - 1) * bins + bc];
+        __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+        for (int j = 0; j < kFoldRows; ++j) {
+          const uint32_t x = (b0 + j < nblk) ? v[j] : 0u;
+          tsum += x;
+          bsum += (b0 + j < blk) ? x : 0u;
+        }
+      }
+      total = tsum;
+      before[k] = bsum;
+    }
     if (bin < bins) {
       L.tot[bin] = total;
       if (chunk > 0) L.aux[bin] = (total + chunk - 1) / chunk;
@@ -362,21 +384,6 @@ __global__ __launch_bounds__(kScanThreads) void k_sort_colscan(uint32_t* __restr
   if (bin < bins) column_scan(cnt, tot, nblk, bins, bin);
 }
 
-__global__ __launch_bounds__(kScanThreads) void k_group_colscan(uint32_t* __restrict__ cnt3,
-                                                                uint32_t* __restrict__ tot3, int n3,
-                                                                uint32_t* __restrict__ cnt2,
-                                                                uint32_t* __restrict__ tot2, int n2,
-                                                                int blocks3,
-                                                                const Counters* __restrict__ ctr) {
-  if ((int)blockIdx.x < blocks3) {
-    const int bin = blockIdx.x * kScanThreads + threadIdx.x;
-    if (bin < n3) column_scan(cnt3, tot3, (ctr->U + kSortItems - 1) / kSortItems, n3, bin);
-  } else {
-    const int bin = (blockIdx.x - blocks3) * kScanThreads + threadIdx.x;
-    if (bin < n2) column_scan(cnt2, tot2, (ctr->Q + kSortItems - 1) / kSortItems, n2, bin);
-  }
-}
-
 // ---------------------------------------------------------------------------------------------
 // Segment discovery over the sorted keys
 
@@ -566,8 +573,7 @@ struct GroupOps2 {
 
 __global__ __launch_bounds__(kSortThreads) void k_group(
     Shape sh, int u_blocks, int bits3, int bits2, const uint32_t* __restrict__ cnt3,
-    const uint32_t* __restrict__ tot3, const uint32_t* __restrict__ cnt2,
-    const uint32_t* __restrict__ tot2, const int* __restrict__ u_i3, const int* __restrict__ u_code,
+    const uint32_t* __restrict__ cnt2, const int* __restrict__ u_i3, const int* __restrict__ u_code,
     const int* __restrict__ u_q, const int* __restrict__ q_i2, const int* __restrict__ q_i1,
     const int* __restrict__ q_us, int* g3_list, int* g3_start, int* c3_start, int4* c3_desc,
     int2* c3_item, int* g2_list, int* g2_start, int* c2_start, int4* c2_desc, int4* c2_item,
@@ -575,11 +581,11 @@ __global__ __launch_bounds__(kSortThreads) void k_group(
   __shared__ ScatterLds L;
   if ((int)blockIdx.x < u_blocks) {
     GroupOps3 ops{u_i3, u_code, u_q, g3_list, c3_item};
-    stable_scatter_block(L, (int)blockIdx.x, ctr->U, (int)sh.n3, bits3, cnt3, tot3, ops, g3_start,
+    stable_scatter_block(L, (int)blockIdx.x, ctr->U, (int)sh.n3, bits3, cnt3, nullptr, ops, g3_start,
                          kChunk3, c3_start, c3_desc, &ctr->nchunk3);
   } else {
     GroupOps2 ops{q_i2, q_i1, q_us, g2_list, c2_item};
-    stable_scatter_block(L, (int)blockIdx.x - u_blocks, ctr->Q, (int)sh.n2, bits2, cnt2, tot2, ops,
+    stable_scatter_block(L, (int)blockIdx.x - u_blocks, ctr->Q, (int)sh.n2, bits2, cnt2, nullptr, ops,
                          g2_start, kChunk2, c2_start, c2_desc, &ctr->nchunk2);
   }
 }
@@ -595,9 +601,13 @@ void launch_sort_pass(const Plan& pl, const Workspace& ws, const IdSource& src, 
   const int shift = pass * pl.bitsPerPass;
   const int bits = std::min(pl.bitsPerPass, pl.keyBits - shift);
   const uint32_t N = pl.sh.N;
+  // with few blocks every scatter block adds up the histogram columns itself: no scan launch
+  const bool folded = blocks <= kFoldScanBlocks;
+  const uint32_t* tot = folded ? nullptr : ws.tot;
   if (which == 2) {
-    k_sort_colscan<<<cdiv(1 << bits, kScanThreads), kScanThreads, 0, st>>>(ws.cnt, ws.tot, blocks,
-                                                                         1 << bits);
+    if (!folded)
+      k_sort_colscan<<<cdiv(1 << bits, kScanThreads), kScanThreads, 0, st>>>(ws.cnt, ws.tot, blocks,
+                                                                           1 << bits);
     return;
   }
   if (pass == 0) {
@@ -607,7 +617,7 @@ void launch_sort_pass(const Plan& pl, const Workspace& ws, const IdSource& src, 
           pl.qBlocksMax * (int)pl.sh.n2, (uint32_t*)ws.g1_first, 2 * (int)pl.sh.n1, ws.ctr);
     } else {
       SortOps<true> ops{src, nullptr, nullptr, ws.key[0], ws.val[0], N, shift, (1u << bits) - 1u};
-      k_sort_scatter<true><<<blocks, kSortThreads, 0, st>>>(ops, B, bits, ws.cnt, ws.tot);
+      k_sort_scatter<true><<<blocks, kSortThreads, 0, st>>>(ops, B, bits, ws.cnt, tot);
     }
   } else {
     const int from = (pass - 1) & 1, dst = pass & 1;
@@ -618,7 +628,7 @@ void launch_sort_pass(const Plan& pl, const Workspace& ws, const IdSource& src, 
     } else {
       SortOps<false> ops{IdSource{}, ws.key[from], ws.val[from], ws.key[dst], ws.val[dst], N, shift,
                          (1u << bits) - 1u};
-      k_sort_scatter<false><<<blocks, kSortThreads, 0, st>>>(ops, B, bits, ws.cnt, ws.tot);
+      k_sort_scatter<false><<<blocks, kSortThreads, 0, st>>>(ops, B, bits, ws.cnt, tot);
     }
   }
 }
@@ -636,18 +646,11 @@ void launch_seg_write(const Plan& pl, const Workspace& ws, int B, hipStream_t st
       ws.u_code, ws.q_us, ws.q_i1, ws.q_i2, ws.cnt3, ws.cnt2, ws.g1_first, ws.g1_end, ws.ctr);
 }
 
-void launch_group_scan(const Plan& pl, const Workspace& ws, hipStream_t st) {
-  const int b3 = cdiv(pl.sh.n3, kScanThreads), b2 = cdiv(pl.sh.n2, kScanThreads);
-  k_group_colscan<<<b3 + b2, kScanThreads, 0, st>>>(ws.cnt3, ws.tot3, (int)pl.sh.n3, ws.cnt2, ws.tot2,
-                                                   (int)pl.sh.n2, b3, ws.ctr);
-}
-
 void launch_group(const Plan& pl, const Workspace& ws, int B, hipStream_t st) {
   // blocks are sized from upper bounds (U <= B, Q <= min(B, n1*n2)); surplus blocks return at once
   const int ub = cdiv(B, kSortItems);
   const int qb = cdiv(std::min((int64_t)B, pl.maxQ), kSortItems);
-  k_group<<<ub + qb, kSortThreads, 0, st>>>(pl.sh, ub, pl.bits3, pl.bits2, ws.cnt3, ws.tot3, ws.cnt2,
-                                           ws.tot2, ws.u_i3, ws.u_code, ws.u_q, ws.q_i2, ws.q_i1,
+  k_group<<<ub + qb, kSortThreads, 0, st>>>(pl.sh, ub, pl.bits3, pl.bits2, ws.cnt3, ws.cnt2, ws.u_i3, ws.u_code, ws.u_q, ws.q_i2, ws.q_i1,
                                            ws.q_us, ws.g3_list, ws.g3_start, ws.c3_start, ws.c3_desc,
                                            ws.c3_item, ws.g2_list, ws.g2_start, ws.c2_start,
                                            ws.c2_desc, ws.c2_item, ws.ctr);

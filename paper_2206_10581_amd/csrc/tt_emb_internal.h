@@ -16,6 +16,8 @@ constexpr int kSortThreads = 1024;
 constexpr int kSortWaves = 16;
 constexpr int kSortWaveItems = 256;
 constexpr int kSortItems = kSortWaves * kSortWaveItems;  // 4096 items per block
+constexpr int kFoldRows = 16;       // histogram rows a thread keeps in flight while it adds up a column
+constexpr int kFoldScanBlocks = 8;  // sort passes with at most this many blocks need no column-scan launch
 constexpr int kMaxBins = 2048;                            // digit / bucket count limit per pass
 
 constexpr int kSegThreads = 256;
@@ -88,8 +90,6 @@ struct Workspace {
   int* q_i2;          // prefix -> i2                    [maxQ]
   uint32_t* cnt3;     // per-block histograms of i3 over unique ids   [uBlocks * n3]
   uint32_t* cnt2;     // per-block histograms of i2 over prefixes     [qBlocks * n2]
-  uint32_t* tot3;     // unique ids per i3  [n3]
-  uint32_t* tot2;     // prefixes per i2    [n2]
   int* g3_list;       // unique ids grouped by i3 (stable)  [maxB]
   int* g3_start;      // [n3+1]
   int* c3_start;      // first chunk of each i3 group [n3+1]
@@ -127,7 +127,6 @@ enum KernelSlot {
   kSlotSortScatter,
   kSlotSegCount,
   kSlotSegWrite,
-  kSlotGroupScan,
   kSlotGroup,
   kSlotPrefixFwd,
   kSlotRowFwd,
