@@ -85,7 +85,7 @@ def main() -> int:
                     help="also run one plain device copy of this many MiB (known traffic, to scale "
                          "a profiler's HBM counters)")
     ap.add_argument("--no-prepare", action="store_true",
-                    help="do not overlap the next step's index work with this step's backward")
+                    help="do not overlap the index work of coming steps with this step's arithmetic")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on ONE GPU (replicated-core data parallelism is described "
@@ -130,7 +130,7 @@ def main() -> int:
         if args.restore:
             flat.copy_(snapshot)
         if not args.no_prepare:
-            emb.prepare(ids)        # index pipeline of the NEXT step, overlapped with this step
+            emb.prepare(ids)        # index pipeline of the step after next, overlapped with this one
         emb.forward(ids, out)
         emb.backward_update(grad, lr)
 
@@ -142,7 +142,8 @@ def main() -> int:
         torch.cuda.synchronize()
         del src, dst
     if not args.no_prepare:
-        emb.prepare(ids)            # the first step's own index work
+        emb.prepare(ids)            # the first two steps' own index work
+        emb.prepare(ids)
     for _ in range(args.warmup):
         step()
     torch.cuda.synchronize()

@@ -25,7 +25,7 @@
  * borrows it and never allocates or frees device memory.  Cores, out and grad_out must be 16-byte
  * aligned, ids 8-byte aligned (TT_EMB_EINVAL otherwise).  The handle owns host bookkeeping only.
  * All calls are asynchronous on the given HIP stream unless stated otherwise (tt_emb_prepare also
- * uses one internal stream of default priority, created on its first call).  A handle must not
+ * uses three internal streams of default priority, created on its first call).  A handle must not
  * be used from two threads or two streams at once.
  *
  * Errors.  Every function returns TT_EMB_OK (0) or a negative code and never aborts.
@@ -121,12 +121,13 @@ int tt_emb_set_reindex(tt_emb_t h, const int32_t* new_id_of, int64_t n_ids);
  * of the library's own that starts once everything enqueued so far on hip_stream has run.  A later
  * tt_emb_forward with the same ids pointer and the same B finds them ready, waits for them on its
  * own stream and skips that work (the oldest such batch if two match); a prepared batch that no
- * forward asks for is eventually overwritten.  The workspace holds two index sets: one may be in
- * use by a forward/backward pair while the other is filled, so at most two batches can be ahead
- * (one while a backward_update is still outstanding).  Typical use, once per step and before the
- * forward of the current batch: prepare(next ids); forward(ids); ...; backward_update(...) - the
- * next batch's index work then overlaps this batch's arithmetic (minibatch samplers know the next
- * ids early).  The ids buffer must keep its contents until that forward has been enqueued.
+ * forward asks for is eventually overwritten (the oldest first).  The workspace holds three index
+ * sets, each with a stream of its own: one may be in use by a forward/backward pair while the other
+ * two are filled, so up to two batches can be ahead, and an index pipeline that is started two steps
+ * early has two steps to finish.  Typical use, once per step and before the forward of the current
+ * batch: prepare(ids of the batch after next); forward(ids); ...; backward_update(...) - the index
+ * work of coming batches then overlaps this batch's arithmetic (minibatch samplers know the next
+ * ids early).  An ids buffer must keep its contents until the forward that uses it has been enqueued.
  * Results are identical with or without it.  tt_emb_get_stats refers to the latest forward only
  * until the next tt_emb_prepare.
  */

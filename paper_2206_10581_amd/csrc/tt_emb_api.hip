@@ -112,10 +112,13 @@ static int make_plan(const tt_emb_config* c, Plan* pl) {
   return TT_EMB_OK;
 }
 
+// Index sets: one serves the forward/backward pair in flight while tt_emb_prepare fills the others
+// for the next two batches (each on a stream of its own, so a pipeline has two steps to finish).
+constexpr int kSets = 3;
+
 // Walks the workspace layout; with base == nullptr only the size is computed.  The index arrays
-// exist twice (ws[0], ws[1]): one set serves the forward/backward pair in flight while
-// tt_emb_prepare fills the other for the next batch; the arithmetic buffers are shared.
-static size_t carve(const Plan& pl, char* base, Workspace* ws /* [2] or nullptr */) {
+// exist kSets times; the arithmetic buffers are shared.
+static size_t carve(const Plan& pl, char* base, Workspace* ws /* [kSets] or nullptr */) {
   size_t off = 0;
   auto take = [&](size_t bytes) -> char* {
     char* p = base ? base + off : nullptr;
@@ -124,8 +127,8 @@ static size_t carve(const Plan& pl, char* base, Workspace* ws /* [2] or nullptr 
   };
   const Shape& s = pl.sh;
   const size_t mB = (size_t)pl.maxB, mQ = (size_t)pl.maxQ;
-  Workspace set[2];
-  for (int i = 0; i < 2; ++i) {
+  Workspace set[kSets];
+  for (int i = 0; i < kSets; ++i) {
     Workspace& w = set[i];
     w.ctr = (Counters*)take(sizeof(Counters));
     for (int k = 0; k < 2; ++k) w.key[k] = (uint32_t*)take(mB * 4);
@@ -170,18 +173,18 @@ static size_t carve(const Plan& pl, char* base, Workspace* ws /* [2] or nullptr 
 #else
   w.trace = nullptr;
 #endif
-  set[1].P = w.P;
-  set[1].gsum = w.gsum;
-  set[1].carry = w.carry;
-  set[1].dPsum = w.dPsum;
-  set[1].dg1part = w.dg1part;
-  set[1].part3 = w.part3;
-  set[1].part2 = w.part2;
-  set[1].trace = w.trace;
-  if (ws) {
-    ws[0] = set[0];
-    ws[1] = set[1];
+  for (int i = 1; i < kSets; ++i) {
+    set[i].P = w.P;
+    set[i].gsum = w.gsum;
+    set[i].carry = w.carry;
+    set[i].dPsum = w.dPsum;
+    set[i].dg1part = w.dg1part;
+    set[i].part3 = w.part3;
+    set[i].part2 = w.part2;
+    set[i].trace = w.trace;
   }
+  if (ws)
+    for (int i = 0; i < kSets; ++i) ws[i] = set[i];
   return off;
 }
 
@@ -197,7 +200,7 @@ using namespace ttemb;
 struct tt_emb {
   tt_emb_config cfg;
   Plan plan;
-  Workspace ws[2];    // two index sets over shared arithmetic buffers
+  Workspace ws[kSets];  // index sets over shared arithmetic buffers
   int cur;            // set of the latest forward (and of the backward that follows it)
   float *g1, *g2, *g3;
   const int32_t* reindex;  // old id -> table row applied in front of the split, or nullptr
@@ -207,7 +210,7 @@ struct tt_emb {
   bool have_forward;
   hipStream_t last_stream;
   // tt_emb_prepare: index pipelines of coming batches on a stream of the library's own
-  hipStream_t side;     // created on first use, default priority
+  hipStream_t side[kSets];  // one per index set, created on first use, default priority
   hipEvent_t ev_fork;   // recorded on the caller's stream, awaited by side
   struct Prepared {
     bool valid;         // this index set holds a batch that no forward has consumed yet
@@ -215,7 +218,7 @@ struct tt_emb {
     int64_t B;
     uint64_t seq;       // order of the prepare calls
     hipEvent_t ready;   // recorded on side when the set is complete
-  } prep[2];
+  } prep[kSets];
   uint64_t prep_seq;
   bool profiling;
   bool mfma;  // matrix-core kernels apply to this shape and are not switched off
@@ -298,10 +301,10 @@ int tt_emb_create(tt_emb_t* out, const tt_emb_config* cfg, float* g1, float* g2,
   h->plan = pl;
   carve(pl, (char*)workspace, h->ws);
   h->cur = 0;
-  h->side = nullptr;
+  for (int i = 0; i < kSets; ++i) h->side[i] = nullptr;
   h->ev_fork = nullptr;
   h->prep_seq = 0;
-  for (int i = 0; i < 2; ++i) h->prep[i] = tt_emb::Prepared{false, nullptr, 0, 0, nullptr};
+  for (int i = 0; i < kSets; ++i) h->prep[i] = tt_emb::Prepared{false, nullptr, 0, 0, nullptr};
   h->g1 = g1;
   h->g2 = g2;
   h->g3 = g3;
@@ -317,7 +320,7 @@ int tt_emb_create(tt_emb_t* out, const tt_emb_config* cfg, float* g1, float* g2,
   std::memset(h->prof_ms, 0, sizeof(h->prof_ms));
 #ifdef TT_EMB_TRACE
   (void)hipMemset(h->ws[0].trace, 0, (size_t)(1u << 17) * 64);
-  for (int i = 0; i < 2; ++i)
+  for (int i = 0; i < kSets; ++i)
     (void)hipMemcpy(&h->ws[i].ctr->trace, &h->ws[i].trace, sizeof(void*), hipMemcpyHostToDevice);
 #endif
   *out = h;
@@ -353,37 +356,41 @@ int tt_emb_prepare(tt_emb_t h, const int64_t* ids, int64_t B64, void* hip_stream
   if (ids == nullptr || ((uintptr_t)ids & 7u) != 0) return TT_EMB_EINVAL;
   hipStream_t st = (hipStream_t)hip_stream;
   hipError_t e;
-  if (h->side == nullptr) {
-    e = hipStreamCreateWithFlags(&h->side, hipStreamNonBlocking);
-    if (e != hipSuccess) return hip_fail(e);
-    e = hipEventCreateWithFlags(&h->ev_fork, hipEventDisableTiming);
-    if (e != hipSuccess) return hip_fail(e);
-    for (int i = 0; i < 2; ++i) {
+  if (h->side[0] == nullptr) {
+    for (int i = 0; i < kSets; ++i) {
+      e = hipStreamCreateWithFlags(&h->side[i], hipStreamNonBlocking);
+      if (e != hipSuccess) return hip_fail(e);
       e = hipEventCreateWithFlags(&h->prep[i].ready, hipEventDisableTiming);
       if (e != hipSuccess) return hip_fail(e);
     }
+    e = hipEventCreateWithFlags(&h->ev_fork, hipEventDisableTiming);
+    if (e != hipSuccess) return hip_fail(e);
   }
   // Pick the index set to fill.  A set is free when no backward_update still has to be enqueued for
   // it (that is only `cur`, between a forward and its backward) and no prepared batch waits in it.
-  // With both taken, the prepared batch that is not the newest is overwritten.
+  // With all taken, the oldest prepared batch is overwritten.
   const bool cur_busy = h->pending_B >= 0;
   int target = -1;
-  for (int s : {h->cur ^ 1, h->cur})
-    if (target < 0 && !h->prep[s].valid && !(s == h->cur && cur_busy)) target = s;
+  for (int k = 1; k <= kSets && target < 0; ++k) {
+    const int s = (h->cur + k) % kSets;
+    if (!h->prep[s].valid && !(s == h->cur && cur_busy)) target = s;
+  }
   if (target < 0) {
-    if (cur_busy || !h->prep[h->cur].valid) target = h->cur ^ 1;
-    else target = h->prep[0].seq < h->prep[1].seq ? 0 : 1;
+    for (int s = 0; s < kSets; ++s)
+      if (!(s == h->cur && cur_busy) && (target < 0 || h->prep[s].seq < h->prep[target].seq))
+        target = s;
   }
   h->prep[target].valid = false;
-  // everything that used this set earlier (its backward_update, or an index pipeline on side that
-  // is now dropped) is ordered before: side is in order, and the fork event covers hip_stream
+  // everything that used this set earlier (its backward_update, or an index pipeline that is now
+  // dropped) is ordered before: the set's stream is in order, and the fork event covers hip_stream
   e = hipEventRecord(h->ev_fork, st);
   if (e != hipSuccess) return hip_fail(e);
-  e = hipStreamWaitEvent(h->side, h->ev_fork, 0);
+  e = hipStreamWaitEvent(h->side[target], h->ev_fork, 0);
   if (e != hipSuccess) return hip_fail(e);
-  int rc = run_index(h, target, IdSource{ids, 0, h->reindex, h->reindex_n}, (int)B64, h->side);
+  int rc = run_index(h, target, IdSource{ids, 0, h->reindex, h->reindex_n}, (int)B64,
+                     h->side[target]);
   if (rc) return rc;
-  e = hipEventRecord(h->prep[target].ready, h->side);
+  e = hipEventRecord(h->prep[target].ready, h->side[target]);
   if (e != hipSuccess) return hip_fail(e);
   h->prep[target].valid = true;
   h->prep[target].ids = ids;
@@ -412,7 +419,7 @@ static int forward_impl(tt_emb* h, const IdSource& src, int64_t B64, float* out,
   int rc;
   // oldest prepared batch with these ids and this size, if any
   int found = -1;
-  for (int s = 0; s < 2; ++s)
+  for (int s = 0; s < kSets; ++s)
     if (ids != nullptr && h->prep[s].valid && h->prep[s].ids == ids && h->prep[s].B == B64 &&
         (found < 0 || h->prep[s].seq < h->prep[found].seq))
       found = s;
@@ -423,14 +430,19 @@ static int forward_impl(tt_emb* h, const IdSource& src, int64_t B64, float* out,
     h->cur = found;
   } else {
     // build the index structures here; take a set no prepared batch waits in, else drop one
-    int target = !h->prep[h->cur].valid ? h->cur : (!h->prep[h->cur ^ 1].valid ? (h->cur ^ 1) : h->cur);
-    if (h->prep[target].valid) {
+    int target = -1;
+    for (int k = 0; k < kSets && target < 0; ++k)
+      if (!h->prep[(h->cur + k) % kSets].valid) target = (h->cur + k) % kSets;
+    if (target < 0) {  // every set holds a prepared batch: the oldest one is dropped
+      target = 0;
+      for (int s = 1; s < kSets; ++s)
+        if (h->prep[s].seq < h->prep[target].seq) target = s;
       hipError_t e = hipStreamWaitEvent(st, h->prep[target].ready, 0);
       if (e != hipSuccess) return hip_fail(e);
       h->prep[target].valid = false;
-    } else if (h->side != nullptr) {
-      // an index pipeline that was dropped earlier may still be writing this set on side
-      hipError_t e = hipEventRecord(h->ev_fork, h->side);
+    } else if (h->side[target] != nullptr) {
+      // an index pipeline that was dropped earlier may still be writing this set on its stream
+      hipError_t e = hipEventRecord(h->ev_fork, h->side[target]);
       if (e != hipSuccess) return hip_fail(e);
       e = hipStreamWaitEvent(st, h->ev_fork, 0);
       if (e != hipSuccess) return hip_fail(e);
@@ -496,7 +508,7 @@ int tt_emb_set_reindex(tt_emb_t h, const int32_t* new_id_of, int64_t n_ids) {
   if (h->pending_B >= 0) return TT_EMB_ESTATE;  // between a forward and its backward_update
   h->reindex = new_id_of;
   h->reindex_n = new_id_of != nullptr ? n_ids : 0;
-  for (int i = 0; i < 2; ++i) h->prep[i].valid = false;  // prepared batches used the old table
+  for (int i = 0; i < kSets; ++i) h->prep[i].valid = false;  // prepared batches used the old table
   return TT_EMB_OK;
 }
 
@@ -602,11 +614,14 @@ int tt_emb_debug_trace(tt_emb_t h, unsigned long long* dst, size_t n) {
 int tt_emb_destroy(tt_emb_t h) {
   if (h == nullptr) return TT_EMB_EINVAL;
   (void)drain_events(h);
-  if (h->side != nullptr) {
-    (void)hipStreamSynchronize(h->side);
-    (void)hipEventDestroy(h->ev_fork);
-    for (int i = 0; i < 2; ++i) (void)hipEventDestroy(h->prep[i].ready);
-    (void)hipStreamDestroy(h->side);
+  if (h->side[0] != nullptr) {
+    for (int i = 0; i < kSets; ++i) {
+      if (h->side[i] == nullptr) continue;
+      (void)hipStreamSynchronize(h->side[i]);
+      if (h->prep[i].ready != nullptr) (void)hipEventDestroy(h->prep[i].ready);
+      (void)hipStreamDestroy(h->side[i]);
+    }
+    if (h->ev_fork != nullptr) (void)hipEventDestroy(h->ev_fork);
   }
   delete h;
   return TT_EMB_OK;

@@ -310,6 +310,37 @@ def test_prepare_pipeline_matches_oracle_over_three_steps():
         assert torch.equal(outs2[k], outs[k]), f"step {k}"
         assert torch.equal(emb2.cores[k], emb.cores[k])
     emb2.close()
+    # the batch after next prepared before every forward (three index sets: one in flight, two
+    # ahead), then a fourth prepare that has to overwrite the oldest waiting batch
+    emb3 = TTEmbedding(w.n, w.d, w.r, 10_000, cores)
+    outs3 = []
+    emb3.prepare(t_ids[0])
+    emb3.prepare(t_ids[1])
+    for k in range(3):
+        if k + 2 < 3:
+            emb3.prepare(t_ids[k + 2])
+        outs3.append(emb3.forward(t_ids[k]))
+        emb3.backward_update(t_grad[k], w.lr)
+    torch.cuda.synchronize()
+    for k in range(3):
+        assert torch.equal(outs3[k], outs[k]), f"step {k}"
+        assert torch.equal(emb3.cores[k], emb.cores[k])
+    snap = [c.clone() for c in emb3.cores]
+    for k in (0, 1, 2, 0):                 # one more than there are sets
+        emb3.prepare(t_ids[k])
+    out_x = emb3.forward(t_ids[1]).clone()  # still waiting: served from its prepared set
+    emb3.backward_update(t_grad[1], w.lr)
+    after_x = [c.clone() for c in emb3.cores]
+    for c, b in zip(emb3.cores, snap):
+        c.copy_(b)
+    out_y = emb3.forward(t_ids[1]).clone()  # nothing matches any more: index work done in place
+    emb3.backward_update(t_grad[1], w.lr)
+    torch.cuda.synchronize()
+    emb3.stats()
+    assert torch.equal(out_x, out_y)
+    for x, y in zip(after_x, emb3.cores):
+        assert torch.equal(x, y)
+    emb3.close()
     # a prepared batch that does not match the next forward is dropped, results unchanged
     base = [c.clone() for c in emb.cores]
     emb.prepare(t_ids[1])
