@@ -116,6 +116,17 @@ int tt_emb_materialize(tt_emb_t h, int64_t first_row, int64_t count, float* out,
 int tt_emb_set_reindex(tt_emb_t h, const int32_t* new_id_of, int64_t n_ids);
 
 /*
+ * Update rule of backward_update (the paper names no optimiser; plain SGD is the default).  With
+ * three state arrays - device fp32, shaped and aligned like g1, g2, g3, zeroed by the caller before
+ * the first step, borrowed until replaced or the handle is destroyed - every later backward_update
+ * applies row-sparse Adagrad to the slices the batch touches:
+ *   S[s] <- S[s] + dG[s]^2 ;  G[s] <- G[s] - lr * dG[s] / (sqrt(S[s]) + eps)      (elementwise)
+ * with dG the same batch-summed gradient as for SGD; untouched slices and their state are not
+ * written.  eps > 0.  Three null pointers return to SGD.  Host-only.
+ */
+int tt_emb_set_adagrad(tt_emb_t h, float* s1, float* s2, float* s3, float eps);
+
+/*
  * Optional: builds the index structures (split, sort, unique ids and prefixes: the part of
  * Section 4.2's sharing that depends on the ids only) of a COMING batch ahead of time, on a stream
  * of the library's own that starts once everything enqueued so far on hip_stream has run.  A later

@@ -173,3 +173,18 @@ def backward_update(shape: Shape, g1, g2, g3, ids, grad, lr: float, tag: str = "
     _lib(tag).tto_backward_update(ctypes.byref(c), _p(n1), _p(n2), _p(n3), _p(ids), ids.size,
                                   _p(grad), ctypes.c_float(lr))
     return n1, n2, n3
+
+
+def adagrad_update(shape: Shape, g1, g2, g3, state, ids, grad, lr: float, eps: float):
+    """One Adagrad step on the batch-summed core gradients (the paper names no optimiser; this is
+    the textbook rule, elementwise per core):  S <- S + dG^2,  G <- G - lr * dG / (sqrt(S) + eps).
+    fp64 throughout, rounded to fp32 once.  Entries no id touches have dG = 0 and stay as they are.
+    Returns (new cores, new state); the inputs are left untouched."""
+    dg = grads(shape, g1, g2, g3, ids, grad)
+    new_cores, new_state = [], []
+    for G, S, d in zip((g1, g2, g3), state, dg):
+        s64 = S.astype(np.float64) + d * d
+        g64 = G.astype(np.float64) - lr * d / (np.sqrt(s64) + eps)
+        new_state.append(s64.astype(np.float32))
+        new_cores.append(g64.astype(np.float32))
+    return tuple(new_cores), tuple(new_state)

@@ -53,6 +53,7 @@ def load_library():
     lib.tt_emb_forward_eval.argtypes = [c_void_p, c_void_p, c_int64, c_void_p, c_void_p]
     lib.tt_emb_materialize.argtypes = [c_void_p, c_int64, c_int64, c_void_p, c_void_p]
     lib.tt_emb_set_reindex.argtypes = [c_void_p, c_void_p, c_int64]
+    lib.tt_emb_set_adagrad.argtypes = [c_void_p, c_void_p, c_void_p, c_void_p, c_float]
     lib.tt_emb_prepare.argtypes = [c_void_p, c_void_p, c_int64, c_void_p]
     lib.tt_emb_get_stats.argtypes = [c_void_p, POINTER(c_int64), POINTER(c_int64), POINTER(c_int64)]
     lib.tt_emb_profile_enable.argtypes = [c_void_p, c_int]
@@ -64,7 +65,7 @@ def load_library():
     lib.tt_emb_strerror.restype = c_char_p
     for name in ("tt_emb_workspace_bytes", "tt_emb_create", "tt_emb_forward", "tt_emb_prepare",
                  "tt_emb_backward_update", "tt_emb_forward_eval", "tt_emb_materialize",
-                 "tt_emb_set_reindex", "tt_emb_get_stats", "tt_emb_profile_enable",
+                 "tt_emb_set_reindex", "tt_emb_set_adagrad", "tt_emb_get_stats", "tt_emb_profile_enable",
                  "tt_emb_profile_slots", "tt_emb_profile_read", "tt_emb_destroy"):
         getattr(lib, name).restype = c_int
     _lib = lib
@@ -117,6 +118,11 @@ def tt_emb_materialize(h, first_row: int, count: int, out_ptr: int, stream: int)
 
 def tt_emb_set_reindex(h, table_ptr: int, n_ids: int) -> int:
     return load_library().tt_emb_set_reindex(h, c_void_p(table_ptr), c_int64(n_ids))
+
+
+def tt_emb_set_adagrad(h, s1_ptr: int, s2_ptr: int, s3_ptr: int, eps: float) -> int:
+    return load_library().tt_emb_set_adagrad(h, c_void_p(s1_ptr), c_void_p(s2_ptr), c_void_p(s3_ptr),
+                                             c_float(eps))
 
 
 def tt_emb_prepare(h, ids_ptr: int, B: int, stream: int) -> int:
@@ -244,6 +250,19 @@ class TTEmbedding:
             rc = tt_emb_set_reindex(self.handle, new_id_of.data_ptr(), new_id_of.numel())
         if rc:
             raise TTEmbError(rc, "tt_emb_set_reindex")
+
+    def set_adagrad(self, eps: float = 1e-10, enable: bool = True):
+        """Switches backward_update to row-sparse Adagrad (state tensors are created here, zeroed)
+        or back to SGD."""
+        torch = self.torch
+        if not enable:
+            self.adagrad_state = None
+            rc = tt_emb_set_adagrad(self.handle, 0, 0, 0, 0.0)
+        else:
+            self.adagrad_state = [torch.zeros_like(c) for c in self.cores]
+            rc = tt_emb_set_adagrad(self.handle, *(t.data_ptr() for t in self.adagrad_state), eps)
+        if rc:
+            raise TTEmbError(rc, "tt_emb_set_adagrad")
 
     def prepare(self, ids):
         """Index work of the next batch, overlapped with whatever follows on the current stream."""

@@ -27,7 +27,7 @@ void launch_dg3(const Plan&, const Workspace&, const float* grad, int B, hipStre
 void launch_prefix_bwd(const Plan&, const Workspace&, const float* g1, const float* g2, int B,
                        hipStream_t);
 void launch_sgd(const Plan&, const Workspace&, float* g1, float* g2, float* g3, float lr,
-                hipStream_t);
+                const Adagrad&, hipStream_t);
 // matrix-core variants for the shapes mfma_shape() accepts
 bool mfma_shape(const Shape&);
 void launch_prefix_fwd_mfma(const Plan&, const Workspace&, const float* g1, const float* g2, int B,
@@ -204,6 +204,7 @@ struct tt_emb {
   int cur;            // set of the latest forward (and of the backward that follows it)
   float *g1, *g2, *g3;
   const int32_t* reindex;  // old id -> table row applied in front of the split, or nullptr
+  Adagrad ada;             // all null: plain SGD
   int64_t reindex_n;
   int64_t pending_B;  // -1: no forward pending
   int64_t last_B;     // batch size of the latest forward
@@ -310,6 +311,7 @@ int tt_emb_create(tt_emb_t* out, const tt_emb_config* cfg, float* g1, float* g2,
   h->g3 = g3;
   h->reindex = nullptr;
   h->reindex_n = 0;
+  h->ada = Adagrad{nullptr, nullptr, nullptr, 0.f};
   h->pending_B = -1;
   h->last_B = 0;
   h->have_forward = false;
@@ -502,6 +504,16 @@ int tt_emb_materialize(tt_emb_t h, int64_t first_row, int64_t count, float* out,
   return TT_EMB_OK;
 }
 
+int tt_emb_set_adagrad(tt_emb_t h, float* s1, float* s2, float* s3, float eps) {
+  if (h == nullptr) return TT_EMB_EINVAL;
+  const bool none = s1 == nullptr && s2 == nullptr && s3 == nullptr;
+  if (!none && (s1 == nullptr || s2 == nullptr || s3 == nullptr)) return TT_EMB_EINVAL;
+  if ((((uintptr_t)s1 | (uintptr_t)s2 | (uintptr_t)s3) & 15u) != 0) return TT_EMB_EINVAL;
+  if (!none && !(eps > 0.f)) return TT_EMB_EINVAL;
+  h->ada = Adagrad{s1, s2, s3, none ? 0.f : eps};
+  return TT_EMB_OK;
+}
+
 int tt_emb_set_reindex(tt_emb_t h, const int32_t* new_id_of, int64_t n_ids) {
   if (h == nullptr || n_ids < 0 || (new_id_of == nullptr && n_ids != 0)) return TT_EMB_EINVAL;
   if (new_id_of != nullptr && ((uintptr_t)new_id_of & 3u) != 0) return TT_EMB_EINVAL;
@@ -554,7 +566,7 @@ int tt_emb_backward_update(tt_emb_t h, const float* grad_out, float lr, void* hi
     });
     if (rc) return rc;
   }
-  rc = run_slot(h, kSlotSgd, st, [&] { launch_sgd(pl, ws, h->g1, h->g2, h->g3, lr, st); });
+  rc = run_slot(h, kSlotSgd, st, [&] { launch_sgd(pl, ws, h->g1, h->g2, h->g3, lr, h->ada, st); });
   if (rc) return rc;
   if (h->profiling) rc = run_slot(h, kSlotEventPair, st, [] {});
   return rc;

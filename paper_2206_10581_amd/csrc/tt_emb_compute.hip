@@ -272,15 +272,17 @@ __global__ __launch_bounds__(kThreads) void k_prefix_bwd(Shape sh, const float* 
   }
 }
 
-// Adds up the partial gradients of every touched slice and applies the SGD step.
+// Adds up the partial gradients of every touched slice and applies the update: the SGD step, or
+// with ADA the Adagrad step  S += dG^2,  G -= lr * dG / (sqrt(S) + eps)  on the same entries.
 // A job owns up to 256*VEC consecutive entries of one slice (VEC = 4 when slice sizes allow 16-byte
 // accesses, else 1).  Its threads are arranged as `parts` groups side by side on the entries; the
 // job's list of partials (chunks for G3 and G2, prefixes for G1) is dealt round-robin to the
 // groups, whose sums are then added in group order.  parts depends on the slice size only and
 // every group walks its share in list order, so the order of each sum is fixed by the list length.
 // Jobs: n3*cdiv(S3, span) for G3, then n2*cdiv(S2, span) for G2, then n1*cdiv(S1, span) for G1.
-template <int VEC>
-__global__ __launch_bounds__(kThreads) void k_sgd(Shape sh, float lr, float* __restrict__ g1,
+template <int VEC, bool ADA>
+__global__ __launch_bounds__(kThreads) void k_sgd(Shape sh, float lr, Adagrad ada,
+                                                  float* __restrict__ g1,
                                                   float* __restrict__ g2, float* __restrict__ g3,
                                                   const float* __restrict__ part3,
                                                   const int* __restrict__ c3_start,
@@ -299,6 +301,7 @@ __global__ __launch_bounds__(kThreads) void k_sgd(Shape sh, float lr, float* __r
   for (int64_t job = blockIdx.x; job < jobs3 + jobs2 + jobs1; job += gridDim.x) {
     const float* src;  // partial k of the list lives at src + k*S
     float* G;
+    float* St = nullptr;  // Adagrad state of the slice
     int l0, l1, o0, S;
     if (job < jobs3) {
       const int bin = (int)(job / sp3);
@@ -308,6 +311,7 @@ __global__ __launch_bounds__(kThreads) void k_sgd(Shape sh, float lr, float* __r
       src = part3;
       S = sh.S3;
       G = g3 + (size_t)bin * sh.S3;
+      if (ADA) St = ada.s3 + (size_t)bin * sh.S3;
     } else if (job < jobs3 + jobs2) {
       const int64_t j = job - jobs3;
       const int bin = (int)(j / sp2);
@@ -317,6 +321,7 @@ __global__ __launch_bounds__(kThreads) void k_sgd(Shape sh, float lr, float* __r
       src = part2;
       S = sh.S2;
       G = g2 + (size_t)bin * sh.S2;
+      if (ADA) St = ada.s2 + (size_t)bin * sh.S2;
     } else {
       const int64_t j = job - jobs3 - jobs2;
       const int i1 = (int)(j / sp1);
@@ -326,6 +331,7 @@ __global__ __launch_bounds__(kThreads) void k_sgd(Shape sh, float lr, float* __r
       src = dg1part;
       S = sh.S1;
       G = g1 + (size_t)i1 * sh.S1;
+      if (ADA) St = ada.s1 + (size_t)i1 * sh.S1;
     }
     if (l1 == l0) continue;  // slice not touched by this batch (uniform for the block)
     // thread layout: `lanes` threads side by side cover the job's entries, `parts` such groups
@@ -371,7 +377,15 @@ __global__ __launch_bounds__(kThreads) void k_sgd(Shape sh, float lr, float* __r
     }
     if (part == 0 && active) {
 #pragma unroll
-      for (int x = 0; x < VEC; ++x) G[o + x] = fmaf(-lr, acc[x], g_old[x]);
+      for (int x = 0; x < VEC; ++x) {
+        if (ADA) {
+          const float sq = fmaf(acc[x], acc[x], St[o + x]);
+          St[o + x] = sq;
+          G[o + x] = g_old[x] - lr * acc[x] / (sqrtf(sq) + ada.eps);
+        } else {
+          G[o + x] = fmaf(-lr, acc[x], g_old[x]);
+        }
+      }
     }
     if (parts > 1) __syncthreads();
   }
@@ -435,19 +449,22 @@ void launch_prefix_bwd(const Plan& pl, const Workspace& ws, const float* g1, con
 }
 
 void launch_sgd(const Plan& pl, const Workspace& ws, float* g1, float* g2, float* g3, float lr,
-                hipStream_t st) {
+                const Adagrad& ada, hipStream_t st) {
   const Shape& s = pl.sh;
   const bool vec = (s.S1 % 4 == 0) && (s.S2 % 4 == 0) && (s.S3 % 4 == 0);
   const int span = kThreads * (vec ? 4 : 1);
   const int64_t jobs = (int64_t)s.n3 * cdiv(s.S3, span) + (int64_t)s.n2 * cdiv(s.S2, span) +
                        (int64_t)s.n1 * cdiv(s.S1, span);
   const int grid = grid_for(jobs, 1 << 16);
-  if (vec)
-    k_sgd<4><<<grid, kThreads, 0, st>>>(pl.sh, lr, g1, g2, g3, ws.part3, ws.c3_start, ws.part2,
-                                        ws.c2_start, ws.dg1part, ws.g1_first, ws.g1_end, ws.ctr);
-  else
-    k_sgd<1><<<grid, kThreads, 0, st>>>(pl.sh, lr, g1, g2, g3, ws.part3, ws.c3_start, ws.part2,
-                                        ws.c2_start, ws.dg1part, ws.g1_first, ws.g1_end, ws.ctr);
+#define TT_SGD(V, A)                                                                              \
+  k_sgd<V, A><<<grid, kThreads, 0, st>>>(pl.sh, lr, ada, g1, g2, g3, ws.part3, ws.c3_start, ws.part2, \
+                                         ws.c2_start, ws.dg1part, ws.g1_first, ws.g1_end, ws.ctr)
+  if (ada.s1 != nullptr) {
+    if (vec) TT_SGD(4, true); else TT_SGD(1, true);
+  } else {
+    if (vec) TT_SGD(4, false); else TT_SGD(1, false);
+  }
+#undef TT_SGD
 }
 
 }  // namespace ttemb

@@ -35,6 +35,12 @@ struct IdSource {
   int64_t n_ids;
 };
 
+// Optional Adagrad state of the update kernel (all null: plain SGD).
+struct Adagrad {
+  float *s1, *s2, *s3;  // running sums of squared gradients, shaped like the cores
+  float eps;
+};
+
 // Table and slice geometry, passed to kernels by value.
 struct Shape {
   uint32_t n1, n2, n3, N;  // node factors and N = n1*n2*n3

@@ -85,6 +85,11 @@ def test_handle_state_machine_without_launches(lib):
     assert lib.tt_emb_materialize(h, 0, 0, 0, 0) == TT_EMB_ESTATE
     assert lib.tt_emb_set_reindex(h, 256, 5) == TT_EMB_ESTATE
     assert lib.tt_emb_backward_update(h, 0, 0.01, 0) == 0
+    assert lib.tt_emb_set_adagrad(h, 256, 0, 256, 1e-8) == TT_EMB_EINVAL   # all three or none
+    assert lib.tt_emb_set_adagrad(h, 256, 512, 768, 0.0) == TT_EMB_EINVAL  # eps must be positive
+    assert lib.tt_emb_set_adagrad(h, 256, 512, 772, 1e-8) == TT_EMB_EINVAL # misaligned
+    assert lib.tt_emb_set_adagrad(h, 256, 512, 768, 1e-8) == 0
+    assert lib.tt_emb_set_adagrad(h, 0, 0, 0, 0.0) == 0                    # back to SGD
     assert lib.tt_emb_profile_slots() >= 10
     assert lib.tt_emb_profile_read(h, 0)[0] == 0 and lib.tt_emb_profile_read(h, 999)[0] == TT_EMB_EINVAL
     assert lib.tt_emb_destroy(h) == 0

@@ -434,6 +434,52 @@ def test_node_reindexing_table():
     emb.close()
 
 
+def test_adagrad_update_two_steps():
+    """Row-sparse Adagrad as the update rule: two steps with the state carried along, against the
+    oracle's textbook rule; then back to SGD."""
+    torch = _torch()
+    from paper_2206_10581_amd import TTEmbedding
+    for cfg, B in ((1, 256), (2, 12_000)):
+        w, cores, _, _ = _workload(cfg)
+        s = Shape(w.n, w.d, w.r)
+        lr, eps = 0.05, 1e-8
+        emb = TTEmbedding(w.n, w.d, w.r, B, cores)
+        emb.set_adagrad(eps)
+        ref = [c.copy() for c in cores]
+        state = [np.zeros_like(c) for c in cores]
+        for step in range(2):
+            ids, grad = wl.make_ids(w, 60 + step, B), wl.make_grads(w, 60 + step, B)
+            ids[:30] = ids[0]
+            out = emb.forward(torch.from_numpy(ids).cuda())
+            emb.backward_update(torch.from_numpy(grad).cuda(), lr)
+            torch.cuda.synchronize()
+            assert row_error(out.cpu().numpy(), ora.forward(s, *ref, ids)) <= ROW_TOL
+            old = ref
+            ref, state = ora.adagrad_update(s, *ref, state, ids, grad, lr, eps)
+            for k in range(3):
+                got = emb.cores[k].cpu().numpy()
+                assert core_error(got, ref[k]) <= CORE_TOL, (cfg, step, k)
+                # the step itself (at most lr per entry) to 1e-4 of lr, plus the rounding of G
+                slack = 2 * np.finfo(np.float32).eps * np.abs(old[k]).max()
+                assert np.abs((old[k].astype(np.float64) - got) - (old[k].astype(np.float64) - ref[k])).max() \
+                    <= STEP_TOL * lr + slack, (cfg, step, k)
+                st = emb.adagrad_state[k].cpu().numpy()
+                assert core_error(st, state[k]) <= CORE_TOL
+                # entries whose gradient was zero keep core and state bit for bit
+                same = state[k] == 0
+                np.testing.assert_array_equal(got[same], cores[k][same])
+                np.testing.assert_array_equal(st[same], 0.0)
+        emb.set_adagrad(enable=False)
+        ids, grad = wl.make_ids(w, 70, B), wl.make_grads(w, 70, B)
+        emb.forward(torch.from_numpy(ids).cuda())
+        emb.backward_update(torch.from_numpy(grad).cuda(), w.lr)
+        torch.cuda.synchronize()
+        ref2 = ora.backward_update(s, *ref, ids, grad, w.lr)
+        for k in range(3):
+            assert core_error(emb.cores[k].cpu().numpy(), ref2[k]) <= CORE_TOL
+        emb.close()
+
+
 def test_abi_error_codes():
     torch = _torch()
     import paper_2206_10581_amd as lib

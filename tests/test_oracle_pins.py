@@ -327,3 +327,30 @@ def test_f32_build_agrees_with_f64_build():
     b = ora.backward_update(s, *g, ids, grad, w.lr)
     for x, y in zip(a, b):
         np.testing.assert_allclose(x, y, rtol=1e-5, atol=1e-7)
+
+
+def test_adagrad_first_step_moves_every_touched_entry_by_lr():
+    """Textbook special case that pins the Adagrad rule of the oracle without re-typing it: from a
+    zero state and with eps -> 0 the first step is  -lr * dG / |dG| = -lr * sign(dG)  wherever the
+    gradient is nonzero, and nothing moves elsewhere; the state becomes dG^2."""
+    s = Shape((5, 4, 6), (2, 3, 2), (3, 2))
+    rng = np.random.default_rng(5)
+    cores = [rng.standard_normal(cs).astype(np.float32) for cs in s.core_shapes()]
+    ids = np.array([0, 1, 7, 30, 31, 31], dtype=np.int64)    # leaves slices of every core untouched
+    grad = rng.standard_normal((ids.size, s.D)).astype(np.float32)
+    dg = ora.grads(s, *cores, ids, grad)                     # pinned by the finite-difference tests
+    zero = [np.zeros_like(c) for c in cores]
+    lr = 0.125
+    new, state = ora.adagrad_update(s, *cores, zero, ids, grad, lr, 1e-30)
+    for G, Gn, S, d in zip(cores, new, state, dg):
+        moved = d != 0
+        assert moved.any() and (~moved).any()
+        np.testing.assert_array_equal(Gn[~moved], G[~moved])
+        np.testing.assert_allclose(Gn[moved], (G.astype(np.float64) - lr * np.sign(d))[moved], rtol=2e-7)
+        np.testing.assert_allclose(S, (d * d).astype(np.float32), rtol=1e-6)
+    # a second step from that state with the same gradient would move by lr/sqrt(2): the state adds up
+    new2, _ = ora.adagrad_update(s, *cores, state, ids, grad, lr, 1e-30)
+    for G, Gn, d in zip(cores, new2, dg):
+        moved = np.abs(d) > 1e-3
+        np.testing.assert_allclose((G.astype(np.float64) - Gn)[moved],
+                                   (lr / np.sqrt(2.0) * np.sign(d))[moved], rtol=1e-5)
