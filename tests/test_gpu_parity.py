@@ -480,6 +480,58 @@ def test_adagrad_update_two_steps():
         emb.close()
 
 
+def test_side_stream_and_graph_replays():
+    """The calls only enqueue on the stream they are given: a step on a non-default stream, and a step
+    captured into a HIP graph and replayed three times (eager work and synchronisation between the
+    replays), give bit for bit what the eager default-stream step gives."""
+    torch = _torch()
+    from paper_2206_10581_amd import TTEmbedding
+    w, cores, ids, grad = _workload(2, batch=20_000)
+    ids[:500] = ids[0]
+    t_ids, t_grad = torch.from_numpy(ids).cuda(), torch.from_numpy(grad).cuda()
+    emb = TTEmbedding(w.n, w.d, w.r, ids.size, cores)
+    snap = [c.clone() for c in emb.cores]
+    out_ref = emb.forward(t_ids).clone()
+    emb.backward_update(t_grad, w.lr)
+    torch.cuda.synchronize()
+    cores_ref = [c.clone() for c in emb.cores]
+
+    def restore():
+        for c, b in zip(emb.cores, snap):
+            c.copy_(b)
+
+    side = torch.cuda.Stream()
+    restore()
+    torch.cuda.synchronize()
+    with torch.cuda.stream(side):
+        out_s = emb.forward(t_ids)
+        emb.backward_update(t_grad, w.lr)
+    side.synchronize()
+    assert torch.equal(out_s, out_ref)
+    for x, y in zip(emb.cores, cores_ref):
+        assert torch.equal(x, y)
+
+    restore()
+    out_g = torch.empty_like(out_ref)
+    torch.cuda.synchronize()
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph):
+        emb.forward(t_ids, out_g)
+        emb.backward_update(t_grad, w.lr)
+    for replay in range(3):
+        restore()
+        out_g.fill_(-1.0)
+        torch.cuda.synchronize()
+        graph.replay()
+        torch.cuda.synchronize()
+        assert torch.equal(out_g, out_ref), f"replay {replay}"
+        for x, y in zip(emb.cores, cores_ref):
+            assert torch.equal(x, y), f"replay {replay}"
+        scratch = (out_g * 2).sum().item()          # eager work between the replays
+        assert np.isfinite(scratch)
+    emb.close()
+
+
 def test_abi_error_codes():
     torch = _torch()
     import paper_2206_10581_amd as lib
