@@ -88,8 +88,8 @@ def main() -> int:
                     help="do not overlap the index work of coming steps with this step's arithmetic")
     args = ap.parse_args()
     if args.gpus != 1:
-        print("bench.py: this build runs on ONE GPU (replicated-core data parallelism is described "
-              "in DESIGN.md, not built); run with --gpus 1", file=sys.stderr)
+        print("bench.py: this build runs on ONE GPU (the paper's scheme for more, replicated cores and "
+              "an all-reduce of the core gradients, is not built); run with --gpus 1", file=sys.stderr)
         return 2
 
     import numpy as np
