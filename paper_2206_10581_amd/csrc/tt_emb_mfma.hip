@@ -75,25 +75,33 @@ __device__ __forceinline__ void stream_load(const float* src, float* v) {
 
 // ---------------------------------------------------------------------------------------------
 // P_q = G1[i1] G2[i2] for the <= 16 prefixes of one by-i2 chunk: rows of up to eight G1 slices
-// stacked (32 x R) times the chunk's G2 slice (R x 4R).  A work unit is (chunk, half of the 4R
+// stacked (32 x R) times the chunk's G2 slice (R x 4R).  A work unit is (chunk, a share of the 4R
 // output columns); one single-wavefront block per unit, so that the units spread evenly over all
 // SIMDs.
-constexpr int kPfUnits = 2;  // units per chunk in the forward prefix kernel
+// Units per chunk: two or four side by side over the 32-column tiles of the product (four shorten
+// the kernel at rank 32 by a fifth; splitting the sixteen prefixes of a chunk over units as well
+// only re-reads the G2 slice, which costs more than it gains).
+constexpr int pf_units(int R) { return R >= 32 ? 4 : 2; }
 
 template <int R>
 __global__ __launch_bounds__(kWave) void k_prefix_fwd_mfma(
     const float* __restrict__ g1, const float* __restrict__ g2, const int4* __restrict__ c2_item,
     const int4* __restrict__ c2_desc, float* __restrict__ P, const Counters* __restrict__ ctr) {
   constexpr int W = 4 * R, PN = 16 * R, S1 = 4 * R, S2 = R * W, KH = R / 2, NT = W / 32;
-  constexpr int NTH = NT / kPfUnits;  // column tiles of one unit
+  constexpr int kPfUnits = pf_units(R);
+  constexpr int UC = kPfUnits < NT ? kPfUnits : NT;  // units side by side over the columns
+  constexpr int UM = kPfUnits / UC;                  // 1: both row tiles in one unit, 2: one each
+  constexpr int NTH = NT / UC, MTH = 2 / UM;         // column and row tiles of one unit
   const int lane = threadIdx.x, half = lane / 32, l32 = lane % 32;
   const int unit = blockIdx.x;
-  const int c = unit / kPfUnits, nt0 = (unit % kPfUnits) * NTH;
+  const int c = unit / kPfUnits, sub = unit % kPfUnits;
+  const int nt0 = (sub / UM) * NTH, mt0 = (sub % UM) * MTH;
   // the chunk's records and descriptor are read together (the grid never exceeds the tables)
   const int4 item = c2_item[(size_t)c * kChunk2 + lane % kChunk2];
   const int4 desc = c2_desc[c];
   if (c >= ctr->nchunk2) return;
   const int bin = desc.x, cnt = desc.z;
+  if (mt0 * 8 >= cnt) return;  // the chunk has no prefix in this unit's row tile
   const float* Bm = g2 + (size_t)bin * S2 + (size_t)(KH * half) * W + nt0 * 32 + l32;
   float b[NTH][KH];
 #pragma unroll
@@ -103,10 +111,10 @@ __global__ __launch_bounds__(kWave) void k_prefix_fwd_mfma(
   const bool mine = lane < cnt;  // records past the chunk's count are unwritten
   const int myq = mine ? item.x : -1;
   const int myi1 = mine ? item.y : 0;
-  float a[2][KH];
+  float a[MTH][KH];
 #pragma unroll
-  for (int mt = 0; mt < 2; ++mt) {
-    const int ql = mt * 8 + l32 / 4, j1 = l32 % 4;
+  for (int mt = 0; mt < MTH; ++mt) {
+    const int ql = (mt0 + mt) * 8 + l32 / 4, j1 = l32 % 4;
     const int q = __shfl(myq, ql), i1 = __shfl(myi1, ql);
     const f4* src = (const f4*)(g1 + (size_t)i1 * S1 + j1 * R + KH * half);
 #pragma unroll
@@ -118,17 +126,17 @@ __global__ __launch_bounds__(kWave) void k_prefix_fwd_mfma(
       a[mt][4 * j + 3] = q >= 0 ? v.w : 0.f;
     }
   }
-  int qrow[2][4];  // prefix of accumulator rows v/4 of each row tile
+  int qrow[MTH][4];  // prefix of accumulator rows v/4 of each row tile
 #pragma unroll
-  for (int mt = 0; mt < 2; ++mt)
+  for (int mt = 0; mt < MTH; ++mt)
 #pragma unroll
-    for (int x = 0; x < 4; ++x) qrow[mt][x] = __shfl(myq, mt * 8 + 2 * x + half);
+    for (int x = 0; x < 4; ++x) qrow[mt][x] = __shfl(myq, (mt0 + mt) * 8 + 2 * x + half);
   TT_LOADS_DONE();
 #pragma unroll
   for (int t = 0; t < NTH; ++t) {
 #pragma unroll
-    for (int mt = 0; mt < 2; ++mt) {
-      if (mt * 8 >= cnt) break;
+    for (int mt = 0; mt < MTH; ++mt) {
+      if ((mt0 + mt) * 8 >= cnt) break;
       f16v acc = TT_ZERO16;
 #pragma unroll
       for (int j = 0; j < KH; ++j) acc = mfma32(a[mt][j], b[t][j], acc);
@@ -924,7 +932,7 @@ void launch_prefix_fwd_mfma(const Plan& pl, const Workspace& ws, const float* g1
                             int B, hipStream_t st) {
   // one block per possible work unit (upper bound from B); blocks past the real count return at once
   const int64_t chunks = cdivi(std::min<int64_t>(B, pl.maxQ), kChunk2) + pl.sh.n2;
-  const int grid = (int)(chunks * kPfUnits);
+  const int grid = (int)(chunks * pf_units(pl.sh.r1));
   TT_DISPATCH_R(pl.sh.r1, (k_prefix_fwd_mfma<R><<<grid, kWave, 0, st>>>(
                               g1, g2, ws.c2_item, ws.c2_desc, ws.P, ws.ctr)));
 }
