@@ -42,7 +42,6 @@ bool mfma_fused_mid(const Shape&);
 void launch_bwd_mid_mfma(const Plan&, const Workspace&, const float* g1, const float* g2,
                          const float* g3, const float* grad, int B, hipStream_t);
 void launch_gsum_block(const Plan&, const Workspace&, const float* grad, int B, hipStream_t);
-void launch_gsum_block_fix(const Plan&, const Workspace&, int B, hipStream_t);
 
 static const char* const kSlotNames[kSlotCount] = {
     "sort_hist", "sort_scan", "sort_scatter", "seg_count", "seg_write",  "group",
@@ -540,11 +539,10 @@ int tt_emb_backward_update(tt_emb_t h, const float* grad_out, float lr, void* hi
     else launch_gsum(pl, ws, grad_out, B, st);
   });
   if (rc) return rc;
-  rc = run_slot(h, kSlotGsumFix, st, [&] {
-    if (h->mfma) launch_gsum_block_fix(pl, ws, B, st);
-    else launch_gsum_fix(pl, ws, B, st);
-  });
-  if (rc) return rc;
+  if (!h->mfma) {  // the matrix-core path sums in blocks of kEntrySlots slots: nothing crosses them
+    rc = run_slot(h, kSlotGsumFix, st, [&] { launch_gsum_fix(pl, ws, B, st); });
+    if (rc) return rc;
+  }
   if (h->mfma && mfma_fused_mid(pl.sh)) {
     // ranks up to 32: per-id and per-prefix gradient steps in one launch
     rc = run_slot(h, kSlotUBwd, st,
@@ -584,7 +582,7 @@ int tt_emb_get_stats(tt_emb_t h, int64_t* U, int64_t* Q, int64_t* out_of_range) 
     if (e != hipSuccess) return hip_fail(e);
     oob = h->last_B - (int64_t)c.nvalid;
   }
-  if (U) *U = c.U;
+  if (U) *U = c.U - c.n_split;
   if (Q) *Q = c.Q;
   if (out_of_range) *out_of_range = oob;
   if (c.err != 0) return TT_EMB_EINTERNAL;

@@ -322,7 +322,10 @@ __global__ __launch_bounds__(kSortThreads) void k_sort_hist(
     for (int i = gtid; i < zero_a_n; i += gn) zero_a[i] = 0u;
     for (int i = gtid; i < zero_b_n; i += gn) zero_b[i] = 0u;
     for (int i = gtid; i < zero_c_n; i += gn) zero_c[i] = 0u;
-    if (gtid == 0) ctr->err = 0;
+    if (gtid == 0) {
+      ctr->err = 0;
+      ctr->n_split = 0;
+    }
   }
   for (int i = tid; i < bins; i += kSortThreads) h[i] = 0u;
   __syncthreads();
@@ -389,7 +392,7 @@ __global__ __launch_bounds__(kScanThreads) void k_sort_colscan(uint32_t* __restr
 
 struct SegFlags {
   uint32_t key[4], prev[4];
-  bool valid[4], newu[4], newq[4], last_valid[4], single[4];
+  bool valid[4], newu[4], newq[4], last_valid[4], single[4], split[4];
 };
 
 __device__ __forceinline__ SegFlags seg_flags(const uint32_t* __restrict__ skey, int B, uint32_t N,
@@ -409,10 +412,14 @@ __device__ __forceinline__ SegFlags seg_flags(const uint32_t* __restrict__ skey,
     f.prev[j] = prev;
     f.valid[j] = (s < B) && (key < N);
     const bool first = (s == 0);
-    f.newu[j] = f.valid[j] && (first || key != prev);
+    // a new entry: a new id, or the next kEntrySlots piece of a long run of one id
+    const bool cut = (s % kEntrySlots) == 0;
+    f.newu[j] = f.valid[j] && (first || key != prev || cut);
+    f.split[j] = f.valid[j] && !first && key == prev && cut;
     f.newq[j] = f.valid[j] && (first || (key / n3) != (prev / n3));
     f.last_valid[j] = f.valid[j] && !(next < N);
-    f.single[j] = f.newu[j] && next != key;  // the id occurs exactly once in the batch
+    // the entry holds exactly one slot: its gradient row is read where it lies
+    f.single[j] = f.newu[j] && (next != key || ((s + 1) % kEntrySlots) == 0);
   }
   return f;
 }
@@ -494,6 +501,7 @@ __global__ __launch_bounds__(kSegThreads) void k_seg_write(
     const int u = (int)ru - 1, q = (int)rq - 1;
     s_u[s] = u;
     const uint32_t k = f.key[j];
+    if (f.split[j]) atomicAdd(&ctr->n_split, 1);
     if (f.newu[j]) {
       const uint32_t i3 = k % sh.n3;
       u_rs[u] = s;

@@ -20,6 +20,13 @@ constexpr int kFoldRows = 16;       // histogram rows a thread keeps in flight w
 constexpr int kFoldScanBlocks = 8;  // sort passes with at most this many blocks need no column-scan launch
 constexpr int kMaxBins = 2048;                            // digit / bucket count limit per pass
 
+// The unit of the gradient sums: a run of equal ids is cut at every multiple of kEntrySlots sorted
+// slots, and each piece ("entry") is carried through the backward pass like an id of its own - all
+// gradient steps are linear in the row gradient, so the pieces of an id simply add up in the same
+// matrix-core accumulations that add up the ids of a prefix or of an i3 group.  A block of the
+// gradient-sum kernel owns kEntrySlots slots, so no sum ever crosses a block.
+constexpr int kEntrySlots = 1024;
+
 constexpr int kSegThreads = 256;
 constexpr int kSegItems = 1024;  // sorted slots per block in the segment kernels (4 per thread)
 
@@ -56,12 +63,13 @@ struct Shape {
 
 // Device-side counters of the latest forward (first bytes of the workspace).
 struct Counters {
-  int U;        // distinct in-range ids
+  int U;        // entries: distinct in-range ids, long runs counted once per kEntrySlots piece
   int Q;        // distinct (i1,i2) prefixes
   int nvalid;   // in-range batch positions (they occupy sorted slots [0, nvalid))
   int nchunk3;  // partial-sum chunks over the by-i3 grouping of unique ids
   int nchunk2;  // partial-sum chunks over the by-i2 grouping of unique prefixes
   int err;      // nonzero: a kernel met an impossible index (bit mask of sites)
+  int n_split;  // entries beyond the first of their id (U - n_split distinct ids)
   unsigned long long* trace;  // debugging builds (TT_EMB_TRACE): per-wavefront time stamps
 };
 

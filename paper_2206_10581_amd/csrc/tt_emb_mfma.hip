@@ -723,11 +723,12 @@ __global__ __launch_bounds__(kMThreads) void k_row_fwd_mfma(
 // its slots (32 at a time, all loads in flight together), adds them up run by run in slot order,
 // and finishes the runs that lie inside its 64 slots; ids that occur once are skipped, later
 // kernels read their row from grad_out directly.  Pieces of runs that cross wavefronts are joined
-// in LDS, pieces that cross blocks leave one partial per block in carry[block][h] (h = 0: the run
-// began in an earlier block, h = 1: it begins here and continues).
+// in LDS.  No run crosses a block: the index pipeline cuts long runs of one id into entries at
+// every multiple of kEntrySlots slots, which is the block size here.
 constexpr int kGsumWaves = 16;
 constexpr int kGsumThreads = kGsumWaves * kWave;
 constexpr int kGsumBlockSlots = kGsumWaves * kWave;  // 1024
+static_assert(kGsumBlockSlots == kEntrySlots, "a block must own exactly one entry span");
 
 template <int VPL>
 struct LaneVec {
@@ -738,8 +739,7 @@ template <int VPL>
 __global__ __launch_bounds__(kGsumThreads) void k_gsum_block(int B, const float* __restrict__ grad,
                                                           const int* __restrict__ s_u,
                                                           const uint32_t* __restrict__ perm,
-                                                          float* __restrict__ gsum,
-                                                          float* __restrict__ carry, Counters* ctr) {
+                                                          float* __restrict__ gsum, Counters* ctr) {
   constexpr int D = kWave * VPL;
   __shared__ float part[kGsumWaves][2][D];  // [wave][0 = head piece, 1 = tail piece]
   __shared__ int head_state[kGsumWaves];    // 0 none, 1 head piece ends in this wave, 2 it runs through
@@ -837,65 +837,12 @@ __global__ __launch_bounds__(kGsumThreads) void k_gsum_block(int B, const float*
         for (int x = 0; x < VPL; ++x) t.v[x] += part[k][0][lane * VPL + x];
         if (head_state[k] == 1) open = false;
       }
-      float* o = open ? carry + ((size_t)bt * 2 + 1) * D : gsum + (size_t)tail_u[w] * D;
-#pragma unroll
-      for (int x = 0; x < VPL; ++x) o[lane * VPL + x] = t.v[x];
-    }
-    // (b) the run that came in from an earlier block
-    if (w == 0 && head_state[0] != 0) {
-      LaneVec<VPL> t;
-#pragma unroll
-      for (int x = 0; x < VPL; ++x) t.v[x] = part[0][0][lane * VPL + x];
-      for (int k = 1; k < kGsumWaves && head_state[k - 1] == 2; ++k) {
-        if (head_state[k] == 0) break;
-#pragma unroll
-        for (int x = 0; x < VPL; ++x) t.v[x] += part[k][0][lane * VPL + x];
-      }
-      float* o = carry + ((size_t)bt * 2) * D;
+      if (open && lane == 0) atomicOr(&ctr->err, 16);  // a run left the block: entries never do
+      float* o = gsum + (size_t)tail_u[w] * D;
 #pragma unroll
       for (int x = 0; x < VPL; ++x) o[lane * VPL + x] = t.v[x];
     }
     __syncthreads();
-  }
-}
-
-// The block in which a block-crossing run begins adds up that run's per-block partials in order.
-template <int VPL>
-__global__ __launch_bounds__(kWave) void k_gsum_block_fix(const int* __restrict__ s_u,
-                                                          const int* __restrict__ u_rs,
-                                                          const float* __restrict__ carry,
-                                                          float* __restrict__ gsum,
-                                                          const Counters* __restrict__ ctr) {
-  constexpr int D = kWave * VPL;
-  const int nvalid = ctr->nvalid, lane = threadIdx.x;
-  const int nbt = (nvalid + kGsumBlockSlots - 1) / kGsumBlockSlots;
-  for (int bt = blockIdx.x; bt < nbt; bt += gridDim.x) {
-    const int t0 = bt * kGsumBlockSlots, t1 = t0 + kGsumBlockSlots;
-    const int u = s_u[min(t1, nvalid) - 1];
-    const int rs = u_rs[u], re = u_rs[u + 1];
-    if (rs < t0 || re <= t1) continue;
-    const int last = (re - 1) / kGsumBlockSlots;
-    LaneVec<VPL> t;
-#pragma unroll
-    for (int x = 0; x < VPL; ++x) t.v[x] = carry[((size_t)bt * 2 + 1) * D + lane * VPL + x];
-    int k = bt + 1;
-    for (; k + 8 <= last + 1; k += 8) {
-      LaneVec<VPL> c[8];
-#pragma unroll
-      for (int j = 0; j < 8; ++j)
-#pragma unroll
-        for (int x = 0; x < VPL; ++x) c[j].v[x] = carry[((size_t)(k + j) * 2) * D + lane * VPL + x];
-      __builtin_amdgcn_sched_barrier(0);
-#pragma unroll
-      for (int j = 0; j < 8; ++j)
-#pragma unroll
-        for (int x = 0; x < VPL; ++x) t.v[x] += c[j].v[x];
-    }
-    for (; k <= last; ++k)
-#pragma unroll
-      for (int x = 0; x < VPL; ++x) t.v[x] += carry[((size_t)k * 2) * D + lane * VPL + x];
-#pragma unroll
-    for (int x = 0; x < VPL; ++x) gsum[(size_t)u * D + lane * VPL + x] = t.v[x];
   }
 }
 
@@ -988,17 +935,9 @@ void launch_gsum_block(const Plan& pl, const Workspace& ws, const float* grad, i
   const int grid = grid_cap(cdivi(B, kGsumBlockSlots), kMGridCap);
   const uint32_t* perm = ws.val[(pl.passes - 1) & 1];
   if (pl.sh.D == 64)
-    k_gsum_block<1><<<grid, kGsumThreads, 0, st>>>(B, grad, ws.s_u, perm, ws.gsum, ws.carry, ws.ctr);
+    k_gsum_block<1><<<grid, kGsumThreads, 0, st>>>(B, grad, ws.s_u, perm, ws.gsum, ws.ctr);
   else
-    k_gsum_block<2><<<grid, kGsumThreads, 0, st>>>(B, grad, ws.s_u, perm, ws.gsum, ws.carry, ws.ctr);
-}
-
-void launch_gsum_block_fix(const Plan& pl, const Workspace& ws, int B, hipStream_t st) {
-  const int grid = grid_cap(cdivi(B, kGsumBlockSlots), kMGridCap);
-  if (pl.sh.D == 64)
-    k_gsum_block_fix<1><<<grid, kWave, 0, st>>>(ws.s_u, ws.u_rs, ws.carry, ws.gsum, ws.ctr);
-  else
-    k_gsum_block_fix<2><<<grid, kWave, 0, st>>>(ws.s_u, ws.u_rs, ws.carry, ws.gsum, ws.ctr);
+    k_gsum_block<2><<<grid, kGsumThreads, 0, st>>>(B, grad, ws.s_u, perm, ws.gsum, ws.ctr);
 }
 
 }  // namespace ttemb

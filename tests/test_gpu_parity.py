@@ -158,6 +158,23 @@ def test_duplicates_out_of_range_and_one_hot_id():
     assert not out[(ids < 0) | (ids >= w.N)].any()
 
 
+@pytest.mark.parametrize("flags", [0, 2])
+def test_long_runs_cut_at_block_boundaries(flags):
+    """Runs of one id longer than the 1024-slot unit of the gradient sums are carried as several
+    pieces; the counts still name distinct ids, and pieces of one slot, runs that end exactly on a
+    boundary and a run that covers whole units all add up to the oracle's gradient."""
+    w, cores, _, _ = _workload(2)
+    # sorted order: id 7 x 1023 | id 9 x 1 (slot 1023) | id 11 x 2049 (slots 1024..3072: two whole
+    # units and one slot) | id 500 x 1023 (ends exactly at slot 4096) | id 501 x 1025 | ids above
+    ids = np.concatenate([np.full(1023, 7), np.full(1, 9), np.full(2049, 11), np.full(1023, 500),
+                          np.full(1025, 501), 600 + np.arange(300)]).astype(np.int64)
+    rng = np.random.default_rng(21)
+    rng.shuffle(ids)
+    grad = rng.standard_normal((ids.size, w.D)).astype(np.float32)
+    _, _, stats = check_against_oracle(w.n, w.d, w.r, cores, ids, grad, w.lr, flags=flags)
+    assert stats["U"] == 305
+
+
 def test_all_ids_out_of_range_and_empty_batch():
     w, cores, _, _ = _workload(1)
     ids = np.array([-5, w.N, w.N + 1], dtype=np.int64)
