@@ -14,9 +14,9 @@ instructions, and the cores stay where they are for hundreds of steps.  `--resto
 protocol instead: the workload's own learning rate, with the cores put back from a snapshot by one
 device-side copy per step inside the timed region (extra work, counted against the rate).
 
-Prints ONE JSON line.  `roofline` describes the kernel with the largest share of the step, timed
-with HIP events on its own stream by the library's profiling hook in a separate, untimed leg;
-`cpu_baseline` is the CPU oracle (fp32 build, OpenMP) on a prefix of the same batch.
+Prints ONE JSON line.  `roofline` describes the longest launch of the step, timed with HIP events
+on its own stream by the library's profiling hook in a separate, untimed leg (an empty event pair
+is timed too and taken off); `cpu_baseline` is the CPU oracle (fp32 build, OpenMP) on the same batch.
 """
 from __future__ import annotations
 
@@ -37,8 +37,8 @@ FP32_PEAK = 157.3e12     # flop/s, MI355X fp32 (vector with packed ops, or fp32 
 # WRITE_SIZE) scaled by the readings for a plain 256 MiB device copy in the same process; the table
 # and the commands are in profiles/step_config3_hbm_traffic.md.  Only the default workload was
 # measured; for anything else `traffic` is null.
-MEASURED_TRAFFIC = {3: {"row_fwd": 41.3e6 + 102.4e6, "gsum": 85.4e6 + 4.8e6, "u_bwd": 155.1e6 + 29.8e6,
-                        "prefix_fwd": 10.4e6 + 34.8e6, "sgd": 32.4e6 + 2.4e6}}
+MEASURED_TRAFFIC = {3: {"row_fwd": 41.4e6 + 102.4e6, "gsum": 85.4e6 + 4.8e6, "u_bwd": 155.4e6 + 29.8e6,
+                        "prefix_fwd": 6.5e6 + 34.8e6, "sgd": 32.4e6 + 2.4e6}}
 
 
 def kernel_work(slot: str, w, B: int, U: int, Q: int, touched_bytes: int, passes: int):
@@ -207,7 +207,8 @@ def main() -> int:
         print(json.dumps(line))
         emb.close()
         return 0
-    dom = max(kernels, key=lambda k: kernels[k]["us_per_step"])
+    # the dominant kernel: the longest single launch of the step
+    dom = max(kernels, key=lambda k: kernels[k]["us_per_step"] / kernels[k]["launches_per_step"])
     kd = kernels[dom]
     launch_s = kd["us_per_step"] * 1e-6 / kd["launches_per_step"]
     by = kd["alg_bytes"] / kd["launches_per_step"]
