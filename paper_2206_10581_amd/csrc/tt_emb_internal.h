@@ -17,7 +17,7 @@ constexpr int kSortWaves = 16;
 constexpr int kSortWaveItems = 256;
 constexpr int kSortItems = kSortWaves * kSortWaveItems;  // 4096 items per block
 constexpr int kFoldRows = 16;       // histogram rows a thread keeps in flight while it adds up a column
-constexpr int kFoldScanBlocks = 8;  // sort passes with at most this many blocks need no column-scan launch
+constexpr int kFoldScanBlocks = 16;  // sort passes with at most this many blocks need no column-scan launch
 constexpr int kMaxBins = 2048;                            // digit / bucket count limit per pass
 
 // The unit of the gradient sums: a run of equal ids is cut at every multiple of kEntrySlots sorted
