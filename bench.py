@@ -122,7 +122,8 @@ def main() -> int:
     ids = torch.from_numpy(ids_np).to(dev)
     grad = torch.from_numpy(grad_np).to(dev)
     out = torch.empty((B, D), dtype=torch.float32, device=dev)
-    emb = TTEmbedding(w.n, w.d, w.r, B, cores, device=dev)
+    # the ids are resident before the timed region starts: TT_EMB_FLAG_IDS_READY (4)
+    emb = TTEmbedding(w.n, w.d, w.r, B, cores, device=dev, flags=4)
 
     lr = w.lr if args.restore else args.lr
 

@@ -25,7 +25,7 @@
  * borrows it and never allocates or frees device memory.  Cores, out and grad_out must be 16-byte
  * aligned, ids 8-byte aligned (TT_EMB_EINVAL otherwise).  The handle owns host bookkeeping only.
  * All calls are asynchronous on the given HIP stream unless stated otherwise (tt_emb_prepare also
- * uses three internal streams of default priority, created on its first call).  A handle must not
+ * uses four internal streams of default priority, created on its first call).  A handle must not
  * be used from two threads or two streams at once.
  *
  * Errors.  Every function returns TT_EMB_OK (0) or a negative code and never aborts.
@@ -54,6 +54,11 @@ enum {
 
 enum {
   TT_EMB_FLAG_CHECK_RANGE = 1u,    /* get_stats returns TT_EMB_ERANGE when an id was out of range */
+  TT_EMB_FLAG_IDS_READY = 4u,      /* the ids given to tt_emb_prepare are complete in device memory
+                                      when the call is made: the library then need not order its
+                                      index stream after what hip_stream holds, only after its own
+                                      earlier use of the index set (a pipeline can start a step
+                                      earlier, and the caller's stream carries one event less)  */
   TT_EMB_FLAG_GENERIC_KERNELS = 2u /* use the any-shape vector-ALU kernels even for shapes that
                                       have matrix-core kernels (d1 = d2 = 4, r1 = r2 in
                                       {16,32,64}, d3 in {4,8}); for comparison and testing       */
@@ -132,9 +137,9 @@ int tt_emb_set_adagrad(tt_emb_t h, float* s1, float* s2, float* s3, float eps);
  * of the library's own that starts once everything enqueued so far on hip_stream has run.  A later
  * tt_emb_forward with the same ids pointer and the same B finds them ready, waits for them on its
  * own stream and skips that work (the oldest such batch if two match); a prepared batch that no
- * forward asks for is eventually overwritten (the oldest first).  The workspace holds three index
- * sets, each with a stream of its own: one may be in use by a forward/backward pair while the other
- * two are filled, so up to two batches can be ahead, and an index pipeline that is started two steps
+ * forward asks for is eventually overwritten (the oldest first).  The workspace holds four index
+ * sets, each with a stream of its own: one may be in use by a forward/backward pair while two
+ * others are filled, so up to two batches can be ahead, and an index pipeline that is started two steps
  * early has two steps to finish.  Typical use, once per step and before the forward of the current
  * batch: prepare(ids of the batch after next); forward(ids); ...; backward_update(...) - the index
  * work of coming batches then overlaps this batch's arithmetic (minibatch samplers know the next

@@ -16,6 +16,7 @@ TT_EMB_OK, TT_EMB_EINVAL, TT_EMB_ENOSPC, TT_EMB_ESTATE, TT_EMB_EHIP, TT_EMB_ERAN
     TT_EMB_EINTERNAL = 0, -1, -2, -3, -4, -5, -6
 TT_EMB_FLAG_CHECK_RANGE = 1
 TT_EMB_FLAG_GENERIC_KERNELS = 2
+TT_EMB_FLAG_IDS_READY = 4
 
 
 class TTEmbConfig(ctypes.Structure):

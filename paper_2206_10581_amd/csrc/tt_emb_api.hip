@@ -111,9 +111,10 @@ static int make_plan(const tt_emb_config* c, Plan* pl) {
   return TT_EMB_OK;
 }
 
-// Index sets: one serves the forward/backward pair in flight while tt_emb_prepare fills the others
-// for the next two batches (each on a stream of its own, so a pipeline has two steps to finish).
-constexpr int kSets = 3;
+// Index sets: one serves the forward/backward pair in flight, two hold the batches prepared ahead,
+// and the one that has been idle longest is the next to be filled (each set has a stream of its
+// own, so a pipeline has two steps to finish and need not wait for the step that has just ended).
+constexpr int kSets = 4;
 
 // Walks the workspace layout; with base == nullptr only the size is computed.  The index arrays
 // exist kSets times; the arithmetic buffers are shared.
@@ -212,6 +213,8 @@ struct tt_emb {
   // tt_emb_prepare: index pipelines of coming batches on a stream of the library's own
   hipStream_t side[kSets];  // one per index set, created on first use, default priority
   hipEvent_t ev_fork;   // recorded on the caller's stream, awaited by side
+  hipEvent_t done[kSets];   // recorded on the caller's stream after the last kernel that reads the set
+  bool done_valid[kSets];   // done[s] covers the latest use of set s
   struct Prepared {
     bool valid;         // this index set holds a batch that no forward has consumed yet
     const int64_t* ids;
@@ -303,6 +306,10 @@ int tt_emb_create(tt_emb_t* out, const tt_emb_config* cfg, float* g1, float* g2,
   h->cur = 0;
   for (int i = 0; i < kSets; ++i) h->side[i] = nullptr;
   h->ev_fork = nullptr;
+  for (int i = 0; i < kSets; ++i) {
+    h->done[i] = nullptr;
+    h->done_valid[i] = false;
+  }
   h->prep_seq = 0;
   for (int i = 0; i < kSets; ++i) h->prep[i] = tt_emb::Prepared{false, nullptr, 0, 0, nullptr};
   h->g1 = g1;
@@ -363,6 +370,8 @@ int tt_emb_prepare(tt_emb_t h, const int64_t* ids, int64_t B64, void* hip_stream
       if (e != hipSuccess) return hip_fail(e);
       e = hipEventCreateWithFlags(&h->prep[i].ready, hipEventDisableTiming);
       if (e != hipSuccess) return hip_fail(e);
+      e = hipEventCreateWithFlags(&h->done[i], hipEventDisableTiming);
+      if (e != hipSuccess) return hip_fail(e);
     }
     e = hipEventCreateWithFlags(&h->ev_fork, hipEventDisableTiming);
     if (e != hipSuccess) return hip_fail(e);
@@ -384,10 +393,16 @@ int tt_emb_prepare(tt_emb_t h, const int64_t* ids, int64_t B64, void* hip_stream
   h->prep[target].valid = false;
   // everything that used this set earlier (its backward_update, or an index pipeline that is now
   // dropped) is ordered before: the set's stream is in order, and the fork event covers hip_stream
-  e = hipEventRecord(h->ev_fork, st);
-  if (e != hipSuccess) return hip_fail(e);
-  e = hipStreamWaitEvent(h->side[target], h->ev_fork, 0);
-  if (e != hipSuccess) return hip_fail(e);
+  if ((h->cfg.flags & TT_EMB_FLAG_IDS_READY) && h->done_valid[target]) {
+    // the ids are in memory already: only the set's own last use has to be over
+    e = hipStreamWaitEvent(h->side[target], h->done[target], 0);
+    if (e != hipSuccess) return hip_fail(e);
+  } else {
+    e = hipEventRecord(h->ev_fork, st);
+    if (e != hipSuccess) return hip_fail(e);
+    e = hipStreamWaitEvent(h->side[target], h->ev_fork, 0);
+    if (e != hipSuccess) return hip_fail(e);
+  }
   int rc = run_index(h, target, IdSource{ids, 0, h->reindex, h->reindex_n}, (int)B64,
                      h->side[target]);
   if (rc) return rc;
@@ -401,6 +416,16 @@ int tt_emb_prepare(tt_emb_t h, const int64_t* ids, int64_t B64, void* hip_stream
 }
 
 }  // extern "C"
+
+// Records that everything that reads index set cur has been enqueued on st (only once
+// tt_emb_prepare is in use with TT_EMB_FLAG_IDS_READY: that is who waits for it).
+static int mark_set_done(tt_emb* h, hipStream_t st) {
+  if (h->done[h->cur] == nullptr || !(h->cfg.flags & TT_EMB_FLAG_IDS_READY)) return TT_EMB_OK;
+  hipError_t e = hipEventRecord(h->done[h->cur], st);
+  if (e != hipSuccess) return hip_fail(e);
+  h->done_valid[h->cur] = true;
+  return TT_EMB_OK;
+}
 
 // Forward of one batch whose ids come from src (a device array, or consecutive table rows).  With
 // arm set the batch stays pending for backward_update.
@@ -452,6 +477,7 @@ static int forward_impl(tt_emb* h, const IdSource& src, int64_t B64, float* out,
     rc = run_index(h, h->cur, src, B, st);
     if (rc) return rc;
   }
+  h->done_valid[h->cur] = false;  // a new use of this set begins
   const Workspace& ws = h->ws[h->cur];
   rc = run_slot(h, kSlotPrefixFwd, st, [&] {
     if (h->mfma) launch_prefix_fwd_mfma(pl, ws, h->g1, h->g2, B, st);
@@ -466,6 +492,7 @@ static int forward_impl(tt_emb* h, const IdSource& src, int64_t B64, float* out,
   h->pending_B = arm ? B : -1;
   h->last_B = B;
   h->have_forward = true;
+  if (!arm) return mark_set_done(h, st);  // no backward will follow: the set's use ends here
   return TT_EMB_OK;
 }
 
@@ -567,7 +594,8 @@ int tt_emb_backward_update(tt_emb_t h, const float* grad_out, float lr, void* hi
   rc = run_slot(h, kSlotSgd, st, [&] { launch_sgd(pl, ws, h->g1, h->g2, h->g3, lr, h->ada, st); });
   if (rc) return rc;
   if (h->profiling) rc = run_slot(h, kSlotEventPair, st, [] {});
-  return rc;
+  if (rc) return rc;
+  return mark_set_done(h, st);
 }
 
 int tt_emb_get_stats(tt_emb_t h, int64_t* U, int64_t* Q, int64_t* out_of_range) {
@@ -629,6 +657,7 @@ int tt_emb_destroy(tt_emb_t h) {
       if (h->side[i] == nullptr) continue;
       (void)hipStreamSynchronize(h->side[i]);
       if (h->prep[i].ready != nullptr) (void)hipEventDestroy(h->prep[i].ready);
+      if (h->done[i] != nullptr) (void)hipEventDestroy(h->done[i]);
       (void)hipStreamDestroy(h->side[i]);
     }
     if (h->ev_fork != nullptr) (void)hipEventDestroy(h->ev_fork);

@@ -282,7 +282,9 @@ def test_bit_reproducible_and_lr_zero():
         np.testing.assert_array_equal(x, y)
 
 
-def test_prepare_pipeline_matches_oracle_over_three_steps():
+@pytest.mark.parametrize("flags", [0, 4])
+def test_prepare_pipeline_matches_oracle_over_three_steps(flags):
+    # flags = 4: the ids are complete in memory at every prepare (they are: synchronised uploads)
     # the next batch's index work is enqueued between forward and backward of the current one;
     # three different batches, cores carried from step to step on both sides
     torch = _torch()
@@ -292,7 +294,7 @@ def test_prepare_pipeline_matches_oracle_over_three_steps():
     sizes = [7000, 2500, 9000]
     batches = [(wl.make_ids(w, 40 + k, B), wl.make_grads(w, 40 + k, B)) for k, B in enumerate(sizes)]
     batches[1][0][:400] = batches[1][0][0]                       # a hot id in the middle batch
-    emb = TTEmbedding(w.n, w.d, w.r, 10_000, cores)
+    emb = TTEmbedding(w.n, w.d, w.r, 10_000, cores, flags=flags)
     t_ids = [torch.from_numpy(b[0]).cuda() for b in batches]
     t_grad = [torch.from_numpy(b[1]).cuda() for b in batches]
     outs = []
@@ -313,7 +315,7 @@ def test_prepare_pipeline_matches_oracle_over_three_steps():
     for k in range(3):
         assert core_error(emb.cores[k].cpu().numpy(), ref[k]) <= CORE_TOL
     # two batches ahead: prepare(next) is called before the forward of the current batch
-    emb2 = TTEmbedding(w.n, w.d, w.r, 10_000, cores)
+    emb2 = TTEmbedding(w.n, w.d, w.r, 10_000, cores, flags=flags)
     outs2 = []
     emb2.prepare(t_ids[0])
     for k in range(3):
@@ -329,7 +331,7 @@ def test_prepare_pipeline_matches_oracle_over_three_steps():
     emb2.close()
     # the batch after next prepared before every forward (three index sets: one in flight, two
     # ahead), then a fourth prepare that has to overwrite the oldest waiting batch
-    emb3 = TTEmbedding(w.n, w.d, w.r, 10_000, cores)
+    emb3 = TTEmbedding(w.n, w.d, w.r, 10_000, cores, flags=flags)
     outs3 = []
     emb3.prepare(t_ids[0])
     emb3.prepare(t_ids[1])
