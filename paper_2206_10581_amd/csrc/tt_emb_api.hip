@@ -27,7 +27,7 @@ void launch_dg3(const Plan&, const Workspace&, const float* grad, int B, hipStre
 void launch_prefix_bwd(const Plan&, const Workspace&, const float* g1, const float* g2, int B,
                        hipStream_t);
 void launch_sgd(const Plan&, const Workspace&, float* g1, float* g2, float* g3, float lr,
-                const Adagrad&, hipStream_t);
+                const Adagrad&, hipEvent_t stop, hipStream_t);
 // matrix-core variants for the shapes mfma_shape() accepts
 bool mfma_shape(const Shape&);
 void launch_prefix_fwd_mfma(const Plan&, const Workspace&, const float* g1, const float* g2, int B,
@@ -370,7 +370,7 @@ int tt_emb_prepare(tt_emb_t h, const int64_t* ids, int64_t B64, void* hip_stream
       if (e != hipSuccess) return hip_fail(e);
       e = hipEventCreateWithFlags(&h->prep[i].ready, hipEventDisableTiming);
       if (e != hipSuccess) return hip_fail(e);
-      e = hipEventCreateWithFlags(&h->done[i], hipEventDisableTiming);
+      e = hipEventCreate(&h->done[i]);  // the extended launch records kernel times into it
       if (e != hipSuccess) return hip_fail(e);
     }
     e = hipEventCreateWithFlags(&h->ev_fork, hipEventDisableTiming);
@@ -591,10 +591,25 @@ int tt_emb_backward_update(tt_emb_t h, const float* grad_out, float lr, void* hi
     });
     if (rc) return rc;
   }
-  rc = run_slot(h, kSlotSgd, st, [&] { launch_sgd(pl, ws, h->g1, h->g2, h->g3, lr, h->ada, st); });
+  // The update kernel is the last reader of the index set.  Outside stream capture and profiling
+  // its completion signal doubles as the set's "done" event.
+  hipEvent_t stop = nullptr;
+  if (h->done[h->cur] != nullptr && (h->cfg.flags & TT_EMB_FLAG_IDS_READY) && !h->profiling) {
+    hipStreamCaptureStatus cap = hipStreamCaptureStatusNone;
+    if (hipStreamIsCapturing(st, &cap) == hipSuccess && cap == hipStreamCaptureStatusNone)
+      stop = h->done[h->cur];
+    else
+      (void)hipGetLastError();
+  }
+  rc = run_slot(h, kSlotSgd, st,
+                [&] { launch_sgd(pl, ws, h->g1, h->g2, h->g3, lr, h->ada, stop, st); });
   if (rc) return rc;
   if (h->profiling) rc = run_slot(h, kSlotEventPair, st, [] {});
   if (rc) return rc;
+  if (stop != nullptr) {
+    h->done_valid[h->cur] = true;
+    return TT_EMB_OK;
+  }
   return mark_set_done(h, st);
 }
 

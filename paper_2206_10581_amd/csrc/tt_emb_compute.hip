@@ -15,6 +15,8 @@
 // bit for bit.
 #include <algorithm>
 
+#include <hip/hip_ext.h>
+
 #include "tt_emb_internal.h"
 
 namespace ttemb {
@@ -449,16 +451,28 @@ void launch_prefix_bwd(const Plan& pl, const Workspace& ws, const float* g1, con
 }
 
 void launch_sgd(const Plan& pl, const Workspace& ws, float* g1, float* g2, float* g3, float lr,
-                const Adagrad& ada, hipStream_t st) {
+                const Adagrad& ada, hipEvent_t stop, hipStream_t st) {
   const Shape& s = pl.sh;
   const bool vec = (s.S1 % 4 == 0) && (s.S2 % 4 == 0) && (s.S3 % 4 == 0);
   const int span = kThreads * (vec ? 4 : 1);
   const int64_t jobs = (int64_t)s.n3 * cdiv(s.S3, span) + (int64_t)s.n2 * cdiv(s.S2, span) +
                        (int64_t)s.n1 * cdiv(s.S1, span);
   const int grid = grid_for(jobs, 1 << 16);
-#define TT_SGD(V, A)                                                                              \
-  k_sgd<V, A><<<grid, kThreads, 0, st>>>(pl.sh, lr, ada, g1, g2, g3, ws.part3, ws.c3_start, ws.part2, \
-                                         ws.c2_start, ws.dg1part, ws.g1_first, ws.g1_end, ws.ctr)
+  // with `stop` the kernel's own completion signal serves as that event: no separate event packet
+  // has to pass through the stream behind the kernel
+#define TT_SGD(V, A)                                                                               \
+  do {                                                                                             \
+    if (stop != nullptr)                                                                           \
+      hipExtLaunchKernelGGL((k_sgd<V, A>), dim3(grid), dim3(kThreads), 0, st, nullptr, stop, 0,    \
+                            pl.sh, lr, ada, g1, g2, g3, (const float*)ws.part3,                   \
+                            (const int*)ws.c3_start, (const float*)ws.part2,                      \
+                            (const int*)ws.c2_start, (const float*)ws.dg1part,                    \
+                            (const int*)ws.g1_first, (const int*)ws.g1_end, ws.ctr);              \
+    else                                                                                           \
+      k_sgd<V, A><<<grid, kThreads, 0, st>>>(pl.sh, lr, ada, g1, g2, g3, ws.part3, ws.c3_start,    \
+                                             ws.part2, ws.c2_start, ws.dg1part, ws.g1_first,       \
+                                             ws.g1_end, ws.ctr);                                   \
+  } while (0)
   if (ada.s1 != nullptr) {
     if (vec) TT_SGD(4, true); else TT_SGD(1, true);
   } else {
