@@ -435,11 +435,13 @@ __global__ __launch_bounds__(kMThreads) void k_id_bwd_mfma(
 // Blocks past the chunk range take the by-i3 chunks of the G3 gradient (dg3_role), one per
 // wavefront; that step only needs the per-id gradient sums and the cached prefix products, so
 // both run side by side.
-constexpr int kMidThreads = 512;
-constexpr int kMidWaves = kMidThreads / kWave;
+// Rank 16 needs half the LDS, so its blocks have four wavefronts (each takes two pairs of prefixes
+// in (i), then (ii), then wavefronts 0 and 1 take (iii)) and twice as many fit a compute unit.
+template <int R>
+constexpr int mid_waves() { return R >= 32 ? 8 : 4; }
 
 template <int R, int D3>
-__global__ __launch_bounds__(kMidThreads, 6) void k_bwd_mid_mfma(
+__global__ __launch_bounds__(mid_waves<R>() * kWave, 6) void k_bwd_mid_mfma(
     const float* __restrict__ g1, const float* __restrict__ g2, const float* __restrict__ g3,
     const float* __restrict__ P, const float* __restrict__ grad, const float* __restrict__ gsum,
     const int* __restrict__ u_code, const int* __restrict__ u_i3, const int4* __restrict__ c2_item,
@@ -453,6 +455,7 @@ __global__ __launch_bounds__(kMidThreads, 6) void k_bwd_mid_mfma(
   __shared__ __align__(16) float T[64 * TS];
   __shared__ __align__(16) float Bl[R * TS];
   __shared__ int q_of[16], i1_of[16], u0_of[16], u1_of[16];
+  constexpr int kMidWaves = mid_waves<R>(), kMidThreads = kMidWaves * kWave;
   const int tid = threadIdx.x, w = tid / kWave, lane = tid % kWave;
   const int trace_id = blockIdx.x * kMidWaves + w;
   (void)trace_id;
@@ -487,15 +490,15 @@ __global__ __launch_bounds__(kMidThreads, 6) void k_bwd_mid_mfma(
   TT_TRACE(ctr, trace_id, 1);
 
   const int l16 = lane % 16, kg = lane / 16;
-  // (i) this wavefront's two prefixes (local numbers 2w, 2w+1)
-  {
+  // (i) this wavefront's pairs of prefixes (local numbers 2*pw, 2*pw+1)
+  for (int pw = w; pw < 8; pw += kMidWaves) {
     f4 acc[2][NT16];
 #pragma unroll
     for (int x = 0; x < 2; ++x)
 #pragma unroll
       for (int nt = 0; nt < NT16; ++nt) acc[x][nt] = f4{0.f, 0.f, 0.f, 0.f};
-    const int u0a = u0_of[2 * w], u0b = u0_of[2 * w + 1];
-    const int na = u1_of[2 * w] - u0a, nb = u1_of[2 * w + 1] - u0b;
+    const int u0a = u0_of[2 * pw], u0b = u0_of[2 * pw + 1];
+    const int na = u1_of[2 * pw] - u0a, nb = u1_of[2 * pw + 1] - u0b;
     const int rounds = (max(na, nb) + UB - 1) / UB;
     for (int r = 0; r < rounds; ++r) {
       // lanes 0..7 hold the round's slots: prefix x = lane/4, id r*UB + lane%4 of its list
@@ -538,7 +541,7 @@ __global__ __launch_bounds__(kMidThreads, 6) void k_bwd_mid_mfma(
       for (int nt = 0; nt < NT16; ++nt)
 #pragma unroll
         for (int v = 0; v < 4; ++v)
-          T[((2 * w + x) * 4 + kg) * TS + v * R + nt * 16 + l16] = acc[x][nt][v];
+          T[((2 * pw + x) * 4 + kg) * TS + v * R + nt * 16 + l16] = acc[x][nt][v];
   }
   TT_TRACE(ctr, trace_id, 2);
   __syncthreads();
@@ -572,7 +575,9 @@ __global__ __launch_bounds__(kMidThreads, 6) void k_bwd_mid_mfma(
 #pragma unroll
         for (int v = 0; v < 4; ++v) dg1part[(size_t)qv * S1 + v * R + 16 * nt + l16] = acc[nt][v];
     }
-  } else if (w - 4 < W / 32) {
+  }
+  const int w3 = kMidWaves == 8 ? w - 4 : w;
+  if (w3 >= 0 && w3 < W / 32) {
     // (iii) G1 rows of the sixteen prefixes (as the contraction index) times 32 columns of the tile
     const int half = lane / 32, l32 = lane % 32;
     float a[32];
@@ -585,7 +590,7 @@ __global__ __launch_bounds__(kMidThreads, 6) void k_bwd_mid_mfma(
 #pragma unroll
     for (int j = 0; j < 32; ++j)
       if (q_of[8 * half + j / 4] < 0 || l32 >= R) a[j] = 0.f;
-    const int n = (w - 4) * 32 + l32;
+    const int n = w3 * 32 + l32;
     f16v acc = TT_ZERO16;
 #pragma unroll
     for (int j = 0; j < 32; ++j) acc = mfma32(a[j], T[(32 * half + j) * TS + n], acc);
@@ -909,9 +914,10 @@ bool mfma_fused_mid(const Shape& s) { return mfma_shape(s) && s.r1 <= 32; }
 void launch_bwd_mid_mfma(const Plan& pl, const Workspace& ws, const float* g1, const float* g2,
                          const float* g3, const float* grad, int B, hipStream_t st) {
   const int chunk_blocks = cdivi(std::min<int64_t>(B, pl.maxQ), kChunk2) + (int)pl.sh.n2;
-  const int dg3_blocks = cdivi(cdivi(B, kChunk3) + (int64_t)pl.sh.n3, kMidWaves);
+  const int waves = pl.sh.r1 == 16 ? mid_waves<16>() : mid_waves<32>();
+  const int dg3_blocks = cdivi(cdivi(B, kChunk3) + (int64_t)pl.sh.n3, waves);
 #define TT_MID(RR, DD)                                                                            \
-  k_bwd_mid_mfma<RR, DD><<<chunk_blocks + dg3_blocks, kMidThreads, 0, st>>>(                        \
+  k_bwd_mid_mfma<RR, DD><<<chunk_blocks + dg3_blocks, waves * kWave, 0, st>>>(                    \
       g1, g2, g3, ws.P, grad, ws.gsum, ws.u_code, ws.u_i3, ws.c2_item, ws.c2_desc, ws.c3_item,    \
       ws.c3_desc, ws.dg1part, ws.part2, ws.part3, chunk_blocks, ws.ctr)
   if (pl.sh.r1 == 16) {
