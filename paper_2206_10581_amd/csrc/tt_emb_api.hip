@@ -152,13 +152,17 @@ static size_t carve(const Plan& pl, char* base, Workspace* ws /* [kSets] or null
     w.c3_start = (int*)take(((size_t)s.n3 + 1) * 4);
     w.c3_desc = (int4*)take((size_t)pl.maxChunk3 * 16);
     w.c3_item = (int2*)take((size_t)pl.maxChunk3 * kChunk3 * 8);
+    w.c3_order = (int*)take((size_t)pl.maxChunk3 * 4);
     w.g2_list = (int*)take(mQ * 4);
     w.g2_start = (int*)take(((size_t)s.n2 + 1) * 4);
     w.c2_start = (int*)take(((size_t)s.n2 + 1) * 4);
     w.c2_desc = (int4*)take((size_t)pl.maxChunk2 * 16);
     w.c2_item = (int4*)take((size_t)pl.maxChunk2 * kChunk2 * 16);
-    w.g1_first = (int*)take((size_t)s.n1 * 8);  // g1_first[n1] followed by g1_end[n1]
+    // g1_first[n1], g1_end[n1], band_cnt, band_cur: one stretch, cleared by the first sort pass
+    w.g1_first = (int*)take((size_t)s.n1 * 8 + 2 * kOrderBands * 4);
     w.g1_end = w.g1_first + s.n1;
+    w.band_cnt = (uint32_t*)(w.g1_end + s.n1);
+    w.band_cur = w.band_cnt + kOrderBands;
   }
   Workspace& w = set[0];
   w.P = (float*)take(mQ * s.PN * 4);

@@ -27,6 +27,12 @@ __device__ __forceinline__ uint32_t key_of_id(const IdSource& src, int idx, uint
   return ((uint64_t)id < (uint64_t)N) ? (uint32_t)id : N;
 }
 
+// band of the prefix range [0, Q) that prefix q falls in
+__device__ __forceinline__ int chunk_band(int q, int Q) {
+  const long long b = (long long)max(q, 0) * kOrderBands / max(Q, 1);
+  return (int)min(b, (long long)kOrderBands - 1);
+}
+
 // ---------------------------------------------------------------------------------------------
 // block-wide helpers; ldsw holds at least one word per wavefront of the block
 
@@ -550,11 +556,14 @@ struct GroupOps3 {
   const int* u_q;
   int* list;
   int2* item;
+  uint32_t* band_cnt;
+  int Q;
   __device__ Item load(int idx) const { return Item{idx, u_i3[idx], u_code[idx], u_q[idx]}; }
   __device__ int digit(Item it) const { return it.i3; }
   __device__ void emit_chunked(uint32_t pos, uint32_t chunk, uint32_t t, Item it) const {
     list[pos] = it.u;
     item[(size_t)chunk * kChunk3 + t] = make_int2(it.code, it.q);
+    if (t == 0) atomicAdd(&band_cnt[chunk_band(it.q, Q)], 1u);  // a chunk counts where it starts
   }
 };
 
@@ -585,16 +594,41 @@ __global__ __launch_bounds__(kSortThreads) void k_group(
     const int* __restrict__ u_q, const int* __restrict__ q_i2, const int* __restrict__ q_i1,
     const int* __restrict__ q_us, int* g3_list, int* g3_start, int* c3_start, int4* c3_desc,
     int2* c3_item, int* g2_list, int* g2_start, int* c2_start, int4* c2_desc, int4* c2_item,
-    Counters* ctr) {
+    uint32_t* band_cnt, Counters* ctr) {
   __shared__ ScatterLds L;
   if ((int)blockIdx.x < u_blocks) {
-    GroupOps3 ops{u_i3, u_code, u_q, g3_list, c3_item};
+    GroupOps3 ops{u_i3, u_code, u_q, g3_list, c3_item, band_cnt, ctr->Q};
     stable_scatter_block(L, (int)blockIdx.x, ctr->U, (int)sh.n3, bits3, cnt3, nullptr, ops, g3_start,
                          kChunk3, c3_start, c3_desc, &ctr->nchunk3);
   } else {
     GroupOps2 ops{q_i2, q_i1, q_us, g2_list, c2_item};
     stable_scatter_block(L, (int)blockIdx.x - u_blocks, ctr->Q, (int)sh.n2, bits2, cnt2, nullptr, ops,
                          g2_start, kChunk2, c2_start, c2_desc, &ctr->nchunk2);
+  }
+}
+
+// The by-i3 chunks in the order of the prefix of their first id, bucketed into kOrderBands bands of
+// the prefix range (the order inside a band is whatever the atomics give).  The G3-gradient step
+// gathers one prefix product per id: walking the chunks in this order makes neighbouring
+// wavefronts gather neighbouring products.  Only the schedule depends on it, never a result.
+// The grouping kernel has counted the chunks per band; every block scans those counts for itself.
+__global__ __launch_bounds__(kSortThreads) void k_chunk_order(const int2* __restrict__ c3_item,
+                                                             const uint32_t* __restrict__ band_cnt,
+                                                             uint32_t* __restrict__ band_cur,
+                                                             int* __restrict__ c3_order,
+                                                             const Counters* __restrict__ ctr) {
+  __shared__ uint32_t band_at[kOrderBands];
+  __shared__ uint32_t ldsw[kSortWaves];
+  static_assert(kOrderBands == kSortThreads, "one band per thread");
+  const int tid = threadIdx.x, n = ctr->nchunk3, c = blockIdx.x * kSortThreads + tid;
+  if ((int)blockIdx.x * kSortThreads >= n) return;
+  const int q = c < n ? c3_item[(size_t)c * kChunk3].y : 0;
+  band_at[tid] = band_cnt[tid];
+  __syncthreads();
+  block_exclusive_scan(band_at, kOrderBands, ldsw);
+  if (c < n) {
+    const int b = chunk_band(q, ctr->Q);
+    c3_order[band_at[b] + atomicAdd(&band_cur[b], 1u)] = c;
   }
 }
 
@@ -622,7 +656,8 @@ void launch_sort_pass(const Plan& pl, const Workspace& ws, const IdSource& src, 
     if (which == 0) {
       k_sort_hist<true><<<blocks, kSortThreads, 0, st>>>(
           src, nullptr, B, N, shift, bits, ws.cnt, ws.cnt3, pl.uBlocksMax * (int)pl.sh.n3, ws.cnt2,
-          pl.qBlocksMax * (int)pl.sh.n2, (uint32_t*)ws.g1_first, 2 * (int)pl.sh.n1, ws.ctr);
+          pl.qBlocksMax * (int)pl.sh.n2, (uint32_t*)ws.g1_first,
+          2 * (int)pl.sh.n1 + 2 * kOrderBands, ws.ctr);
     } else {
       SortOps<true> ops{src, nullptr, nullptr, ws.key[0], ws.val[0], N, shift, (1u << bits) - 1u};
       k_sort_scatter<true><<<blocks, kSortThreads, 0, st>>>(ops, B, bits, ws.cnt, tot);
@@ -661,7 +696,10 @@ void launch_group(const Plan& pl, const Workspace& ws, int B, hipStream_t st) {
   k_group<<<ub + qb, kSortThreads, 0, st>>>(pl.sh, ub, pl.bits3, pl.bits2, ws.cnt3, ws.cnt2, ws.u_i3, ws.u_code, ws.u_q, ws.q_i2, ws.q_i1,
                                            ws.q_us, ws.g3_list, ws.g3_start, ws.c3_start, ws.c3_desc,
                                            ws.c3_item, ws.g2_list, ws.g2_start, ws.c2_start,
-                                           ws.c2_desc, ws.c2_item, ws.ctr);
+                                           ws.c2_desc, ws.c2_item, ws.band_cnt, ws.ctr);
+  if (chunks_ordered(pl, B))
+    k_chunk_order<<<cdiv(cdiv(B, kChunk3) + (int64_t)pl.sh.n3, kSortThreads), kSortThreads, 0, st>>>(
+      ws.c3_item, ws.band_cnt, ws.band_cur, ws.c3_order, ws.ctr);
 }
 
 }  // namespace ttemb

@@ -33,6 +33,7 @@ constexpr int kSegItems = 1024;  // sorted slots per block in the segment kernel
 constexpr int kTileSlots = 32;   // sorted slots per wavefront tile in the row kernels
 constexpr int kChunk3 = 16;       // unique ids per partial sum of a G3 slice gradient
 constexpr int kChunk2 = 16;      // unique prefixes per partial sum of a G2 slice gradient
+constexpr int kOrderBands = 1024;  // bands of the prefix range the by-i3 chunks are ordered by
 
 // Where the ids of a batch come from, passed to the first sort pass by value.
 struct IdSource {
@@ -109,6 +110,7 @@ struct Workspace {
   int* c3_start;      // first chunk of each i3 group [n3+1]
   int4* c3_desc;      // chunk -> {i3, first list item, items, 0}  [maxChunk3]
   int2* c3_item;      // chunk, t -> {gradient-row code, prefix} of its t-th id [maxChunk3][kChunk3]
+  int* c3_order;      // by-i3 chunks in the order of the prefix of their first id [maxChunk3]
   int* g2_list;       // prefixes grouped by i2 (stable) [maxQ]
   int* g2_start;      // [n2+1]
   int* c2_start;      // [n2+1]
@@ -116,6 +118,8 @@ struct Workspace {
   int4* c2_item;      // chunk, t -> {q, i1, first unique id, end} of its t-th prefix [maxChunk2][kChunk2]
   int* g1_first;      // i1 -> first prefix with that i1 (prefixes are sorted by i1) [n1]
   int* g1_end;        // i1 -> one past its last prefix; directly follows g1_first  [n1]
+  uint32_t* band_cnt;  // by-i3 chunks per band of their first prefix; directly follows g1_end
+  uint32_t* band_cur;  // chunks placed so far per band; directly follows band_cnt [kOrderBands]
   float* P;           // prefix products G1[i1] G2[i2]   [maxQ][PN]
   float* gsum;        // per unique id, sum of its rows' gradients [maxB][D]
   float* carry;       // per tile: head and tail partial sums [tiles][2][D]
@@ -134,6 +138,13 @@ struct Plan {
   int keyBits, passes, bitsPerPass;
   int bits2, bits3;  // bits of n2-1, n3-1 (for the ballot match in the grouping scatter)
 };
+
+// The by-i3 chunks are put in prefix order only when the prefix products of a batch of B ids can
+// exceed one XCD's L2 (4 MiB); below that the gathers hit the L2 in any order.
+inline bool chunks_ordered(const Plan& pl, int64_t B) {
+  const int64_t q = B < pl.maxQ ? B : pl.maxQ;
+  return q * pl.sh.PN * 4 > (int64_t)4 << 20;
+}
 
 enum KernelSlot {
   kSlotSortHist = 0,

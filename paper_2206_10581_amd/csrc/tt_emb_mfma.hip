@@ -354,15 +354,14 @@ __device__ __forceinline__ void u_bwd_role(
 // part3[c]^T = sum over the <= 16 unique ids u of one by-i3 chunk of g_u^T P_q(u)
 // (D3 x 16 times 16 x R; the D3 rows occupy the first rows of a 16-row tile), UB ids at a time.
 template <int R, int D3, int UB>
-__device__ __forceinline__ void dg3_role(
-    int wave, int nwaves, const float* __restrict__ P, const float* __restrict__ grad,
+__device__ __forceinline__ void dg3_chunk(
+    int c, const float* __restrict__ P, const float* __restrict__ grad,
     const float* __restrict__ gsum, const int2* __restrict__ c3_item,
-    const int4* __restrict__ c3_desc, float* __restrict__ part3, const Counters* __restrict__ ctr) {
+    const int4* __restrict__ c3_desc, float* __restrict__ part3) {
   constexpr int PN = 16 * R, S3 = R * D3, D = 16 * D3, NT = R / 16;
   const int lane = threadIdx.x % kWave;
   const int l16 = lane % 16, kg = lane / 16;
-  const int nchunk = ctr->nchunk3;
-  for (int c = wave; c < nchunk; c += nwaves) {
+  {
     const int2 item = c3_item[(size_t)c * kChunk3 + lane % kChunk3];
     const int cnt = c3_desc[c].z;
     // records past the chunk's count are unwritten; only lanes below cnt are ever read
@@ -406,6 +405,17 @@ __device__ __forceinline__ void dg3_role(
   }
 }
 
+// chunks wave, wave + nwaves, ... in index order
+template <int R, int D3, int UB>
+__device__ __forceinline__ void dg3_role(
+    int wave, int nwaves, const float* __restrict__ P, const float* __restrict__ grad,
+    const float* __restrict__ gsum, const int2* __restrict__ c3_item,
+    const int4* __restrict__ c3_desc, float* __restrict__ part3, const Counters* __restrict__ ctr) {
+  const int nchunk = ctr->nchunk3;
+  for (int c = wave; c < nchunk; c += nwaves)
+    dg3_chunk<R, D3, UB>(c, P, grad, gsum, c3_item, c3_desc, part3);
+}
+
 // ---------------------------------------------------------------------------------------------
 // The two gradient steps that only need the per-id gradient sums run side by side in one launch:
 // even blocks form dPsum per prefix, odd blocks the partial G3 gradients per by-i3 chunk.
@@ -439,6 +449,7 @@ __global__ __launch_bounds__(kMThreads) void k_id_bwd_mfma(
 // in (i), then (ii), then wavefronts 0 and 1 take (iii)) and twice as many fit a compute unit.
 template <int R>
 constexpr int mid_waves() { return R >= 32 ? 8 : 4; }
+constexpr int kXcds = 8;
 
 template <int R, int D3>
 __global__ __launch_bounds__(mid_waves<R>() * kWave, 6) void k_bwd_mid_mfma(
@@ -446,8 +457,9 @@ __global__ __launch_bounds__(mid_waves<R>() * kWave, 6) void k_bwd_mid_mfma(
     const float* __restrict__ P, const float* __restrict__ grad, const float* __restrict__ gsum,
     const int* __restrict__ u_code, const int* __restrict__ u_i3, const int4* __restrict__ c2_item,
     const int4* __restrict__ c2_desc, const int2* __restrict__ c3_item,
-    const int4* __restrict__ c3_desc, float* __restrict__ dg1part, float* __restrict__ part2,
-    float* __restrict__ part3, int chunk_blocks, const Counters* __restrict__ ctr) {
+    const int4* __restrict__ c3_desc, const int* __restrict__ c3_order,
+    float* __restrict__ dg1part, float* __restrict__ part2, float* __restrict__ part3,
+    int chunk_blocks, const Counters* __restrict__ ctr) {
   static_assert(R == 16 || R == 32, "the LDS tiles are sized for ranks up to 32");
   constexpr int W = 4 * R, S1 = 4 * R, S2 = R * W, S3 = R * D3, D = 16 * D3;
   constexpr int TS = W + 4;  // padded row stride of the LDS tiles (keeps 16-byte alignment)
@@ -460,11 +472,17 @@ __global__ __launch_bounds__(mid_waves<R>() * kWave, 6) void k_bwd_mid_mfma(
   const int trace_id = blockIdx.x * kMidWaves + w;
   (void)trace_id;
   TT_TRACE(ctr, trace_id, 0);
-  // blocks past the by-i2 chunk range take the by-i3 chunks, one per wavefront
+  // Blocks past the by-i2 chunk range take the by-i3 chunks, one per wavefront, in the order of
+  // the chunks' first prefixes.  Workgroups go to the eight XCDs round robin, so XCD x takes the
+  // x-th eighth of that order and walks it front to back: the prefix products a chunk gathers
+  // were then just read by its neighbours through the same L2.
   if ((int)blockIdx.x >= chunk_blocks) {
-    dg3_role<R, D3, 4>(((int)blockIdx.x - chunk_blocks) * kMidWaves + w,
-                       ((int)gridDim.x - chunk_blocks) * kMidWaves, P, grad, gsum, c3_item, c3_desc,
-                       part3, ctr);
+    const int rel = (int)blockIdx.x - chunk_blocks, xcd = (int)blockIdx.x % kXcds;
+    const int per_xcd = ((int)gridDim.x - chunk_blocks) / kXcds * kMidWaves;
+    const int n = ctr->nchunk3;
+    const int lo = (int)((long long)n * xcd / kXcds), hi = (int)((long long)n * (xcd + 1) / kXcds);
+    for (int i = lo + rel / kXcds * kMidWaves + w; i < hi; i += per_xcd)
+      dg3_chunk<R, D3, 4>(c3_order ? c3_order[i] : i, P, grad, gsum, c3_item, c3_desc, part3);
     TT_TRACE(ctr, trace_id, 4);
     return;
   }
@@ -915,11 +933,14 @@ void launch_bwd_mid_mfma(const Plan& pl, const Workspace& ws, const float* g1, c
                          const float* g3, const float* grad, int B, hipStream_t st) {
   const int chunk_blocks = cdivi(std::min<int64_t>(B, pl.maxQ), kChunk2) + (int)pl.sh.n2;
   const int waves = pl.sh.r1 == 16 ? mid_waves<16>() : mid_waves<32>();
-  const int dg3_blocks = cdivi(cdivi(B, kChunk3) + (int64_t)pl.sh.n3, waves);
+  const int* order = chunks_ordered(pl, B) ? ws.c3_order : nullptr;
+  // the same number of by-i3 blocks on every XCD
+  const int dg3_blocks =
+      kXcds * cdivi(cdivi(cdivi(B, kChunk3) + (int64_t)pl.sh.n3, kXcds), waves);
 #define TT_MID(RR, DD)                                                                            \
   k_bwd_mid_mfma<RR, DD><<<chunk_blocks + dg3_blocks, waves * kWave, 0, st>>>(                    \
       g1, g2, g3, ws.P, grad, ws.gsum, ws.u_code, ws.u_i3, ws.c2_item, ws.c2_desc, ws.c3_item,    \
-      ws.c3_desc, ws.dg1part, ws.part2, ws.part3, chunk_blocks, ws.ctr)
+      ws.c3_desc, order, ws.dg1part, ws.part2, ws.part3, chunk_blocks, ws.ctr)
   if (pl.sh.r1 == 16) {
     if (pl.sh.d3 == 4) TT_MID(16, 4); else TT_MID(16, 8);
   } else {

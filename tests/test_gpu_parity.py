@@ -136,6 +136,21 @@ def test_matrix_core_shape_family(n, B, R, d3, flags):
     check_against_oracle(n, d, r, cores, ids, grad, 0.01, flags=flags)
 
 
+@pytest.mark.parametrize("n,R,B", [((48, 50, 60), 32, 5000), ((70, 60, 9), 16, 6000)])
+def test_prefix_ordered_chunk_schedule(n, R, B):
+    # enough prefixes that the cached products can exceed one L2 (4 MiB): the G3-gradient chunks
+    # are then walked in prefix order, one eighth of the order per XCD
+    rng = np.random.default_rng(R + B)
+    d, r = (4, 4, 8), (R, R)
+    s = Shape(n, d, r)
+    assert min(B, n[0] * n[1]) * 16 * R * 4 > 4 << 20
+    cores = tuple((rng.standard_normal(cs) / np.sqrt(R)).astype(np.float32) for cs in s.core_shapes())
+    ids = rng.integers(0, s.N, size=B, dtype=np.int64)
+    ids[: B // 8] = ids[1]
+    grad = rng.standard_normal((B, s.D)).astype(np.float32)
+    check_against_oracle(n, d, r, cores, ids, grad, 0.01)
+
+
 @pytest.mark.parametrize("B", [1, 2, 31, 32, 33, 63, 64, 65, 1023, 1025, 4095, 4096, 8193])
 def test_ragged_batch_sizes(B):
     w, cores, _, _ = _workload(2)
