@@ -39,6 +39,7 @@ void launch_id_bwd_mfma(const Plan&, const Workspace&, const float* g3, const fl
 void launch_prefix_bwd_mfma(const Plan&, const Workspace&, const float* g1, const float* g2, int B,
                             hipStream_t);
 bool mfma_fused_mid(const Shape&);
+bool mfma_shape(const Shape&);
 void launch_bwd_mid_mfma(const Plan&, const Workspace&, const float* g1, const float* g2,
                          const float* g3, const float* grad, int B, hipStream_t);
 void launch_gsum_block(const Plan&, const Workspace&, const float* grad, int B, hipStream_t);
@@ -65,23 +66,49 @@ static int make_plan(const tt_emb_config* c, Plan* pl) {
       return TT_EMB_EINVAL;
   if (c->r[0] <= 0 || c->r[1] <= 0 || c->r[0] > 4096 || c->r[1] > 4096) return TT_EMB_EINVAL;
   if (c->max_batch < 1 || c->max_batch >= (int64_t(1) << 30)) return TT_EMB_EINVAL;
-  const int64_t n12 = c->n[0] * c->n[1];
+  int64_t n12 = c->n[0] * c->n[1];
   if (n12 >= (int64_t(1) << 31)) return TT_EMB_EINVAL;
-  const int64_t N = n12 * c->n[2];
+  int64_t N = n12 * c->n[2];
   if (N >= (int64_t(1) << 31)) return TT_EMB_EINVAL;
+  pl->split = 1;
+  pl->user_maxB = c->max_batch;
+  pl->user_N = N;
   if (c->n[1] > kMaxBins || c->n[2] > kMaxBins) return TT_EMB_EINVAL;
-  const int64_t D = (int64_t)c->d[0] * c->d[1] * c->d[2];
+  int64_t D = (int64_t)c->d[0] * c->d[1] * c->d[2];
   if (D > 4096) return TT_EMB_EINVAL;
+  pl->user_D = (int)D;
   const int64_t S2 = (int64_t)c->r[0] * c->d[1] * c->r[1];
   const int64_t PN = (int64_t)c->d[0] * c->d[1] * c->r[1];
   if (S2 > (1 << 24) || PN > (1 << 24)) return TT_EMB_EINVAL;
 
+  // slab split: d1 = 8, 12, ... with everything else fit for the matrix-core kernels, and the
+  // enlarged table and batch still inside the 31-bit key and index ranges
+  int64_t n1 = c->n[0], maxB = c->max_batch;
+  int d1 = c->d[0];
+  if (!(c->flags & TT_EMB_FLAG_GENERIC_KERNELS) && d1 > 4 && d1 % 4 == 0 && d1 <= 32) {
+    const int k = d1 / 4;
+    Shape t{};
+    t.d1 = 4;
+    t.d2 = c->d[1];
+    t.d3 = c->d[2];
+    t.r1 = c->r[0];
+    t.r2 = c->r[1];
+    if (mfma_shape(t) && N * k < (int64_t(1) << 31) && maxB * k < (int64_t(1) << 30)) {
+      pl->split = k;
+      n1 *= k;
+      n12 *= k;
+      N *= k;
+      maxB *= k;
+      D /= k;
+      d1 = 4;
+    }
+  }
   Shape& s = pl->sh;
-  s.n1 = (uint32_t)c->n[0];
+  s.n1 = (uint32_t)n1;
   s.n2 = (uint32_t)c->n[1];
   s.n3 = (uint32_t)c->n[2];
   s.N = (uint32_t)N;
-  s.d1 = c->d[0];
+  s.d1 = d1;
   s.d2 = c->d[1];
   s.d3 = c->d[2];
   s.r1 = c->r[0];
@@ -94,8 +121,8 @@ static int make_plan(const tt_emb_config* c, Plan* pl) {
   s.S2 = s.r1 * s.W;
   s.S3 = s.r2 * s.d3;
 
-  pl->maxB = c->max_batch;
-  pl->maxQ = std::min<int64_t>(c->max_batch, n12);
+  pl->maxB = maxB;
+  pl->maxQ = std::min<int64_t>(maxB, n12);
   pl->sortBlocksMax = (int)cdiv64(pl->maxB, kSortItems);
   pl->segBlocksMax = (int)cdiv64(pl->maxB, kSegItems);
   pl->uBlocksMax = (int)cdiv64(pl->maxB, kSortItems);
@@ -234,6 +261,12 @@ struct tt_emb {
   double prof_ms[kSlotCount];
 };
 
+static IdSource id_source(const tt_emb* h, const int64_t* ids, int64_t base, bool reindexed) {
+  const Plan& pl = h->plan;
+  return IdSource{ids, base, reindexed ? h->reindex : nullptr, reindexed ? h->reindex_n : 0,
+                  pl.split, pl.user_N, (int64_t)pl.sh.n2 * pl.sh.n3};
+}
+
 static int hip_fail(hipError_t e) {
   g_hip_error = std::string("HIP: ") + hipGetErrorString(e);
   return TT_EMB_EHIP;
@@ -363,7 +396,7 @@ static int run_index(tt_emb* h, int set, const IdSource& src, int B, hipStream_t
 
 int tt_emb_prepare(tt_emb_t h, const int64_t* ids, int64_t B64, void* hip_stream) {
   if (h == nullptr || B64 < 0) return TT_EMB_EINVAL;
-  if (B64 > h->plan.maxB) return TT_EMB_ENOSPC;
+  if (B64 > h->plan.user_maxB) return TT_EMB_ENOSPC;
   if (B64 == 0) return TT_EMB_OK;  // nothing to prepare; forward handles the empty batch itself
   if (ids == nullptr || ((uintptr_t)ids & 7u) != 0) return TT_EMB_EINVAL;
   hipStream_t st = (hipStream_t)hip_stream;
@@ -407,7 +440,7 @@ int tt_emb_prepare(tt_emb_t h, const int64_t* ids, int64_t B64, void* hip_stream
     e = hipStreamWaitEvent(h->side[target], h->ev_fork, 0);
     if (e != hipSuccess) return hip_fail(e);
   }
-  int rc = run_index(h, target, IdSource{ids, 0, h->reindex, h->reindex_n}, (int)B64,
+  int rc = run_index(h, target, id_source(h, ids, 0, true), (int)(B64 * h->plan.split),
                      h->side[target]);
   if (rc) return rc;
   e = hipEventRecord(h->prep[target].ready, h->side[target]);
@@ -443,8 +476,8 @@ static int forward_impl(tt_emb* h, const IdSource& src, int64_t B64, float* out,
     return TT_EMB_OK;
   }
   if (out == nullptr || ((uintptr_t)out & 15u) != 0) return TT_EMB_EINVAL;
-  const int B = (int)B64;
   const Plan& pl = h->plan;
+  const int B = (int)(B64 * pl.split);  // items of the index pipeline, rows of D/split floats
   h->pending_B = -1;
   int rc;
   // oldest prepared batch with these ids and this size, if any
@@ -504,30 +537,30 @@ extern "C" {
 
 int tt_emb_forward(tt_emb_t h, const int64_t* ids, int64_t B64, float* out, void* hip_stream) {
   if (h == nullptr || B64 < 0) return TT_EMB_EINVAL;
-  if (B64 > h->plan.maxB) return TT_EMB_ENOSPC;
+  if (B64 > h->plan.user_maxB) return TT_EMB_ENOSPC;
   if (B64 > 0 && (ids == nullptr || ((uintptr_t)ids & 7u) != 0)) return TT_EMB_EINVAL;
-  return forward_impl(h, IdSource{ids, 0, h->reindex, h->reindex_n}, B64, out,
+  return forward_impl(h, id_source(h, ids, 0, true), B64, out,
                       (hipStream_t)hip_stream, true);
 }
 
 int tt_emb_forward_eval(tt_emb_t h, const int64_t* ids, int64_t B64, float* out, void* hip_stream) {
   if (h == nullptr || B64 < 0) return TT_EMB_EINVAL;
-  if (B64 > h->plan.maxB) return TT_EMB_ENOSPC;
+  if (B64 > h->plan.user_maxB) return TT_EMB_ENOSPC;
   if (B64 > 0 && (ids == nullptr || ((uintptr_t)ids & 7u) != 0)) return TT_EMB_EINVAL;
   if (h->pending_B >= 0) return TT_EMB_ESTATE;  // would overwrite what the pending backward needs
-  return forward_impl(h, IdSource{ids, 0, h->reindex, h->reindex_n}, B64, out,
+  return forward_impl(h, id_source(h, ids, 0, true), B64, out,
                       (hipStream_t)hip_stream, false);
 }
 
 int tt_emb_materialize(tt_emb_t h, int64_t first_row, int64_t count, float* out, void* hip_stream) {
   if (h == nullptr || first_row < 0 || count < 0) return TT_EMB_EINVAL;
-  if (first_row + count > (int64_t)h->plan.sh.N) return TT_EMB_EINVAL;
+  if (first_row + count > h->plan.user_N) return TT_EMB_EINVAL;
   if (count > 0 && out == nullptr) return TT_EMB_EINVAL;
   if (h->pending_B >= 0) return TT_EMB_ESTATE;  // would overwrite what the pending backward needs
-  const int64_t D = h->plan.sh.D;
-  for (int64_t off = 0; off < count; off += h->plan.maxB) {
-    const int64_t nb = std::min<int64_t>(h->plan.maxB, count - off);
-    int rc = forward_impl(h, IdSource{nullptr, first_row + off, nullptr, 0}, nb, out + off * D,
+  const int64_t D = h->plan.user_D;
+  for (int64_t off = 0; off < count; off += h->plan.user_maxB) {
+    const int64_t nb = std::min<int64_t>(h->plan.user_maxB, count - off);
+    int rc = forward_impl(h, id_source(h, nullptr, first_row + off, false), nb, out + off * D,
                           (hipStream_t)hip_stream, false);
     if (rc) return rc;
   }
@@ -629,8 +662,11 @@ int tt_emb_get_stats(tt_emb_t h, int64_t* U, int64_t* Q, int64_t* out_of_range) 
     if (e != hipSuccess) return hip_fail(e);
     oob = h->last_B - (int64_t)c.nvalid;
   }
-  if (U) *U = c.U - c.n_split;
-  if (Q) *Q = c.Q;
+  // with a slab split every id, prefix and position was counted once per slab
+  const int k = h->plan.split;
+  oob /= k;
+  if (U) *U = (c.U - c.n_split) / k;
+  if (Q) *Q = c.Q / k;
   if (out_of_range) *out_of_range = oob;
   if (c.err != 0) return TT_EMB_EINTERNAL;
   if ((h->cfg.flags & TT_EMB_FLAG_CHECK_RANGE) && oob > 0) return TT_EMB_ERANGE;

@@ -16,15 +16,26 @@
 namespace ttemb {
 
 __device__ __forceinline__ uint32_t key_of_id(const IdSource& src, int idx, uint32_t N) {
-  int64_t id = src.ids != nullptr ? src.ids[idx] : src.base + idx;
+  int pos = idx, slab = 0;
+  if (src.split > 1) {
+    pos = idx / src.split;
+    slab = idx - pos * src.split;
+  }
+  int64_t id = src.ids != nullptr ? src.ids[pos] : src.base + pos;
   if (src.reindex != nullptr) {
     // node re-indexing (paper Section 4.2: ids renumbered so that a partition's nodes are
     // consecutive): one gather in front of the split
     if ((uint64_t)id >= (uint64_t)src.n_ids) return N;
     id = src.reindex[id];
   }
-  // ids outside [0, N) (negative ones included) become the sentinel N and sort to the end
-  return ((uint64_t)id < (uint64_t)N) ? (uint32_t)id : N;
+  // ids outside the table (negative ones included) become the sentinel N and sort to the end
+  if ((uint64_t)id >= (uint64_t)src.rows) return N;
+  if (src.split > 1) {
+    // first-core index i1 -> split*i1 + slab, the other two coordinates stay
+    const int64_t i1 = id / src.n23;
+    id += ((int64_t)(src.split - 1) * i1 + slab) * src.n23;
+  }
+  return (uint32_t)id;
 }
 
 // band of the prefix range [0, Q) that prefix q falls in

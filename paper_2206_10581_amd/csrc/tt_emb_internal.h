@@ -41,6 +41,10 @@ struct IdSource {
   int64_t base;
   const int32_t* reindex;  // device [n_ids] old id -> table row, or nullptr (ids are table rows)
   int64_t n_ids;
+  // Slab split (see Plan::split): item idx of the pipeline is slab idx % split of batch position
+  // idx / split; rows is the caller's table size N and n23 = n2*n3.
+  int split;
+  int64_t rows, n23;
 };
 
 // Optional Adagrad state of the update kernel (all null: plain SGD).
@@ -131,6 +135,15 @@ struct Workspace {
 };
 
 struct Plan {
+  // Slab split: with d1 = 4*split (split > 1) and the other factors fit for the matrix-core
+  // kernels, G1[i1] (d1 x r1) is read as split slices of 4 x r1, i.e. as a table with split*n1
+  // first-core slices and d1 = 4 whose row for (split*i1 + h, i2, i3) is the h-th run of D/split
+  // floats of the caller's row for (i1, i2, i3).  A batch of B ids is then a batch of split*B ids
+  // of that table, out/grad [B][D] are its [split*B][D/split] arrays, and the cores are the same
+  // memory.  sh, maxB and maxQ describe the table the kernels see; user_* what the caller sees.
+  int split;
+  int64_t user_maxB, user_N;
+  int user_D;
   Shape sh;
   int64_t maxB, maxQ;
   int sortBlocksMax, segBlocksMax, uBlocksMax, qBlocksMax, tilesMax;

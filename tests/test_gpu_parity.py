@@ -216,6 +216,9 @@ def test_config2_in_full():
     ("ogbn-arxiv", (55, 55, 56), (8, 4, 4), 16, 20_000),
     ("ogbn-products", (125, 140, 140), (4, 5, 5), 8, 20_000),       # D = 100, rows of 400 bytes
     ("ogbn-papers100M", (480, 500, 500), (8, 4, 4), 8, 30_000),
+    ("ogbn-papers100M rank 16", (480, 500, 500), (8, 4, 4), 16, 30_000),   # slab split, d1 = 2*4
+    ("ogbn-arxiv rank 32", (55, 55, 56), (8, 4, 4), 32, 20_000),
+    ("d1 = 12, d3 = 8, rank 64", (20, 30, 25), (12, 4, 8), 64, 6_000),     # three slabs
     ("unequal ranks", (40, 60, 50), (4, 4, 8), (16, 32), 10_000),
 ])
 def test_paper_table_shapes(name, n, d, R, B):
@@ -422,6 +425,66 @@ def test_lookup_only_calls_and_dense_materialisation():
     part = emb.materialize(first, count).cpu().numpy()
     ref = ora.forward(s, *cores, np.arange(first, first + count, dtype=np.int64))
     assert row_error(part, ref) <= ROW_TOL
+    emb.close()
+
+
+def test_slab_split_shape_through_every_entry_point():
+    """d = (8,4,4), rank 16 runs as a table with twice the first-core slices and d1 = 4 (each row
+    two half rows); counts, out-of-range handling, the prepared pipeline, the lookup-only calls,
+    the re-indexing table and Adagrad must all look as for any other shape."""
+    torch = _torch()
+    from paper_2206_10581_amd import TTEmbedding
+    n, d, r = (6, 7, 9), (8, 4, 4), (16, 16)
+    s = Shape(n, d, r)
+    rng = np.random.default_rng(844)
+    cores = tuple((rng.standard_normal(cs) / 4).astype(np.float32) for cs in s.core_shapes())
+    B = 3000
+    ids = rng.integers(0, s.N, B).astype(np.int64)
+    ids[:500] = ids[0]
+    ids[600:606] = [-1, s.N, s.N + 3, 1 << 40, s.N - 1, 0]
+    grad = rng.standard_normal((B, s.D)).astype(np.float32)
+    out, new, stats = check_against_oracle(n, d, r, cores, ids, grad, 0.01)
+    assert stats["out_of_range"] == 4
+    with_generic = run_gpu(n, d, r, cores, ids, grad, 0.01, flags=2)     # the any-shape kernels
+    assert row_error(out, with_generic[0]) <= ROW_TOL and with_generic[2] == stats
+
+    emb = TTEmbedding(n, d, r, 1000, cores)
+    table = emb.materialize().cpu().numpy()                              # 378 rows
+    assert row_error(table, ora.forward(s, *cores, np.arange(s.N, dtype=np.int64))) <= ROW_TOL
+    part = emb.materialize(100, 200).cpu().numpy()
+    np.testing.assert_array_equal(part, table[100:300])
+    # three steps with the index work prepared ahead, then the same rows from a lookup-only call
+    cur = [c.copy() for c in cores]
+    batches = [rng.integers(0, s.N, 1000).astype(np.int64) for _ in range(3)]
+    t_b = [torch.from_numpy(b).cuda() for b in batches]
+    g = torch.from_numpy(grad[:1000]).cuda()
+    emb.prepare(t_b[0])
+    for k in range(3):
+        if k + 1 < 3:
+            emb.prepare(t_b[k + 1])
+        o = emb.forward(t_b[k]).cpu().numpy()
+        assert row_error(o, ora.forward(s, *cur, batches[k])) <= ROW_TOL
+        emb.backward_update(g, 0.01)
+        cur = [c.astype(np.float32) for c in ora.backward_update(s, *cur, batches[k], grad[:1000], 0.01)]
+    for k in range(3):
+        assert core_error(emb.cores[k].cpu().numpy(), cur[k]) <= CORE_TOL
+    # re-indexing table in front of the split
+    perm = rng.permutation(s.N).astype(np.int32)
+    emb.set_reindex(torch.from_numpy(perm).cuda())
+    o = emb.forward_eval(t_b[0]).cpu().numpy()
+    now = [c.cpu().numpy() for c in emb.cores]
+    assert row_error(o, ora.forward(s, *now, perm[batches[0]].astype(np.int64))) <= ROW_TOL
+    emb.set_reindex(None)
+    # Adagrad from a zero state
+    emb.set_adagrad(1e-6)
+    emb.forward(t_b[1])
+    emb.backward_update(g, 0.05)
+    torch.cuda.synchronize()
+    ref_new, ref_state = ora.adagrad_update(s, *now, [np.zeros_like(c) for c in now], batches[1],
+                                            grad[:1000], 0.05, 1e-6)
+    for k in range(3):
+        assert core_error(emb.cores[k].cpu().numpy(), ref_new[k]) <= CORE_TOL
+        assert core_error(emb.adagrad_state[k].cpu().numpy(), ref_state[k]) <= CORE_TOL
     emb.close()
 
 

@@ -53,6 +53,14 @@ CONFIGS = {
                 "zipf_affine", zipf_s=1.0, init_std=1 / math.sqrt(16)),
     5: Workload("c5_111m_r64_clusters", (480, 480, 482), (4, 4, 8), (64, 64), 500_000, "clusters",
                 init_std=1 / math.sqrt(64), extra={"blocks": 500, "block_len": 1000}),
+    # The paper's own factorisations and dimension orders (Table "ogb-dim-tt"), with the id streams
+    # of configs 2-4: not benchmark configurations, measured beside them.
+    6: Workload("p_arxiv_55x55x56_d8x4x4_r16", (55, 55, 56), (8, 4, 4), (16, 16), 50_000, "uniform",
+                init_std=1 / math.sqrt(16)),
+    7: Workload("p_products_125x140x140_d4x5x5_r32", (125, 140, 140), (4, 5, 5), (32, 32), 200_000,
+                "zipf_perm", zipf_s=1.1, init_std=1 / math.sqrt(32)),
+    8: Workload("p_papers100m_480x500x500_d8x4x4_r16", (480, 500, 500), (8, 4, 4), (16, 16),
+                500_000, "zipf_affine", zipf_s=1.0, init_std=1 / math.sqrt(16)),
 }
 
 
