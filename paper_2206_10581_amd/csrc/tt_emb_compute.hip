@@ -35,29 +35,91 @@ __device__ __forceinline__ const float* grad_of_unique(int u, const int* __restr
 }
 
 // ---------------------------------------------------------------------------------------------
+// C(m, n) = sum over k < K of A(m, k) * B(k, n) for m < M, n < N, by one block of kThreads threads:
+// 64 x 64 output tiles, the operands staged through LDS sixteen k at a time, sixteen outputs per
+// thread.  fa(m, k), fb(k, n) fetch one operand element, fc(m, n, value) takes one result; the
+// *_KFAST flags say which index neighbouring threads should vary while staging (the one that is
+// contiguous in memory).  Every sum runs in ascending k.  All threads of the block must call it
+// with the same M, N, K.
+constexpr int kGemmTile = 64, kGemmDepth = 16;
+struct GemmLds {
+  float a[kGemmDepth][kGemmTile + 4];
+  float b[kGemmDepth][kGemmTile + 4];
+};
+
+template <bool A_KFAST, bool B_KFAST, class FA, class FB, class FC>
+__device__ __forceinline__ void block_gemm(GemmLds& L, int M, int N, int K, FA fa, FB fb, FC fc) {
+  static_assert(kThreads == 256, "sixteen by sixteen threads of 4 x 4 outputs");
+  const int t = threadIdx.x, tm = (t / 16) * 4, tn = (t % 16) * 4;
+  for (int m0 = 0; m0 < M; m0 += kGemmTile)
+    for (int n0 = 0; n0 < N; n0 += kGemmTile) {
+      float acc[4][4];
+#pragma unroll
+      for (int i = 0; i < 4; ++i)
+#pragma unroll
+        for (int j = 0; j < 4; ++j) acc[i][j] = 0.f;
+      for (int k0 = 0; k0 < K; k0 += kGemmDepth) {
+#pragma unroll
+        for (int i = 0; i < kGemmTile * kGemmDepth / kThreads; ++i) {
+          const int e = t + i * kThreads;
+          const int ak = A_KFAST ? e % kGemmDepth : e / kGemmTile;
+          const int am = A_KFAST ? e / kGemmDepth : e % kGemmTile;
+          L.a[ak][am] = (m0 + am < M && k0 + ak < K) ? fa(m0 + am, k0 + ak) : 0.f;
+          const int bk = B_KFAST ? e % kGemmDepth : e / kGemmTile;
+          const int bn = B_KFAST ? e / kGemmDepth : e % kGemmTile;
+          L.b[bk][bn] = (n0 + bn < N && k0 + bk < K) ? fb(k0 + bk, n0 + bn) : 0.f;
+        }
+        __syncthreads();
+#pragma unroll
+        for (int kk = 0; kk < kGemmDepth; ++kk) {
+          const float4 av = *(const float4*)&L.a[kk][tm];
+          const float4 bv = *(const float4*)&L.b[kk][tn];
+          const float a4[4] = {av.x, av.y, av.z, av.w}, b4[4] = {bv.x, bv.y, bv.z, bv.w};
+#pragma unroll
+          for (int i = 0; i < 4; ++i)
+#pragma unroll
+            for (int j = 0; j < 4; ++j) acc[i][j] = fmaf(a4[i], b4[j], acc[i][j]);
+        }
+        __syncthreads();
+      }
+#pragma unroll
+      for (int i = 0; i < 4; ++i)
+#pragma unroll
+        for (int j = 0; j < 4; ++j)
+          if (m0 + tm + i < M && n0 + tn + j < N) fc(m0 + tm + i, n0 + tn + j, acc[i][j]);
+    }
+}
+
+// ---------------------------------------------------------------------------------------------
 // forward
 
-// P_q = A * Bm, A = G1[i1] (d1 x r1), Bm = G2[i2] (r1 x d2*r2).  Prefixes are visited in by-i2
-// order so that neighbouring blocks read the same G2 slice.
+// P_q = A * Bm, A = G1[i1] (d1 x r1), Bm = G2[i2] (r1 x d2*r2), for the <= 16 prefixes of one
+// by-i2 chunk at a time: their A stacked are the rows of one product with the shared Bm.
 __global__ __launch_bounds__(kThreads) void k_prefix_fwd(Shape sh, const float* __restrict__ g1,
                                                          const float* __restrict__ g2,
-                                                         const int* __restrict__ g2_list,
-                                                         const int* __restrict__ q_i1,
-                                                         const int* __restrict__ q_i2,
+                                                         const int4* __restrict__ c2_desc,
+                                                         const int4* __restrict__ c2_item,
                                                          float* __restrict__ P,
                                                          const Counters* __restrict__ ctr) {
-  const int Q = ctr->Q;
-  for (int k = blockIdx.x; k < Q; k += gridDim.x) {
-    const int q = g2_list[k];
-    const float* A = g1 + (size_t)q_i1[q] * sh.S1;
-    const float* Bm = g2 + (size_t)q_i2[q] * sh.S2;
-    float* Pq = P + (size_t)q * sh.PN;
-    for (int o = threadIdx.x; o < sh.PN; o += kThreads) {
-      const int j1 = o / sh.W, col = o % sh.W;
-      float acc = 0.f;
-      for (int a = 0; a < sh.r1; ++a) acc = fmaf(A[j1 * sh.r1 + a], Bm[a * sh.W + col], acc);
-      Pq[o] = acc;
+  __shared__ GemmLds L;
+  __shared__ int q_of[kChunk2], i1_of[kChunk2];
+  const int nchunk = ctr->nchunk2;
+  for (int c = blockIdx.x; c < nchunk; c += gridDim.x) {
+    const int4 desc = c2_desc[c];
+    const int cnt = desc.z;
+    __syncthreads();  // the previous chunk's readers of q_of / i1_of are done
+    if ((int)threadIdx.x < cnt) {
+      const int4 it = c2_item[(size_t)c * kChunk2 + threadIdx.x];
+      q_of[threadIdx.x] = it.x;
+      i1_of[threadIdx.x] = it.y;
     }
+    __syncthreads();
+    const float* Bm = g2 + (size_t)desc.x * sh.S2;
+    block_gemm<true, false>(
+        L, cnt * sh.d1, sh.W, sh.r1,
+        [&](int m, int k) { return g1[(size_t)i1_of[m / sh.d1] * sh.S1 + (m % sh.d1) * sh.r1 + k]; },
+        [&](int k, int n) { return Bm[(size_t)k * sh.W + n]; },
+        [&](int m, int n, float v) { P[(size_t)q_of[m / sh.d1] * sh.PN + (m % sh.d1) * sh.W + n] = v; });
   }
 }
 
@@ -100,6 +162,74 @@ __global__ __launch_bounds__(kThreads) void k_row_fwd(Shape sh, int B, const flo
           for (int c = 0; c < sh.r2; ++c) acc = fmaf(Pq[m * sh.r2 + c], C[c * sh.d3 + j3], acc);
           E[e] = acc;
         }
+      }
+      for (int e = lane; e < sh.D; e += kWave) o[e] = E[e];
+    }
+  }
+}
+
+// The same with the operands staged: a wavefront reads the ids, positions, prefixes and i3 of its
+// 32 slots in one go, copies P_q (rows padded by one float against bank conflicts) and G3[i3] into
+// LDS of its own when they change, and forms E from there.  Needs
+// kWavesPerBlock * (D + M*(r2+1) + S3) floats of LDS; larger shapes take k_row_fwd.
+__global__ __launch_bounds__(kThreads) void k_row_fwd_staged(
+    Shape sh, int B, const float* __restrict__ g3, const float* __restrict__ P,
+    const int* __restrict__ s_u, const uint32_t* __restrict__ perm, const int* __restrict__ u_i3,
+    const int* __restrict__ u_q, float* __restrict__ out, Counters* ctr) {
+  extern __shared__ float lds[];
+  static_assert(kTileSlots <= kWave, "one lane per slot");
+  const int w = threadIdx.x / kWave, lane = threadIdx.x % kWave;
+  const int ps = sh.r2 + 1;
+  float* E = lds + (size_t)w * (sh.D + sh.M * ps + sh.S3);
+  float* Pl = E + sh.D;
+  float* Cl = Pl + sh.M * ps;
+  const int ntiles = (B + kTileSlots - 1) / kTileSlots;
+  for (int tile = blockIdx.x * kWavesPerBlock + w; tile < ntiles;
+       tile += gridDim.x * kWavesPerBlock) {
+    const int s = tile * kTileSlots + lane;
+    const bool mine = lane < kTileSlots && s < B;
+    const int mysu = mine ? s_u[s] : -1;
+    const uint32_t myb = mine ? perm[s] : 0u;
+    const int myq = mysu >= 0 ? u_q[mysu] : 0;
+    const int myi3 = mysu >= 0 ? u_i3[mysu] : 0;
+    const int nslots = min(kTileSlots, B - tile * kTileSlots);
+    int cur = -2, curq = -1, curi3 = -1;
+    for (int k = 0; k < nslots; ++k) {
+      const int u = __shfl(mysu, k);
+      const uint32_t b = (uint32_t)__shfl((int)myb, k);
+      if (b >= (uint32_t)B) {
+        flag_error(ctr, 1);
+        continue;
+      }
+      float* o = out + (size_t)b * sh.D;
+      if (u < 0) {
+        for (int e = lane; e < sh.D; e += kWave) o[e] = 0.f;
+        continue;
+      }
+      if (u != cur) {
+        cur = u;
+        const int q = __shfl(myq, k), i3 = __shfl(myi3, k);
+        if (q != curq) {
+          curq = q;
+          const float* Pq = P + (size_t)q * sh.PN;
+          for (int e = lane; e < sh.PN; e += kWave) Pl[(e / sh.r2) * ps + e % sh.r2] = Pq[e];
+        }
+        if (i3 != curi3) {
+          curi3 = i3;
+          const float* C = g3 + (size_t)i3 * sh.S3;
+          for (int e = lane; e < sh.S3; e += kWave) Cl[e] = C[e];
+        }
+        __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+        __builtin_amdgcn_wave_barrier();
+        for (int e = lane; e < sh.D; e += kWave) {
+          const float* pr = Pl + (e / sh.d3) * ps;
+          const float* cc = Cl + e % sh.d3;
+          float acc = 0.f;
+          for (int c = 0; c < sh.r2; ++c) acc = fmaf(pr[c], cc[c * sh.d3], acc);
+          E[e] = acc;
+        }
+        __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+        __builtin_amdgcn_wave_barrier();
       }
       for (int e = lane; e < sh.D; e += kWave) o[e] = E[e];
     }
@@ -179,7 +309,8 @@ __global__ __launch_bounds__(kThreads) void k_gsum_fix(Shape sh, const int* __re
   }
 }
 
-// dPsum_q = sum over the unique ids u of prefix q of g_u * G3[i3(u)]^T, g_u read as (d1*d2) x d3.
+// dPsum_q = sum over the unique ids u of prefix q of g_u * G3[i3(u)]^T, g_u read as (d1*d2) x d3:
+// one product per prefix whose contraction index runs over (u, j3).
 __global__ __launch_bounds__(kThreads) void k_u_bwd(Shape sh, const float* __restrict__ g3,
                                                     const float* __restrict__ grad,
                                                     const float* __restrict__ gsum,
@@ -188,89 +319,152 @@ __global__ __launch_bounds__(kThreads) void k_u_bwd(Shape sh, const float* __res
                                                     const int* __restrict__ q_us,
                                                     float* __restrict__ dPsum,
                                                     const Counters* __restrict__ ctr) {
+  __shared__ GemmLds L;
   const int Q = ctr->Q;
   for (int q = blockIdx.x; q < Q; q += gridDim.x) {
     const int u0 = q_us[q], u1 = q_us[q + 1];
-    for (int o = threadIdx.x; o < sh.PN; o += kThreads) {
-      const int m = o / sh.r2, c = o % sh.r2;
-      float acc = 0.f;
-      for (int u = u0; u < u1; ++u) {
-        const float* g = grad_of_unique(u, u_code, grad, gsum, sh.D) + m * sh.d3;
-        const float* C = g3 + (size_t)u_i3[u] * sh.S3 + c * sh.d3;
-        for (int j3 = 0; j3 < sh.d3; ++j3) acc = fmaf(g[j3], C[j3], acc);
-      }
-      dPsum[(size_t)q * sh.PN + o] = acc;
-    }
+    float* dst = dPsum + (size_t)q * sh.PN;
+    block_gemm<true, true>(
+        L, sh.M, sh.r2, (u1 - u0) * sh.d3,
+        [&](int m, int k) {
+          return grad_of_unique(u0 + k / sh.d3, u_code, grad, gsum, sh.D)[m * sh.d3 + k % sh.d3];
+        },
+        [&](int k, int n) { return g3[(size_t)u_i3[u0 + k / sh.d3] * sh.S3 + n * sh.d3 + k % sh.d3]; },
+        [&](int m, int n, float v) { dst[m * sh.r2 + n] = v; });
   }
 }
 
-// part3[c] = sum over the unique ids u of chunk c (all with one i3) of P_q(u)^T g_u   (r2 x d3)
+// part3[c] = sum over the unique ids u of chunk c (all with one i3) of P_q(u)^T g_u   (r2 x d3):
+// one product per chunk whose contraction index runs over (u, row of P).
 __global__ __launch_bounds__(kThreads) void k_dg3(Shape sh, const float* __restrict__ P,
                                                   const float* __restrict__ grad,
                                                   const float* __restrict__ gsum,
-                                                  const int* __restrict__ u_code,
-                                                  const int* __restrict__ u_q,
-                                                  const int* __restrict__ g3_list,
+                                                  const int2* __restrict__ c3_item,
                                                   const int4* __restrict__ c3_desc,
                                                   float* __restrict__ part3,
                                                   const Counters* __restrict__ ctr) {
+  __shared__ GemmLds L;
+  __shared__ const float* g_of[kChunk3];
+  __shared__ const float* p_of[kChunk3];
   const int nchunk = ctr->nchunk3;
   for (int c = blockIdx.x; c < nchunk; c += gridDim.x) {
-    const int4 desc = c3_desc[c];
-    const int k0 = desc.y, k1 = desc.y + desc.z;
-    for (int o = threadIdx.x; o < sh.S3; o += kThreads) {
-      const int cc = o / sh.d3, j3 = o % sh.d3;
-      float acc = 0.f;
-      for (int k = k0; k < k1; ++k) {
-        const int u = g3_list[k];
-        const float* Pq = P + (size_t)u_q[u] * sh.PN + cc;
-        const float* g = grad_of_unique(u, u_code, grad, gsum, sh.D) + j3;
-        for (int m = 0; m < sh.M; ++m) acc = fmaf(Pq[m * sh.r2], g[m * sh.d3], acc);
+    const int cnt = c3_desc[c].z;
+    __syncthreads();
+    if ((int)threadIdx.x < cnt) {
+      const int2 it = c3_item[(size_t)c * kChunk3 + threadIdx.x];  // {gradient-row code, prefix}
+      g_of[threadIdx.x] = it.x >= 0 ? grad + (size_t)it.x * sh.D : gsum + (size_t)(-it.x - 1) * sh.D;
+      p_of[threadIdx.x] = P + (size_t)it.y * sh.PN;
+    }
+    __syncthreads();
+    float* dst = part3 + (size_t)c * sh.S3;
+    block_gemm<false, false>(
+        L, sh.r2, sh.d3, cnt * sh.M,
+        [&](int m, int k) { return p_of[k / sh.M][(k % sh.M) * sh.r2 + m]; },
+        [&](int k, int n) { return g_of[k / sh.M][(k % sh.M) * sh.d3 + n]; },
+        [&](int m, int n, float v) { dst[m * sh.d3 + n] = v; });
+  }
+}
+
+// The same for shapes whose P_q and gradient row fit the LDS a few ids at a time: the output is
+// small (r2 x d3) and the contraction long, so each thread keeps its outputs and the block walks
+// the ids of the chunk, `group` of them per LDS fill, in list order.
+__global__ __launch_bounds__(kThreads) void k_dg3_staged(Shape sh, int group,
+                                                         const float* __restrict__ P,
+                                                         const float* __restrict__ grad,
+                                                         const float* __restrict__ gsum,
+                                                         const int2* __restrict__ c3_item,
+                                                         const int4* __restrict__ c3_desc,
+                                                         float* __restrict__ part3,
+                                                         const Counters* __restrict__ ctr) {
+  extern __shared__ float lds[];  // group * (PN + D) floats
+  __shared__ const float* g_of[kChunk3];
+  __shared__ const float* p_of[kChunk3];
+  constexpr int kOut = 4;  // outputs per thread per pass
+  const int nchunk = ctr->nchunk3;
+  const int per = sh.PN + sh.D;
+  for (int c = blockIdx.x; c < nchunk; c += gridDim.x) {
+    const int cnt = c3_desc[c].z;
+    __syncthreads();
+    if ((int)threadIdx.x < cnt) {
+      const int2 it = c3_item[(size_t)c * kChunk3 + threadIdx.x];
+      g_of[threadIdx.x] = it.x >= 0 ? grad + (size_t)it.x * sh.D : gsum + (size_t)(-it.x - 1) * sh.D;
+      p_of[threadIdx.x] = P + (size_t)it.y * sh.PN;
+    }
+    __syncthreads();
+    float* dst = part3 + (size_t)c * sh.S3;
+    for (int o0 = 0; o0 < sh.S3; o0 += kThreads * kOut) {
+      float acc[kOut];
+#pragma unroll
+      for (int x = 0; x < kOut; ++x) acc[x] = 0.f;
+      for (int t0 = 0; t0 < cnt; t0 += group) {
+        const int nt = min(group, cnt - t0);
+        __syncthreads();  // the previous fill has been used
+        for (int t = 0; t < nt; ++t) {
+          float* pl = lds + (size_t)t * per;
+          for (int e = threadIdx.x; e < sh.PN; e += kThreads) pl[e] = p_of[t0 + t][e];
+          for (int e = threadIdx.x; e < sh.D; e += kThreads) pl[sh.PN + e] = g_of[t0 + t][e];
+        }
+        __syncthreads();
+#pragma unroll
+        for (int x = 0; x < kOut; ++x) {
+          const int o = o0 + x * kThreads + (int)threadIdx.x;
+          if (o < sh.S3) {
+            const int b = o / sh.d3, j3 = o % sh.d3;
+            for (int t = 0; t < nt; ++t) {
+              const float* pl = lds + (size_t)t * per + b;
+              const float* gl = lds + (size_t)t * per + sh.PN + j3;
+              for (int m = 0; m < sh.M; ++m) acc[x] = fmaf(pl[m * sh.r2], gl[m * sh.d3], acc[x]);
+            }
+          }
+        }
       }
-      part3[(size_t)c * sh.S3 + o] = acc;
+#pragma unroll
+      for (int x = 0; x < kOut; ++x) {
+        const int o = o0 + x * kThreads + (int)threadIdx.x;
+        if (o < sh.S3) dst[o] = acc[x];
+      }
     }
   }
 }
 
 // For the prefixes q of chunk c (all with one i2, Bm = G2[i2]):
-//   dg1part[q] = dPsum_q * Bm^T                      (d1 x r1), one per prefix
-//   part2[c]   = sum over q of G1[i1(q)]^T * dPsum_q  (r1 x d2*r2)
+//   dg1part[q] = dPsum_q * Bm^T                      (d1 x r1), the prefixes stacked: one product
+//   part2[c]   = sum over q of G1[i1(q)]^T * dPsum_q  (r1 x d2*r2), contraction over (q, j1)
 __global__ __launch_bounds__(kThreads) void k_prefix_bwd(Shape sh, const float* __restrict__ g1,
                                                          const float* __restrict__ g2,
                                                          const float* __restrict__ dPsum,
-                                                         const int* __restrict__ q_i1,
-                                                         const int* __restrict__ g2_list,
                                                          const int4* __restrict__ c2_desc,
+                                                         const int4* __restrict__ c2_item,
                                                          float* __restrict__ dg1part,
                                                          float* __restrict__ part2,
                                                          const Counters* __restrict__ ctr) {
+  __shared__ GemmLds L;
+  __shared__ int q_of[kChunk2], i1_of[kChunk2];
   const int nchunk = ctr->nchunk2;
   for (int c = blockIdx.x; c < nchunk; c += gridDim.x) {
     const int4 desc = c2_desc[c];
-    const int bin = desc.x, k0 = desc.y, k1 = desc.y + desc.z;
-    const float* Bm = g2 + (size_t)bin * sh.S2;
-    for (int k = k0; k < k1; ++k) {
-      const int q = g2_list[k];
-      const float* dP = dPsum + (size_t)q * sh.PN;
-      for (int o = threadIdx.x; o < sh.S1; o += kThreads) {
-        const int j1 = o / sh.r1, a = o % sh.r1;
-        float acc = 0.f;
-        for (int col = 0; col < sh.W; ++col)
-          acc = fmaf(dP[j1 * sh.W + col], Bm[a * sh.W + col], acc);
-        dg1part[(size_t)q * sh.S1 + o] = acc;
-      }
+    const int cnt = desc.z;
+    __syncthreads();
+    if ((int)threadIdx.x < cnt) {
+      const int4 it = c2_item[(size_t)c * kChunk2 + threadIdx.x];
+      q_of[threadIdx.x] = it.x;
+      i1_of[threadIdx.x] = it.y;
     }
-    for (int o = threadIdx.x; o < sh.S2; o += kThreads) {
-      const int a = o / sh.W, col = o % sh.W;
-      float acc = 0.f;
-      for (int k = k0; k < k1; ++k) {
-        const int q = g2_list[k];
-        const float* A = g1 + (size_t)q_i1[q] * sh.S1 + a;
-        const float* dP = dPsum + (size_t)q * sh.PN + col;
-        for (int j1 = 0; j1 < sh.d1; ++j1) acc = fmaf(A[j1 * sh.r1], dP[j1 * sh.W], acc);
-      }
-      part2[(size_t)c * sh.S2 + o] = acc;
-    }
+    __syncthreads();
+    const float* Bm = g2 + (size_t)desc.x * sh.S2;
+    block_gemm<true, true>(
+        L, cnt * sh.d1, sh.r1, sh.W,
+        [&](int m, int k) { return dPsum[(size_t)q_of[m / sh.d1] * sh.PN + (m % sh.d1) * sh.W + k]; },
+        [&](int k, int n) { return Bm[(size_t)n * sh.W + k]; },
+        [&](int m, int n, float v) {
+          dg1part[(size_t)q_of[m / sh.d1] * sh.S1 + (m % sh.d1) * sh.r1 + n] = v;
+        });
+    float* dst = part2 + (size_t)c * sh.S2;
+    block_gemm<false, false>(
+        L, sh.r1, sh.W, cnt * sh.d1,
+        [&](int m, int k) { return g1[(size_t)i1_of[k / sh.d1] * sh.S1 + (k % sh.d1) * sh.r1 + m]; },
+        [&](int k, int n) { return dPsum[(size_t)q_of[k / sh.d1] * sh.PN + (k % sh.d1) * sh.W + n]; },
+        [&](int m, int n, float v) { dst[(size_t)m * sh.W + n] = v; });
   }
 }
 
@@ -401,17 +595,27 @@ static inline int grid_for(int64_t work_items, int cap) {
   return (int)std::max<int64_t>(1, std::min<int64_t>(work_items, cap));
 }
 constexpr int kGridCap = 256 * 8;  // persistent blocks: 8 per compute unit
+constexpr size_t kLdsBudget = 48 * 1024;  // dynamic LDS a block of the staged kernels may ask for
 
 void launch_prefix_fwd(const Plan& pl, const Workspace& ws, const float* g1, const float* g2, int B,
                        hipStream_t st) {
-  const int grid = grid_for(std::min<int64_t>(B, pl.maxQ), kGridCap);
-  k_prefix_fwd<<<grid, kThreads, 0, st>>>(pl.sh, g1, g2, ws.g2_list, ws.q_i1, ws.q_i2, ws.P, ws.ctr);
+  const int grid = grid_for(cdiv(std::min<int64_t>(B, pl.maxQ), kChunk2) + pl.sh.n2, kGridCap);
+  k_prefix_fwd<<<grid, kThreads, 0, st>>>(pl.sh, g1, g2, ws.c2_desc, ws.c2_item, ws.P, ws.ctr);
 }
 
 void launch_row_fwd(const Plan& pl, const Workspace& ws, const float* g3, int B, float* out,
                     hipStream_t st) {
   const int tiles = cdiv(B, kTileSlots);
   const int grid = grid_for(cdiv(tiles, kWavesPerBlock), kGridCap);
+  const Shape& s = pl.sh;
+  const size_t staged =
+      (size_t)kWavesPerBlock * ((size_t)s.D + (size_t)s.M * (s.r2 + 1) + s.S3) * sizeof(float);
+  if (staged <= kLdsBudget) {
+    k_row_fwd_staged<<<grid, kThreads, staged, st>>>(s, B, g3, ws.P, ws.s_u,
+                                                     ws.val[(pl.passes - 1) & 1], ws.u_i3, ws.u_q,
+                                                     out, ws.ctr);
+    return;
+  }
   const size_t lds = (size_t)kWavesPerBlock * pl.sh.D * sizeof(float);
   k_row_fwd<<<grid, kThreads, lds, st>>>(pl.sh, B, g3, ws.P, ws.s_u, ws.val[(pl.passes - 1) & 1],
                                          ws.u_i3, ws.u_q, out, ws.ctr);
@@ -439,14 +643,21 @@ void launch_u_bwd(const Plan& pl, const Workspace& ws, const float* g3, const fl
 
 void launch_dg3(const Plan& pl, const Workspace& ws, const float* grad, int B, hipStream_t st) {
   const int grid = grid_for(cdiv(B, kChunk3) + pl.sh.n3, kGridCap);
-  k_dg3<<<grid, kThreads, 0, st>>>(pl.sh, ws.P, grad, ws.gsum, ws.u_code, ws.u_q, ws.g3_list,
-                                   ws.c3_desc, ws.part3, ws.ctr);
+  const size_t per = ((size_t)pl.sh.PN + pl.sh.D) * sizeof(float);
+  if (per <= kLdsBudget) {
+    const int group = (int)std::min<size_t>(4, kLdsBudget / per);
+    k_dg3_staged<<<grid, kThreads, group * per, st>>>(pl.sh, group, ws.P, grad, ws.gsum, ws.c3_item,
+                                                      ws.c3_desc, ws.part3, ws.ctr);
+    return;
+  }
+  k_dg3<<<grid, kThreads, 0, st>>>(pl.sh, ws.P, grad, ws.gsum, ws.c3_item, ws.c3_desc, ws.part3,
+                                   ws.ctr);
 }
 
 void launch_prefix_bwd(const Plan& pl, const Workspace& ws, const float* g1, const float* g2, int B,
                        hipStream_t st) {
   const int grid = grid_for(cdiv(std::min<int64_t>(B, pl.maxQ), kChunk2) + pl.sh.n2, kGridCap);
-  k_prefix_bwd<<<grid, kThreads, 0, st>>>(pl.sh, g1, g2, ws.dPsum, ws.q_i1, ws.g2_list, ws.c2_desc,
+  k_prefix_bwd<<<grid, kThreads, 0, st>>>(pl.sh, g1, g2, ws.dPsum, ws.c2_desc, ws.c2_item,
                                           ws.dg1part, ws.part2, ws.ctr);
 }
 
