@@ -50,6 +50,7 @@ struct GemmLds {
 template <bool A_KFAST, bool B_KFAST, class FA, class FB, class FC>
 __device__ __forceinline__ void block_gemm(GemmLds& L, int M, int N, int K, FA fa, FB fb, FC fc) {
   static_assert(kThreads == 256, "sixteen by sixteen threads of 4 x 4 outputs");
+  constexpr int kPer = kGemmTile * kGemmDepth / kThreads;  // operand elements a thread stages
   const int t = threadIdx.x, tm = (t / 16) * 4, tn = (t % 16) * 4;
   for (int m0 = 0; m0 < M; m0 += kGemmTile)
     for (int n0 = 0; n0 < N; n0 += kGemmTile) {
@@ -58,18 +59,30 @@ __device__ __forceinline__ void block_gemm(GemmLds& L, int M, int N, int K, FA f
       for (int i = 0; i < 4; ++i)
 #pragma unroll
         for (int j = 0; j < 4; ++j) acc[i][j] = 0.f;
-      for (int k0 = 0; k0 < K; k0 += kGemmDepth) {
+      // the operands of step k0 + kGemmDepth are fetched while step k0 is multiplied
+      float ra[kPer], rb[kPer];
+      auto fetch = [&](int k0) {
 #pragma unroll
-        for (int i = 0; i < kGemmTile * kGemmDepth / kThreads; ++i) {
+        for (int i = 0; i < kPer; ++i) {
           const int e = t + i * kThreads;
           const int ak = A_KFAST ? e % kGemmDepth : e / kGemmTile;
           const int am = A_KFAST ? e / kGemmDepth : e % kGemmTile;
-          L.a[ak][am] = (m0 + am < M && k0 + ak < K) ? fa(m0 + am, k0 + ak) : 0.f;
+          ra[i] = (m0 + am < M && k0 + ak < K) ? fa(m0 + am, k0 + ak) : 0.f;
           const int bk = B_KFAST ? e % kGemmDepth : e / kGemmTile;
           const int bn = B_KFAST ? e / kGemmDepth : e % kGemmTile;
-          L.b[bk][bn] = (n0 + bn < N && k0 + bk < K) ? fb(k0 + bk, n0 + bn) : 0.f;
+          rb[i] = (n0 + bn < N && k0 + bk < K) ? fb(k0 + bk, n0 + bn) : 0.f;
+        }
+      };
+      fetch(0);
+      for (int k0 = 0; k0 < K; k0 += kGemmDepth) {
+#pragma unroll
+        for (int i = 0; i < kPer; ++i) {
+          const int e = t + i * kThreads;
+          L.a[A_KFAST ? e % kGemmDepth : e / kGemmTile][A_KFAST ? e / kGemmDepth : e % kGemmTile] = ra[i];
+          L.b[B_KFAST ? e % kGemmDepth : e / kGemmTile][B_KFAST ? e / kGemmDepth : e % kGemmTile] = rb[i];
         }
         __syncthreads();
+        if (k0 + kGemmDepth < K) fetch(k0 + kGemmDepth);
 #pragma unroll
         for (int kk = 0; kk < kGemmDepth; ++kk) {
           const float4 av = *(const float4*)&L.a[kk][tm];
