@@ -60,14 +60,21 @@ enum {
                                       earlier use of the index set (a pipeline can start a step
                                       earlier, and the caller's stream carries one event less)  */
   TT_EMB_FLAG_GENERIC_KERNELS = 2u /* use the any-shape vector-ALU kernels even for shapes that
-                                      have matrix-core kernels (d1 = d2 = 4, r1 = r2 in
-                                      {16,32,64}, d3 in {4,8}); for comparison and testing       */
+                                      have matrix-core kernels (d1 in {4,8,...,32}, d2 = 4,
+                                      r1 = r2 in {16,32,64}, d3 in {4,8}); for comparison and
+                                      testing                                                    */
 };
 
 typedef struct {
   int64_t n[3];      /* node factors n1,n2,n3 (paper m_k); N = n1*n2*n3 must be below 2^31;
                         n2 and n3 at most 2048                                                  */
-  int32_t d[3];      /* embedding-dimension factors d1,d2,d3 (paper n_k); D = d1*d2*d3 <= 4096  */
+  int32_t d[3];      /* embedding-dimension factors d1,d2,d3 (paper n_k); D = d1*d2*d3 <= 4096.
+                        d1 = 8, 12, ... 32 with d2 = 4, d3 in {4,8}, r1 = r2 in {16,32,64} also
+                        runs on the matrix-core kernels: G1[i1] is treated as d1/4 slabs of
+                        4 x r1 (a table with d1/4 times the first-core slices and quarter-height
+                        rows over the same memory); this needs (d1/4)*N < 2^31 and
+                        (d1/4)*max_batch < 2^30, enlarges the workspace accordingly and is
+                        invisible at this interface                                             */
   int32_t r[2];      /* inner TT ranks r1, r2 (paper R_1, R_2)                                  */
   int64_t max_batch; /* upper bound on B, sizes the workspace; 1 <= max_batch < 2^30            */
   int32_t device;    /* HIP device ordinal the buffers live on                                  */
