@@ -399,6 +399,43 @@ def test_prepare_pipeline_matches_oracle_over_three_steps(flags):
     emb.close()
 
 
+@pytest.mark.parametrize("flags", [0, 4])
+def test_prepare_with_reused_ids_buffers(flags):
+    """Ten steps through two ids buffers whose contents change every step (the index sets rotate
+    underneath, every set meets every buffer several times), each step against the oracle."""
+    torch = _torch()
+    from paper_2206_10581_amd import TTEmbedding
+    n, d, r, B, steps = (9, 21, 13), (4, 4, 8), (16, 16), 3000, 10
+    s = Shape(n, d, r)
+    rng = np.random.default_rng(4242 + flags)
+    cur = [(rng.standard_normal(cs) / 4).astype(np.float32) for cs in s.core_shapes()]
+    batches = [rng.integers(0, s.N, B).astype(np.int64) for _ in range(steps)]
+    for b in batches:
+        b[:200] = b[0]
+    grad = rng.standard_normal((B, s.D)).astype(np.float32)
+    g = torch.from_numpy(grad).cuda()
+    emb = TTEmbedding(n, d, r, B, cur, flags=flags)
+    bufs = [torch.empty(B, dtype=torch.int64, device="cuda") for _ in range(2)]
+    bufs[0].copy_(torch.from_numpy(batches[0]))
+    torch.cuda.synchronize()
+    emb.prepare(bufs[0])
+    for k in range(steps):
+        if k + 1 < steps:
+            torch.cuda.synchronize()                      # the buffer's earlier reader is done
+            bufs[(k + 1) % 2].copy_(torch.from_numpy(batches[k + 1]))
+            torch.cuda.synchronize()                      # ids complete before prepare (flag 4)
+            emb.prepare(bufs[(k + 1) % 2])
+        out = emb.forward(bufs[k % 2]).cpu().numpy()
+        assert row_error(out, ora.forward(s, *cur, batches[k])) <= ROW_TOL, k
+        st = emb.stats(check=False)
+        assert st["U"] == np.unique(batches[k]).size, k
+        emb.backward_update(g, 0.01)
+        cur = [c.astype(np.float32) for c in ora.backward_update(s, *cur, batches[k], grad, 0.01)]
+        for j in range(3):
+            assert core_error(emb.cores[j].cpu().numpy(), cur[j]) <= CORE_TOL, (k, j)
+    emb.close()
+
+
 def test_lookup_only_calls_and_dense_materialisation():
     """forward_eval gives the rows of forward and arms no backward; materialize writes the dense
     table the cores define (all of config 1's 1000 rows, and a window of a rank-32 table that is
