@@ -684,25 +684,36 @@ __global__ __launch_bounds__(kMThreads) void k_row_fwd_mfma(
         }
       }
       float a[NB][KQ], b[NB][KQ];
+      int qx[NB];
 #pragma unroll
       for (int x = 0; x < NB; ++x) {
         const int first = st[x] >= 0 ? st[x] : 0;
         const int q = lane_value(myq, first);
+        qx[x] = q;
         const int i3 = __shfl(myi3, min(first + ul, nu - 1));
-        const f4* pa = (const f4*)(P + (size_t)(q >= 0 ? q : 0) * PN + l16 * R + KQ * kg);
         const float* pc = g3 + (size_t)i3 * S3 + (KQ * kg) * D3 + j3;
+        // a group whose prefix is the previous group's takes that group's P operand
+        if (x == 0 || q != qx[x - 1]) {
+          const f4* pa = (const f4*)(P + (size_t)(q >= 0 ? q : 0) * PN + l16 * R + KQ * kg);
 #pragma unroll
-        for (int j = 0; j < KQ / 4; ++j) {
-          const f4 v = pa[j];
-          a[x][4 * j + 0] = v.x;
-          a[x][4 * j + 1] = v.y;
-          a[x][4 * j + 2] = v.z;
-          a[x][4 * j + 3] = v.w;
+          for (int j = 0; j < KQ / 4; ++j) {
+            const f4 v = pa[j];
+            a[x][4 * j + 0] = v.x;
+            a[x][4 * j + 1] = v.y;
+            a[x][4 * j + 2] = v.z;
+            a[x][4 * j + 3] = v.w;
+          }
         }
 #pragma unroll
         for (int j = 0; j < KQ; ++j) b[x][j] = pc[j * D3];
       }
       TT_LOADS_DONE();
+#pragma unroll
+      for (int x = 1; x < NB; ++x)
+        if (qx[x] == qx[x - 1]) {
+#pragma unroll
+          for (int j = 0; j < KQ; ++j) a[x][j] = a[x - 1][j];
+        }
 #pragma unroll
       for (int x = 0; x < NB; ++x) {
         f4 acc = {0.f, 0.f, 0.f, 0.f};
