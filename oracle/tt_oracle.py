@@ -188,3 +188,43 @@ def adagrad_update(shape: Shape, g1, g2, g3, state, ids, grad, lr: float, eps: f
         new_state.append(s64.astype(np.float32))
         new_cores.append(g64.astype(np.float32))
     return tuple(new_cores), tuple(new_state)
+
+
+def touched_slices(shape: Shape, ids):
+    """Boolean masks over the slices of the three cores: which G1[i1], G2[i2], G3[i3] some in-range
+    id of the batch selects (index split of Section 3)."""
+    ids = _ids(ids)
+    ok = ids[(ids >= 0) & (ids < shape.N)]
+    n1, n2, n3 = shape.n
+    masks = [np.zeros(n, dtype=bool) for n in (n1, n2, n3)]
+    masks[0][ok // (n2 * n3)] = True
+    masks[1][(ok // n3) % n2] = True
+    masks[2][ok % n3] = True
+    return masks
+
+
+def adam_update(shape: Shape, g1, g2, g3, m, v, step: int, ids, grad, lr: float,
+                beta1: float, beta2: float, eps: float):
+    """One Adam step in the row-sparse ("lazy") form on the batch-summed core gradients; the paper
+    names no optimiser, this is the textbook rule (Kingma & Ba, Algorithm 1) applied to the slices
+    the batch touches and to nothing else:
+        m <- beta1 m + (1 - beta1) dG,   v <- beta2 v + (1 - beta2) dG^2,
+        G <- G - lr * (m / (1 - beta1^t)) / (sqrt(v / (1 - beta2^t)) + eps),   t = step = 1, 2, ...
+    Slices no id touches keep core, m and v as they are (their moments do not decay).  fp64
+    throughout, rounded to fp32 once.  Returns (new cores, new m, new v)."""
+    assert step >= 1
+    dg = grads(shape, g1, g2, g3, ids, grad)
+    masks = touched_slices(shape, ids)
+    c1, c2 = 1.0 - beta1 ** step, 1.0 - beta2 ** step
+    out_g, out_m, out_v = [], [], []
+    for G, M, V, d, mask in zip((g1, g2, g3), m, v, dg, masks):
+        G64, M64, V64 = G.astype(np.float64), M.astype(np.float64), V.astype(np.float64)
+        t = mask.reshape((-1,) + (1,) * (G.ndim - 1))        # broadcast over the slice
+        m_new = beta1 * M64 + (1.0 - beta1) * d
+        v_new = beta2 * V64 + (1.0 - beta2) * d * d
+        g_new = G64 - lr * (m_new / c1) / (np.sqrt(v_new / c2) + eps)
+        out_m.append(np.where(t, m_new, M64).astype(np.float32))
+        out_v.append(np.where(t, v_new, V64).astype(np.float32))
+        out_g.append(np.where(t, g_new, G64).astype(np.float32))
+    return tuple(out_g), tuple(out_m), tuple(out_v)
+

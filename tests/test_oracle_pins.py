@@ -354,3 +354,60 @@ def test_adagrad_first_step_moves_every_touched_entry_by_lr():
         moved = np.abs(d) > 1e-3
         np.testing.assert_allclose((G.astype(np.float64) - Gn)[moved],
                                    (lr / np.sqrt(2.0) * np.sign(d))[moved], rtol=1e-5)
+
+
+def test_adam_first_step_constant_gradient_and_untouched_slices():
+    """Pins of the oracle's Adam rule that do not re-type it.  (a) From zero moments the first step
+    is -lr * dG / (|dG| + eps): the bias corrections cancel the (1 - beta) factors, so with
+    eps -> 0 every entry with a nonzero gradient moves by exactly lr against the sign of its
+    gradient, whatever beta1 and beta2 are.  (b) With beta1 = beta2 = 0 there is no memory and every
+    step has that form.  (c) Slices no id touches keep core and moments bit for bit, even when
+    their moments are nonzero.  (d) Feeding the same gradient again: the corrected moments of a
+    constant gradient are that gradient and its square at every step (closed form of the two
+    geometric sums), so the second step moves by lr * sign(dG) again."""
+    s = Shape((5, 4, 6), (2, 3, 2), (3, 2))
+    rng = np.random.default_rng(11)
+    cores = [rng.standard_normal(cs).astype(np.float32) for cs in s.core_shapes()]
+    ids = np.array([0, 1, 7, 30, 31, 31], dtype=np.int64)
+    grad = rng.standard_normal((ids.size, s.D)).astype(np.float32)
+    dg = ora.grads(s, *cores, ids, grad)
+    masks = ora.touched_slices(s, ids)
+    # by hand (n2*n3 = 24): ids 0,1,7 -> (0,0,0),(0,0,1),(0,1,1); 30,31 -> (1,1,0),(1,1,1)
+    for mk in masks:
+        assert list(np.nonzero(mk)[0]) == [0, 1]
+    lr = 0.125
+    zero = [np.zeros_like(c) for c in cores]
+    for b1, b2 in ((0.9, 0.999), (0.5, 0.25), (0.0, 0.0)):
+        new, m, v = ora.adam_update(s, *cores, zero, zero, 1, ids, grad, lr, b1, b2, 1e-30)
+        for G, Gn, d, mk in zip(cores, new, dg, masks):
+            moved = d != 0
+            assert moved.any() and (~moved).any()
+            np.testing.assert_array_equal(Gn[~moved], G[~moved])
+            np.testing.assert_allclose(Gn[moved], (G.astype(np.float64) - lr * np.sign(d))[moved],
+                                       rtol=2e-7)
+        if b1 == 0.0:   # (b) any step number, any moments coming in: same step
+            junk = [np.abs(rng.standard_normal(c.shape)).astype(np.float32) for c in cores]
+            again, _, _ = ora.adam_update(s, *cores, junk, junk, 7, ids, grad, lr, 0.0, 0.0, 1e-30)
+            for Gn, Ga, mk in zip(new, again, masks):
+                np.testing.assert_array_equal(Ga[mk], Gn[mk])
+    # (c) untouched slices
+    m0 = [rng.standard_normal(c.shape).astype(np.float32) for c in cores]
+    v0 = [np.abs(rng.standard_normal(c.shape)).astype(np.float32) for c in cores]
+    new, m1, v1 = ora.adam_update(s, *cores, m0, v0, 3, ids, grad, lr, 0.9, 0.999, 1e-8)
+    for G, Gn, a, an, b, bn, mk in zip(cores, new, m0, m1, v0, v1, masks):
+        assert (~mk).any()
+        np.testing.assert_array_equal(Gn[~mk], G[~mk])
+        np.testing.assert_array_equal(an[~mk], a[~mk])
+        np.testing.assert_array_equal(bn[~mk], b[~mk])
+        assert not np.array_equal(an[mk], a[mk])
+    # (d) constant gradient: the loss is linear in each core, so dG3 does not depend on G3; keep
+    # G1, G2 fixed and step G3 twice with the moments carried along
+    b1, b2 = 0.9, 0.999
+    st1, m, v = ora.adam_update(s, *cores, zero, zero, 1, ids, grad, lr, b1, b2, 1e-30)
+    mixed = (cores[0], cores[1], st1[2])
+    st2, _, _ = ora.adam_update(s, *mixed, m, v, 2, ids, grad, lr, b1, b2, 1e-30)
+    d3 = dg[2]
+    moved = np.abs(d3) > 1e-3
+    np.testing.assert_allclose((st1[2].astype(np.float64) - st2[2])[moved], (lr * np.sign(d3))[moved],
+                               rtol=1e-5)
+
