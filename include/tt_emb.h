@@ -139,6 +139,20 @@ int tt_emb_set_reindex(tt_emb_t h, const int32_t* new_id_of, int64_t n_ids);
 int tt_emb_set_adagrad(tt_emb_t h, float* s1, float* s2, float* s3, float eps);
 
 /*
+ * The same for Adam in its row-sparse ("lazy") form: six state arrays (first moments m1..m3, second
+ * moments v1..v3; device fp32, shaped and aligned like the cores, borrowed), and for the slices a
+ * batch touches, with t = steps_done + 1, + 2, ... counting the backward_update calls that had a
+ * non-empty batch:
+ *   m <- beta1 m + (1 - beta1) dG ;  v <- beta2 v + (1 - beta2) dG^2
+ *   G <- G - lr * (m / (1 - beta1^t)) / (sqrt(v / (1 - beta2^t)) + eps)          (elementwise)
+ * Untouched slices keep core and moments (their moments do not decay).  0 <= beta < 1, eps > 0;
+ * steps_done is 0 for zeroed moments, or the step count the moments were saved at.  Six null
+ * pointers return to SGD; tt_emb_set_adagrad and tt_emb_set_adam replace each other.  Host-only.
+ */
+int tt_emb_set_adam(tt_emb_t h, float* m1, float* m2, float* m3, float* v1, float* v2, float* v3,
+                    float beta1, float beta2, float eps, int64_t steps_done);
+
+/*
  * Optional: builds the index structures (split, sort, unique ids and prefixes: the part of
  * Section 4.2's sharing that depends on the ids only) of a COMING batch ahead of time, on a stream
  * of the library's own that starts once everything enqueued so far on hip_stream has run.  A later

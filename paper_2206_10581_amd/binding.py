@@ -55,6 +55,7 @@ def load_library():
     lib.tt_emb_materialize.argtypes = [c_void_p, c_int64, c_int64, c_void_p, c_void_p]
     lib.tt_emb_set_reindex.argtypes = [c_void_p, c_void_p, c_int64]
     lib.tt_emb_set_adagrad.argtypes = [c_void_p, c_void_p, c_void_p, c_void_p, c_float]
+    lib.tt_emb_set_adam.argtypes = [c_void_p] + [c_void_p] * 6 + [c_float, c_float, c_float, c_int64]
     lib.tt_emb_prepare.argtypes = [c_void_p, c_void_p, c_int64, c_void_p]
     lib.tt_emb_get_stats.argtypes = [c_void_p, POINTER(c_int64), POINTER(c_int64), POINTER(c_int64)]
     lib.tt_emb_profile_enable.argtypes = [c_void_p, c_int]
@@ -66,7 +67,7 @@ def load_library():
     lib.tt_emb_strerror.restype = c_char_p
     for name in ("tt_emb_workspace_bytes", "tt_emb_create", "tt_emb_forward", "tt_emb_prepare",
                  "tt_emb_backward_update", "tt_emb_forward_eval", "tt_emb_materialize",
-                 "tt_emb_set_reindex", "tt_emb_set_adagrad", "tt_emb_get_stats", "tt_emb_profile_enable",
+                 "tt_emb_set_reindex", "tt_emb_set_adagrad", "tt_emb_set_adam", "tt_emb_get_stats", "tt_emb_profile_enable",
                  "tt_emb_profile_slots", "tt_emb_profile_read", "tt_emb_destroy"):
         getattr(lib, name).restype = c_int
     _lib = lib
@@ -119,6 +120,12 @@ def tt_emb_materialize(h, first_row: int, count: int, out_ptr: int, stream: int)
 
 def tt_emb_set_reindex(h, table_ptr: int, n_ids: int) -> int:
     return load_library().tt_emb_set_reindex(h, c_void_p(table_ptr), c_int64(n_ids))
+
+
+def tt_emb_set_adam(h, m_ptrs, v_ptrs, beta1: float, beta2: float, eps: float, steps_done: int = 0) -> int:
+    ptrs = [c_void_p(p) for p in (*m_ptrs, *v_ptrs)]
+    return load_library().tt_emb_set_adam(h, *ptrs, c_float(beta1), c_float(beta2), c_float(eps),
+                                          c_int64(steps_done))
 
 
 def tt_emb_set_adagrad(h, s1_ptr: int, s2_ptr: int, s3_ptr: int, eps: float) -> int:
@@ -264,6 +271,23 @@ class TTEmbedding:
             rc = tt_emb_set_adagrad(self.handle, *(t.data_ptr() for t in self.adagrad_state), eps)
         if rc:
             raise TTEmbError(rc, "tt_emb_set_adagrad")
+
+    def set_adam(self, beta1: float = 0.9, beta2: float = 0.999, eps: float = 1e-8,
+                 enable: bool = True):
+        """Switches backward_update to row-sparse Adam (moment tensors are created here, zeroed) or
+        back to SGD."""
+        torch = self.torch
+        self.adagrad_state = None
+        if not enable:
+            self.adam_state = None
+            rc = tt_emb_set_adam(self.handle, (0, 0, 0), (0, 0, 0), 0.0, 0.0, 0.0)
+        else:
+            self.adam_state = ([torch.zeros_like(c) for c in self.cores],
+                               [torch.zeros_like(c) for c in self.cores])
+            rc = tt_emb_set_adam(self.handle, [t.data_ptr() for t in self.adam_state[0]],
+                                 [t.data_ptr() for t in self.adam_state[1]], beta1, beta2, eps)
+        if rc:
+            raise TTEmbError(rc, "tt_emb_set_adam")
 
     def prepare(self, ids):
         """Index work of the next batch, overlapped with whatever follows on the current stream."""

@@ -1,5 +1,6 @@
 // C ABI of libtt_emb.so: argument checks, workspace carving, launch sequences, timing slots.
 #include <algorithm>
+#include <cmath>
 #include <cstdio>
 #include <cstring>
 #include <new>
@@ -27,7 +28,7 @@ void launch_dg3(const Plan&, const Workspace&, const float* grad, int B, hipStre
 void launch_prefix_bwd(const Plan&, const Workspace&, const float* g1, const float* g2, int B,
                        hipStream_t);
 void launch_sgd(const Plan&, const Workspace&, float* g1, float* g2, float* g3, float lr,
-                const Adagrad&, hipEvent_t stop, hipStream_t);
+                const UpdateRule&, hipEvent_t stop, hipStream_t);
 // matrix-core variants for the shapes mfma_shape() accepts
 bool mfma_shape(const Shape&);
 void launch_prefix_fwd_mfma(const Plan&, const Workspace&, const float* g1, const float* g2, int B,
@@ -235,7 +236,8 @@ struct tt_emb {
   int cur;            // set of the latest forward (and of the backward that follows it)
   float *g1, *g2, *g3;
   const int32_t* reindex;  // old id -> table row applied in front of the split, or nullptr
-  Adagrad ada;             // all null: plain SGD
+  UpdateRule ada;          // kind kUpdateSgd: plain SGD
+  int64_t adam_step;       // Adam: updates made since tt_emb_set_adam
   int64_t reindex_n;
   int64_t pending_B;  // -1: no forward pending
   int64_t last_B;     // batch size of the latest forward
@@ -354,7 +356,8 @@ int tt_emb_create(tt_emb_t* out, const tt_emb_config* cfg, float* g1, float* g2,
   h->g3 = g3;
   h->reindex = nullptr;
   h->reindex_n = 0;
-  h->ada = Adagrad{nullptr, nullptr, nullptr, 0.f};
+  h->ada = UpdateRule{};
+  h->adam_step = 0;
   h->pending_B = -1;
   h->last_B = 0;
   h->have_forward = false;
@@ -573,7 +576,45 @@ int tt_emb_set_adagrad(tt_emb_t h, float* s1, float* s2, float* s3, float eps) {
   if (!none && (s1 == nullptr || s2 == nullptr || s3 == nullptr)) return TT_EMB_EINVAL;
   if ((((uintptr_t)s1 | (uintptr_t)s2 | (uintptr_t)s3) & 15u) != 0) return TT_EMB_EINVAL;
   if (!none && !(eps > 0.f)) return TT_EMB_EINVAL;
-  h->ada = Adagrad{s1, s2, s3, none ? 0.f : eps};
+  h->ada = UpdateRule{};
+  if (!none) {
+    h->ada.kind = kUpdateAdagrad;
+    h->ada.s1 = s1;
+    h->ada.s2 = s2;
+    h->ada.s3 = s3;
+    h->ada.eps = eps;
+  }
+  return TT_EMB_OK;
+}
+
+int tt_emb_set_adam(tt_emb_t h, float* m1, float* m2, float* m3, float* v1, float* v2, float* v3,
+                    float beta1, float beta2, float eps, int64_t steps_done) {
+  if (h == nullptr) return TT_EMB_EINVAL;
+  float* p[6] = {m1, m2, m3, v1, v2, v3};
+  int nulls = 0;
+  uintptr_t bits = 0;
+  for (float* q : p) {
+    nulls += q == nullptr;
+    bits |= (uintptr_t)q;
+  }
+  if ((nulls != 0 && nulls != 6) || (bits & 15u) != 0) return TT_EMB_EINVAL;
+  h->ada = UpdateRule{};
+  h->adam_step = 0;
+  if (nulls == 6) return TT_EMB_OK;
+  if (!(eps > 0.f) || !(beta1 >= 0.f && beta1 < 1.f) || !(beta2 >= 0.f && beta2 < 1.f) ||
+      steps_done < 0)
+    return TT_EMB_EINVAL;
+  h->ada.kind = kUpdateAdam;
+  h->ada.s1 = m1;
+  h->ada.s2 = m2;
+  h->ada.s3 = m3;
+  h->ada.v1 = v1;
+  h->ada.v2 = v2;
+  h->ada.v3 = v3;
+  h->ada.eps = eps;
+  h->ada.beta1 = beta1;
+  h->ada.beta2 = beta2;
+  h->adam_step = steps_done;
   return TT_EMB_OK;
 }
 
@@ -637,6 +678,12 @@ int tt_emb_backward_update(tt_emb_t h, const float* grad_out, float lr, void* hi
       stop = h->done[h->cur];
     else
       (void)hipGetLastError();
+  }
+  if (h->ada.kind == kUpdateAdam) {
+    // bias corrections of step t = 1, 2, ... (every backward_update with a batch counts)
+    const double t = (double)++h->adam_step;
+    h->ada.corr1 = (float)(1.0 / (1.0 - std::pow((double)h->ada.beta1, t)));
+    h->ada.corr2 = (float)(1.0 / (1.0 - std::pow((double)h->ada.beta2, t)));
   }
   rc = run_slot(h, kSlotSgd, st,
                 [&] { launch_sgd(pl, ws, h->g1, h->g2, h->g3, lr, h->ada, stop, st); });

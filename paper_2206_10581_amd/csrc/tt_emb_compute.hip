@@ -481,16 +481,18 @@ __global__ __launch_bounds__(kThreads) void k_prefix_bwd(Shape sh, const float* 
   }
 }
 
-// Adds up the partial gradients of every touched slice and applies the update: the SGD step, or
-// with ADA the Adagrad step  S += dG^2,  G -= lr * dG / (sqrt(S) + eps)  on the same entries.
+// Adds up the partial gradients of every touched slice and applies the update: the SGD step, the
+// Adagrad step  S += dG^2,  G -= lr * dG / (sqrt(S) + eps),  or the Adam step
+// m = b1 m + (1-b1) dG,  v = b2 v + (1-b2) dG^2,  G -= lr * (m corr1) / (sqrt(v corr2) + eps)
+// on the same entries (moments of untouched slices are left alone).
 // A job owns up to 256*VEC consecutive entries of one slice (VEC = 4 when slice sizes allow 16-byte
 // accesses, else 1).  Its threads are arranged as `parts` groups side by side on the entries; the
 // job's list of partials (chunks for G3 and G2, prefixes for G1) is dealt round-robin to the
 // groups, whose sums are then added in group order.  parts depends on the slice size only and
 // every group walks its share in list order, so the order of each sum is fixed by the list length.
 // Jobs: n3*cdiv(S3, span) for G3, then n2*cdiv(S2, span) for G2, then n1*cdiv(S1, span) for G1.
-template <int VEC, bool ADA>
-__global__ __launch_bounds__(kThreads) void k_sgd(Shape sh, float lr, Adagrad ada,
+template <int VEC, int RULE>
+__global__ __launch_bounds__(kThreads) void k_sgd(Shape sh, float lr, UpdateRule ada,
                                                   float* __restrict__ g1,
                                                   float* __restrict__ g2, float* __restrict__ g3,
                                                   const float* __restrict__ part3,
@@ -510,7 +512,9 @@ __global__ __launch_bounds__(kThreads) void k_sgd(Shape sh, float lr, Adagrad ad
   for (int64_t job = blockIdx.x; job < jobs3 + jobs2 + jobs1; job += gridDim.x) {
     const float* src;  // partial k of the list lives at src + k*S
     float* G;
-    float* St = nullptr;  // Adagrad state of the slice
+    float* St = nullptr;  // state of the slice: Adagrad sums or Adam first moments
+    float* Vt = nullptr;  // Adam second moments
+    constexpr bool ADA = RULE != kUpdateSgd, ADAM = RULE == kUpdateAdam;
     int l0, l1, o0, S;
     if (job < jobs3) {
       const int bin = (int)(job / sp3);
@@ -521,6 +525,7 @@ __global__ __launch_bounds__(kThreads) void k_sgd(Shape sh, float lr, Adagrad ad
       S = sh.S3;
       G = g3 + (size_t)bin * sh.S3;
       if (ADA) St = ada.s3 + (size_t)bin * sh.S3;
+      if (ADAM) Vt = ada.v3 + (size_t)bin * sh.S3;
     } else if (job < jobs3 + jobs2) {
       const int64_t j = job - jobs3;
       const int bin = (int)(j / sp2);
@@ -531,6 +536,7 @@ __global__ __launch_bounds__(kThreads) void k_sgd(Shape sh, float lr, Adagrad ad
       S = sh.S2;
       G = g2 + (size_t)bin * sh.S2;
       if (ADA) St = ada.s2 + (size_t)bin * sh.S2;
+      if (ADAM) Vt = ada.v2 + (size_t)bin * sh.S2;
     } else {
       const int64_t j = job - jobs3 - jobs2;
       const int i1 = (int)(j / sp1);
@@ -541,6 +547,7 @@ __global__ __launch_bounds__(kThreads) void k_sgd(Shape sh, float lr, Adagrad ad
       S = sh.S1;
       G = g1 + (size_t)i1 * sh.S1;
       if (ADA) St = ada.s1 + (size_t)i1 * sh.S1;
+      if (ADAM) Vt = ada.v1 + (size_t)i1 * sh.S1;
     }
     if (l1 == l0) continue;  // slice not touched by this batch (uniform for the block)
     // thread layout: `lanes` threads side by side cover the job's entries, `parts` such groups
@@ -587,7 +594,13 @@ __global__ __launch_bounds__(kThreads) void k_sgd(Shape sh, float lr, Adagrad ad
     if (part == 0 && active) {
 #pragma unroll
       for (int x = 0; x < VEC; ++x) {
-        if (ADA) {
+        if (ADAM) {
+          const float m = fmaf(ada.beta1, St[o + x], (1.f - ada.beta1) * acc[x]);
+          const float v = fmaf(ada.beta2, Vt[o + x], (1.f - ada.beta2) * acc[x] * acc[x]);
+          St[o + x] = m;
+          Vt[o + x] = v;
+          G[o + x] = g_old[x] - lr * (m * ada.corr1) / (sqrtf(v * ada.corr2) + ada.eps);
+        } else if (ADA) {
           const float sq = fmaf(acc[x], acc[x], St[o + x]);
           St[o + x] = sq;
           G[o + x] = g_old[x] - lr * acc[x] / (sqrtf(sq) + ada.eps);
@@ -675,7 +688,7 @@ void launch_prefix_bwd(const Plan& pl, const Workspace& ws, const float* g1, con
 }
 
 void launch_sgd(const Plan& pl, const Workspace& ws, float* g1, float* g2, float* g3, float lr,
-                const Adagrad& ada, hipEvent_t stop, hipStream_t st) {
+                const UpdateRule& ada, hipEvent_t stop, hipStream_t st) {
   const Shape& s = pl.sh;
   const bool vec = (s.S1 % 4 == 0) && (s.S2 % 4 == 0) && (s.S3 % 4 == 0);
   const int span = kThreads * (vec ? 4 : 1);
@@ -697,10 +710,12 @@ void launch_sgd(const Plan& pl, const Workspace& ws, float* g1, float* g2, float
                                              ws.part2, ws.c2_start, ws.dg1part, ws.g1_first,       \
                                              ws.g1_end, ws.ctr);                                   \
   } while (0)
-  if (ada.s1 != nullptr) {
-    if (vec) TT_SGD(4, true); else TT_SGD(1, true);
+  if (ada.kind == kUpdateAdam) {
+    if (vec) TT_SGD(4, kUpdateAdam); else TT_SGD(1, kUpdateAdam);
+  } else if (ada.kind == kUpdateAdagrad) {
+    if (vec) TT_SGD(4, kUpdateAdagrad); else TT_SGD(1, kUpdateAdagrad);
   } else {
-    if (vec) TT_SGD(4, false); else TT_SGD(1, false);
+    if (vec) TT_SGD(4, kUpdateSgd); else TT_SGD(1, kUpdateSgd);
   }
 #undef TT_SGD
 }

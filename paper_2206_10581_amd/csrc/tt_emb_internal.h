@@ -47,10 +47,15 @@ struct IdSource {
   int64_t rows, n23;
 };
 
-// Optional Adagrad state of the update kernel (all null: plain SGD).
-struct Adagrad {
-  float *s1, *s2, *s3;  // running sums of squared gradients, shaped like the cores
+// Update rule of the update kernel and its caller-owned state (arrays shaped like the cores).
+enum UpdateKind { kUpdateSgd = 0, kUpdateAdagrad = 1, kUpdateAdam = 2 };
+struct UpdateRule {
+  int kind;
+  float *s1, *s2, *s3;  // Adagrad: running sums of squared gradients; Adam: first moments
+  float *v1, *v2, *v3;  // Adam: second moments
   float eps;
+  float beta1, beta2;   // Adam decay rates
+  float corr1, corr2;   // Adam bias corrections 1/(1 - beta1^t), 1/(1 - beta2^t) of this step
 };
 
 // Table and slice geometry, passed to kernels by value.

@@ -90,6 +90,16 @@ def test_handle_state_machine_without_launches(lib):
     assert lib.tt_emb_set_adagrad(h, 256, 512, 772, 1e-8) == TT_EMB_EINVAL # misaligned
     assert lib.tt_emb_set_adagrad(h, 256, 512, 768, 1e-8) == 0
     assert lib.tt_emb_set_adagrad(h, 0, 0, 0, 0.0) == 0                    # back to SGD
+    adam = lambda ptrs, b1, b2, eps, t=0: lib.tt_emb_set_adam(h, ptrs[:3], ptrs[3:], b1, b2, eps, t)
+    six = (256, 512, 768, 1024, 1280, 1536)
+    assert adam((256, 512, 768, 0, 0, 0), 0.9, 0.999, 1e-8) == TT_EMB_EINVAL   # all six or none
+    assert adam(six, 1.0, 0.999, 1e-8) == TT_EMB_EINVAL                        # beta below one
+    assert adam(six, 0.9, -0.1, 1e-8) == TT_EMB_EINVAL
+    assert adam(six, 0.9, 0.999, 0.0) == TT_EMB_EINVAL                         # eps must be positive
+    assert adam(six, 0.9, 0.999, 1e-8, -1) == TT_EMB_EINVAL                    # steps done so far
+    assert adam(six[:5] + (1540,), 0.9, 0.999, 1e-8) == TT_EMB_EINVAL          # misaligned
+    assert adam(six, 0.9, 0.999, 1e-8, 12) == 0
+    assert adam((0,) * 6, 0.0, 0.0, 0.0) == 0                                  # back to SGD
     assert lib.tt_emb_profile_slots() >= 10
     assert lib.tt_emb_profile_read(h, 0)[0] == 0 and lib.tt_emb_profile_read(h, 999)[0] == TT_EMB_EINVAL
     assert lib.tt_emb_destroy(h) == 0

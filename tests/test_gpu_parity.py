@@ -618,6 +618,77 @@ def test_adagrad_update_two_steps():
         emb.close()
 
 
+@pytest.mark.parametrize("n,d,r,B", [
+    ((10, 10, 10), (2, 2, 2), (4, 4), 256),          # any-shape kernels
+    ((56, 56, 56), (4, 4, 4), (16, 16), 12_000),     # matrix-core kernels
+    ((9, 11, 13), (8, 4, 8), (32, 32), 4_000),       # ... through the slab split
+])
+def test_adam_update_three_steps(n, d, r, B):
+    """Row-sparse Adam as the update rule: three steps with the moments carried along (batches that
+    leave slices untouched, so that lazily kept moments matter), against the oracle's textbook
+    rule; then the moments are handed to a second handle with steps_done and both take a step."""
+    torch = _torch()
+    from paper_2206_10581_amd import TTEmbedding
+    from paper_2206_10581_amd.binding import tt_emb_set_adam
+    s = Shape(n, d, r)
+    rng = np.random.default_rng(B)
+    cores = [(rng.standard_normal(cs) / np.sqrt(r[0])).astype(np.float32) for cs in s.core_shapes()]
+    lr, b1, b2, eps = 0.01, 0.9, 0.99, 1e-6
+    emb = TTEmbedding(n, d, r, B, cores)
+    emb.set_adam(b1, b2, eps)
+    ref = [c.copy() for c in cores]
+    m = [np.zeros_like(c) for c in cores]
+    v = [np.zeros_like(c) for c in cores]
+    for step in range(1, 4):
+        ids = rng.integers(0, s.N // 2 if step == 2 else s.N, B).astype(np.int64)   # step 2: half the i1
+        ids[:40] = ids[0]
+        grad = rng.standard_normal((B, s.D)).astype(np.float32)
+        out = emb.forward(torch.from_numpy(ids).cuda())
+        emb.backward_update(torch.from_numpy(grad).cuda(), lr)
+        torch.cuda.synchronize()
+        assert row_error(out.cpu().numpy(), ora.forward(s, *ref, ids)) <= ROW_TOL
+        old = ref
+        ref, m, v = ora.adam_update(s, *ref, m, v, step, ids, grad, lr, b1, b2, eps)
+        for k in range(3):
+            got = emb.cores[k].cpu().numpy()
+            assert core_error(got, ref[k]) <= CORE_TOL, (step, k)
+            # the step itself (about lr per entry) to 1e-4 of lr, plus the rounding of G
+            slack = 2 * np.finfo(np.float32).eps * np.abs(old[k]).max()
+            moved_gpu = old[k].astype(np.float64) - got
+            moved_ref = old[k].astype(np.float64) - ref[k]
+            assert np.abs(moved_gpu - moved_ref).max() <= STEP_TOL * max(lr, np.abs(moved_ref).max()) + slack
+            assert core_error(emb.adam_state[0][k].cpu().numpy(), m[k]) <= CORE_TOL
+            assert core_error(emb.adam_state[1][k].cpu().numpy(), v[k]) <= CORE_TOL
+    # a second handle over copies of cores and moments, told that three steps were made
+    cores2 = [c.cpu().numpy().copy() for c in emb.cores]
+    emb2 = TTEmbedding(n, d, r, B, cores2)
+    m2 = [t.clone() for t in emb.adam_state[0]]
+    v2 = [t.clone() for t in emb.adam_state[1]]
+    rc = tt_emb_set_adam(emb2.handle, [t.data_ptr() for t in m2], [t.data_ptr() for t in v2],
+                         b1, b2, eps, 3)
+    assert rc == 0
+    ids = torch.from_numpy(rng.integers(0, s.N, B).astype(np.int64)).cuda()
+    grad = torch.from_numpy(rng.standard_normal((B, s.D)).astype(np.float32)).cuda()
+    for e in (emb, emb2):
+        e.forward(ids)
+        e.backward_update(grad, lr)
+    torch.cuda.synchronize()
+    for k in range(3):
+        np.testing.assert_array_equal(emb.cores[k].cpu().numpy(), emb2.cores[k].cpu().numpy())
+    emb2.close()
+    emb.set_adam(enable=False)                               # back to SGD
+    ids_np = rng.integers(0, s.N, B).astype(np.int64)
+    grad_np = rng.standard_normal((B, s.D)).astype(np.float32)
+    now = [c.cpu().numpy() for c in emb.cores]
+    emb.forward(torch.from_numpy(ids_np).cuda())
+    emb.backward_update(torch.from_numpy(grad_np).cuda(), lr)
+    torch.cuda.synchronize()
+    ref2 = ora.backward_update(s, *now, ids_np, grad_np, lr)
+    for k in range(3):
+        assert core_error(emb.cores[k].cpu().numpy(), ref2[k]) <= CORE_TOL
+    emb.close()
+
+
 def test_side_stream_and_graph_replays():
     """The calls only enqueue on the stream they are given: a step on a non-default stream, and a step
     captured into a HIP graph and replayed three times (eager work and synchronisation between the
