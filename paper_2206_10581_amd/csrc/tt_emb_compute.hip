@@ -1,4 +1,5 @@
-// Arithmetic kernels of the TT-embedding path for any table shape (gfx950, fp32 on the vector ALUs).
+// Arithmetic kernels of the TT-embedding path for any table shape (gfx950, fp32; the block products
+// run on the matrix cores, the rest on the vector ALUs).
 //
 // Forward (paper Section 3, the row construction after Eq. "tt-embedding"):
 //   P_q = G1[i1] G2[i2]            once per distinct (i1,i2) prefix q, kept for the backward pass
@@ -36,29 +37,35 @@ __device__ __forceinline__ const float* grad_of_unique(int u, const int* __restr
 
 // ---------------------------------------------------------------------------------------------
 // C(m, n) = sum over k < K of A(m, k) * B(k, n) for m < M, n < N, by one block of kThreads threads:
-// 64 x 64 output tiles, the operands staged through LDS sixteen k at a time, sixteen outputs per
-// thread.  fa(m, k), fb(k, n) fetch one operand element, fc(m, n, value) takes one result; the
+// 64 x 64 output tiles, the operands staged through LDS sixteen k at a time (zero beyond M, N, K),
+// each of the four wavefronts forming a 32 x 32 quadrant with v_mfma_f32_16x16x4f32 (fp32 in, fp32
+// accumulate).  fa(m, k), fb(k, n) fetch one operand element, fc(m, n, value) takes one result; the
 // *_KFAST flags say which index neighbouring threads should vary while staging (the one that is
-// contiguous in memory).  Every sum runs in ascending k.  All threads of the block must call it
-// with the same M, N, K.
+// contiguous in memory).  The order of every sum is fixed by M, N, K alone.  All threads of the
+// block must call it with the same M, N, K.
 constexpr int kGemmTile = 64, kGemmDepth = 16;
+constexpr int kGemmStride = kGemmTile + 16;  // row stride 16 mod 32 banks: the four k of an MFMA
+                                             // operand read land on disjoint bank halves
 struct GemmLds {
-  float a[kGemmDepth][kGemmTile + 4];
-  float b[kGemmDepth][kGemmTile + 4];
+  float a[kGemmDepth][kGemmStride];
+  float b[kGemmDepth][kGemmStride];
 };
+typedef float gemm_f4 __attribute__((ext_vector_type(4)));
 
 template <bool A_KFAST, bool B_KFAST, class FA, class FB, class FC>
 __device__ __forceinline__ void block_gemm(GemmLds& L, int M, int N, int K, FA fa, FB fb, FC fc) {
-  static_assert(kThreads == 256, "sixteen by sixteen threads of 4 x 4 outputs");
+  static_assert(kThreads == 256, "four wavefronts, one 32 x 32 quadrant each");
   constexpr int kPer = kGemmTile * kGemmDepth / kThreads;  // operand elements a thread stages
-  const int t = threadIdx.x, tm = (t / 16) * 4, tn = (t % 16) * 4;
+  const int t = threadIdx.x, w = t / kWave, lane = t % kWave;
+  const int l16 = lane % 16, kg = lane / 16;
+  const int wm = (w / 2) * 32, wn = (w % 2) * 32;
   for (int m0 = 0; m0 < M; m0 += kGemmTile)
     for (int n0 = 0; n0 < N; n0 += kGemmTile) {
-      float acc[4][4];
+      gemm_f4 acc[2][2];
 #pragma unroll
-      for (int i = 0; i < 4; ++i)
+      for (int i = 0; i < 2; ++i)
 #pragma unroll
-        for (int j = 0; j < 4; ++j) acc[i][j] = 0.f;
+        for (int j = 0; j < 2; ++j) acc[i][j] = gemm_f4{0.f, 0.f, 0.f, 0.f};
       // the operands of step k0 + kGemmDepth are fetched while step k0 is multiplied
       float ra[kPer], rb[kPer];
       auto fetch = [&](int k0) {
@@ -74,6 +81,8 @@ __device__ __forceinline__ void block_gemm(GemmLds& L, int M, int N, int K, FA f
         }
       };
       fetch(0);
+      // quadrants that lie entirely beyond M or N have nothing to multiply (wavefront-uniform)
+      const bool live = m0 + wm < M && n0 + wn < N;
       for (int k0 = 0; k0 < K; k0 += kGemmDepth) {
 #pragma unroll
         for (int i = 0; i < kPer; ++i) {
@@ -83,23 +92,30 @@ __device__ __forceinline__ void block_gemm(GemmLds& L, int M, int N, int K, FA f
         }
         __syncthreads();
         if (k0 + kGemmDepth < K) fetch(k0 + kGemmDepth);
+        if (live) {
 #pragma unroll
-        for (int kk = 0; kk < kGemmDepth; ++kk) {
-          const float4 av = *(const float4*)&L.a[kk][tm];
-          const float4 bv = *(const float4*)&L.b[kk][tn];
-          const float a4[4] = {av.x, av.y, av.z, av.w}, b4[4] = {bv.x, bv.y, bv.z, bv.w};
-#pragma unroll
-          for (int i = 0; i < 4; ++i)
-#pragma unroll
-            for (int j = 0; j < 4; ++j) acc[i][j] = fmaf(a4[i], b4[j], acc[i][j]);
+          for (int ks = 0; ks < kGemmDepth / 4; ++ks) {
+            // operand layouts of the instruction: A[i][k] in lane 16*k + i, B[k][j] in lane 16*k + j
+            const float a0 = L.a[4 * ks + kg][wm + l16], a1 = L.a[4 * ks + kg][wm + 16 + l16];
+            const float b0 = L.b[4 * ks + kg][wn + l16], b1 = L.b[4 * ks + kg][wn + 16 + l16];
+            acc[0][0] = __builtin_amdgcn_mfma_f32_16x16x4f32(a0, b0, acc[0][0], 0, 0, 0);
+            acc[0][1] = __builtin_amdgcn_mfma_f32_16x16x4f32(a0, b1, acc[0][1], 0, 0, 0);
+            acc[1][0] = __builtin_amdgcn_mfma_f32_16x16x4f32(a1, b0, acc[1][0], 0, 0, 0);
+            acc[1][1] = __builtin_amdgcn_mfma_f32_16x16x4f32(a1, b1, acc[1][1], 0, 0, 0);
+          }
         }
         __syncthreads();
       }
+      // accumulator element v of lane (kg, l16) is C[4*kg + v][l16] of its 16 x 16 tile
 #pragma unroll
-      for (int i = 0; i < 4; ++i)
+      for (int i = 0; i < 2; ++i)
 #pragma unroll
-        for (int j = 0; j < 4; ++j)
-          if (m0 + tm + i < M && n0 + tn + j < N) fc(m0 + tm + i, n0 + tn + j, acc[i][j]);
+        for (int j = 0; j < 2; ++j)
+#pragma unroll
+          for (int v = 0; v < 4; ++v) {
+            const int m = m0 + wm + 16 * i + 4 * kg + v, n = n0 + wn + 16 * j + l16;
+            if (m < M && n < N) fc(m, n, acc[i][j][v]);
+          }
     }
 }
 
@@ -621,7 +637,7 @@ static inline int grid_for(int64_t work_items, int cap) {
   return (int)std::max<int64_t>(1, std::min<int64_t>(work_items, cap));
 }
 constexpr int kGridCap = 256 * 8;  // persistent blocks: 8 per compute unit
-constexpr size_t kLdsBudget = 48 * 1024;  // dynamic LDS a block of the staged kernels may ask for
+constexpr size_t kLdsBudget = 64 * 1024;  // dynamic LDS a block of the staged kernels may ask for
 
 void launch_prefix_fwd(const Plan& pl, const Workspace& ws, const float* g1, const float* g2, int B,
                        hipStream_t st) {
