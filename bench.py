@@ -84,6 +84,8 @@ def main() -> int:
     ap.add_argument("--calib-copy-mib", type=int, default=0,
                     help="also run one plain device copy of this many MiB (known traffic, to scale "
                          "a profiler's HBM counters)")
+    ap.add_argument("--free-running", action="store_true",
+                    help="let the host run arbitrarily far ahead of the device (no tt_emb_wait_backward)")
     ap.add_argument("--no-prepare", action="store_true",
                     help="do not overlap the index work of coming steps with this step's arithmetic")
     args = ap.parse_args()
@@ -128,6 +130,10 @@ def main() -> int:
     lr = w.lr if args.restore else args.lr
 
     def step():
+        if not args.free_running:
+            # host-side flow control (enqueues nothing): at most two steps ahead of the device, so
+            # that forward finds the pipeline of its prepared batch finished and need not wait for it
+            emb.wait_backward(1)
         if args.restore:
             flat.copy_(snapshot)
         if not args.no_prepare:
@@ -274,6 +280,7 @@ def main() -> int:
                    "batch": B, "ids": w.ids, "zipf_s": w.zipf_s, "seed": seed, "lr": lr,
                    "protocol": "restore_each_step" if args.restore else "small_lr_no_restore",
                    "next_batch_index_overlap": not args.no_prepare,
+                   "host_steps_ahead": "unbounded" if args.free_running else "at most 2",
                    "U": U, "Q": Q, "max_multiplicity": struct["max_multiplicity"]},
         "roofline": roofline, "cpu_baseline": cpu, "path_roofline": path, "kernels": kernels,
     }

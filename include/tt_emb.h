@@ -153,6 +153,17 @@ int tt_emb_set_adam(tt_emb_t h, float* m1, float* m2, float* m3, float* v1, floa
                     float beta1, float beta2, float eps, int64_t steps_done);
 
 /*
+ * Optional flow control for loops that never synchronise: blocks the calling host thread until the
+ * backward_update made `age` calls before the latest one (age 0: the latest, at most 2) has
+ * finished on the device.  Only calls made on a handle with TT_EMB_FLAG_IDS_READY after
+ * tt_emb_prepare has been used are tracked (they are the ones that leave an event behind);
+ * anything else returns at once.  Calling it with age 1 before every step keeps the host at most
+ * two steps ahead of the device, which is when tt_emb_forward finds the pipeline of its prepared
+ * batch finished and need not put a wait for it on the caller's stream.  Enqueues nothing.
+ */
+int tt_emb_wait_backward(tt_emb_t h, int age);
+
+/*
  * Optional: builds the index structures (split, sort, unique ids and prefixes: the part of
  * Section 4.2's sharing that depends on the ids only) of a COMING batch ahead of time, on a stream
  * of the library's own that starts once everything enqueued so far on hip_stream has run.  A later

@@ -55,6 +55,7 @@ def load_library():
     lib.tt_emb_materialize.argtypes = [c_void_p, c_int64, c_int64, c_void_p, c_void_p]
     lib.tt_emb_set_reindex.argtypes = [c_void_p, c_void_p, c_int64]
     lib.tt_emb_set_adagrad.argtypes = [c_void_p, c_void_p, c_void_p, c_void_p, c_float]
+    lib.tt_emb_wait_backward.argtypes = [c_void_p, c_int]
     lib.tt_emb_set_adam.argtypes = [c_void_p] + [c_void_p] * 6 + [c_float, c_float, c_float, c_int64]
     lib.tt_emb_prepare.argtypes = [c_void_p, c_void_p, c_int64, c_void_p]
     lib.tt_emb_get_stats.argtypes = [c_void_p, POINTER(c_int64), POINTER(c_int64), POINTER(c_int64)]
@@ -67,7 +68,7 @@ def load_library():
     lib.tt_emb_strerror.restype = c_char_p
     for name in ("tt_emb_workspace_bytes", "tt_emb_create", "tt_emb_forward", "tt_emb_prepare",
                  "tt_emb_backward_update", "tt_emb_forward_eval", "tt_emb_materialize",
-                 "tt_emb_set_reindex", "tt_emb_set_adagrad", "tt_emb_set_adam", "tt_emb_get_stats", "tt_emb_profile_enable",
+                 "tt_emb_set_reindex", "tt_emb_set_adagrad", "tt_emb_set_adam", "tt_emb_wait_backward", "tt_emb_get_stats", "tt_emb_profile_enable",
                  "tt_emb_profile_slots", "tt_emb_profile_read", "tt_emb_destroy"):
         getattr(lib, name).restype = c_int
     _lib = lib
@@ -120,6 +121,10 @@ def tt_emb_materialize(h, first_row: int, count: int, out_ptr: int, stream: int)
 
 def tt_emb_set_reindex(h, table_ptr: int, n_ids: int) -> int:
     return load_library().tt_emb_set_reindex(h, c_void_p(table_ptr), c_int64(n_ids))
+
+
+def tt_emb_wait_backward(h, age: int) -> int:
+    return load_library().tt_emb_wait_backward(h, c_int(age))
 
 
 def tt_emb_set_adam(h, m_ptrs, v_ptrs, beta1: float, beta2: float, eps: float, steps_done: int = 0) -> int:
@@ -288,6 +293,13 @@ class TTEmbedding:
                                  [t.data_ptr() for t in self.adam_state[1]], beta1, beta2, eps)
         if rc:
             raise TTEmbError(rc, "tt_emb_set_adam")
+
+    def wait_backward(self, age: int = 1):
+        """Host-side flow control: returns once the backward_update made `age` calls before the
+        latest one has finished on the device."""
+        rc = tt_emb_wait_backward(self.handle, age)
+        if rc:
+            raise TTEmbError(rc, "tt_emb_wait_backward")
 
     def prepare(self, ids):
         """Index work of the next batch, overlapped with whatever follows on the current stream."""

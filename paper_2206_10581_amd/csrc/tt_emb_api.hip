@@ -248,6 +248,7 @@ struct tt_emb {
   hipEvent_t ev_fork;   // recorded on the caller's stream, awaited by side
   hipEvent_t done[kSets];   // recorded on the caller's stream after the last kernel that reads the set
   bool done_valid[kSets];   // done[s] covers the latest use of set s
+  int recent[kSets];        // index sets of the latest backward_update calls, newest first (-1: none)
   struct Prepared {
     bool valid;         // this index set holds a batch that no forward has consumed yet
     const int64_t* ids;
@@ -350,6 +351,7 @@ int tt_emb_create(tt_emb_t* out, const tt_emb_config* cfg, float* g1, float* g2,
     h->done_valid[i] = false;
   }
   h->prep_seq = 0;
+  for (int i = 0; i < kSets; ++i) h->recent[i] = -1;
   for (int i = 0; i < kSets; ++i) h->prep[i] = tt_emb::Prepared{false, nullptr, 0, 0, nullptr};
   h->g1 = g1;
   h->g2 = g2;
@@ -490,7 +492,15 @@ static int forward_impl(tt_emb* h, const IdSource& src, int64_t B64, float* out,
         (found < 0 || h->prep[s].seq < h->prep[found].seq))
       found = s;
   if (found >= 0) {
-    hipError_t e = hipStreamWaitEvent(st, h->prep[found].ready, 0);
+    // A pipeline that has already finished needs no wait on the caller's stream (its kernels
+    // have completed, their results are visible to every later launch); one that has not is
+    // awaited on the device.  No event may be queried while the stream is being captured.
+    bool finished = false;
+    hipStreamCaptureStatus cap = hipStreamCaptureStatusNone;
+    if (hipStreamIsCapturing(st, &cap) == hipSuccess && cap == hipStreamCaptureStatusNone)
+      finished = hipEventQuery(h->prep[found].ready) == hipSuccess;
+    (void)hipGetLastError();  // "not ready" is an answer, not an error
+    hipError_t e = finished ? hipSuccess : hipStreamWaitEvent(st, h->prep[found].ready, 0);
     if (e != hipSuccess) return hip_fail(e);
     h->prep[found].valid = false;
     h->cur = found;
@@ -690,11 +700,25 @@ int tt_emb_backward_update(tt_emb_t h, const float* grad_out, float lr, void* hi
   if (rc) return rc;
   if (h->profiling) rc = run_slot(h, kSlotEventPair, st, [] {});
   if (rc) return rc;
+  for (int i = kSets - 1; i > 0; --i) h->recent[i] = h->recent[i - 1];
+  h->recent[0] = h->cur;
   if (stop != nullptr) {
     h->done_valid[h->cur] = true;
     return TT_EMB_OK;
   }
   return mark_set_done(h, st);
+}
+
+int tt_emb_wait_backward(tt_emb_t h, int age) {
+  if (h == nullptr || age < 0) return TT_EMB_EINVAL;
+  if (age >= kSets - 1) return TT_EMB_OK;  // that set may have been taken again: nothing to wait for
+  const int set = h->recent[age];
+  if (set < 0 || h->done[set] == nullptr || !h->done_valid[set]) return TT_EMB_OK;
+  // the set must not have served a later backward_update (its event would be that later one's)
+  for (int i = 0; i < age; ++i)
+    if (h->recent[i] == set) return TT_EMB_OK;
+  const hipError_t e = hipEventSynchronize(h->done[set]);
+  return e == hipSuccess ? TT_EMB_OK : hip_fail(e);
 }
 
 int tt_emb_get_stats(tt_emb_t h, int64_t* U, int64_t* Q, int64_t* out_of_range) {

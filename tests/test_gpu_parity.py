@@ -436,6 +436,41 @@ def test_prepare_with_reused_ids_buffers(flags):
     emb.close()
 
 
+def test_wait_backward_flow_control():
+    """tt_emb_wait_backward(age) returns once that backward_update has finished on the device: after
+    age 0 the stream is idle; an age the handle cannot know about, a handle that never prepared,
+    and a fresh handle return at once; results are what they are without it."""
+    torch = _torch()
+    from paper_2206_10581_amd import TTEmbedding
+    w, cores, ids, grad = _workload(2, batch=20_000)
+    s = Shape(w.n, w.d, w.r)
+    t_ids, t_grad = torch.from_numpy(ids).cuda(), torch.from_numpy(grad).cuda()
+    emb = TTEmbedding(w.n, w.d, w.r, ids.size, cores, flags=4)
+    emb.wait_backward(0)                                   # nothing has happened yet
+    ref = [c.copy() for c in cores]
+    emb.prepare(t_ids)
+    emb.prepare(t_ids)
+    for k in range(6):
+        emb.wait_backward(1)
+        if k < 4:
+            emb.prepare(t_ids)
+        emb.forward(t_ids)
+        emb.backward_update(t_grad, w.lr * 0.01)
+        ref = [c.astype(np.float32) for c in ora.backward_update(s, *ref, ids, grad, w.lr * 0.01)]
+    emb.wait_backward(0)
+    assert torch.cuda.current_stream().query()             # the update kernel was the last launch
+    emb.wait_backward(2)
+    emb.wait_backward(7)
+    for k in range(3):
+        assert core_error(emb.cores[k].cpu().numpy(), ref[k]) <= CORE_TOL
+    emb.close()
+    plain = TTEmbedding(w.n, w.d, w.r, ids.size, cores)    # no prepare, no flag: nothing tracked
+    plain.forward(t_ids)
+    plain.backward_update(t_grad, w.lr)
+    plain.wait_backward(0)
+    plain.close()
+
+
 def test_lookup_only_calls_and_dense_materialisation():
     """forward_eval gives the rows of forward and arms no backward; materialize writes the dense
     table the cores define (all of config 1's 1000 rows, and a window of a rank-32 table that is
