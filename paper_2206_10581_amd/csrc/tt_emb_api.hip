@@ -166,6 +166,7 @@ static size_t carve(const Plan& pl, char* base, Workspace* ws /* [kSets] or null
     w.seg_nu = (uint32_t*)take((size_t)pl.segBlocksMax * 4);
     w.seg_nq = (uint32_t*)take((size_t)pl.segBlocksMax * 4);
     w.s_u = (int*)take(mB * 4);
+    w.s_rec = (int4*)take(mB * 16);
     w.u_rs = (int*)take((mB + 1) * 4);
     w.u_i3 = (int*)take(mB * 4);
     w.u_q = (int*)take(mB * 4);

@@ -469,7 +469,7 @@ __global__ __launch_bounds__(kSegThreads) void k_seg_count(const uint32_t* __res
 __global__ __launch_bounds__(kSegThreads) void k_seg_write(
     const uint32_t* __restrict__ skey, const uint32_t* __restrict__ perm, int B, Shape sh,
     const uint32_t* __restrict__ seg_nu, const uint32_t* __restrict__ seg_nq, int* __restrict__ s_u,
-    int* __restrict__ u_rs, int* __restrict__ u_i3, int* __restrict__ u_q, int* __restrict__ u_code,
+    int4* __restrict__ s_rec, int* __restrict__ u_rs, int* __restrict__ u_i3, int* __restrict__ u_q, int* __restrict__ u_code,
     int* __restrict__ q_us, int* __restrict__ q_i1, int* __restrict__ q_i2,
     uint32_t* __restrict__ cnt3, uint32_t* __restrict__ cnt2, int* __restrict__ g1_first,
     int* __restrict__ g1_end, Counters* __restrict__ ctr) {
@@ -511,6 +511,7 @@ __global__ __launch_bounds__(kSegThreads) void k_seg_write(
     if (s >= B) break;
     if (!f.valid[j]) {
       s_u[s] = -1;
+      s_rec[s] = make_int4(-1, (int)bpos[j], 0, 0);
       continue;
     }
     ru += f.newu[j];
@@ -518,6 +519,8 @@ __global__ __launch_bounds__(kSegThreads) void k_seg_write(
     const int u = (int)ru - 1, q = (int)rq - 1;
     s_u[s] = u;
     const uint32_t k = f.key[j];
+    // everything the row kernel needs about a slot in one record (one load instead of a chain)
+    s_rec[s] = make_int4(u, (int)bpos[j], q, (int)(k % sh.n3));
     if (f.split[j]) atomicAdd(&ctr->n_split, 1);
     if (f.newu[j]) {
       const uint32_t i3 = k % sh.n3;
@@ -696,7 +699,7 @@ void launch_seg_count(const Plan& pl, const Workspace& ws, int B, hipStream_t st
 void launch_seg_write(const Plan& pl, const Workspace& ws, int B, hipStream_t st) {
   const int f = (pl.passes - 1) & 1;
   k_seg_write<<<cdiv(B, kSegItems), kSegThreads, 0, st>>>(
-      ws.key[f], ws.val[f], B, pl.sh, ws.seg_nu, ws.seg_nq, ws.s_u, ws.u_rs, ws.u_i3, ws.u_q,
+      ws.key[f], ws.val[f], B, pl.sh, ws.seg_nu, ws.seg_nq, ws.s_u, ws.s_rec, ws.u_rs, ws.u_i3, ws.u_q,
       ws.u_code, ws.q_us, ws.q_i1, ws.q_i2, ws.cnt3, ws.cnt2, ws.g1_first, ws.g1_end, ws.ctr);
 }
 

@@ -105,6 +105,7 @@ struct Workspace {
   uint32_t* seg_nu;   // new-id flags per segment block     [segBlocks]
   uint32_t* seg_nq;   // new-prefix flags per segment block [segBlocks]
   int* s_u;           // sorted slot -> unique-id index (-1 for out-of-range ids) [maxB]
+  int4* s_rec;        // sorted slot -> {unique-id index, batch position, prefix, i3} [maxB]
   int* u_rs;          // unique id -> first sorted slot  [maxB+1]
   int* u_i3;          // unique id -> i3                 [maxB]
   int* u_q;           // unique id -> prefix index       [maxB]

@@ -630,9 +630,8 @@ __global__ __launch_bounds__(mid_waves<R>() * kWave, 6) void k_bwd_mid_mfma(
 // reads them back.
 template <int R, int D3>
 __global__ __launch_bounds__(kMThreads) void k_row_fwd_mfma(
-    int B, const float* __restrict__ g3, const float* __restrict__ P, const int* __restrict__ s_u,
-    const uint32_t* __restrict__ perm, const int* __restrict__ u_i3, const int* __restrict__ u_q,
-    float* __restrict__ out, Counters* ctr) {
+    int B, const float* __restrict__ g3, const float* __restrict__ P,
+    const int4* __restrict__ s_rec, float* __restrict__ out, Counters* ctr) {
   constexpr int PN = 16 * R, S3 = R * D3, D = 16 * D3, UPT = 16 / D3, KQ = R / 4, VPL = D / kWave;
   constexpr int NB = 3;  // groups per batch: 4 cost two wavefronts per SIMD of occupancy
   __shared__ float ebuf[kMWaves][NB * UPT * D];
@@ -644,8 +643,9 @@ __global__ __launch_bounds__(kMThreads) void k_row_fwd_mfma(
   const int ntiles = (B + TSL - 1) / TSL;
   for (int tile = blockIdx.x * kMWaves + w; tile < ntiles; tile += gridDim.x * kMWaves) {
     const int s = lane < TSL ? tile * TSL + lane : B;
-    int mysu = s_u[min(s, B - 1)];
-    uint32_t myb = perm[min(s, B - 1)];
+    const int4 rec = s_rec[min(s, B - 1)];  // {unique-id index, batch position, prefix, i3}
+    int mysu = rec.x;
+    const uint32_t myb = (uint32_t)rec.y;
     if (s >= B) mysu = -2;  // lanes past the batch: neither an id nor an out-of-range slot
     if (s < B && myb >= (uint32_t)B) atomicOr(&ctr->err, 4);
     // out-of-range ids (the tail of the sorted order) get zero rows
@@ -660,9 +660,21 @@ __global__ __launch_bounds__(kMThreads) void k_row_fwd_mfma(
     const int nv = __popcll(__ballot(mysu >= 0));
     if (nv == 0) continue;
     const int u_lo = lane_value(mysu, 0), nu = lane_value(mysu, nv - 1) - u_lo + 1;
-    int myq = u_q[u_lo + min(lane, nu - 1)];
-    const int myi3 = u_i3[u_lo + min(lane, nu - 1)];
+    // lane e takes prefix and i3 of the tile's e-th distinct id from that id's first slot
+    int* xch = (int*)E;
+    const int su_before = __shfl_up(mysu, 1);
+    if (mysu >= 0 && (lane == 0 || mysu != su_before)) {
+      xch[mysu - u_lo] = rec.z;
+      xch[TSL + mysu - u_lo] = rec.w;
+    }
+    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+    __builtin_amdgcn_wave_barrier();
+    __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+    int myq = xch[min(lane, nu - 1)];
+    const int myi3 = xch[TSL + min(lane, nu - 1)];
     if (lane >= nu) myq = -1;
+    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+    __builtin_amdgcn_wave_barrier();
     // group starts: every UPT-th id of a run of ids with one prefix
     const int q_before = __shfl_up(myq, 1);
     const unsigned long long run_starts = __ballot(lane < nu && (lane == 0 || myq != q_before));
@@ -963,9 +975,8 @@ void launch_bwd_mid_mfma(const Plan& pl, const Workspace& ws, const float* g1, c
 void launch_row_fwd_mfma(const Plan& pl, const Workspace& ws, const float* g3, int B, float* out,
                          hipStream_t st) {
   const int grid = grid_cap(cdivi(cdivi(B, kRowTile), kMWaves), 1 << 20);
-  const uint32_t* perm = ws.val[(pl.passes - 1) & 1];
   TT_DISPATCH_RD(pl.sh.r1, pl.sh.d3, (k_row_fwd_mfma<R, D3><<<grid, kMThreads, 0, st>>>(
-                                         B, g3, ws.P, ws.s_u, perm, ws.u_i3, ws.u_q, out, ws.ctr)));
+                                         B, g3, ws.P, ws.s_rec, out, ws.ctr)));
 }
 
 void launch_gsum_block(const Plan& pl, const Workspace& ws, const float* grad, int B,
