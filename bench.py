@@ -14,7 +14,12 @@ instructions, and the cores stay where they are for hundreds of steps.  `--resto
 protocol instead: the workload's own learning rate, with the cores put back from a snapshot by one
 device-side copy per step inside the timed region (extra work, counted against the rate).
 
-Prints ONE JSON line.  `roofline` describes the longest launch of the step, timed with HIP events
+The loop is the one a training loop would run: tt_emb_wait_backward(1) (host-side flow control, at
+most two steps in flight; `--free-running` leaves it out), tt_emb_prepare for the batch two steps
+ahead (its index work overlaps this step's arithmetic; `--no-prepare` leaves it out), forward,
+backward_update.
+
+Prints ONE JSON line.  `roofline` describes the longest launch on the caller's stream, timed with HIP events
 on its own stream by the library's profiling hook in a separate, untimed leg (an empty event pair
 is timed too and taken off); `cpu_baseline` is the CPU oracle (fp32 build, OpenMP) on the same batch.
 """
