@@ -358,9 +358,12 @@ __device__ __forceinline__ void dg3_chunk(
     int c, const float* __restrict__ P, const float* __restrict__ grad,
     const float* __restrict__ gsum, const int2* __restrict__ c3_item,
     const int4* __restrict__ c3_desc, float* __restrict__ part3) {
-  constexpr int PN = 16 * R, S3 = R * D3, D = 16 * D3, NT = R / 16;
+  constexpr int PN = 16 * R, S3 = R * D3, D = 16 * D3, NT = (R + 15) / 16;
   const int lane = threadIdx.x % kWave;
   const int l16 = lane % 16, kg = lane / 16;
+  // rank 8: half of the 16 columns of the only tile exist; the others load column 0 and are dropped
+  const bool col_on = R >= 16 || l16 < R;
+  const int lcol = col_on ? l16 : 0;
   {
     const int2 item = c3_item[(size_t)c * kChunk3 + lane % kChunk3];
     const int cnt = c3_desc[c].z;
@@ -376,7 +379,7 @@ __device__ __forceinline__ void dg3_chunk(
         const int i = min(i0 + x, cnt - 1);
         const float* gp = grad_row_ptr(lane_value(mycode, i), grad, gsum, D) + (4 * kg) * D3 +
                           (l16 < D3 ? l16 : 0);
-        const float* pp = P + (size_t)lane_value(myq, i) * PN + (4 * kg) * R + l16;
+        const float* pp = P + (size_t)lane_value(myq, i) * PN + (4 * kg) * R + lcol;
 #pragma unroll
         for (int s = 0; s < 4; ++s) a[x][s] = gp[s * D3];
 #pragma unroll
@@ -400,7 +403,7 @@ __device__ __forceinline__ void dg3_chunk(
 #pragma unroll
       for (int v = 0; v < 4; ++v) {
         const int j3 = 4 * kg + v;
-        if (j3 < D3) dst[(nt * 16 + l16) * D3 + j3] = acc[nt][v];
+        if (j3 < D3 && col_on) dst[(nt * 16 + l16) * D3 + j3] = acc[nt][v];
       }
   }
 }
@@ -460,10 +463,10 @@ __global__ __launch_bounds__(mid_waves<R>() * kWave, 6) void k_bwd_mid_mfma(
     const int4* __restrict__ c3_desc, const int* __restrict__ c3_order,
     float* __restrict__ dg1part, float* __restrict__ part2, float* __restrict__ part3,
     int chunk_blocks, const Counters* __restrict__ ctr) {
-  static_assert(R == 16 || R == 32, "the LDS tiles are sized for ranks up to 32");
+  static_assert(R == 8 || R == 16 || R == 32, "the LDS tiles are sized for ranks up to 32");
   constexpr int W = 4 * R, S1 = 4 * R, S2 = R * W, S3 = R * D3, D = 16 * D3;
   constexpr int TS = W + 4;  // padded row stride of the LDS tiles (keeps 16-byte alignment)
-  constexpr int NT16 = R / 16, KS = D3 / 4, UB = 4;
+  constexpr int NT16 = (R + 15) / 16, KS = D3 / 4, UB = 4;
   __shared__ __align__(16) float T[64 * TS];
   __shared__ __align__(16) float Bl[R * TS];
   __shared__ int q_of[16], i1_of[16], u0_of[16], u1_of[16];
@@ -508,6 +511,10 @@ __global__ __launch_bounds__(mid_waves<R>() * kWave, 6) void k_bwd_mid_mfma(
   TT_TRACE(ctr, trace_id, 1);
 
   const int l16 = lane % 16, kg = lane / 16;
+  // rank 8: rows / columns 8..15 of the only 16-wide tile do not exist; such lanes read row 0 and
+  // their results are dropped
+  const bool rank_on = R >= 16 || l16 < R;
+  const int lrow = rank_on ? l16 : 0;
   // (i) this wavefront's pairs of prefixes (local numbers 2*pw, 2*pw+1)
   for (int pw = w; pw < 8; pw += kMidWaves) {
     f4 acc[2][NT16];
@@ -529,7 +536,7 @@ __global__ __launch_bounds__(mid_waves<R>() * kWave, 6) void k_bwd_mid_mfma(
 #pragma unroll
       for (int sl = 0; sl < 2 * UB; ++sl) {
         const float* gp = grad_row_ptr(lane_value(mycode, sl), grad, gsum, D) + l16 * D3 + KS * kg;
-        const float* cp = g3 + (size_t)lane_value(myi3, sl) * S3 + l16 * D3 + KS * kg;
+        const float* cp = g3 + (size_t)lane_value(myi3, sl) * S3 + lrow * D3 + KS * kg;
 #pragma unroll
         for (int k = 0; k < KS; ++k) a[sl][k] = gp[k];
 #pragma unroll
@@ -559,7 +566,7 @@ __global__ __launch_bounds__(mid_waves<R>() * kWave, 6) void k_bwd_mid_mfma(
       for (int nt = 0; nt < NT16; ++nt)
 #pragma unroll
         for (int v = 0; v < 4; ++v)
-          T[((2 * pw + x) * 4 + kg) * TS + v * R + nt * 16 + l16] = acc[x][nt][v];
+          if (rank_on) T[((2 * pw + x) * 4 + kg) * TS + v * R + nt * 16 + l16] = acc[x][nt][v];
   }
   TT_TRACE(ctr, trace_id, 2);
   __syncthreads();
@@ -578,7 +585,7 @@ __global__ __launch_bounds__(mid_waves<R>() * kWave, 6) void k_bwd_mid_mfma(
       const f4 x = arow[j];
 #pragma unroll
       for (int nt = 0; nt < NT16; ++nt) {
-        const f4 y = *(const f4*)&Bl[(16 * nt + l16) * TS + KQ * kg + 4 * j];
+        const f4 y = *(const f4*)&Bl[(16 * nt + lrow) * TS + KQ * kg + 4 * j];
         acc[nt] = mfma16(x.x, y.x, acc[nt]);
         acc[nt] = mfma16(x.y, y.y, acc[nt]);
         acc[nt] = mfma16(x.z, y.z, acc[nt]);
@@ -591,7 +598,8 @@ __global__ __launch_bounds__(mid_waves<R>() * kWave, 6) void k_bwd_mid_mfma(
 #pragma unroll
       for (int nt = 0; nt < NT16; ++nt)
 #pragma unroll
-        for (int v = 0; v < 4; ++v) dg1part[(size_t)qv * S1 + v * R + 16 * nt + l16] = acc[nt][v];
+        for (int v = 0; v < 4; ++v)
+          if (rank_on) dg1part[(size_t)qv * S1 + v * R + 16 * nt + l16] = acc[nt][v];
     }
   }
   const int w3 = kMidWaves == 8 ? w - 4 : w;
@@ -706,14 +714,20 @@ __global__ __launch_bounds__(kMThreads) void k_row_fwd_mfma(
         const float* pc = g3 + (size_t)i3 * S3 + (KQ * kg) * D3 + j3;
         // a group whose prefix is the previous group's takes that group's P operand
         if (x == 0 || q != qx[x - 1]) {
-          const f4* pa = (const f4*)(P + (size_t)(q >= 0 ? q : 0) * PN + l16 * R + KQ * kg);
+          const float* pf = P + (size_t)(q >= 0 ? q : 0) * PN + l16 * R + KQ * kg;
+          if constexpr (KQ % 4 == 0) {
+            const f4* pa = (const f4*)pf;
 #pragma unroll
-          for (int j = 0; j < KQ / 4; ++j) {
-            const f4 v = pa[j];
-            a[x][4 * j + 0] = v.x;
-            a[x][4 * j + 1] = v.y;
-            a[x][4 * j + 2] = v.z;
-            a[x][4 * j + 3] = v.w;
+            for (int j = 0; j < KQ / 4; ++j) {
+              const f4 v = pa[j];
+              a[x][4 * j + 0] = v.x;
+              a[x][4 * j + 1] = v.y;
+              a[x][4 * j + 2] = v.z;
+              a[x][4 * j + 3] = v.w;
+            }
+          } else {  // rank 8: two floats per lane
+#pragma unroll
+            for (int j = 0; j < KQ; ++j) a[x][j] = pf[j];
           }
         }
 #pragma unroll
@@ -896,7 +910,8 @@ __global__ __launch_bounds__(kGsumThreads) void k_gsum_block(int B, const float*
 // dispatch
 
 bool mfma_shape(const Shape& s) {
-  return s.d1 == 4 && s.d2 == 4 && s.r1 == s.r2 && (s.r1 == 16 || s.r1 == 32 || s.r1 == 64) &&
+  return s.d1 == 4 && s.d2 == 4 && s.r1 == s.r2 &&
+         (s.r1 == 8 || s.r1 == 16 || s.r1 == 32 || s.r1 == 64) &&
          (s.d3 == 4 || s.d3 == 8);
 }
 
@@ -912,6 +927,15 @@ constexpr int kMGridCap = 256 * 8;
     case 32: { constexpr int R = 32; CALL; } break; \
     default: { constexpr int R = 64; CALL; } break; \
   }
+// the kernels that also exist for rank 8 (prefix products and rows; rank 8 takes the fused middle
+// kernel in the backward pass)
+#define TT_DISPATCH_R8(R_, CALL)                    \
+  if ((R_) == 8) {                                  \
+    constexpr int R = 8;                            \
+    CALL;                                           \
+  } else {                                          \
+    TT_DISPATCH_R(R_, CALL)                         \
+  }
 #define TT_DISPATCH_RD(R_, D3_, CALL)                 \
   if ((D3_) == 4) {                                   \
     constexpr int D3 = 4;                             \
@@ -926,8 +950,8 @@ void launch_prefix_fwd_mfma(const Plan& pl, const Workspace& ws, const float* g1
   // one block per possible work unit (upper bound from B); blocks past the real count return at once
   const int64_t chunks = cdivi(std::min<int64_t>(B, pl.maxQ), kChunk2) + pl.sh.n2;
   const int grid = (int)(chunks * pf_units(pl.sh.r1));
-  TT_DISPATCH_R(pl.sh.r1, (k_prefix_fwd_mfma<R><<<grid, kWave, 0, st>>>(
-                              g1, g2, ws.c2_item, ws.c2_desc, ws.P, ws.ctr)));
+  TT_DISPATCH_R8(pl.sh.r1, (k_prefix_fwd_mfma<R><<<grid, kWave, 0, st>>>(
+                               g1, g2, ws.c2_item, ws.c2_desc, ws.P, ws.ctr)));
 }
 
 void launch_prefix_bwd_mfma(const Plan& pl, const Workspace& ws, const float* g1, const float* g2,
@@ -955,7 +979,7 @@ bool mfma_fused_mid(const Shape& s) { return mfma_shape(s) && s.r1 <= 32; }
 void launch_bwd_mid_mfma(const Plan& pl, const Workspace& ws, const float* g1, const float* g2,
                          const float* g3, const float* grad, int B, hipStream_t st) {
   const int chunk_blocks = cdivi(std::min<int64_t>(B, pl.maxQ), kChunk2) + (int)pl.sh.n2;
-  const int waves = pl.sh.r1 == 16 ? mid_waves<16>() : mid_waves<32>();
+  const int waves = pl.sh.r1 <= 16 ? mid_waves<16>() : mid_waves<32>();
   const int* order = chunks_ordered(pl, B) ? ws.c3_order : nullptr;
   // the same number of by-i3 blocks on every XCD
   const int dg3_blocks =
@@ -964,7 +988,9 @@ void launch_bwd_mid_mfma(const Plan& pl, const Workspace& ws, const float* g1, c
   k_bwd_mid_mfma<RR, DD><<<chunk_blocks + dg3_blocks, waves * kWave, 0, st>>>(                    \
       g1, g2, g3, ws.P, grad, ws.gsum, ws.u_code, ws.u_i3, ws.c2_item, ws.c2_desc, ws.c3_item,    \
       ws.c3_desc, order, ws.dg1part, ws.part2, ws.part3, chunk_blocks, ws.ctr)
-  if (pl.sh.r1 == 16) {
+  if (pl.sh.r1 == 8) {
+    if (pl.sh.d3 == 4) TT_MID(8, 4); else TT_MID(8, 8);
+  } else if (pl.sh.r1 == 16) {
     if (pl.sh.d3 == 4) TT_MID(16, 4); else TT_MID(16, 8);
   } else {
     if (pl.sh.d3 == 4) TT_MID(32, 4); else TT_MID(32, 8);
@@ -975,8 +1001,15 @@ void launch_bwd_mid_mfma(const Plan& pl, const Workspace& ws, const float* g1, c
 void launch_row_fwd_mfma(const Plan& pl, const Workspace& ws, const float* g3, int B, float* out,
                          hipStream_t st) {
   const int grid = grid_cap(cdivi(cdivi(B, kRowTile), kMWaves), 1 << 20);
-  TT_DISPATCH_RD(pl.sh.r1, pl.sh.d3, (k_row_fwd_mfma<R, D3><<<grid, kMThreads, 0, st>>>(
-                                         B, g3, ws.P, ws.s_rec, out, ws.ctr)));
+  if (pl.sh.d3 == 4) {
+    constexpr int D3 = 4;
+    TT_DISPATCH_R8(pl.sh.r1, (k_row_fwd_mfma<R, D3><<<grid, kMThreads, 0, st>>>(
+                                 B, g3, ws.P, ws.s_rec, out, ws.ctr)));
+  } else {
+    constexpr int D3 = 8;
+    TT_DISPATCH_R8(pl.sh.r1, (k_row_fwd_mfma<R, D3><<<grid, kMThreads, 0, st>>>(
+                                 B, g3, ws.P, ws.s_rec, out, ws.ctr)));
+  }
 }
 
 void launch_gsum_block(const Plan& pl, const Workspace& ws, const float* grad, int B,
