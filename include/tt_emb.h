@@ -25,7 +25,7 @@
  * borrows it and never allocates or frees device memory.  Cores, out and grad_out must be 16-byte
  * aligned, ids 8-byte aligned (TT_EMB_EINVAL otherwise).  The handle owns host bookkeeping only.
  * All calls are asynchronous on the given HIP stream unless stated otherwise (tt_emb_prepare also
- * uses four internal streams of default priority, created on its first call).  A handle must not
+ * uses two internal streams of default priority, created on its first call).  A handle must not
  * be used from two threads or two streams at once.
  *
  * Errors.  Every function returns TT_EMB_OK (0) or a negative code and never aborts.

@@ -143,6 +143,11 @@ static int make_plan(const tt_emb_config* c, Plan* pl) {
 // and the one that has been idle longest is the next to be filled (each set has a stream of its
 // own, so a pipeline has two steps to finish and need not wait for the step that has just ended).
 constexpr int kSets = 4;
+// The index pipelines run on kSideStreams streams of the library's own, set s on stream
+// s % kSideStreams.  Two measure best: with one, a pipeline cannot start before the previous one has
+// ended (+11 us per step at config 3); with four, the process has more streams than hardware
+// queues (+0.5 us, +1.5 us when the host runs far ahead).
+constexpr int kSideStreams = 2;
 
 // Walks the workspace layout; with base == nullptr only the size is computed.  The index arrays
 // exist kSets times; the arithmetic buffers are shared.
@@ -245,7 +250,8 @@ struct tt_emb {
   bool have_forward;
   hipStream_t last_stream;
   // tt_emb_prepare: index pipelines of coming batches on a stream of the library's own
-  hipStream_t side[kSets];  // one per index set, created on first use, default priority
+  hipStream_t side[kSets];  // stream of each index set (kSideStreams distinct ones), created on
+                            // first use, default priority
   hipEvent_t ev_fork;   // recorded on the caller's stream, awaited by side
   hipEvent_t done[kSets];   // recorded on the caller's stream after the last kernel that reads the set
   bool done_valid[kSets];   // done[s] covers the latest use of set s
@@ -409,8 +415,12 @@ int tt_emb_prepare(tt_emb_t h, const int64_t* ids, int64_t B64, void* hip_stream
   hipError_t e;
   if (h->side[0] == nullptr) {
     for (int i = 0; i < kSets; ++i) {
-      e = hipStreamCreateWithFlags(&h->side[i], hipStreamNonBlocking);
-      if (e != hipSuccess) return hip_fail(e);
+      if (i < kSideStreams) {
+        e = hipStreamCreateWithFlags(&h->side[i], hipStreamNonBlocking);
+        if (e != hipSuccess) return hip_fail(e);
+      } else {
+        h->side[i] = h->side[i % kSideStreams];
+      }
       e = hipEventCreateWithFlags(&h->prep[i].ready, hipEventDisableTiming);
       if (e != hipSuccess) return hip_fail(e);
       e = hipEventCreate(&h->done[i]);  // the extended launch records kernel times into it
@@ -785,8 +795,9 @@ int tt_emb_destroy(tt_emb_t h) {
       (void)hipStreamSynchronize(h->side[i]);
       if (h->prep[i].ready != nullptr) (void)hipEventDestroy(h->prep[i].ready);
       if (h->done[i] != nullptr) (void)hipEventDestroy(h->done[i]);
-      (void)hipStreamDestroy(h->side[i]);
     }
+    for (int i = 0; i < kSideStreams; ++i)
+      if (h->side[i] != nullptr) (void)hipStreamDestroy(h->side[i]);
     if (h->ev_fork != nullptr) (void)hipEventDestroy(h->ev_fork);
   }
   delete h;
