@@ -140,8 +140,8 @@ static int make_plan(const tt_emb_config* c, Plan* pl) {
 }
 
 // Index sets: one serves the forward/backward pair in flight, two hold the batches prepared ahead,
-// and the one that has been idle longest is the next to be filled (each set has a stream of its
-// own, so a pipeline has two steps to finish and need not wait for the step that has just ended).
+// and the one that has been idle longest is the next to be filled (a pipeline started two steps
+// early has two steps to finish and need not wait for the step that has just ended).
 constexpr int kSets = 4;
 // The index pipelines run on kSideStreams streams of the library's own, set s on stream
 // s % kSideStreams.  Two measure best: with one, a pipeline cannot start before the previous one has
