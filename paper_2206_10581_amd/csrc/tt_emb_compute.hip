@@ -197,70 +197,94 @@ __global__ __launch_bounds__(kThreads) void k_row_fwd(Shape sh, int B, const flo
   }
 }
 
-// The same with the operands staged: a wavefront reads the ids, positions, prefixes and i3 of its
-// 32 slots in one go, copies P_q (rows padded by one float against bank conflicts) and G3[i3] into
-// LDS of its own when they change, and forms E from there.  Needs
-// kWavesPerBlock * (D + M*(r2+1) + S3) floats of LDS; larger shapes take k_row_fwd.
+// The same with the operands staged, and the work cut so that no wavefront has a long chain of
+// dependent steps.  Three kinds of job share the launch, one wavefront each:
+//   * a distinct id (entry) with at most kTileSlots positions: the wavefront copies P_q (rows padded
+//     by one float against bank conflicts) and G3[i3] into LDS of its own, forms E from there and
+//     stores it to all positions of the id - the tail of a batch whose ids all differ costs one
+//     round trip per wavefront, not one per slot of a tile in turn;
+//   * a tile of kTileSlots sorted slots, for the slots of longer entries only (a tile meets at
+//     most two of those): E is formed again per tile, so a hot id's thousand stores are spread
+//     over thirty wavefronts;
+//   * a tile of out-of-range slots (zero rows).
+// Needs kWavesPerBlock * (D + M*(r2+1) + S3) floats of LDS; larger shapes take k_row_fwd.
 __global__ __launch_bounds__(kThreads) void k_row_fwd_staged(
     Shape sh, int B, const float* __restrict__ g3, const float* __restrict__ P,
-    const int* __restrict__ s_u, const uint32_t* __restrict__ perm, const int* __restrict__ u_i3,
-    const int* __restrict__ u_q, float* __restrict__ out, Counters* ctr) {
+    const int* __restrict__ s_u, const uint32_t* __restrict__ perm, const int* __restrict__ u_rs,
+    const int* __restrict__ u_i3, const int* __restrict__ u_q, float* __restrict__ out,
+    Counters* ctr) {
   extern __shared__ float lds[];
-  static_assert(kTileSlots <= kWave, "one lane per slot");
   const int w = threadIdx.x / kWave, lane = threadIdx.x % kWave;
   const int ps = sh.r2 + 1;
   float* E = lds + (size_t)w * (sh.D + sh.M * ps + sh.S3);
   float* Pl = E + sh.D;
   float* Cl = Pl + sh.M * ps;
-  const int ntiles = (B + kTileSlots - 1) / kTileSlots;
-  for (int tile = blockIdx.x * kWavesPerBlock + w; tile < ntiles;
-       tile += gridDim.x * kWavesPerBlock) {
-    const int s = tile * kTileSlots + lane;
-    const bool mine = lane < kTileSlots && s < B;
-    const int mysu = mine ? s_u[s] : -1;
-    const uint32_t myb = mine ? perm[s] : 0u;
-    const int myq = mysu >= 0 ? u_q[mysu] : 0;
-    const int myi3 = mysu >= 0 ? u_i3[mysu] : 0;
-    const int nslots = min(kTileSlots, B - tile * kTileSlots);
-    int cur = -2, curq = -1, curi3 = -1;
-    for (int k = 0; k < nslots; ++k) {
-      const int u = __shfl(mysu, k);
+  const int U = ctr->U, nvalid = ctr->nvalid;
+  const int long_tiles = (nvalid + kTileSlots - 1) / kTileSlots;
+  const int zero_tiles = (B - nvalid + kTileSlots - 1) / kTileSlots;
+  const int stride = gridDim.x * kWavesPerBlock;
+  // E = reshape(P_q) * G3[i3] of entry u, left in LDS
+  auto form_row = [&](int u) {
+    const float* Pq = P + (size_t)u_q[u] * sh.PN;
+    const float* C = g3 + (size_t)u_i3[u] * sh.S3;
+    for (int e = lane; e < sh.PN; e += kWave) Pl[(e / sh.r2) * ps + e % sh.r2] = Pq[e];
+    for (int e = lane; e < sh.S3; e += kWave) Cl[e] = C[e];
+    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+    __builtin_amdgcn_wave_barrier();
+    for (int e = lane; e < sh.D; e += kWave) {
+      const float* pr = Pl + (e / sh.d3) * ps;
+      const float* cc = Cl + e % sh.d3;
+      float acc = 0.f;
+      for (int c = 0; c < sh.r2; ++c) acc = fmaf(pr[c], cc[c * sh.d3], acc);
+      E[e] = acc;
+    }
+    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+    __builtin_amdgcn_wave_barrier();
+  };
+  // E to the batch positions of slots [s0, s1), at most a wavefront's worth
+  auto store_rows = [&](int s0, int s1) {
+    const int n = s1 - s0;
+    const uint32_t myb = lane < n ? perm[s0 + lane] : 0u;
+    for (int k = 0; k < n; ++k) {
       const uint32_t b = (uint32_t)__shfl((int)myb, k);
       if (b >= (uint32_t)B) {
         flag_error(ctr, 1);
         continue;
       }
       float* o = out + (size_t)b * sh.D;
-      if (u < 0) {
-        for (int e = lane; e < sh.D; e += kWave) o[e] = 0.f;
-        continue;
-      }
-      if (u != cur) {
-        cur = u;
-        const int q = __shfl(myq, k), i3 = __shfl(myi3, k);
-        if (q != curq) {
-          curq = q;
-          const float* Pq = P + (size_t)q * sh.PN;
-          for (int e = lane; e < sh.PN; e += kWave) Pl[(e / sh.r2) * ps + e % sh.r2] = Pq[e];
-        }
-        if (i3 != curi3) {
-          curi3 = i3;
-          const float* C = g3 + (size_t)i3 * sh.S3;
-          for (int e = lane; e < sh.S3; e += kWave) Cl[e] = C[e];
-        }
-        __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
-        __builtin_amdgcn_wave_barrier();
-        for (int e = lane; e < sh.D; e += kWave) {
-          const float* pr = Pl + (e / sh.d3) * ps;
-          const float* cc = Cl + e % sh.d3;
-          float acc = 0.f;
-          for (int c = 0; c < sh.r2; ++c) acc = fmaf(pr[c], cc[c * sh.d3], acc);
-          E[e] = acc;
-        }
-        __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
-        __builtin_amdgcn_wave_barrier();
-      }
       for (int e = lane; e < sh.D; e += kWave) o[e] = E[e];
+    }
+    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+    __builtin_amdgcn_wave_barrier();
+  };
+  for (int job = blockIdx.x * kWavesPerBlock + w; job < U + long_tiles + zero_tiles; job += stride) {
+    if (job < U) {
+      const int rs = u_rs[job], re = u_rs[job + 1];
+      if (re - rs > kTileSlots) continue;  // its tiles take it
+      form_row(job);
+      store_rows(rs, re);
+    } else if (job < U + long_tiles) {
+      const int t0 = (job - U) * kTileSlots, t1 = min(t0 + kTileSlots, nvalid);
+      // every lane looks at one slot; the long entries that begin or continue here are found with
+      // one ballot (two dependent loads for the whole tile, not two per entry)
+      const bool in = lane < kTileSlots && t0 + lane < t1;
+      const int mysu = in ? s_u[t0 + lane] : -1;
+      const int my_rs = in ? u_rs[mysu] : 0, my_re = in ? u_rs[mysu + 1] : 0;
+      const int before = __shfl_up(mysu, 1);
+      unsigned long long starts =
+          __ballot(in && my_re - my_rs > kTileSlots && (lane == 0 || mysu != before));
+      while (starts) {
+        const int k = __ffsll((long long)starts) - 1;
+        starts &= starts - 1;
+        form_row(__shfl(mysu, k));
+        store_rows(t0 + k, min(__shfl(my_re, k), t1));
+      }
+    } else {
+      const int s0 = nvalid + (job - U - long_tiles) * kTileSlots, s1 = min(s0 + kTileSlots, B);
+      for (int e = lane; e < sh.D; e += kWave) E[e] = 0.f;
+      __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+      __builtin_amdgcn_wave_barrier();
+      store_rows(s0, s1);
     }
   }
 }
@@ -653,9 +677,10 @@ void launch_row_fwd(const Plan& pl, const Workspace& ws, const float* g3, int B,
   const size_t staged =
       (size_t)kWavesPerBlock * ((size_t)s.D + (size_t)s.M * (s.r2 + 1) + s.S3) * sizeof(float);
   if (staged <= kLdsBudget) {
-    k_row_fwd_staged<<<grid, kThreads, staged, st>>>(s, B, g3, ws.P, ws.s_u,
-                                                     ws.val[(pl.passes - 1) & 1], ws.u_i3, ws.u_q,
-                                                     out, ws.ctr);
+    // one wavefront per distinct id (at most B of them) and per tile of slots
+    const int jobs = B + cdiv(B, kTileSlots) + 1;
+    k_row_fwd_staged<<<grid_for(cdiv(jobs, kWavesPerBlock), kGridCap * 4), kThreads, staged, st>>>(
+        s, B, g3, ws.P, ws.s_u, ws.val[(pl.passes - 1) & 1], ws.u_rs, ws.u_i3, ws.u_q, out, ws.ctr);
     return;
   }
   const size_t lds = (size_t)kWavesPerBlock * pl.sh.D * sizeof(float);
