@@ -40,7 +40,7 @@ void launch_id_bwd_mfma(const Plan&, const Workspace&, const float* g3, const fl
 void launch_prefix_bwd_mfma(const Plan&, const Workspace&, const float* g1, const float* g2, int B,
                             hipStream_t);
 bool mfma_fused_mid(const Shape&);
-bool mfma_shape(const Shape&);
+bool gsum_block_rows(const Shape&);
 void launch_bwd_mid_mfma(const Plan&, const Workspace&, const float* g1, const float* g2,
                          const float* g3, const float* grad, int B, hipStream_t);
 void launch_gsum_block(const Plan&, const Workspace&, const float* grad, int B, hipStream_t);
@@ -660,12 +660,15 @@ int tt_emb_backward_update(tt_emb_t h, const float* grad_out, float lr, void* hi
   const Plan& pl = h->plan;
   const Workspace& ws = h->ws[h->cur];
   int rc;
+  // rows of up to 256 floats are summed in blocks of kEntrySlots slots, which no entry crosses;
+  // longer rows tile by tile, with a second kernel that joins the runs that cross tiles
+  const bool block_sums = h->mfma || gsum_block_rows(pl.sh);
   rc = run_slot(h, kSlotGsum, st, [&] {
-    if (h->mfma) launch_gsum_block(pl, ws, grad_out, B, st);
+    if (block_sums) launch_gsum_block(pl, ws, grad_out, B, st);
     else launch_gsum(pl, ws, grad_out, B, st);
   });
   if (rc) return rc;
-  if (!h->mfma) {  // the matrix-core path sums in blocks of kEntrySlots slots: nothing crosses them
+  if (!block_sums) {
     rc = run_slot(h, kSlotGsumFix, st, [&] { launch_gsum_fix(pl, ws, B, st); });
     if (rc) return rc;
   }

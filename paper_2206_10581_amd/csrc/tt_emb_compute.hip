@@ -691,9 +691,10 @@ void launch_row_fwd(const Plan& pl, const Workspace& ws, const float* g3, int B,
 void launch_gsum(const Plan& pl, const Workspace& ws, const float* grad, int B, hipStream_t st) {
   const int tiles = cdiv(B, kTileSlots);
   const int grid = grid_for(cdiv(tiles, kWavesPerBlock), kGridCap);
+  const uint32_t* perm = ws.val[(pl.passes - 1) & 1];
   const size_t lds = (size_t)kWavesPerBlock * pl.sh.D * sizeof(float);
-  k_gsum<<<grid, kThreads, lds, st>>>(pl.sh, B, grad, ws.s_u, ws.val[(pl.passes - 1) & 1], ws.u_rs,
-                                      ws.gsum, ws.carry, ws.ctr);
+  k_gsum<<<grid, kThreads, lds, st>>>(pl.sh, B, grad, ws.s_u, perm, ws.u_rs, ws.gsum, ws.carry,
+                                      ws.ctr);
 }
 
 void launch_gsum_fix(const Plan& pl, const Workspace& ws, int B, hipStream_t st) {

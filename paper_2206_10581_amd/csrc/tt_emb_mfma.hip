@@ -795,13 +795,18 @@ struct LaneVec {
   float v[VPL];
 };
 
-template <int VPL>
-__global__ __launch_bounds__(kGsumThreads) void k_gsum_block(int B, const float* __restrict__ grad,
+// RAGGED: rows of Drt <= 64*VPL floats (any length); lanes past the end of a row carry zeros, and
+// rows are read with plain dword loads (their starts need not be 8-byte aligned).
+template <int VPL, bool RAGGED = false>
+__global__ __launch_bounds__(kGsumThreads) void k_gsum_block(int B, int Drt,
+                                                          const float* __restrict__ grad,
                                                           const int* __restrict__ s_u,
                                                           const uint32_t* __restrict__ perm,
                                                           float* __restrict__ gsum, Counters* ctr) {
-  constexpr int D = kWave * VPL;
-  __shared__ float part[kGsumWaves][2][D];  // [wave][0 = head piece, 1 = tail piece]
+  constexpr int DP = kWave * VPL;          // padded row length
+  const int D = RAGGED ? Drt : DP;
+  constexpr int kRows = VPL <= 2 ? 32 : 64 / VPL;  // rows a wavefront has in flight (64 registers)
+  __shared__ float part[kGsumWaves][2][DP];  // [wave][0 = head piece, 1 = tail piece]
   __shared__ int head_state[kGsumWaves];    // 0 none, 1 head piece ends in this wave, 2 it runs through
   __shared__ int tail_u[kGsumWaves];        // id whose run starts in this wave and continues, or -1
   const int w = threadIdx.x / kWave, lane = threadIdx.x % kWave;
@@ -836,7 +841,8 @@ __global__ __launch_bounds__(kGsumThreads) void k_gsum_block(int B, const float*
         if (end_slot - cur_first > 1) {
           float* o = gsum + (size_t)cur * D + lane * VPL;
 #pragma unroll
-          for (int x = 0; x < VPL; ++x) o[x] = acc.v[x];
+          for (int x = 0; x < VPL; ++x)
+            if (!RAGGED || lane * VPL + x < D) o[x] = acc.v[x];
         }
       } else {
         const int h = starts_here ? 1 : 0;
@@ -848,23 +854,31 @@ __global__ __launch_bounds__(kGsumThreads) void k_gsum_block(int B, const float*
         }
       }
     };
-    for (int half = 0; half < 2; ++half) {
-      if (half * 32 >= nv) break;
-      LaneVec<VPL> r[32];
+    for (int half = 0; half < kWave / kRows; ++half) {
+      if (half * kRows >= nv) break;
+      LaneVec<VPL> r[kRows];
 #pragma unroll
-      for (int k = 0; k < 32; ++k) {
-        const int slot = half * 32 + k;
+      for (int k = 0; k < kRows; ++k) {
+        const int slot = half * kRows + k;
         const uint32_t b_row = (uint32_t)lane_value((int)myb, slot);
         if ((need_mask >> slot) & 1ull) {
-          stream_load<VPL>(grad + (size_t)b_row * D + lane * VPL, r[k].v);
+          if constexpr (RAGGED) {
+#pragma unroll
+            for (int x = 0; x < VPL; ++x)
+              r[k].v[x] = lane * VPL + x < D
+                              ? __builtin_nontemporal_load(grad + (size_t)b_row * D + lane * VPL + x)
+                              : 0.f;
+          } else {
+            stream_load<VPL>(grad + (size_t)b_row * D + lane * VPL, r[k].v);
+          }
         } else {
 #pragma unroll
           for (int x = 0; x < VPL; ++x) r[k].v[x] = 0.f;
         }
       }
 #pragma unroll
-      for (int k = 0; k < 32; ++k) {
-        const int slot = half * 32 + k;
+      for (int k = 0; k < kRows; ++k) {
+        const int slot = half * kRows + k;
         if (slot < nv) {
           const int u = lane_value(mysu, slot);
           if (u != cur) {
@@ -900,7 +914,8 @@ __global__ __launch_bounds__(kGsumThreads) void k_gsum_block(int B, const float*
       if (open && lane == 0) atomicOr(&ctr->err, 16);  // a run left the block: entries never do
       float* o = gsum + (size_t)tail_u[w] * D;
 #pragma unroll
-      for (int x = 0; x < VPL; ++x) o[lane * VPL + x] = t.v[x];
+      for (int x = 0; x < VPL; ++x)
+        if (!RAGGED || lane * VPL + x < D) o[lane * VPL + x] = t.v[x];
     }
     __syncthreads();
   }
@@ -1016,10 +1031,20 @@ void launch_gsum_block(const Plan& pl, const Workspace& ws, const float* grad, i
                        hipStream_t st) {
   const int grid = grid_cap(cdivi(B, kGsumBlockSlots), kMGridCap);
   const uint32_t* perm = ws.val[(pl.passes - 1) & 1];
-  if (pl.sh.D == 64)
-    k_gsum_block<1><<<grid, kGsumThreads, 0, st>>>(B, grad, ws.s_u, perm, ws.gsum, ws.ctr);
+  const int D = pl.sh.D;
+  if (D == 64)
+    k_gsum_block<1><<<grid, kGsumThreads, 0, st>>>(B, D, grad, ws.s_u, perm, ws.gsum, ws.ctr);
+  else if (D == 128)
+    k_gsum_block<2><<<grid, kGsumThreads, 0, st>>>(B, D, grad, ws.s_u, perm, ws.gsum, ws.ctr);
+  else if (D <= 64)
+    k_gsum_block<1, true><<<grid, kGsumThreads, 0, st>>>(B, D, grad, ws.s_u, perm, ws.gsum, ws.ctr);
+  else if (D <= 128)
+    k_gsum_block<2, true><<<grid, kGsumThreads, 0, st>>>(B, D, grad, ws.s_u, perm, ws.gsum, ws.ctr);
   else
-    k_gsum_block<2><<<grid, kGsumThreads, 0, st>>>(B, grad, ws.s_u, perm, ws.gsum, ws.ctr);
+    k_gsum_block<4, true><<<grid, kGsumThreads, 0, st>>>(B, D, grad, ws.s_u, perm, ws.gsum, ws.ctr);
 }
+
+// rows this long have a block version of the gradient sums (any shape)
+bool gsum_block_rows(const Shape& s) { return s.D <= 4 * kWave; }
 
 }  // namespace ttemb
