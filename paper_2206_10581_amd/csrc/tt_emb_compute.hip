@@ -119,6 +119,64 @@ __device__ __forceinline__ void block_gemm(GemmLds& L, int M, int N, int K, FA f
     }
 }
 
+// The same product by one wavefront alone (32 x 32 output tiles, LDS of its own, no block barrier):
+// for many small products it keeps all four wavefronts of a block busy on different ones.
+constexpr int kWaveTile = 32;
+constexpr int kWaveStride = kWaveTile + 16;
+struct WaveGemmLds {
+  float a[kGemmDepth][kWaveStride];
+  float b[kGemmDepth][kWaveStride];
+};
+
+template <bool A_KFAST, bool B_KFAST, class FA, class FB, class FC>
+__device__ __forceinline__ void wave_gemm(WaveGemmLds& L, int M, int N, int K, FA fa, FB fb, FC fc) {
+  constexpr int kPer = kWaveTile * kGemmDepth / kWave;  // operand elements a lane stages
+  const int lane = threadIdx.x % kWave, l16 = lane % 16, kg = lane / 16;
+  for (int m0 = 0; m0 < M; m0 += kWaveTile)
+    for (int n0 = 0; n0 < N; n0 += kWaveTile) {
+      gemm_f4 acc[2][2];
+#pragma unroll
+      for (int i = 0; i < 2; ++i)
+#pragma unroll
+        for (int j = 0; j < 2; ++j) acc[i][j] = gemm_f4{0.f, 0.f, 0.f, 0.f};
+      for (int k0 = 0; k0 < K; k0 += kGemmDepth) {
+#pragma unroll
+        for (int i = 0; i < kPer; ++i) {
+          const int e = lane + i * kWave;
+          const int ak = A_KFAST ? e % kGemmDepth : e / kWaveTile;
+          const int am = A_KFAST ? e / kGemmDepth : e % kWaveTile;
+          L.a[ak][am] = (m0 + am < M && k0 + ak < K) ? fa(m0 + am, k0 + ak) : 0.f;
+          const int bk = B_KFAST ? e % kGemmDepth : e / kWaveTile;
+          const int bn = B_KFAST ? e / kGemmDepth : e % kWaveTile;
+          L.b[bk][bn] = (n0 + bn < N && k0 + bk < K) ? fb(k0 + bk, n0 + bn) : 0.f;
+        }
+        __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+        __builtin_amdgcn_wave_barrier();
+        __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+#pragma unroll
+        for (int ks = 0; ks < kGemmDepth / 4; ++ks) {
+          const float a0 = L.a[4 * ks + kg][l16], a1 = L.a[4 * ks + kg][16 + l16];
+          const float b0 = L.b[4 * ks + kg][l16], b1 = L.b[4 * ks + kg][16 + l16];
+          acc[0][0] = __builtin_amdgcn_mfma_f32_16x16x4f32(a0, b0, acc[0][0], 0, 0, 0);
+          acc[0][1] = __builtin_amdgcn_mfma_f32_16x16x4f32(a0, b1, acc[0][1], 0, 0, 0);
+          acc[1][0] = __builtin_amdgcn_mfma_f32_16x16x4f32(a1, b0, acc[1][0], 0, 0, 0);
+          acc[1][1] = __builtin_amdgcn_mfma_f32_16x16x4f32(a1, b1, acc[1][1], 0, 0, 0);
+        }
+        __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+        __builtin_amdgcn_wave_barrier();
+      }
+#pragma unroll
+      for (int i = 0; i < 2; ++i)
+#pragma unroll
+        for (int j = 0; j < 2; ++j)
+#pragma unroll
+          for (int v = 0; v < 4; ++v) {
+            const int m = m0 + 16 * i + 4 * kg + v, n = n0 + 16 * j + l16;
+            if (m < M && n < N) fc(m, n, acc[i][j][v]);
+          }
+    }
+}
+
 // ---------------------------------------------------------------------------------------------
 // forward
 
@@ -363,7 +421,7 @@ __global__ __launch_bounds__(kThreads) void k_gsum_fix(Shape sh, const int* __re
 }
 
 // dPsum_q = sum over the unique ids u of prefix q of g_u * G3[i3(u)]^T, g_u read as (d1*d2) x d3:
-// one product per prefix whose contraction index runs over (u, j3).
+// one product per prefix whose contraction index runs over (u, j3), one wavefront per prefix.
 __global__ __launch_bounds__(kThreads) void k_u_bwd(Shape sh, const float* __restrict__ g3,
                                                     const float* __restrict__ grad,
                                                     const float* __restrict__ gsum,
@@ -372,13 +430,13 @@ __global__ __launch_bounds__(kThreads) void k_u_bwd(Shape sh, const float* __res
                                                     const int* __restrict__ q_us,
                                                     float* __restrict__ dPsum,
                                                     const Counters* __restrict__ ctr) {
-  __shared__ GemmLds L;
-  const int Q = ctr->Q;
-  for (int q = blockIdx.x; q < Q; q += gridDim.x) {
+  __shared__ WaveGemmLds L[kWavesPerBlock];
+  const int Q = ctr->Q, w = threadIdx.x / kWave;
+  for (int q = blockIdx.x * kWavesPerBlock + w; q < Q; q += gridDim.x * kWavesPerBlock) {
     const int u0 = q_us[q], u1 = q_us[q + 1];
     float* dst = dPsum + (size_t)q * sh.PN;
-    block_gemm<true, true>(
-        L, sh.M, sh.r2, (u1 - u0) * sh.d3,
+    wave_gemm<true, true>(
+        L[w], sh.M, sh.r2, (u1 - u0) * sh.d3,
         [&](int m, int k) {
           return grad_of_unique(u0 + k / sh.d3, u_code, grad, gsum, sh.D)[m * sh.d3 + k % sh.d3];
         },
@@ -704,7 +762,7 @@ void launch_gsum_fix(const Plan& pl, const Workspace& ws, int B, hipStream_t st)
 
 void launch_u_bwd(const Plan& pl, const Workspace& ws, const float* g3, const float* grad, int B,
                   hipStream_t st) {
-  const int grid = grid_for(std::min<int64_t>(B, pl.maxQ), kGridCap);
+  const int grid = grid_for(cdiv(std::min<int64_t>(B, pl.maxQ), kWavesPerBlock), kGridCap * 4);
   k_u_bwd<<<grid, kThreads, 0, st>>>(pl.sh, g3, grad, ws.gsum, ws.u_code, ws.u_i3, ws.q_us, ws.dPsum,
                                      ws.ctr);
 }
