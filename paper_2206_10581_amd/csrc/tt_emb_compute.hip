@@ -35,6 +35,26 @@ __device__ __forceinline__ const float* grad_of_unique(int u, const int* __restr
   return code >= 0 ? grad + (size_t)code * D : gsum + (size_t)(-code - 1) * D;
 }
 
+// Copies n elements with NT threads (tid = 0..NT-1), eight loads of a thread in flight together:
+// a plain `for (e...) dst[e] = src[e]` with a run-time bound waits for every load in turn.
+template <int NT, class LD, class ST>
+__device__ __forceinline__ void staged_copy(int n, int tid, LD load, ST store) {
+  constexpr int kFlight = 8;
+  for (int e0 = tid; e0 < n; e0 += kFlight * NT) {
+    float v[kFlight];
+#pragma unroll
+    for (int j = 0; j < kFlight; ++j) {
+      const int e = e0 + j * NT;
+      v[j] = e < n ? load(e) : 0.f;
+    }
+#pragma unroll
+    for (int j = 0; j < kFlight; ++j) {
+      const int e = e0 + j * NT;
+      if (e < n) store(e, v[j]);
+    }
+  }
+}
+
 // ---------------------------------------------------------------------------------------------
 // C(m, n) = sum over k < K of A(m, k) * B(k, n) for m < M, n < N, by one block of kThreads threads:
 // 64 x 64 output tiles, the operands staged through LDS sixteen k at a time (zero beyond M, N, K),
@@ -510,11 +530,14 @@ __global__ __launch_bounds__(kThreads) void k_dg3_staged(Shape sh, int group,
       for (int t0 = 0; t0 < cnt; t0 += group) {
         const int nt = min(group, cnt - t0);
         __syncthreads();  // the previous fill has been used
-        for (int t = 0; t < nt; ++t) {
-          float* pl = lds + (size_t)t * per;
-          for (int e = threadIdx.x; e < sh.PN; e += kThreads) pl[e] = p_of[t0 + t][e];
-          for (int e = threadIdx.x; e < sh.D; e += kThreads) pl[sh.PN + e] = g_of[t0 + t][e];
-        }
+        // the fill as one copy of nt * (PN + D) floats: the loads of all its ids overlap
+        staged_copy<kThreads>(
+            nt * per, (int)threadIdx.x,
+            [&](int f) {
+              const int t = f / per, e = f % per;
+              return e < sh.PN ? p_of[t0 + t][e] : g_of[t0 + t][e - sh.PN];
+            },
+            [&](int f, float v) { lds[f] = v; });
         __syncthreads();
 #pragma unroll
         for (int x = 0; x < kOut; ++x) {
