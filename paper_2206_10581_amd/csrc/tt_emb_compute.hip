@@ -285,7 +285,8 @@ __global__ __launch_bounds__(kThreads) void k_row_fwd(Shape sh, int B, const flo
 //     most two of those): E is formed again per tile, so a hot id's thousand stores are spread
 //     over thirty wavefronts;
 //   * a tile of out-of-range slots (zero rows).
-// Needs kWavesPerBlock * (D + M*(r2+1) + S3) floats of LDS; larger shapes take k_row_fwd.
+// Needs D + M*(r2+1) + S3 floats of LDS per wavefront (blocks have as many wavefronts, up to four,
+// as the budget allows); shapes too large for even one take k_row_fwd.
 __global__ __launch_bounds__(kThreads) void k_row_fwd_staged(
     Shape sh, int B, const float* __restrict__ g3, const float* __restrict__ P,
     const int* __restrict__ s_u, const uint32_t* __restrict__ perm, const int* __restrict__ u_rs,
@@ -300,7 +301,8 @@ __global__ __launch_bounds__(kThreads) void k_row_fwd_staged(
   const int U = ctr->U, nvalid = ctr->nvalid;
   const int long_tiles = (nvalid + kTileSlots - 1) / kTileSlots;
   const int zero_tiles = (B - nvalid + kTileSlots - 1) / kTileSlots;
-  const int stride = gridDim.x * kWavesPerBlock;
+  const int wpb = (int)blockDim.x / kWave;  // fewer wavefronts per block when the operands are large
+  const int stride = gridDim.x * wpb;
   // E = reshape(P_q) * G3[i3] of entry u, left in LDS
   auto form_row = [&](int u) {
     const float* Pq = P + (size_t)u_q[u] * sh.PN;
@@ -335,7 +337,7 @@ __global__ __launch_bounds__(kThreads) void k_row_fwd_staged(
     __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
     __builtin_amdgcn_wave_barrier();
   };
-  for (int job = blockIdx.x * kWavesPerBlock + w; job < U + long_tiles + zero_tiles; job += stride) {
+  for (int job = blockIdx.x * wpb + w; job < U + long_tiles + zero_tiles; job += stride) {
     if (job < U) {
       const int rs = u_rs[job], re = u_rs[job + 1];
       if (re - rs > kTileSlots) continue;  // its tiles take it
@@ -755,12 +757,13 @@ void launch_row_fwd(const Plan& pl, const Workspace& ws, const float* g3, int B,
   const int tiles = cdiv(B, kTileSlots);
   const int grid = grid_for(cdiv(tiles, kWavesPerBlock), kGridCap);
   const Shape& s = pl.sh;
-  const size_t staged =
-      (size_t)kWavesPerBlock * ((size_t)s.D + (size_t)s.M * (s.r2 + 1) + s.S3) * sizeof(float);
-  if (staged <= kLdsBudget) {
+  const size_t per_wave = ((size_t)s.D + (size_t)s.M * (s.r2 + 1) + s.S3) * sizeof(float);
+  if (per_wave <= kLdsBudget) {
+    const int wpb = (int)std::min<size_t>(kWavesPerBlock, kLdsBudget / per_wave);
+    const size_t staged = wpb * per_wave;
     // one wavefront per distinct id (at most B of them) and per tile of slots
     const int jobs = B + cdiv(B, kTileSlots) + 1;
-    k_row_fwd_staged<<<grid_for(cdiv(jobs, kWavesPerBlock), kGridCap * 4), kThreads, staged, st>>>(
+    k_row_fwd_staged<<<grid_for(cdiv(jobs, wpb), kGridCap * 4), wpb * kWave, staged, st>>>(
         s, B, g3, ws.P, ws.s_u, ws.val[(pl.passes - 1) & 1], ws.u_rs, ws.u_i3, ws.u_q, out, ws.ctr);
     return;
   }

@@ -110,8 +110,8 @@ def test_config1_tiny_in_full():
     ((7, 5, 9), (1, 2, 5), (2, 7), 1000),
     ((5, 300, 6), (3, 1, 2), (6, 1), 5000),    # wide middle factor, rank-1 tail
     ((40, 33, 70), (2, 2, 3), (8, 8), 4097),   # one item past a 4096 sort block
-    ((6, 9, 11), (8, 8, 2), (4, 64), 1500),    # prefix product too large for the staged row kernel
-    ((5, 7, 6), (8, 8, 1), (2, 260), 700),     # ... and for the staged G3-gradient kernel
+    ((6, 9, 11), (8, 8, 2), (4, 64), 1500),    # staged row kernel with three wavefronts per block
+    ((5, 7, 6), (8, 8, 1), (2, 260), 700),     # too large for the staged row and G3-gradient kernels
     ((9, 8, 7), (3, 7, 5), (5, 3), 2500),      # several 64-wide tiles with ragged edges (D = 105)
     ((4, 6, 5), (20, 1, 9), (70, 2), 900),     # stacked prefixes exceed one tile (16 * d1 = 320 rows)
 ])
