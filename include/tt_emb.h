@@ -61,7 +61,7 @@ enum {
                                       earlier, and the caller's stream carries one event less)  */
   TT_EMB_FLAG_GENERIC_KERNELS = 2u /* use the any-shape vector-ALU kernels even for shapes that
                                       have matrix-core kernels (d1 in {4,8,...,32}, d2 = 4,
-                                      r1 = r2 in {8,16,32,64}, d3 in {4,8}); for comparison and
+                                      r1 = r2 in {8,16,32,64,128}, d3 in {4,8}); for comparison and
                                       testing                                                    */
 };
 
@@ -69,7 +69,7 @@ typedef struct {
   int64_t n[3];      /* node factors n1,n2,n3 (paper m_k); N = n1*n2*n3 must be below 2^31;
                         n2 and n3 at most 2048                                                  */
   int32_t d[3];      /* embedding-dimension factors d1,d2,d3 (paper n_k); D = d1*d2*d3 <= 4096.
-                        d1 = 8, 12, ... 32 with d2 = 4, d3 in {4,8}, r1 = r2 in {8,16,32,64} also
+                        d1 = 8, 12, ... 32 with d2 = 4, d3 in {4,8}, r1 = r2 in {8,...,128} also
                         runs on the matrix-core kernels: G1[i1] is treated as d1/4 slabs of
                         4 x r1 (a table with d1/4 times the first-core slices and quarter-height
                         rows over the same memory); this needs (d1/4)*N < 2^31 and

@@ -81,7 +81,8 @@ __device__ __forceinline__ void stream_load(const float* src, float* v) {
 // Units per chunk: two or four side by side over the 32-column tiles of the product (four shorten
 // the kernel at rank 32 by a fifth; splitting the sixteen prefixes of a chunk over units as well
 // only re-reads the G2 slice, which costs more than it gains).
-constexpr int pf_units(int R) { return R >= 32 ? 4 : 2; }
+// (At rank 128 a unit is a single 32 x 32 tile: its two operand strips alone are 128 registers.)
+constexpr int pf_units(int R) { return R >= 128 ? 32 : R >= 32 ? 4 : 2; }
 
 template <int R>
 __global__ __launch_bounds__(kWave) void k_prefix_fwd_mfma(
@@ -154,9 +155,11 @@ __global__ __launch_bounds__(kWave) void k_prefix_fwd_mfma(
 // per chunk, one single-wavefront block each:
 //   unit 0,1  dg1part[q] = dPsum_q Bm^T for the first / second eight prefixes: their dPsum rows
 //             stacked (32 x 4R) times Bm^T (4R x R)
-//   unit 2,3  one half of the columns of part2[c] = sum_q G1[i1(q)]^T dPsum_q
+//   unit 2..  one half of the columns of part2[c] = sum_q G1[i1(q)]^T dPsum_q (rank 128: and one
+//             half of its rows)
 //             ((R x 4 cnt) times (4 cnt x 4R))
-constexpr int kPbUnits = 4;
+// (At rank 128 the part2 units are split over the rows as well, two by two: six units.)
+constexpr int pb_units(int R) { return R >= 128 ? 6 : 4; }
 
 template <int R>
 __global__ __launch_bounds__(kWave) void k_prefix_bwd_mfma(
@@ -167,6 +170,7 @@ __global__ __launch_bounds__(kWave) void k_prefix_bwd_mfma(
   const int lane = threadIdx.x, half = lane / 32, l32 = lane % 32;
   const int unit = blockIdx.x;
   TT_TRACE(ctr, unit, 0);
+  constexpr int kPbUnits = pb_units(R);
   const int c = unit / kPbUnits, part = unit % kPbUnits;
   const int4 item = c2_item[(size_t)c * kChunk2 + lane % kChunk2];
   const int4 desc = c2_desc[c];
@@ -235,8 +239,10 @@ __global__ __launch_bounds__(kWave) void k_prefix_bwd_mfma(
       }
     }
   } else {
-    constexpr int MT = (R + 31) / 32, NT = W / 32, NTH = NT / 2;
-    const int nt0 = (part - 2) * NTH;
+    constexpr int MSPLIT = R >= 128 ? 2 : 1;                // units over the rows of part2
+    constexpr int MT = (R + 31) / 32 / MSPLIT, NT = W / 32, NTH = NT / 2;
+    const int nt0 = ((part - 2) % 2) * NTH;
+    const int mrow0 = ((part - 2) / 2) * MT * 32;           // first row of this unit
     int qh[8], ih[8];  // the eight prefixes whose rows this half of the wavefront feeds as k
 #pragma unroll
     for (int jq = 0; jq < 8; ++jq) {
@@ -246,7 +252,7 @@ __global__ __launch_bounds__(kWave) void k_prefix_bwd_mfma(
     float a[MT][32];
 #pragma unroll
     for (int mt = 0; mt < MT; ++mt) {
-      const int m = mt * 32 + l32;
+      const int m = mrow0 + mt * 32 + l32;
 #pragma unroll
       for (int j = 0; j < 32; ++j) a[mt][j] = g1[(size_t)ih[j / 4] * S1 + (j % 4) * R + (m < R ? m : 0)];
     }
@@ -261,7 +267,7 @@ __global__ __launch_bounds__(kWave) void k_prefix_bwd_mfma(
 #endif
 #pragma unroll
     for (int mt = 0; mt < MT; ++mt) {
-      const int m = mt * 32 + l32;
+      const int m = mrow0 + mt * 32 + l32;
 #pragma unroll
       for (int j = 0; j < 32; ++j) a[mt][j] = (qh[j / 4] >= 0 && m < R) ? a[mt][j] : 0.f;
     }
@@ -282,7 +288,7 @@ __global__ __launch_bounds__(kWave) void k_prefix_bwd_mfma(
         for (int j = 0; j < 32; ++j) acc = mfma32(a[mt][j], b[t & 1][j], acc);
 #pragma unroll
         for (int v = 0; v < 16; ++v) {
-          const int mrow = mt * 32 + 8 * (v / 4) + 4 * half + (v % 4);
+          const int mrow = mrow0 + mt * 32 + 8 * (v / 4) + 4 * half + (v % 4);
           if (mrow < R) part2[(size_t)c * S2 + (size_t)mrow * W + n] = acc[v];
         }
       }
@@ -339,7 +345,8 @@ __device__ __forceinline__ void u_bwd_role(
         }
       };
       int i0 = 0;
-      for (; i0 + 16 <= n; i0 += 16) round(std::integral_constant<int, 16>{}, i0);
+      if constexpr (R <= 64)  // sixteen ids in flight: 288 registers at rank 128
+        for (; i0 + 16 <= n; i0 += 16) round(std::integral_constant<int, 16>{}, i0);
       for (; i0 < n; i0 += UB) round(std::integral_constant<int, UB>{}, i0);
     }
     float* dst = dPsum + (size_t)q * PN;
@@ -433,7 +440,7 @@ __global__ __launch_bounds__(kMThreads) void k_id_bwd_mfma(
   if (role == 0)
     u_bwd_role<R, D3>(block, nblocks, g3, grad, gsum, u_code, u_i3, q_us, dPsum, ctr);
   else
-    dg3_role<R, D3, (R == 64) ? 4 : 8>(block * kMWaves + (int)threadIdx.x / kWave, nblocks * kMWaves,
+    dg3_role<R, D3, (R >= 128) ? 2 : (R == 64) ? 4 : 8>(block * kMWaves + (int)threadIdx.x / kWave, nblocks * kMWaves,
                                        P, grad, gsum, c3_item, c3_desc, part3, ctr);
 }
 
@@ -641,7 +648,9 @@ __global__ __launch_bounds__(kMThreads) void k_row_fwd_mfma(
     int B, const float* __restrict__ g3, const float* __restrict__ P,
     const int4* __restrict__ s_rec, float* __restrict__ out, Counters* ctr) {
   constexpr int PN = 16 * R, S3 = R * D3, D = 16 * D3, UPT = 16 / D3, KQ = R / 4, VPL = D / kWave;
-  constexpr int NB = 3;  // groups per batch: 4 cost two wavefronts per SIMD of occupancy
+  // groups per batch: 4 cost two wavefronts per SIMD of occupancy; at rank 128 one group's operands
+  // are 64 registers already
+  constexpr int NB = R >= 128 ? 1 : 3;
   __shared__ float ebuf[kMWaves][NB * UPT * D];
   const int w = threadIdx.x / kWave, lane = threadIdx.x % kWave;
   const int l16 = lane % 16, kg = lane / 16;
@@ -926,7 +935,7 @@ __global__ __launch_bounds__(kGsumThreads) void k_gsum_block(int B, int Drt,
 
 bool mfma_shape(const Shape& s) {
   return s.d1 == 4 && s.d2 == 4 && s.r1 == s.r2 &&
-         (s.r1 == 8 || s.r1 == 16 || s.r1 == 32 || s.r1 == 64) &&
+         (s.r1 == 8 || s.r1 == 16 || s.r1 == 32 || s.r1 == 64 || s.r1 == 128) &&
          (s.d3 == 4 || s.d3 == 8);
 }
 
@@ -940,7 +949,8 @@ constexpr int kMGridCap = 256 * 8;
   switch (R_) {                      \
     case 16: { constexpr int R = 16; CALL; } break; \
     case 32: { constexpr int R = 32; CALL; } break; \
-    default: { constexpr int R = 64; CALL; } break; \
+    case 64: { constexpr int R = 64; CALL; } break; \
+    default: { constexpr int R = 128; CALL; } break; \
   }
 // the kernels that also exist for rank 8 (prefix products and rows; rank 8 takes the fused middle
 // kernel in the backward pass)
@@ -972,7 +982,7 @@ void launch_prefix_fwd_mfma(const Plan& pl, const Workspace& ws, const float* g1
 void launch_prefix_bwd_mfma(const Plan& pl, const Workspace& ws, const float* g1, const float* g2,
                             int B, hipStream_t st) {
   const int64_t chunks = cdivi(std::min<int64_t>(B, pl.maxQ), kChunk2) + pl.sh.n2;
-  const int grid = (int)(chunks * kPbUnits);
+  const int grid = (int)(chunks * pb_units(pl.sh.r1));
   TT_DISPATCH_R(pl.sh.r1, (k_prefix_bwd_mfma<R><<<grid, kWave, 0, st>>>(
                               g1, g2, ws.dPsum, ws.c2_item, ws.c2_desc, ws.dg1part, ws.part2,
                               ws.ctr)));

@@ -125,7 +125,8 @@ def test_generic_shapes(n, d, r, B):
 
 
 @pytest.mark.parametrize("flags", [0, 2])          # 2 = TT_EMB_FLAG_GENERIC_KERNELS
-@pytest.mark.parametrize("R,d3", [(8, 4), (8, 8), (16, 4), (16, 8), (32, 8), (64, 8), (32, 4), (64, 4)])
+@pytest.mark.parametrize("R,d3", [(8, 4), (8, 8), (16, 4), (16, 8), (32, 8), (64, 8), (32, 4), (64, 4),
+                                  (128, 4), (128, 8)])
 @pytest.mark.parametrize("n,B", [((9, 21, 13), 6000), ((40, 50, 60), 5000), ((3, 2, 700), 3000)])
 def test_matrix_core_shape_family(n, B, R, d3, flags):
     # d1 = d2 = 4 with equal ranks: the shapes that have matrix-core kernels; dense sharing
