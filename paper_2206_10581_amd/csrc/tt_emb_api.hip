@@ -129,7 +129,7 @@ static int make_plan(const tt_emb_config* c, Plan* pl) {
   pl->uBlocksMax = (int)cdiv64(pl->maxB, kSortItems);
   pl->qBlocksMax = (int)cdiv64(pl->maxQ, kSortItems);
   pl->tilesMax = (int)cdiv64(pl->maxB, kTileSlots);
-  pl->maxChunk3 = cdiv64(pl->maxB, kChunk3) + s.n3;
+  pl->maxChunk3 = cdiv64(pl->maxB, kChunk3Min) + s.n3;
   pl->maxChunk2 = cdiv64(pl->maxQ, kChunk2) + s.n2;
   pl->keyBits = bits_for(s.N);  // the sentinel N itself must be representable
   pl->passes = (pl->keyBits + 10) / 11;

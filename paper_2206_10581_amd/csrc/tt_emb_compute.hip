@@ -794,7 +794,7 @@ void launch_u_bwd(const Plan& pl, const Workspace& ws, const float* g3, const fl
 }
 
 void launch_dg3(const Plan& pl, const Workspace& ws, const float* grad, int B, hipStream_t st) {
-  const int grid = grid_for(cdiv(B, kChunk3) + pl.sh.n3, kGridCap);
+  const int grid = grid_for(cdiv(B, chunk3_fill(B)) + pl.sh.n3, kGridCap);
   const size_t per = ((size_t)pl.sh.PN + pl.sh.D) * sizeof(float);
   if (per <= kLdsBudget) {
     const int group = (int)std::min<size_t>(4, kLdsBudget / per);

@@ -603,7 +603,7 @@ struct GroupOps2 {
 };
 
 __global__ __launch_bounds__(kSortThreads) void k_group(
-    Shape sh, int u_blocks, int bits3, int bits2, const uint32_t* __restrict__ cnt3,
+    Shape sh, int u_blocks, int chunk3, int bits3, int bits2, const uint32_t* __restrict__ cnt3,
     const uint32_t* __restrict__ cnt2, const int* __restrict__ u_i3, const int* __restrict__ u_code,
     const int* __restrict__ u_q, const int* __restrict__ q_i2, const int* __restrict__ q_i1,
     const int* __restrict__ q_us, int* g3_list, int* g3_start, int* c3_start, int4* c3_desc,
@@ -613,7 +613,7 @@ __global__ __launch_bounds__(kSortThreads) void k_group(
   if ((int)blockIdx.x < u_blocks) {
     GroupOps3 ops{u_i3, u_code, u_q, g3_list, c3_item, band_cnt, ctr->Q};
     stable_scatter_block(L, (int)blockIdx.x, ctr->U, (int)sh.n3, bits3, cnt3, nullptr, ops, g3_start,
-                         kChunk3, c3_start, c3_desc, &ctr->nchunk3);
+                         chunk3, c3_start, c3_desc, &ctr->nchunk3);
   } else {
     GroupOps2 ops{q_i2, q_i1, q_us, g2_list, c2_item};
     stable_scatter_block(L, (int)blockIdx.x - u_blocks, ctr->Q, (int)sh.n2, bits2, cnt2, nullptr, ops,
@@ -707,12 +707,13 @@ void launch_group(const Plan& pl, const Workspace& ws, int B, hipStream_t st) {
   // blocks are sized from upper bounds (U <= B, Q <= min(B, n1*n2)); surplus blocks return at once
   const int ub = cdiv(B, kSortItems);
   const int qb = cdiv(std::min((int64_t)B, pl.maxQ), kSortItems);
-  k_group<<<ub + qb, kSortThreads, 0, st>>>(pl.sh, ub, pl.bits3, pl.bits2, ws.cnt3, ws.cnt2, ws.u_i3, ws.u_code, ws.u_q, ws.q_i2, ws.q_i1,
+  k_group<<<ub + qb, kSortThreads, 0, st>>>(pl.sh, ub, chunk3_fill(B), pl.bits3, pl.bits2, ws.cnt3, ws.cnt2, ws.u_i3, ws.u_code, ws.u_q, ws.q_i2, ws.q_i1,
                                            ws.q_us, ws.g3_list, ws.g3_start, ws.c3_start, ws.c3_desc,
                                            ws.c3_item, ws.g2_list, ws.g2_start, ws.c2_start,
                                            ws.c2_desc, ws.c2_item, ws.band_cnt, ws.ctr);
   if (chunks_ordered(pl, B))
-    k_chunk_order<<<cdiv(cdiv(B, kChunk3) + (int64_t)pl.sh.n3, kSortThreads), kSortThreads, 0, st>>>(
+    k_chunk_order<<<cdiv(cdiv(B, chunk3_fill(B)) + (int64_t)pl.sh.n3, kSortThreads), kSortThreads, 0,
+                    st>>>(
       ws.c3_item, ws.band_cnt, ws.band_cur, ws.c3_order, ws.ctr);
 }
 

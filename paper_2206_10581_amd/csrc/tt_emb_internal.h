@@ -31,7 +31,13 @@ constexpr int kSegThreads = 256;
 constexpr int kSegItems = 1024;  // sorted slots per block in the segment kernels (4 per thread)
 
 constexpr int kTileSlots = 32;   // sorted slots per wavefront tile in the row kernels
-constexpr int kChunk3 = 16;       // unique ids per partial sum of a G3 slice gradient
+constexpr int kChunk3 = 16;       // record slots per partial sum (chunk) of a G3 slice gradient
+// Batches of up to kSmallBatch rows are cut finer where that puts more wavefronts in flight: by-i3
+// chunks of 8 ids instead of 16 (-3.7 us per step at 200,000 rows, +6..18 us at 500,000), row tiles
+// of 16 slots instead of 32.
+constexpr int kSmallBatch = 1 << 18;
+constexpr int kChunk3Min = 8;
+inline int chunk3_fill(int64_t B) { return B <= kSmallBatch ? kChunk3Min : kChunk3; }
 constexpr int kChunk2 = 16;      // unique prefixes per partial sum of a G2 slice gradient
 constexpr int kOrderBands = 1024;  // bands of the prefix range the by-i3 chunks are ordered by
 

@@ -27,7 +27,7 @@ constexpr int kMWaves = kMThreads / kWave;
 // sorted slots per wavefront in the row kernel: 16 for batches up to kRowSmallBatch rows (more
 // wavefronts in flight: -2.6 us per step at 200,000 rows), 32 above (fewer repeated operand loads:
 // -7 us at 500,000 rows)
-constexpr int kRowSmallBatch = 1 << 18;
+constexpr int kRowSmallBatch = kSmallBatch;
 
 __device__ __forceinline__ f16v mfma32(float a, float b, f16v c) {
   return __builtin_amdgcn_mfma_f32_32x32x2f32(a, b, c, 0, 0, 0);
@@ -993,7 +993,7 @@ void launch_prefix_bwd_mfma(const Plan& pl, const Workspace& ws, const float* g1
 void launch_id_bwd_mfma(const Plan& pl, const Workspace& ws, const float* g3, const float* grad,
                         int B, hipStream_t st) {
   // both roles loop over their work with a stride of half the grid (which must be even)
-  const int64_t waves_q = std::min<int64_t>(B, pl.maxQ), waves_c = cdivi(B, kChunk3) + (int64_t)pl.sh.n3;
+  const int64_t waves_q = std::min<int64_t>(B, pl.maxQ), waves_c = cdivi(B, chunk3_fill(B)) + (int64_t)pl.sh.n3;
   const int per_role = grid_cap(cdivi(std::max(waves_q, waves_c), kMWaves), kMGridCap);
   TT_DISPATCH_RD(pl.sh.r1, pl.sh.d3, (k_id_bwd_mfma<R, D3><<<2 * per_role, kMThreads, 0, st>>>(
                                          g3, ws.P, grad, ws.gsum, ws.u_code, ws.u_i3, ws.q_us,
@@ -1010,7 +1010,7 @@ void launch_bwd_mid_mfma(const Plan& pl, const Workspace& ws, const float* g1, c
   const int* order = chunks_ordered(pl, B) ? ws.c3_order : nullptr;
   // the same number of by-i3 blocks on every XCD
   const int dg3_blocks =
-      kXcds * cdivi(cdivi(cdivi(B, kChunk3) + (int64_t)pl.sh.n3, kXcds), waves);
+      kXcds * cdivi(cdivi(cdivi(B, chunk3_fill(B)) + (int64_t)pl.sh.n3, kXcds), waves);
 #define TT_MID(RR, DD)                                                                            \
   k_bwd_mid_mfma<RR, DD><<<chunk_blocks + dg3_blocks, waves * kWave, 0, st>>>(                    \
       g1, g2, g3, ws.P, grad, ws.gsum, ws.u_code, ws.u_i3, ws.c2_item, ws.c2_desc, ws.c3_item,    \
