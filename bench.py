@@ -42,8 +42,8 @@ FP32_PEAK = 157.3e12     # flop/s, MI355X fp32 (vector with packed ops, or fp32 
 # WRITE_SIZE) scaled by the readings for a plain 256 MiB device copy in the same process; the table
 # and the commands are in profiles/step_config3_hbm_traffic.md.  Only the default workload was
 # measured; for anything else `traffic` is null.
-MEASURED_TRAFFIC = {3: {"row_fwd": 43.1e6 + 102.4e6, "gsum": 85.4e6 + 4.8e6, "u_bwd": 115.1e6 + 29.8e6,
-                        "prefix_fwd": 6.5e6 + 34.8e6, "sgd": 32.4e6 + 2.4e6}}
+MEASURED_TRAFFIC = {3: {"row_fwd": 43.1e6 + 102.4e6, "gsum": 85.4e6 + 4.8e6, "u_bwd": 107.4e6 + 32.8e6,
+                        "prefix_fwd": 6.5e6 + 34.8e6, "sgd": 35.3e6 + 2.4e6}}
 
 
 def kernel_work(slot: str, w, B: int, U: int, Q: int, touched_bytes: int, passes: int):
