@@ -411,3 +411,66 @@ def test_adam_first_step_constant_gradient_and_untouched_slices():
     np.testing.assert_allclose((st1[2].astype(np.float64) - st2[2])[moved], (lr * np.sign(d3))[moved],
                                rtol=1e-5)
 
+
+
+def test_adam_two_steps_with_a_changing_gradient():
+    """Pins the decay rates to their moments.  Every pin above feeds a constant gradient, where the
+    bias corrections cancel the decay weights and a swap of beta1 and beta2 between the two moments
+    would go unseen.  Here the gradient changes between the steps by a known factor: the loss is
+    linear in each core, so dG3 does not depend on G3, and with G1, G2 held fixed a batch whose row
+    gradients are four times larger (exact in fp32) gives exactly 4*dG3.  For one entry with first
+    gradient d, worked by hand from the textbook recursion (zero moments, eps -> 0):
+        step 1:  m = (1-b1) d,             v = (1-b2) d^2
+        step 2:  m = b1 (1-b1) d + (1-b1) 4d = (1-b1)(b1+4) d
+                 v = b2 (1-b2) d^2 + (1-b2) 16 d^2 = (1-b2)(b2+16) d^2
+                 m / (1-b1^2) = (b1+4)/(1+b1) d,   v / (1-b2^2) = (b2+16)/(1+b2) d^2
+                 second move = lr * sign(d) * [(b1+4)/(1+b1)] / sqrt[(b2+16)/(1+b2)]
+    With b1 = 1/2, b2 = 1/4:  (4.5/1.5) / sqrt(16.25/1.25) = 3/sqrt(13) = 0.832050...; the swapped
+    assignment would give (4.25/1.25) / sqrt(16.5/1.5) = 1.025141..."""
+    s = Shape((5, 4, 6), (2, 3, 2), (3, 2))
+    rng = np.random.default_rng(23)
+    cores = [rng.standard_normal(cs).astype(np.float32) for cs in s.core_shapes()]
+    ids = np.array([0, 1, 7, 30, 31, 31], dtype=np.int64)
+    grad = rng.standard_normal((ids.size, s.D)).astype(np.float32)
+    d3 = ora.grads(s, *cores, ids, grad)[2]
+    np.testing.assert_allclose(ora.grads(s, *cores, ids, 4 * grad)[2], 4 * d3, rtol=1e-14)
+    lr, b1, b2 = 0.125, 0.5, 0.25
+    zero = [np.zeros_like(c) for c in cores]
+    st1, m, v = ora.adam_update(s, *cores, zero, zero, 1, ids, grad, lr, b1, b2, 1e-30)
+    np.testing.assert_allclose(m[2], 0.5 * d3, rtol=1e-6)            # (1-b1) d
+    np.testing.assert_allclose(v[2], 0.75 * d3 * d3, rtol=1e-6)      # (1-b2) d^2
+    mixed = (cores[0], cores[1], st1[2])
+    st2, m2, v2 = ora.adam_update(s, *mixed, m, v, 2, ids, 4 * grad, lr, b1, b2, 1e-30)
+    np.testing.assert_allclose(m2[2], 0.5 * 4.5 * d3, rtol=1e-6)     # (1-b1)(b1+4) d
+    np.testing.assert_allclose(v2[2], 0.75 * 16.25 * d3 * d3, rtol=1e-6)
+    factor = 3.0 / np.sqrt(13.0)
+    moved = np.abs(d3) > 1e-3
+    assert moved.sum() >= 8
+    np.testing.assert_allclose((st1[2].astype(np.float64) - st2[2])[moved],
+                               (lr * factor * np.sign(d3))[moved], rtol=1e-5)
+
+
+def test_eps_sits_outside_the_square_root():
+    """Pins the place of eps in both adaptive rules with an eps as large as the gradients (all other
+    pins run at eps = 1e-30, where sqrt(S) + eps and sqrt(S + eps) cannot be told apart).  From a
+    zero state the first step has S = dG^2 (Adagrad) and bias-corrected moments dG and dG^2 (Adam),
+    so both rules move an entry by  lr * d / (|d| + eps);  the other placement would give
+    lr * d / sqrt(d^2 + eps), which at eps = 1/2 differs in the first digit."""
+    s = Shape((5, 4, 6), (2, 3, 2), (3, 2))
+    rng = np.random.default_rng(29)
+    cores = [rng.standard_normal(cs).astype(np.float32) for cs in s.core_shapes()]
+    ids = np.array([0, 1, 7, 30, 31, 31], dtype=np.int64)
+    grad = rng.standard_normal((ids.size, s.D)).astype(np.float32)
+    dg = ora.grads(s, *cores, ids, grad)
+    zero = [np.zeros_like(c) for c in cores]
+    lr, eps = 0.125, 0.5
+    ada, _ = ora.adagrad_update(s, *cores, zero, ids, grad, lr, eps)
+    adam, _, _ = ora.adam_update(s, *cores, zero, zero, 1, ids, grad, lr, 0.9, 0.999, eps)
+    for G, Ga, Gm, d in zip(cores, ada, adam, dg):
+        want = lr * d / (np.abs(d) + eps)
+        other = lr * d / np.sqrt(d * d + eps)
+        moved = np.abs(d) > 1e-2
+        assert moved.sum() >= 8 and np.abs(want - other)[moved].min() > 1e-4
+        for got in (Ga, Gm):
+            np.testing.assert_allclose((G.astype(np.float64) - got)[moved], want[moved], rtol=2e-5,
+                                       atol=2e-7)
