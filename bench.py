@@ -4,30 +4,44 @@
 A step is one whole pass of the path over one synthetic minibatch that is already resident in HBM:
 tt_emb_forward (index split, sort, dedup, prefix products, rows) followed by
 tt_emb_backward_update (gradient sums, core gradients, SGD).  The metric is rows per second,
-duplicates counted.  The default workload is the 2.5M-node rank-32 table with a 200,000-row Zipf
-batch; `--config K` picks another of the synthetic workloads (6-8: the paper's own table shapes).
+duplicates counted.  The default workload is the 2.5M-node rank-32 table with 200,000-row Zipf
+batches; `--config K` picks another of the synthetic workloads (6-8: the paper's own table shapes).
+The timed loop rotates over three different batches (seeds K, K+100, K+200), each with its own
+ids, gradient and output buffers, so that no step finds its rows in a cache.
+
+Two figures are measured in the same run and printed in the same line:
+  * `value` / `ms_per_step`: the training loop with look-ahead.  Before the forward of batch k the
+    loop calls tt_emb_prepare for batch k+2, whose index work (split, sort, dedup: it needs the ids
+    only) then runs on a stream of the library's own beside the arithmetic of batch k, and
+    tt_emb_wait_backward(1) keeps the host at most two steps ahead of the device.  All work of all
+    K batches lies inside the timed region.
+  * `plain`: one tt_emb_forward + one tt_emb_backward_update per step and nothing else - every
+    step does its own index work on the caller's stream, nothing overlaps.
+Also reported: the look-ahead loop with the host free to run any distance ahead (`free_running`),
+the plain step replayed as one captured HIP graph (`graph_replay`), per-step times from event
+pairs (p10 / median / p90), the fraction of the binding roofline against the nominal peaks and
+against a copy and an fp32 matrix-core loop measured in the same run, per-kernel durations from
+the library's own event hooks, and the CPU oracle timed on the same batch.
 
 Repeated SGD steps on the same random gradients feed back through the three cores and overflow
-within a few steps at the workloads' learning rate (the hottest id occurs 24,000 times in the default
-batch), so the timed steps use a learning rate of 1e-8: the kernels execute exactly the same
-instructions, and the cores stay where they are for hundreds of steps.  `--restore` times the other
-protocol instead: the workload's own learning rate, with the cores put back from a snapshot by one
-device-side copy per step inside the timed region (extra work, counted against the rate).
+within a few steps at the workloads' learning rate (the hottest id occurs 24,000 times in the
+default batch), so the timed steps use a learning rate of 1e-8: the kernels execute exactly the
+same instructions, and the cores stay where they are for hundreds of steps.  `--restore` times the
+other protocol instead: the workload's own learning rate, with the cores put back from a snapshot
+by one device-side copy per step inside the timed region.
 
-The loop is the one a training loop would run: tt_emb_wait_backward(1) (host-side flow control, at
-most two steps in flight; `--free-running` leaves it out), tt_emb_prepare for the batch two steps
-ahead (its index work overlaps this step's arithmetic; `--no-prepare` leaves it out), forward,
-backward_update.
+After the timed loops, outside them, every mode's results are checked against the CPU oracle at
+the workload's learning rate (sampled rows of every batch, all three updated cores of one batch);
+a mismatch makes the run exit non-zero.
 
-Prints ONE JSON line.  `roofline` describes the longest launch on the caller's stream, timed with HIP events
-on its own stream by the library's profiling hook in a separate, untimed leg (an empty event pair
-is timed too and taken off); `cpu_baseline` is the CPU oracle (fp32 build, OpenMP) on the same batch.
+Prints ONE JSON line.
 """
 from __future__ import annotations
 
 import argparse
 import json
 import os
+import re
 import sys
 import time
 
@@ -36,17 +50,34 @@ if ROOT not in sys.path:
     sys.path.insert(0, ROOT)
 
 HBM_PEAK = 8.0e12        # bytes/s, MI355X HBM3E
-FP32_PEAK = 157.3e12     # flop/s, MI355X fp32 (vector with packed ops, or fp32 MFMA)
+FP32_PEAK = 157.3e12     # flop/s, MI355X fp32 (fp32 MFMA; the vector ALUs reach it with packed ops only)
+ROW_TOL, CORE_TOL, STEP_TOL = 1e-5, 1e-4, 1e-4   # the tolerances of tests/test_gpu_parity.py
 
-# Bytes beyond L2 per launch (fetched + written), from two `rocprofv3 --pmc` runs (FETCH_SIZE,
-# WRITE_SIZE) scaled by the readings for a plain 256 MiB device copy in the same process; the table
-# and the commands are in profiles/step_config3_hbm_traffic.md.  Only the default workload was
-# measured; for anything else `traffic` is null.
-MEASURED_TRAFFIC = {3: {"row_fwd": 43.1e6 + 102.4e6, "gsum": 85.4e6 + 4.8e6, "u_bwd": 107.4e6 + 32.8e6,
-                        "prefix_fwd": 6.5e6 + 34.8e6, "sgd": 35.3e6 + 2.4e6}}
+# kernel slot of the library's timing hooks -> kernel name in the rocprofv3 summaries
+SLOT_KERNEL = {"row_fwd": "k_row_fwd_mfma", "gsum": "k_gsum_block", "u_bwd": "k_bwd_mid_mfma",
+               "prefix_fwd": "k_prefix_fwd_mfma", "sgd": "k_sgd", "prefix_bwd": "k_prefix_bwd_mfma"}
 
 
-def kernel_work(slot: str, w, B: int, U: int, Q: int, touched_bytes: int, passes: int):
+def measured_traffic(config: int, slot: str):
+    """HBM-side bytes per launch (fetched + written) of a kernel slot, read from the rocprofv3
+    counter summary under profiles/ (scaled FETCH_SIZE + WRITE_SIZE columns); None if that
+    workload or kernel has no summary."""
+    path = os.path.join(ROOT, "profiles", f"step_config{config}_hbm_traffic.md")
+    kernel = SLOT_KERNEL.get(slot)
+    if kernel is None or not os.path.exists(path):
+        return None
+    for line in open(path):
+        m = re.match(r"\|\s*`(k_[a-z0-9_]+)[^`]*`\s*\|(.*)\|\s*$", line)
+        if m and m.group(1) == kernel:
+            cols = [c.strip() for c in m.group(2).split("|")]
+            try:
+                return (float(cols[-2]) + float(cols[-1])) * 1e6
+            except ValueError:
+                return None
+    return None
+
+
+def kernel_work(slot: str, w, B: int, U: float, Q: float, touched_bytes: float):
     """Algorithmic (HBM bytes, fp32 flops) one step asks of a kernel slot.  Bytes are the slot's
     share of the path's compulsory traffic, 8 + 8*D per row plus touched core slices twice;
     intermediates that are meant to stay in cache count for nothing."""
@@ -57,14 +88,9 @@ def kernel_work(slot: str, w, B: int, U: int, Q: int, touched_bytes: int, passes
     F2 = 2 * d1 * d2 * r2 * d3          # one row product
     table = {
         "sort_hist": (8 * B, 0),        # reads the int64 ids (first pass)
-        "sort_scatter": (0, 0),
-        "seg_count": (0, 0),
-        "seg_write": (0, 0),
-        "group": (0, 0),
         "prefix_fwd": (0, Q * F1),
         "row_fwd": (4 * D * B, U * F2),
         "gsum": (4 * D * B, (B - U) * D),
-        "gsum_fix": (0, 0),
         "u_bwd": (0, U * F2),
         "dg3": (0, U * F2),
         "prefix_bwd": (0, 2 * Q * F1),
@@ -73,15 +99,62 @@ def kernel_work(slot: str, w, B: int, U: int, Q: int, touched_bytes: int, passes
     return table.get(slot, (0, 0))
 
 
+# ---- the loops that are timed (tests/test_gpu_parity.py runs the same functions at full size)
+
+def prime_lookahead(emb, ids_seq):
+    """Index work of the first two batches, before the loop starts."""
+    emb.prepare(ids_seq[0])
+    emb.prepare(ids_seq[1 % len(ids_seq)])
+
+
+def run_lookahead(emb, ids_seq, grad_seq, out_seq, lr, steps, first=0, flow_control=True,
+                  before_step=None, after_step=None):
+    """`steps` steps of the training loop with look-ahead over the rotating batches; step k works on
+    batch (first + k) mod n.  Enqueues only (the flow control is a host-side wait)."""
+    n = len(ids_seq)
+    for k in range(first, first + steps):
+        if flow_control:
+            emb.wait_backward(1)     # at most two steps ahead of the device; enqueues nothing
+        if before_step is not None:
+            before_step(k)
+        emb.prepare(ids_seq[(k + 2) % n])       # index pipeline of the batch after next
+        emb.forward(ids_seq[k % n], out_seq[k % n])
+        emb.backward_update(grad_seq[k % n], lr)
+        if after_step is not None:
+            after_step(k)
+
+
+def run_plain(emb, ids_seq, grad_seq, out_seq, lr, steps, first=0, before_step=None,
+              after_step=None):
+    """`steps` plain steps: forward + backward_update, each doing its own index work."""
+    n = len(ids_seq)
+    for k in range(first, first + steps):
+        if before_step is not None:
+            before_step(k)
+        emb.forward(ids_seq[k % n], out_seq[k % n])
+        emb.backward_update(grad_seq[k % n], lr)
+        if after_step is not None:
+            after_step(k)
+
+
+def percentiles(us):
+    import numpy as np
+    a = np.asarray(us, dtype=np.float64)
+    return {"p10": round(float(np.percentile(a, 10)), 2), "p50": round(float(np.percentile(a, 50)), 2),
+            "p90": round(float(np.percentile(a, 90)), 2)}
+
+
 def main() -> int:
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=200)
     ap.add_argument("--warmup", type=int, default=20)
     ap.add_argument("--config", type=int, default=3, choices=[1, 2, 3, 4, 5, 6, 7, 8])
-    ap.add_argument("--seed", type=int, default=None)
-    ap.add_argument("--profile-steps", type=int, default=20)
+    ap.add_argument("--seed", type=int, default=None, help="seed of the first batch (default: the config number)")
+    ap.add_argument("--batches", type=int, default=3, help="different batches the loop rotates over")
+    ap.add_argument("--profile-steps", type=int, default=21)
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-check", action="store_true", help="skip the oracle check after the timed loops")
     ap.add_argument("--restore", action="store_true",
                     help="workload learning rate, cores restored from a snapshot every step")
     ap.add_argument("--lr", type=float, default=1e-8,
@@ -89,10 +162,8 @@ def main() -> int:
     ap.add_argument("--calib-copy-mib", type=int, default=0,
                     help="also run one plain device copy of this many MiB (known traffic, to scale "
                          "a profiler's HBM counters)")
-    ap.add_argument("--free-running", action="store_true",
-                    help="let the host run arbitrarily far ahead of the device (no tt_emb_wait_backward)")
-    ap.add_argument("--no-prepare", action="store_true",
-                    help="do not overlap the index work of coming steps with this step's arithmetic")
+    ap.add_argument("--only", choices=["lookahead", "plain"], default=None,
+                    help="time only this loop and print a short line (for runs under a profiler)")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on ONE GPU (the paper's scheme for more, replicated cores and "
@@ -102,6 +173,7 @@ def main() -> int:
     import numpy as np
     import torch
     import workloads as wl
+    import paper_2206_10581_amd as lib
     from paper_2206_10581_amd import TTEmbedding
 
     if not torch.cuda.is_available():
@@ -109,14 +181,23 @@ def main() -> int:
         return 3
     dev = torch.device("cuda:0")
     w = wl.CONFIGS[args.config]
-    seed = args.config if args.seed is None else args.seed
+    seed0 = args.config if args.seed is None else args.seed
+    seeds = [seed0 + 100 * j for j in range(max(1, args.batches))]
     B, D = w.batch, w.D
-    cores_np = wl.make_cores(w, seed)
-    ids_np = wl.make_ids(w, seed)
-    grad_np = wl.make_grads(w, seed)
-    struct = wl.batch_structure(w, ids_np)
+    n2, n3 = w.n[1], w.n[2]
+    (d1, d2, d3), (r1, r2) = w.d, w.r
+    cores_np = wl.make_cores(w, seed0)
+    ids_np = [wl.make_ids(w, s) for s in seeds]
+    grad_np = [wl.make_grads(w, s) for s in seeds]
+    structs = [wl.batch_structure(w, i) for i in ids_np]
+    touched = []
+    for i in ids_np:
+        ok = i[(i >= 0) & (i < w.N)]
+        touched.append(4 * (np.unique(ok // (n2 * n3)).size * d1 * r1
+                            + np.unique((ok // n3) % n2).size * r1 * d2 * r2
+                            + np.unique(ok % n3).size * r2 * d3))
 
-    # cores live in one flat buffer so that the per-step restore is a single device copy
+    # cores live in one flat buffer so that a restore is a single device copy
     sizes = [c.size for c in cores_np]
     offs = [0]
     for s in sizes:
@@ -126,29 +207,19 @@ def main() -> int:
     for t, c in zip(cores, cores_np):
         t.copy_(torch.from_numpy(c))
     snapshot = flat.clone()
-    ids = torch.from_numpy(ids_np).to(dev)
-    grad = torch.from_numpy(grad_np).to(dev)
-    out = torch.empty((B, D), dtype=torch.float32, device=dev)
-    # the ids are resident before the timed region starts: TT_EMB_FLAG_IDS_READY (4)
+    ids = [torch.from_numpy(i).to(dev) for i in ids_np]
+    grad = [torch.from_numpy(g).to(dev) for g in grad_np]
+    out = [torch.empty((B, D), dtype=torch.float32, device=dev) for _ in seeds]
+    torch.cuda.synchronize()
+    # look-ahead handle: the ids are resident before the timed region starts (TT_EMB_FLAG_IDS_READY);
+    # plain handle: default flags, never prepared (so it can also be captured into a graph).  Both
+    # work on the same cores.
     emb = TTEmbedding(w.n, w.d, w.r, B, cores, device=dev, flags=4)
+    emb_plain = TTEmbedding(w.n, w.d, w.r, B, cores, device=dev, flags=0)
 
     lr = w.lr if args.restore else args.lr
-
-    waited = [0.0]                  # host seconds spent in the flow-control wait
-
-    def step():
-        if not args.free_running:
-            # host-side flow control (enqueues nothing): at most two steps ahead of the device, so
-            # that forward finds the pipeline of its prepared batch finished and need not wait for it
-            w0 = time.perf_counter()
-            emb.wait_backward(1)
-            waited[0] += time.perf_counter() - w0
-        if args.restore:
-            flat.copy_(snapshot)
-        if not args.no_prepare:
-            emb.prepare(ids)        # index pipeline of the step after next, overlapped with this one
-        emb.forward(ids, out)
-        emb.backward_update(grad, lr)
+    restore = (lambda k: flat.copy_(snapshot)) if args.restore else None
+    nb = len(seeds)
 
     if args.calib_copy_mib > 0:
         src = torch.ones(args.calib_copy_mib << 18, dtype=torch.float32, device=dev)
@@ -157,120 +228,239 @@ def main() -> int:
         dst.copy_(src)              # one copy kernel that reads and writes calib_copy_mib MiB
         torch.cuda.synchronize()
         del src, dst
-    if not args.no_prepare:
-        emb.prepare(ids)            # the first two steps' own index work
-        emb.prepare(ids)
-    for _ in range(args.warmup):
-        step()
-    torch.cuda.synchronize()
-    stats = emb.stats()
-    assert stats["U"] == struct["U"] and stats["Q"] == struct["Q"], (stats, struct)
 
-    waited[0] = 0.0
-    t0 = time.perf_counter()
-    for _ in range(args.steps):
-        step()
-    t_enq = time.perf_counter()     # host side done: every launch of the timed steps is enqueued
-    torch.cuda.synchronize()
-    t1 = time.perf_counter()
-    ms_per_step = (t1 - t0) * 1e3 / args.steps
-    host_ms_per_step = (t_enq - t0 - waited[0]) * 1e3 / args.steps   # enqueue work, waits taken off
+    def timed(fn, steps):
+        """Wall time per step of fn(steps), bracketed by synchronisation."""
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        fn(steps)
+        t_enq = time.perf_counter()
+        torch.cuda.synchronize()
+        t1 = time.perf_counter()
+        return (t1 - t0) * 1e3 / steps, (t_enq - t0) * 1e3 / steps
+
+    def event_timed(fn_one, steps):
+        """Per-step durations (us) from one event pair per step on the caller's stream."""
+        ev = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True))
+              for _ in range(steps)]
+        fn_one(steps, lambda k: ev[k % steps][0].record(), lambda k: ev[k % steps][1].record())
+        torch.cuda.synchronize()
+        return [a.elapsed_time(b) * 1e3 for a, b in ev]
+
+    def look(steps, first=0, flow=True, before=None, after=None):
+        def both(k):
+            if restore:
+                restore(k)
+            if before:
+                before(k)
+        run_lookahead(emb, ids, grad, out, lr, steps, first, flow, both if (restore or before) else None,
+                      after)
+
+    def plain(steps, first=0, before=None, after=None):
+        def both(k):
+            if restore:
+                restore(k)
+            if before:
+                before(k)
+        run_plain(emb_plain, ids, grad, out, lr, steps, first, both if (restore or before) else None, after)
+
+    K, W = args.steps, args.warmup
+    res = {}
+    # ---- look-ahead loop (the headline)
+    if args.only in (None, "lookahead"):
+        prime_lookahead(emb, ids)
+        look(W)
+        torch.cuda.synchronize()
+        stats = emb.stats()
+        last = (W - 1) % nb if W > 0 else None
+        if last is not None:
+            assert stats["U"] == structs[last]["U"] and stats["Q"] == structs[last]["Q"], (stats, structs[last])
+        ms, host_ms = timed(lambda n: look(n, first=W), K)
+        res["lookahead"] = {"ms_per_step": ms, "host_enqueue_ms_per_step": host_ms}
+    # ---- plain loop
+    if args.only in (None, "plain"):
+        plain(max(2, W // 2))
+        ms, host_ms = timed(lambda n: plain(n), K)
+        res["plain"] = {"ms_per_step": ms, "host_enqueue_ms_per_step": host_ms}
+    if args.only is not None:
+        r = res[args.only]
+        line = {"metric": "TT-embedding rows/s (fwd+bwd+update)", "value": B / (r["ms_per_step"] * 1e-3),
+                "unit": "rows/s", "n_gpus": 1, "steps": K, "warmup": W, "ms_per_step": r["ms_per_step"],
+                "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "f32",
+                "data": "synthetic", "config": {"workload": w.name, "batch": B, "loop": args.only,
+                                                "batches": [{"seed": s, "U": st["U"], "Q": st["Q"]}
+                                                            for s, st in zip(seeds, structs)]}}
+        print(json.dumps(line))
+        emb.close()
+        emb_plain.close()
+        return 0
+
+    ms_per_step = res["lookahead"]["ms_per_step"]
     rows_per_s = B / (ms_per_step * 1e-3)
-    # the same K steps with the host free to run any distance ahead (no host-side wait inside the
-    # loop), reported beside the main figure
-    other = None
-    if not args.free_running and not args.no_prepare:
-        args.free_running = True
-        for _ in range(max(2, args.warmup // 2)):
-            step()
+    # per-step event pairs (these add an event packet or two to every step, so they get legs of their own)
+    n_ev = min(K, 120)
+    look(4, first=W + K)
+    look_us = event_timed(lambda n, b, a: look(n, first=W + K + 4, before=b, after=a), n_ev)
+    plain(2)
+    plain_us = event_timed(lambda n, b, a: plain(n, before=b, after=a), n_ev)
+    # the look-ahead loop with the host free to run any distance ahead
+    look(max(2, W // 2), first=0, flow=False)
+    f_ms, _ = timed(lambda n: look(n, first=0, flow=False), K)
+    # the plain step as one captured graph (one batch: a graph holds its pointers)
+    graph_ms = None
+    try:
         torch.cuda.synchronize()
-        f0 = time.perf_counter()
-        for _ in range(args.steps):
-            step()
-        torch.cuda.synchronize()
-        f_ms = (time.perf_counter() - f0) * 1e3 / args.steps
-        args.free_running = False
-        other = {"ms_per_step": f_ms, "value": B / (f_ms * 1e-3), "host_steps_ahead": "unbounded"}
-    if not bool(torch.isfinite(flat).all()) or not bool(torch.isfinite(out).all()):
+        g = torch.cuda.CUDAGraph()
+        with torch.cuda.graph(g):
+            emb_plain.forward(ids[0], out[0])
+            emb_plain.backward_update(grad[0], lr)
+        for _ in range(3):
+            g.replay()
+        graph_ms, _ = timed(lambda n: [g.replay() for _ in range(n)], K)
+        del g
+    except Exception as exc:                      # reported, never fatal: it is a side figure
+        graph_ms = None
+        print(f"bench.py: graph leg skipped: {exc}", file=sys.stderr)
+    if not bool(torch.isfinite(flat).all()) or not all(bool(torch.isfinite(o).all()) for o in out):
         print("bench.py: cores or rows overflowed during the timed steps", file=sys.stderr)
         return 4
 
-    # untimed leg: per-kernel durations from HIP events recorded on the launch stream
+    # ---- untimed leg: per-kernel durations from HIP events recorded on the launch stream
     prof = {}
-    if args.profile_steps > 0:
+    psteps = args.profile_steps - args.profile_steps % nb if args.profile_steps >= nb else 0
+    if psteps > 0:
+        look(2, first=0)
+        torch.cuda.synchronize()
         emb.profile(True)
-        for _ in range(args.profile_steps):
-            step()
+        look(psteps, first=2)
         torch.cuda.synchronize()
         prof = emb.profile_read()
         emb.profile(False)
 
-    U, Q = stats["U"], stats["Q"]
-    ok = ids_np[(ids_np >= 0) & (ids_np < w.N)]
-    n2, n3 = w.n[1], w.n[2]
-    (d1, d2, d3), (r1, r2) = w.d, w.r
-    touched_bytes = 4 * (np.unique(ok // (n2 * n3)).size * d1 * r1
-                         + np.unique((ok // n3) % n2).size * r1 * d2 * r2
-                         + np.unique(ok % n3).size * r2 * d3)
+    # ---- device calibration in the same run: streaming copy and fp32 matrix-core loop
+    cal = torch.empty(1 << 30, dtype=torch.uint8, device=dev)
+    rc, copy_bps, mfma_fps = lib.tt_emb_profile_peaks(cal.data_ptr(), cal.numel(),
+                                                      int(torch.cuda.current_stream().cuda_stream))
+    del cal
+    if rc:
+        print(f"bench.py: tt_emb_profile_peaks failed ({rc})", file=sys.stderr)
+        return 5
+
+    # ---- oracle check of both loops, at the workload's learning rate, outside every timed region
+    check = None
+    if not args.no_check:
+        from oracle import tt_oracle as ora
+        s = ora.Shape(w.n, w.d, w.r)
+        F1, F2 = 2 * d1 * r1 * d2 * r2, 2 * d1 * d2 * r2 * d3
+        full_cost = 3.0 * B * (F1 + F2)                     # flops of the oracle's backward on one batch
+        rng = np.random.default_rng(12345)
+        sample = np.sort(rng.choice(B, size=min(B, 2048), replace=False))
+        check = {"rows_sampled_per_batch": int(sample.size), "row_tol": ROW_TOL, "core_tol": CORE_TOL,
+                 "row_err": 0.0, "core_err": None, "step_err": None, "ok": True, "loops": []}
+        for name, runner, handle in (("lookahead", look, emb), ("plain", plain, emb_plain)):
+            flat.copy_(snapshot)
+            torch.cuda.synchronize()
+            snaps = []
+            saved_lr, saved_restore = lr, restore
+            lr, restore = w.lr, (lambda k: flat.copy_(snapshot))     # every step starts from the snapshot
+            if name == "lookahead":
+                prime_lookahead(emb, ids)
+            runner(nb, first=0, after=lambda k: snaps.append(flat.clone()))
+            torch.cuda.synchronize()
+            lr, restore = saved_lr, saved_restore
+            for j in range(nb):
+                ref_rows = ora.forward(s, *cores_np, ids_np[j][sample])
+                got = out[j][torch.from_numpy(sample).to(dev)].cpu().numpy()
+                num = np.abs(got.astype(np.float64) - ref_rows).max(axis=1)
+                den = np.abs(ref_rows).max(axis=1)
+                err = float((num[den > 0] / den[den > 0]).max()) if (den > 0).any() else 0.0
+                if (num[den == 0] != 0).any():
+                    err = float("inf")
+                check["row_err"] = max(check["row_err"], err)
+            if full_cost <= 6e10:                           # a few seconds of oracle time
+                ref_new = ora.backward_update(s, *cores_np, ids_np[0], grad_np[0], w.lr)
+                got_flat = snaps[0].cpu().numpy()
+                cerr, serr = [], []
+                for k in range(3):
+                    gk = got_flat[offs[k]:offs[k] + sizes[k]].reshape(cores_np[k].shape)
+                    cerr.append(float(np.abs(gk.astype(np.float64) - ref_new[k]).max() / np.abs(ref_new[k]).max()))
+                    sg = (cores_np[k].astype(np.float64) - gk) / w.lr
+                    sr = (cores_np[k].astype(np.float64) - ref_new[k]) / w.lr
+                    slack = 2 * np.finfo(np.float32).eps * np.abs(cores_np[k]).max() / w.lr
+                    serr.append(float(max(0.0, np.abs(sg - sr).max() - slack) / np.abs(sr).max()))
+                check["core_err"] = max(cerr + ([check["core_err"]] if check["core_err"] else []))
+                check["step_err"] = max(serr + ([check["step_err"]] if check["step_err"] else []))
+            check["loops"].append(name)
+        check["ok"] = bool(check["row_err"] <= ROW_TOL
+                           and (check["core_err"] is None or check["core_err"] <= CORE_TOL)
+                           and (check["step_err"] is None or check["step_err"] <= STEP_TOL))
+        if check["core_err"] is None:
+            check["cores"] = "not checked here (oracle cost); tests/test_gpu_parity.py checks them at full size"
+        flat.copy_(snapshot)
+        torch.cuda.synchronize()
+        if not check["ok"]:
+            print(f"bench.py: results do not match the oracle: {check}", file=sys.stderr)
+            return 6
+
+    # ---- roofline figures
+    U = float(np.mean([st["U"] for st in structs]))
+    Q = float(np.mean([st["Q"] for st in structs]))
+    touched_bytes = float(np.mean(touched))
     kernels = {}
-    # what a HIP event pair adds by itself (measured with nothing between the two events) is taken
-    # off every launch, so that the durations are the kernels' own, as a profiler would report them
     ep = prof.pop("event_pair", {"launches": 0, "ms": 0.0})
     pair_us = ep["ms"] * 1e3 / ep["launches"] if ep["launches"] else 0.0
     for name, rec in prof.items():
         if rec["launches"] == 0:
             continue
-        launches = rec["launches"] / max(args.profile_steps, 1)
-        per_step_us = max(rec["ms"] * 1e3 / max(args.profile_steps, 1) - pair_us * launches, 0.0)
-        by, fl = kernel_work(name, w, B, U, Q, touched_bytes, 0)
+        launches = rec["launches"] / max(psteps, 1)
+        per_step_us = max(rec["ms"] * 1e3 / max(psteps, 1) - pair_us * launches, 0.0)
+        by, fl = kernel_work(name, w, B, U, Q, touched_bytes)
         if name == "u_bwd" and prof.get("dg3", {}).get("launches", 0) == 0:
             fl *= 2          # matrix-core shapes: dPsum and the dG3 partials share one launch
             if prof.get("prefix_bwd", {}).get("launches", 0) == 0:
-                # ranks up to 32: the prefix-level gradients are formed in that launch too
-                fl += kernel_work("prefix_bwd", w, B, U, Q, touched_bytes, 0)[1]
+                fl += kernel_work("prefix_bwd", w, B, U, Q, touched_bytes)[1]
         kernels[name] = {"us_per_step": round(per_step_us, 2), "launches_per_step": launches,
                          "alg_bytes": int(by), "alg_flops": int(fl)}
-    if not kernels:          # --profile-steps 0: no per-kernel leg (used under an external profiler)
-        line = {"metric": "TT-embedding rows/s (fwd+bwd+update)", "value": rows_per_s,
-                "unit": "rows/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
-                "ms_per_step": ms_per_step, "higher_is_better": True, "scaling": "weak",
-                "vs_baseline": None, "dtype": "f32", "data": "synthetic",
-                "config": {"workload": w.name, "batch": B, "U": U, "Q": Q}}
-        print(json.dumps(line))
-        emb.close()
-        return 0
-    # the dominant kernel: the longest single launch on the caller's stream (the index kernels run
-    # beside the arithmetic on the library's own streams and are not on the step's critical path)
-    chain = [k for k in kernels if k in ("prefix_fwd", "row_fwd", "gsum", "gsum_fix", "u_bwd", "dg3",
-                                         "prefix_bwd", "sgd")] or list(kernels)
-    dom = max(chain, key=lambda k: kernels[k]["us_per_step"] / kernels[k]["launches_per_step"])
-    kd = kernels[dom]
-    launch_s = kd["us_per_step"] * 1e-6 / kd["launches_per_step"]
-    by = kd["alg_bytes"] / kd["launches_per_step"]
-    fl = kd["alg_flops"] / kd["launches_per_step"]
-    if by / HBM_PEAK >= fl / FP32_PEAK:
-        roofline = {"kernel": dom, "bound": "hbm", "achieved": by / launch_s / 1e9,
-                    "peak": HBM_PEAK / 1e9, "unit": "GB/s", "frac": by / launch_s / HBM_PEAK,
-                    "traffic": None}
-    else:
-        roofline = {"kernel": dom, "bound": "mfma", "achieved": fl / launch_s / 1e12,
-                    "peak": FP32_PEAK / 1e12, "unit": "TFLOP/s", "frac": fl / launch_s / FP32_PEAK,
-                    "traffic": None}
-    roofline["avg_launch_us"] = round(launch_s * 1e6, 2)
-    roofline["event_pair_us"] = round(pair_us, 2)     # already subtracted from avg_launch_us
-    if args.seed is None:
-        roofline["traffic"] = MEASURED_TRAFFIC.get(args.config, {}).get(dom)
-
-    # the path as a whole against its binding bound
     F1, F2 = 2 * d1 * r1 * d2 * r2, 2 * d1 * d2 * r2 * d3
     alg_bytes = B * (8 + 8 * D) + 2 * touched_bytes
     alg_flops = 3 * (Q * F1 + U * F2) + (B - U) * D
     t_hbm, t_alu = alg_bytes / HBM_PEAK, alg_flops / FP32_PEAK
+    t_bound = max(t_hbm, t_alu)
+    t_bound_meas = max(alg_bytes / copy_bps, alg_flops / mfma_fps)
+    plain_ms = res["plain"]["ms_per_step"]
     path = {"alg_bytes": int(alg_bytes), "alg_flops": int(alg_flops),
             "t_hbm_us": round(t_hbm * 1e6, 2), "t_fp32_us": round(t_alu * 1e6, 2),
             "bound": "hbm" if t_hbm >= t_alu else "alu",
-            "frac": max(t_hbm, t_alu) / (ms_per_step * 1e-3),
+            "frac": t_bound / (ms_per_step * 1e-3),
+            "frac_plain": t_bound / (plain_ms * 1e-3),
+            "frac_of_measured_peaks": t_bound_meas / (ms_per_step * 1e-3),
+            "frac_plain_of_measured_peaks": t_bound_meas / (plain_ms * 1e-3),
             "kernel_sum_us": round(sum(k["us_per_step"] for k in kernels.values()), 2)}
+    roofline = None
+    if kernels:
+        # the dominant kernel: the longest single launch on the caller's stream
+        chain = [k for k in kernels if k in ("prefix_fwd", "row_fwd", "gsum", "gsum_fix", "u_bwd", "dg3",
+                                             "prefix_bwd", "sgd")] or list(kernels)
+        dom = max(chain, key=lambda k: kernels[k]["us_per_step"] / kernels[k]["launches_per_step"])
+        kd = kernels[dom]
+        launch_s = kd["us_per_step"] * 1e-6 / kd["launches_per_step"]
+        by = kd["alg_bytes"] / kd["launches_per_step"]
+        fl = kd["alg_flops"] / kd["launches_per_step"]
+        if by / HBM_PEAK >= fl / FP32_PEAK:
+            roofline = {"kernel": dom, "bound": "hbm", "achieved": by / launch_s / 1e9,
+                        "peak": HBM_PEAK / 1e9, "unit": "GB/s", "frac": by / launch_s / HBM_PEAK,
+                        "frac_of_measured_peak": by / launch_s / copy_bps}
+        else:
+            roofline = {"kernel": dom, "bound": "mfma", "achieved": fl / launch_s / 1e12,
+                        "peak": FP32_PEAK / 1e12, "unit": "TFLOP/s", "frac": fl / launch_s / FP32_PEAK,
+                        "frac_of_measured_peak": fl / launch_s / mfma_fps}
+        roofline["traffic"] = measured_traffic(args.config, dom) if args.seed is None else None
+        roofline["avg_launch_us"] = round(launch_s * 1e6, 2)
+        roofline["event_pair_us"] = round(pair_us, 2)     # already subtracted from avg_launch_us
+        roofline["scope"] = "the longest launch of a step; the step as a whole: path_roofline"
+        roofline["path_bound"] = path["bound"]
+        roofline["path_frac"] = path["frac"]
+        roofline["path_frac_plain"] = path["frac_plain"]
 
     cpu = None
     if not args.no_cpu_baseline:
@@ -278,8 +468,8 @@ def main() -> int:
         s = ora.Shape(w.n, w.d, w.r)
 
         def oracle_step(rows):
-            ora.forward(s, *cores_np, ids_np[:rows], tag="f32")
-            ora.backward_update(s, *cores_np, ids_np[:rows], grad_np[:rows], w.lr, tag="f32")
+            ora.forward(s, *cores_np, ids_np[0][:rows], tag="f32")
+            ora.backward_update(s, *cores_np, ids_np[0][:rows], grad_np[0][:rows], w.lr, tag="f32")
 
         oracle_step(256)                                   # loads the library
         probe = min(B, 20_000)
@@ -301,20 +491,36 @@ def main() -> int:
 
     line = {
         "metric": "TT-embedding rows/s (fwd+bwd+update)", "value": rows_per_s, "unit": "rows/s",
-        "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": ms_per_step,
-        "host_enqueue_ms_per_step": host_ms_per_step, "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "f32",
+        "n_gpus": 1, "steps": K, "warmup": W, "ms_per_step": ms_per_step,
+        "host_enqueue_ms_per_step": res["lookahead"]["host_enqueue_ms_per_step"],
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "f32",
         "data": "synthetic",
         "config": {"workload": w.name, "N": w.N, "n": list(w.n), "d": list(w.d), "ranks": list(w.r),
-                   "batch": B, "ids": w.ids, "zipf_s": w.zipf_s, "seed": seed, "lr": lr,
+                   "batch": B, "ids": w.ids, "zipf_s": w.zipf_s, "lr": lr,
                    "protocol": "restore_each_step" if args.restore else "small_lr_no_restore",
-                   "next_batch_index_overlap": not args.no_prepare,
-                   "host_steps_ahead": "unbounded" if args.free_running else "at most 2",
-                   "U": U, "Q": Q, "max_multiplicity": struct["max_multiplicity"]},
-        "roofline": roofline, "cpu_baseline": cpu, "path_roofline": path,
-        "free_running": other, "kernels": kernels,
+                   "loop": "look-ahead: index work of batch k+2 beside the arithmetic of batch k; "
+                           "host at most 2 steps ahead",
+                   "batches": [{"seed": sd, "U": st["U"], "Q": st["Q"],
+                                "max_multiplicity": st["max_multiplicity"]}
+                               for sd, st in zip(seeds, structs)]},
+        "step_us": percentiles(look_us),
+        "plain": {"loop": "forward + backward_update only, index work inside every step",
+                  "ms_per_step": plain_ms, "value": B / (plain_ms * 1e-3),
+                  "host_enqueue_ms_per_step": res["plain"]["host_enqueue_ms_per_step"],
+                  "step_us": percentiles(plain_us), "frac": path["frac_plain"]},
+        "free_running": {"ms_per_step": f_ms, "value": B / (f_ms * 1e-3), "host_steps_ahead": "unbounded"},
+        "graph_replay": (None if graph_ms is None else
+                         {"loop": "the plain step of one batch captured once, replayed",
+                          "ms_per_step": graph_ms, "value": B / (graph_ms * 1e-3)}),
+        "peaks_measured": {"copy_GBps": round(copy_bps / 1e9, 1), "mfma_fp32_TFLOPs": round(mfma_fps / 1e12, 1),
+                           "how": "tt_emb_profile_peaks in this run: 512 MiB streaming copy (read + "
+                                  "written bytes), register-resident v_mfma_f32_32x32x2f32 loop"},
+        "roofline": roofline, "cpu_baseline": cpu, "path_roofline": path, "check": check,
+        "kernels": kernels,
     }
     print(json.dumps(line))
     emb.close()
+    emb_plain.close()
     return 0
 
 

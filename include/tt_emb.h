@@ -22,11 +22,19 @@
  * Output column order is j = (j1*d2 + j2)*d3 + j3 (Eq. "tt-embedding").
  *
  * Memory.  Every pointer named "device" is HIP device memory owned by the caller; the library
- * borrows it and never allocates or frees device memory.  Cores, out and grad_out must be 16-byte
- * aligned, ids 8-byte aligned (TT_EMB_EINVAL otherwise).  The handle owns host bookkeeping only.
+ * borrows it and never allocates or frees device memory.  Cores must be 16-byte aligned, ids
+ * 8-byte aligned, out and grad_out 16-byte aligned for the shapes that run on the matrix-core
+ * kernels (see TT_EMB_FLAG_GENERIC_KERNELS) and 4-byte aligned otherwise (TT_EMB_EINVAL if not).
+ * The handle owns host bookkeeping only.
  * All calls are asynchronous on the given HIP stream unless stated otherwise (tt_emb_prepare also
  * uses two internal streams of default priority, created on its first call).  A handle must not
  * be used from two threads or two streams at once.
+ *
+ * Graph capture.  forward, forward_eval, materialize and backward_update only enqueue kernels on
+ * hip_stream and may be captured into a HIP graph, as long as the handle has never been given to
+ * tt_emb_prepare: a handle that has orders its index sets through events on streams of its own,
+ * which a capture cannot contain, so every call on it (tt_emb_prepare included) returns
+ * TT_EMB_ESTATE while hip_stream is being captured.  Use a second handle for captured steps.
  *
  * Errors.  Every function returns TT_EMB_OK (0) or a negative code and never aborts.
  */
@@ -46,7 +54,8 @@ enum {
   TT_EMB_OK = 0,
   TT_EMB_EINVAL = -1,    /* null pointer, non-positive factor, unsupported size, B < 0          */
   TT_EMB_ENOSPC = -2,    /* B > max_batch, or the workspace is smaller than workspace_bytes()   */
-  TT_EMB_ESTATE = -3,    /* backward_update without a pending forward                           */
+  TT_EMB_ESTATE = -3,    /* backward_update without a pending forward; a call that the handle's
+                            state does not allow (see the functions)                            */
   TT_EMB_EHIP = -4,      /* a HIP call failed; tt_emb_strerror(code) carries HIP's message      */
   TT_EMB_ERANGE = -5,    /* get_stats only: some id of the last batch was outside [0, N)        */
   TT_EMB_EINTERNAL = -6  /* get_stats only: a kernel met an index it could not have produced    */
@@ -81,13 +90,18 @@ typedef struct {
   uint32_t flags;    /* TT_EMB_FLAG_*                                                           */
 } tt_emb_config;
 
-/* Bytes of device workspace that tt_emb_create needs for this configuration. */
+/* Bytes of device workspace that tt_emb_create needs for this configuration (Section 3: the
+ * factorisations and ranks of cfg fix the sizes of the cores and of every intermediate). */
 int tt_emb_workspace_bytes(const tt_emb_config* cfg, size_t* bytes);
 
 /*
- * Creates a handle over caller-owned cores (device, layout above, updated in place by
- * backward_update) and a caller-owned workspace (device, at least workspace_bytes(), 256-byte
- * aligned).  Both must stay alive until tt_emb_destroy.  Host-only: enqueues nothing.
+ * Creates a handle for the table that three TT cores define (Section 3, Eq. "tt-matrix": a matrix
+ * with N = n1*n2*n3 rows and D = d1*d2*d3 columns held as cores of ranks (1, r1, r2, 1); cfg gives
+ * the two factorisations and the ranks) over caller-owned cores (device, layout above, updated in
+ * place by backward_update) and a caller-owned workspace (device, at least workspace_bytes(),
+ * 256-byte aligned).  Both must stay alive until tt_emb_destroy.  Host-only: enqueues nothing.
+ * Returns TT_EMB_EINVAL for a null pointer, a misaligned buffer or a configuration outside the
+ * limits stated at tt_emb_config, TT_EMB_ENOSPC when workspace_bytes is too small.
  */
 int tt_emb_create(tt_emb_t* out, const tt_emb_config* cfg, float* g1, float* g2, float* g3,
                   void* workspace, size_t workspace_bytes);
@@ -187,7 +201,8 @@ int tt_emb_prepare(tt_emb_t h, const int64_t* ids, int64_t B, void* hip_stream);
  * cores as they are when the call starts (all positions add, no averaging), then applies
  * Gk[s] <- Gk[s] - lr*dGk[s] to every slice s the batch touches; other slices are not written.
  * Sums are formed in a fixed order: the same inputs give bit-identical cores.  Consumes the
- * pending forward (a second call without a new forward returns TT_EMB_ESTATE).
+ * pending forward (a second call without a new forward returns TT_EMB_ESTATE); a call that is
+ * rejected for its arguments (TT_EMB_EINVAL) leaves the forward pending.
  */
 int tt_emb_backward_update(tt_emb_t h, const float* grad_out, float lr, void* hip_stream);
 
@@ -211,6 +226,16 @@ int tt_emb_get_stats(tt_emb_t h, int64_t* U, int64_t* Q, int64_t* out_of_range);
 int tt_emb_profile_enable(tt_emb_t h, int enable);
 int tt_emb_profile_slots(void);
 int tt_emb_profile_read(tt_emb_t h, int slot, const char** name, int64_t* launches, double* ms);
+
+/*
+ * Device calibration for roofline figures (not part of the path): times a plain streaming copy of
+ * the first half of device_buf (caller-owned, 256-byte aligned, at least 4 MiB; the larger, the
+ * closer to the HBM rate) onto its second half, and a register-resident loop of fp32 matrix-core
+ * instructions on every compute unit; best of five launches each.  Reports bytes read + written
+ * per second and fp32 flop per second.  Synchronises hip_stream; overwrites device_buf.
+ */
+int tt_emb_profile_peaks(void* device_buf, size_t bytes, void* hip_stream, double* copy_bytes_per_s,
+                         double* mfma_flops_per_s);
 
 /* Frees the handle (host memory only). */
 int tt_emb_destroy(tt_emb_t h);

@@ -63,13 +63,15 @@ def load_library():
     lib.tt_emb_profile_slots.argtypes = []
     lib.tt_emb_profile_read.argtypes = [c_void_p, c_int, POINTER(c_char_p), POINTER(c_int64),
                                         POINTER(c_double)]
+    lib.tt_emb_profile_peaks.argtypes = [c_void_p, c_size_t, c_void_p, POINTER(c_double),
+                                         POINTER(c_double)]
     lib.tt_emb_destroy.argtypes = [c_void_p]
     lib.tt_emb_strerror.argtypes = [c_int]
     lib.tt_emb_strerror.restype = c_char_p
     for name in ("tt_emb_workspace_bytes", "tt_emb_create", "tt_emb_forward", "tt_emb_prepare",
                  "tt_emb_backward_update", "tt_emb_forward_eval", "tt_emb_materialize",
                  "tt_emb_set_reindex", "tt_emb_set_adagrad", "tt_emb_set_adam", "tt_emb_wait_backward", "tt_emb_get_stats", "tt_emb_profile_enable",
-                 "tt_emb_profile_slots", "tt_emb_profile_read", "tt_emb_destroy"):
+                 "tt_emb_profile_slots", "tt_emb_profile_read", "tt_emb_profile_peaks", "tt_emb_destroy"):
         getattr(lib, name).restype = c_int
     _lib = lib
     return lib
@@ -164,6 +166,13 @@ def tt_emb_profile_read(h, slot: int):
     name, n, ms = c_char_p(None), c_int64(0), c_double(0.0)
     rc = load_library().tt_emb_profile_read(h, c_int(slot), byref(name), byref(n), byref(ms))
     return rc, (name.value or b"").decode(), int(n.value), float(ms.value)
+
+
+def tt_emb_profile_peaks(buf_ptr: int, nbytes: int, stream: int):
+    copy, mfma = c_double(0.0), c_double(0.0)
+    rc = load_library().tt_emb_profile_peaks(c_void_p(buf_ptr), c_size_t(nbytes), c_void_p(stream),
+                                             byref(copy), byref(mfma))
+    return rc, float(copy.value), float(mfma.value)
 
 
 def tt_emb_destroy(h) -> int:

@@ -7,7 +7,8 @@ import subprocess
 HERE = os.path.dirname(os.path.abspath(__file__))
 ROOT = os.path.dirname(HERE)
 CSRC = os.path.join(HERE, "csrc")
-SOURCES = ["tt_emb_index.hip", "tt_emb_compute.hip", "tt_emb_mfma.hip", "tt_emb_api.hip"]
+SOURCES = ["tt_emb_index.hip", "tt_emb_compute.hip", "tt_emb_mfma.hip", "tt_emb_calib.hip",
+           "tt_emb_api.hip"]
 LIB = os.path.join(HERE, "libtt_emb.so")
 
 

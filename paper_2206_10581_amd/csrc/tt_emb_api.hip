@@ -44,6 +44,8 @@ bool gsum_block_rows(const Shape&);
 void launch_bwd_mid_mfma(const Plan&, const Workspace&, const float* g1, const float* g2,
                          const float* g3, const float* grad, int B, hipStream_t);
 void launch_gsum_block(const Plan&, const Workspace&, const float* grad, int B, hipStream_t);
+hipError_t calibrate(void* buf, size_t bytes, hipStream_t, double* copy_bytes_per_s,
+                     double* mfma_flops_per_s);
 
 static const char* const kSlotNames[kSlotCount] = {
     "sort_hist", "sort_scan", "sort_scatter", "seg_count", "seg_write",  "group",
@@ -150,8 +152,10 @@ constexpr int kSets = 4;
 constexpr int kSideStreams = 2;
 
 // Walks the workspace layout; with base == nullptr only the size is computed.  The index arrays
-// exist kSets times; the arithmetic buffers are shared.
-static size_t carve(const Plan& pl, char* base, Workspace* ws /* [kSets] or nullptr */) {
+// exist `sets` times (ws[sets..kSets) repeat set 0); the arithmetic buffers are shared.  With
+// lookup_only the buffers that only the backward pass uses are left out (their pointers are null).
+static size_t carve(const Plan& pl, char* base, Workspace* ws /* [kSets] or nullptr */,
+                    int sets = kSets, bool lookup_only = false) {
   size_t off = 0;
   auto take = [&](size_t bytes) -> char* {
     char* p = base ? base + off : nullptr;
@@ -161,7 +165,7 @@ static size_t carve(const Plan& pl, char* base, Workspace* ws /* [kSets] or null
   const Shape& s = pl.sh;
   const size_t mB = (size_t)pl.maxB, mQ = (size_t)pl.maxQ;
   Workspace set[kSets];
-  for (int i = 0; i < kSets; ++i) {
+  for (int i = 0; i < sets; ++i) {
     Workspace& w = set[i];
     w.ctr = (Counters*)take(sizeof(Counters));
     for (int k = 0; k < 2; ++k) w.key[k] = (uint32_t*)take(mB * 4);
@@ -200,18 +204,17 @@ static size_t carve(const Plan& pl, char* base, Workspace* ws /* [kSets] or null
   }
   Workspace& w = set[0];
   w.P = (float*)take(mQ * s.PN * 4);
-  w.gsum = (float*)take(mB * s.D * 4);
-  w.carry = (float*)take((size_t)pl.tilesMax * 2 * s.D * 4);
-  w.dPsum = (float*)take(mQ * s.PN * 4);
-  w.dg1part = (float*)take(mQ * s.S1 * 4);
-  w.part3 = (float*)take((size_t)pl.maxChunk3 * s.S3 * 4);
-  w.part2 = (float*)take((size_t)pl.maxChunk2 * s.S2 * 4);
-#ifdef TT_EMB_TRACE
-  w.trace = (unsigned long long*)take((size_t)(1u << 17) * 8 * 8);
-#else
-  w.trace = nullptr;
-#endif
-  for (int i = 1; i < kSets; ++i) {
+  w.gsum = w.carry = w.dPsum = w.dg1part = w.part3 = w.part2 = nullptr;
+  if (!lookup_only) {
+    w.gsum = (float*)take(mB * s.D * 4);
+    w.carry = (float*)take((size_t)pl.tilesMax * 2 * s.D * 4);
+    w.dPsum = (float*)take(mQ * s.PN * 4);
+    w.dg1part = (float*)take(mQ * s.S1 * 4);
+    w.part3 = (float*)take((size_t)pl.maxChunk3 * s.S3 * 4);
+    w.part2 = (float*)take((size_t)pl.maxChunk2 * s.S2 * 4);
+  }
+  for (int i = sets; i < kSets; ++i) set[i] = set[0];
+  for (int i = 1; i < sets; ++i) {
     set[i].P = w.P;
     set[i].gsum = w.gsum;
     set[i].carry = w.carry;
@@ -219,7 +222,6 @@ static size_t carve(const Plan& pl, char* base, Workspace* ws /* [kSets] or null
     set[i].dg1part = w.dg1part;
     set[i].part3 = w.part3;
     set[i].part2 = w.part2;
-    set[i].trace = w.trace;
   }
   if (ws)
     for (int i = 0; i < kSets; ++i) ws[i] = set[i];
@@ -324,32 +326,11 @@ static int drain_events(tt_emb* h) {
   return rc;
 }
 
-extern "C" {
-
-int tt_emb_workspace_bytes(const tt_emb_config* cfg, size_t* bytes) {
-  Plan pl;
-  int rc = make_plan(cfg, &pl);
-  if (rc != TT_EMB_OK) return rc;
-  if (bytes == nullptr) return TT_EMB_EINVAL;
-  *bytes = carve(pl, nullptr, nullptr);
-  return TT_EMB_OK;
-}
-
-int tt_emb_create(tt_emb_t* out, const tt_emb_config* cfg, float* g1, float* g2, float* g3,
-                  void* workspace, size_t workspace_bytes) {
-  if (out == nullptr || g1 == nullptr || g2 == nullptr || g3 == nullptr || workspace == nullptr)
-    return TT_EMB_EINVAL;
-  Plan pl;
-  int rc = make_plan(cfg, &pl);
-  if (rc != TT_EMB_OK) return rc;
-  if (((uintptr_t)workspace & 255u) != 0) return TT_EMB_EINVAL;
-  if ((((uintptr_t)g1 | (uintptr_t)g2 | (uintptr_t)g3) & 15u) != 0) return TT_EMB_EINVAL;
-  if (workspace_bytes < carve(pl, nullptr, nullptr)) return TT_EMB_ENOSPC;
-  tt_emb* h = new (std::nothrow) tt_emb();
-  if (h == nullptr) return TT_EMB_EINVAL;
+// Host-side state of a fresh handle (no workspace yet).
+static void init_handle(tt_emb* h, const tt_emb_config* cfg, const Plan& pl, float* g1, float* g2,
+                        float* g3) {
   h->cfg = *cfg;
   h->plan = pl;
-  carve(pl, (char*)workspace, h->ws);
   h->cur = 0;
   for (int i = 0; i < kSets; ++i) h->side[i] = nullptr;
   h->ev_fork = nullptr;
@@ -375,12 +356,77 @@ int tt_emb_create(tt_emb_t* out, const tt_emb_config* cfg, float* g1, float* g2,
   h->mfma = mfma_shape(pl.sh) && !(cfg->flags & TT_EMB_FLAG_GENERIC_KERNELS);
   std::memset(h->prof_launches, 0, sizeof(h->prof_launches));
   std::memset(h->prof_ms, 0, sizeof(h->prof_ms));
-#ifdef TT_EMB_TRACE
-  (void)hipMemset(h->ws[0].trace, 0, (size_t)(1u << 17) * 64);
-  for (int i = 0; i < kSets; ++i)
-    (void)hipMemcpy(&h->ws[i].ctr->trace, &h->ws[i].trace, sizeof(void*), hipMemcpyHostToDevice);
-#endif
+}
+
+extern "C" {
+
+int tt_emb_workspace_bytes(const tt_emb_config* cfg, size_t* bytes) {
+  Plan pl;
+  int rc = make_plan(cfg, &pl);
+  if (rc != TT_EMB_OK) return rc;
+  if (bytes == nullptr) return TT_EMB_EINVAL;
+  *bytes = carve(pl, nullptr, nullptr);
+  return TT_EMB_OK;
+}
+
+int tt_emb_create(tt_emb_t* out, const tt_emb_config* cfg, float* g1, float* g2, float* g3,
+                  void* workspace, size_t workspace_bytes) {
+  if (out == nullptr || g1 == nullptr || g2 == nullptr || g3 == nullptr || workspace == nullptr)
+    return TT_EMB_EINVAL;
+  Plan pl;
+  int rc = make_plan(cfg, &pl);
+  if (rc != TT_EMB_OK) return rc;
+  if (((uintptr_t)workspace & 255u) != 0) return TT_EMB_EINVAL;
+  if ((((uintptr_t)g1 | (uintptr_t)g2 | (uintptr_t)g3) & 15u) != 0) return TT_EMB_EINVAL;
+  if (workspace_bytes < carve(pl, nullptr, nullptr)) return TT_EMB_ENOSPC;
+  tt_emb* h = new (std::nothrow) tt_emb();
+  if (h == nullptr) return TT_EMB_EINVAL;
+  init_handle(h, cfg, pl, g1, g2, g3);
+  carve(pl, (char*)workspace, h->ws);
   *out = h;
+  return TT_EMB_OK;
+}
+
+// True while st is being captured into a graph.
+static bool stream_is_capturing(hipStream_t st) {
+  hipStreamCaptureStatus cap = hipStreamCaptureStatusNone;
+  if (hipStreamIsCapturing(st, &cap) != hipSuccess) {
+    (void)hipGetLastError();
+    return false;
+  }
+  return cap != hipStreamCaptureStatusNone;
+}
+
+// Streams and events of tt_emb_prepare, created on its first call: all of them or none (a failure
+// half way leaves the handle as it was).
+static int setup_side_streams(tt_emb* h) {
+  hipStream_t side[kSideStreams] = {};
+  hipEvent_t ready[kSets] = {}, done[kSets] = {}, fork = nullptr;
+  hipError_t e = hipSuccess;
+  for (int i = 0; i < kSideStreams && e == hipSuccess; ++i)
+    e = hipStreamCreateWithFlags(&side[i], hipStreamNonBlocking);
+  for (int i = 0; i < kSets && e == hipSuccess; ++i) {
+    e = hipEventCreateWithFlags(&ready[i], hipEventDisableTiming);
+    // the extended launch of the update kernel records kernel times into this one
+    if (e == hipSuccess) e = hipEventCreate(&done[i]);
+  }
+  if (e == hipSuccess) e = hipEventCreateWithFlags(&fork, hipEventDisableTiming);
+  if (e != hipSuccess) {
+    for (int i = 0; i < kSideStreams; ++i)
+      if (side[i] != nullptr) (void)hipStreamDestroy(side[i]);
+    for (int i = 0; i < kSets; ++i) {
+      if (ready[i] != nullptr) (void)hipEventDestroy(ready[i]);
+      if (done[i] != nullptr) (void)hipEventDestroy(done[i]);
+    }
+    if (fork != nullptr) (void)hipEventDestroy(fork);
+    return hip_fail(e);
+  }
+  for (int i = 0; i < kSets; ++i) {
+    h->side[i] = side[i % kSideStreams];
+    h->prep[i].ready = ready[i];
+    h->done[i] = done[i];
+  }
+  h->ev_fork = fork;
   return TT_EMB_OK;
 }
 
@@ -413,21 +459,10 @@ int tt_emb_prepare(tt_emb_t h, const int64_t* ids, int64_t B64, void* hip_stream
   if (ids == nullptr || ((uintptr_t)ids & 7u) != 0) return TT_EMB_EINVAL;
   hipStream_t st = (hipStream_t)hip_stream;
   hipError_t e;
+  if (stream_is_capturing(st)) return TT_EMB_ESTATE;  // side streams cannot join a capture
   if (h->side[0] == nullptr) {
-    for (int i = 0; i < kSets; ++i) {
-      if (i < kSideStreams) {
-        e = hipStreamCreateWithFlags(&h->side[i], hipStreamNonBlocking);
-        if (e != hipSuccess) return hip_fail(e);
-      } else {
-        h->side[i] = h->side[i % kSideStreams];
-      }
-      e = hipEventCreateWithFlags(&h->prep[i].ready, hipEventDisableTiming);
-      if (e != hipSuccess) return hip_fail(e);
-      e = hipEventCreate(&h->done[i]);  // the extended launch records kernel times into it
-      if (e != hipSuccess) return hip_fail(e);
-    }
-    e = hipEventCreateWithFlags(&h->ev_fork, hipEventDisableTiming);
-    if (e != hipSuccess) return hip_fail(e);
+    int rc0 = setup_side_streams(h);
+    if (rc0) return rc0;
   }
   // Pick the index set to fill.  A set is free when no backward_update still has to be enqueued for
   // it (that is only `cur`, between a forward and its backward) and no prepared batch waits in it.
@@ -491,8 +526,14 @@ static int forward_impl(tt_emb* h, const IdSource& src, int64_t B64, float* out,
     h->have_forward = false;
     return TT_EMB_OK;
   }
-  if (out == nullptr || ((uintptr_t)out & 15u) != 0) return TT_EMB_EINVAL;
+  // the matrix-core kernels store rows with 8- and 16-byte accesses; the any-shape kernels store
+  // float by float
+  if (out == nullptr || ((uintptr_t)out & (h->mfma ? 15u : 3u)) != 0) return TT_EMB_EINVAL;
   const Plan& pl = h->plan;
+  // A handle that has used tt_emb_prepare orders its index sets through events on streams of its
+  // own, which a capture cannot contain: such a handle is not captured (use a second handle).
+  const bool capturing = stream_is_capturing(st);
+  if (capturing && h->side[0] != nullptr) return TT_EMB_ESTATE;
   const int B = (int)(B64 * pl.split);  // items of the index pipeline, rows of D/split floats
   h->pending_B = -1;
   int rc;
@@ -505,11 +546,8 @@ static int forward_impl(tt_emb* h, const IdSource& src, int64_t B64, float* out,
   if (found >= 0) {
     // A pipeline that has already finished needs no wait on the caller's stream (its kernels
     // have completed, their results are visible to every later launch); one that has not is
-    // awaited on the device.  No event may be queried while the stream is being captured.
-    bool finished = false;
-    hipStreamCaptureStatus cap = hipStreamCaptureStatusNone;
-    if (hipStreamIsCapturing(st, &cap) == hipSuccess && cap == hipStreamCaptureStatusNone)
-      finished = hipEventQuery(h->prep[found].ready) == hipSuccess;
+    // awaited on the device.
+    const bool finished = hipEventQuery(h->prep[found].ready) == hipSuccess;
     (void)hipGetLastError();  // "not ready" is an answer, not an error
     hipError_t e = finished ? hipSuccess : hipStreamWaitEvent(st, h->prep[found].ready, 0);
     if (e != hipSuccess) return hip_fail(e);
@@ -579,8 +617,11 @@ int tt_emb_forward_eval(tt_emb_t h, const int64_t* ids, int64_t B64, float* out,
 int tt_emb_materialize(tt_emb_t h, int64_t first_row, int64_t count, float* out, void* hip_stream) {
   if (h == nullptr || first_row < 0 || count < 0) return TT_EMB_EINVAL;
   if (first_row + count > h->plan.user_N) return TT_EMB_EINVAL;
-  if (count > 0 && out == nullptr) return TT_EMB_EINVAL;
+  if (count > 0 && (out == nullptr || ((uintptr_t)out & (h->mfma ? 15u : 3u)) != 0))
+    return TT_EMB_EINVAL;
   if (h->pending_B >= 0) return TT_EMB_ESTATE;  // would overwrite what the pending backward needs
+  // (every piece starts a multiple of max_batch rows into out: the matrix-core shapes have rows of
+  // a multiple of 16 bytes, so the pieces are aligned like out itself)
   const int64_t D = h->plan.user_D;
   for (int64_t off = 0; off < count; off += h->plan.user_maxB) {
     const int64_t nb = std::min<int64_t>(h->plan.user_maxB, count - off);
@@ -653,10 +694,13 @@ int tt_emb_backward_update(tt_emb_t h, const float* grad_out, float lr, void* hi
   if (h == nullptr) return TT_EMB_EINVAL;
   if (h->pending_B < 0) return TT_EMB_ESTATE;
   const int B = (int)h->pending_B;
+  // arguments are checked before any state changes: a rejected call leaves the forward pending
+  if (B > 0 && (grad_out == nullptr || ((uintptr_t)grad_out & (h->mfma ? 15u : 3u)) != 0))
+    return TT_EMB_EINVAL;
+  hipStream_t st = (hipStream_t)hip_stream;
+  if (B > 0 && h->side[0] != nullptr && stream_is_capturing(st)) return TT_EMB_ESTATE;
   h->pending_B = -1;
   if (B == 0) return TT_EMB_OK;
-  if (grad_out == nullptr || ((uintptr_t)grad_out & 15u) != 0) return TT_EMB_EINVAL;
-  hipStream_t st = (hipStream_t)hip_stream;
   const Plan& pl = h->plan;
   const Workspace& ws = h->ws[h->cur];
   int rc;
@@ -695,23 +739,20 @@ int tt_emb_backward_update(tt_emb_t h, const float* grad_out, float lr, void* hi
   }
   // The update kernel is the last reader of the index set.  Outside stream capture and profiling
   // its completion signal doubles as the set's "done" event.
+  // (a handle with side streams is never captured, see forward_impl)
   hipEvent_t stop = nullptr;
-  if (h->done[h->cur] != nullptr && (h->cfg.flags & TT_EMB_FLAG_IDS_READY) && !h->profiling) {
-    hipStreamCaptureStatus cap = hipStreamCaptureStatusNone;
-    if (hipStreamIsCapturing(st, &cap) == hipSuccess && cap == hipStreamCaptureStatusNone)
-      stop = h->done[h->cur];
-    else
-      (void)hipGetLastError();
-  }
+  if (h->done[h->cur] != nullptr && (h->cfg.flags & TT_EMB_FLAG_IDS_READY) && !h->profiling)
+    stop = h->done[h->cur];
   if (h->ada.kind == kUpdateAdam) {
     // bias corrections of step t = 1, 2, ... (every backward_update with a batch counts)
-    const double t = (double)++h->adam_step;
+    const double t = (double)(h->adam_step + 1);
     h->ada.corr1 = (float)(1.0 / (1.0 - std::pow((double)h->ada.beta1, t)));
     h->ada.corr2 = (float)(1.0 / (1.0 - std::pow((double)h->ada.beta2, t)));
   }
   rc = run_slot(h, kSlotSgd, st,
                 [&] { launch_sgd(pl, ws, h->g1, h->g2, h->g3, lr, h->ada, stop, st); });
   if (rc) return rc;
+  if (h->ada.kind == kUpdateAdam) ++h->adam_step;  // the step counts once its update is enqueued
   if (h->profiling) rc = run_slot(h, kSlotEventPair, st, [] {});
   if (rc) return rc;
   for (int i = kSets - 1; i > 0; --i) h->recent[i] = h->recent[i - 1];
@@ -780,14 +821,16 @@ int tt_emb_profile_read(tt_emb_t h, int slot, const char** name, int64_t* launch
   return rc;
 }
 
-#ifdef TT_EMB_TRACE
-int tt_emb_debug_trace(tt_emb_t h, unsigned long long* dst, size_t n) {
-  (void)hipDeviceSynchronize();
-  int rc = (int)hipMemcpy(dst, h->ws[0].trace, n * 8, hipMemcpyDeviceToHost);
-  (void)hipMemset(h->ws[0].trace, 0, (size_t)(1u << 17) * 64);
-  return rc;
+
+int tt_emb_profile_peaks(void* device_buf, size_t bytes, void* hip_stream, double* copy_bytes_per_s,
+                         double* mfma_flops_per_s) {
+  if (device_buf == nullptr || copy_bytes_per_s == nullptr || mfma_flops_per_s == nullptr)
+    return TT_EMB_EINVAL;
+  if (((uintptr_t)device_buf & 255u) != 0 || bytes < ((size_t)4 << 20)) return TT_EMB_EINVAL;
+  const hipError_t e = calibrate(device_buf, bytes, (hipStream_t)hip_stream, copy_bytes_per_s,
+                                 mfma_flops_per_s);
+  return e == hipSuccess ? TT_EMB_OK : hip_fail(e);
 }
-#endif
 
 int tt_emb_destroy(tt_emb_t h) {
   if (h == nullptr) return TT_EMB_EINVAL;
@@ -812,7 +855,7 @@ const char* tt_emb_strerror(int code) {
     case TT_EMB_OK: return "ok";
     case TT_EMB_EINVAL: return "invalid argument (null pointer, non-positive or unsupported size)";
     case TT_EMB_ENOSPC: return "batch larger than max_batch, or workspace too small";
-    case TT_EMB_ESTATE: return "backward_update without a pending forward";
+    case TT_EMB_ESTATE: return "the handle's state does not allow this call (no pending forward, a pending forward, or a capture on a handle that has prepared)";
     case TT_EMB_EHIP: return g_hip_error.c_str();
     case TT_EMB_ERANGE: return "an id of the last batch was outside [0, N)";
     case TT_EMB_EINTERNAL: return "internal error: a kernel met an impossible index";

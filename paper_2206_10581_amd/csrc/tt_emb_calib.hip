@@ -1,0 +1,93 @@
+// Device calibration for benchmarks: what a plain streaming copy and a register-resident fp32
+// matrix-core loop reach on the device the handle lives on.  Roofline fractions can then be quoted
+// against measured peaks beside the nominal ones.  Not on the lookup path.
+#include <algorithm>
+
+#include "tt_emb_internal.h"
+
+namespace ttemb {
+
+typedef float f4c __attribute__((ext_vector_type(4)));
+typedef float f16c __attribute__((ext_vector_type(16)));
+
+// dst[i] = src[i] over n 16-byte words, grid-stride, four loads in flight per thread
+__global__ __launch_bounds__(256) void k_calib_copy(const f4c* __restrict__ src, f4c* __restrict__ dst,
+                                                   size_t n) {
+  const size_t stride = (size_t)gridDim.x * blockDim.x;
+  size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
+  for (; i + 3 * stride < n; i += 4 * stride) {
+    const f4c a = src[i], b = src[i + stride], c = src[i + 2 * stride], d = src[i + 3 * stride];
+    dst[i] = a;
+    dst[i + stride] = b;
+    dst[i + 2 * stride] = c;
+    dst[i + 3 * stride] = d;
+  }
+  for (; i < n; i += stride) dst[i] = src[i];
+}
+
+// iters rounds of four independent v_mfma_f32_32x32x2f32 chains per wavefront (operands in
+// registers, no memory traffic); one float per thread is stored so that nothing is optimised away
+__global__ __launch_bounds__(256) void k_calib_mfma(float* __restrict__ sink, int iters) {
+  const float a = 1.0f + (float)(threadIdx.x % 7) * 0.125f, b = 0.5f + (float)(threadIdx.x % 5) * 0.25f;
+  f16c acc[4];
+#pragma unroll
+  for (int k = 0; k < 4; ++k)
+#pragma unroll
+    for (int v = 0; v < 16; ++v) acc[k][v] = 0.f;
+  for (int it = 0; it < iters; ++it) {
+#pragma unroll
+    for (int k = 0; k < 4; ++k) acc[k] = __builtin_amdgcn_mfma_f32_32x32x2f32(a, b, acc[k], 0, 0, 0);
+  }
+  float s = 0.f;
+#pragma unroll
+  for (int k = 0; k < 4; ++k)
+#pragma unroll
+    for (int v = 0; v < 16; ++v) s += acc[k][v];
+  sink[(size_t)blockIdx.x * blockDim.x + threadIdx.x] = s;
+}
+
+// Best of `reps` timed launches each; returns a HIP error or hipSuccess.
+hipError_t calibrate(void* buf, size_t bytes, hipStream_t st, double* copy_bytes_per_s,
+                     double* mfma_flops_per_s) {
+  hipEvent_t a = nullptr, b = nullptr;
+  hipError_t e = hipEventCreate(&a);
+  if (e == hipSuccess) e = hipEventCreate(&b);
+  const int reps = 5;
+  double best_copy = 0.0, best_mfma = 0.0;
+  // copy: first half of the buffer to the second half
+  const size_t words = bytes / 32;  // 16-byte words per half
+  const int grid = 256 * 16;
+  for (int r = 0; r < reps && e == hipSuccess; ++r) {
+    e = hipEventRecord(a, st);
+    if (e != hipSuccess) break;
+    k_calib_copy<<<grid, 256, 0, st>>>((const f4c*)buf, (f4c*)buf + words, words);
+    e = hipGetLastError();
+    if (e == hipSuccess) e = hipEventRecord(b, st);
+    if (e == hipSuccess) e = hipEventSynchronize(b);
+    float ms = 0.f;
+    if (e == hipSuccess) e = hipEventElapsedTime(&ms, a, b);
+    if (e == hipSuccess && ms > 0.f)
+      best_copy = std::max(best_copy, 2.0 * (double)words * 16.0 / (ms * 1e-3));  // read + write
+  }
+  // matrix cores: 256 CUs x 8 blocks x 4 wavefronts, 4 chains x iters MFMAs of 32*32*2*2 flops
+  const int mgrid = 256 * 8, iters = 4096;
+  for (int r = 0; r < reps && e == hipSuccess; ++r) {
+    e = hipEventRecord(a, st);
+    if (e != hipSuccess) break;
+    k_calib_mfma<<<mgrid, 256, 0, st>>>((float*)buf, iters);
+    e = hipGetLastError();
+    if (e == hipSuccess) e = hipEventRecord(b, st);
+    if (e == hipSuccess) e = hipEventSynchronize(b);
+    float ms = 0.f;
+    if (e == hipSuccess) e = hipEventElapsedTime(&ms, a, b);
+    const double flops = (double)mgrid * 4 /*wavefronts*/ * 4 /*chains*/ * iters * (32.0 * 32 * 2 * 2);
+    if (e == hipSuccess && ms > 0.f) best_mfma = std::max(best_mfma, flops / (ms * 1e-3));
+  }
+  if (a) (void)hipEventDestroy(a);
+  if (b) (void)hipEventDestroy(b);
+  *copy_bytes_per_s = best_copy;
+  *mfma_flops_per_s = best_mfma;
+  return e;
+}
+
+}  // namespace ttemb

@@ -86,20 +86,7 @@ struct Counters {
   int nchunk2;  // partial-sum chunks over the by-i2 grouping of unique prefixes
   int err;      // nonzero: a kernel met an impossible index (bit mask of sites)
   int n_split;  // entries beyond the first of their id (U - n_split distinct ids)
-  unsigned long long* trace;  // debugging builds (TT_EMB_TRACE): per-wavefront time stamps
 };
-
-// Debugging aid, compiled in only with -DTT_EMB_TRACE: wavefront `gw` stores the 100 MHz wall clock
-// in slot 0..7 of its record.  tt_emb_debug_trace() copies the records to the host.
-#ifdef TT_EMB_TRACE
-#define TT_TRACE(ctr, gw, slot)                                                        \
-  do {                                                                                 \
-    if ((threadIdx.x % 64) == 0 && (size_t)(gw) < (1u << 17))                          \
-      (ctr)->trace[(size_t)(gw) * 8 + (slot)] = wall_clock64();                        \
-  } while (0)
-#else
-#define TT_TRACE(ctr, gw, slot) do { } while (0)
-#endif
 
 // All device arrays carved out of the caller's workspace.
 struct Workspace {
@@ -143,7 +130,6 @@ struct Workspace {
   float* dg1part;     // per prefix: its term of dG1[i1]      [maxQ][S1]
   float* part3;       // per chunk: partial dG3 slice         [maxChunk3][S3]
   float* part2;       // per chunk: partial dG2 slice         [maxChunk2][S2]
-  unsigned long long* trace;  // TT_EMB_TRACE builds only: 2^17 records of 8 stamps
 };
 
 struct Plan {

@@ -172,7 +172,6 @@ __global__ __launch_bounds__(kWave) void k_prefix_bwd_mfma(
   constexpr int W = 4 * R, PN = 16 * R, S1 = 4 * R, S2 = R * W;
   const int lane = threadIdx.x, half = lane / 32, l32 = lane % 32;
   const int unit = blockIdx.x;
-  TT_TRACE(ctr, unit, 0);
   constexpr int kPbUnits = pb_units(R);
   const int c = unit / kPbUnits, part = unit % kPbUnits;
   const int4 item = c2_item[(size_t)c * kChunk2 + lane % kChunk2];
@@ -183,11 +182,6 @@ __global__ __launch_bounds__(kWave) void k_prefix_bwd_mfma(
   const bool mine = lane < cnt;  // records past the chunk's count are unwritten
   const int myq = mine ? item.x : -1;
   const int myi1 = mine ? item.y : 0;
-#ifdef TT_EMB_TRACE
-  if (myq + myi1 == -12345) dg1part[0] = 0.f;
-  TT_TRACE(ctr, unit, 1);
-  if (lane == 0) ctr->trace[(size_t)unit * 8 + 6] = part + 1;
-#endif
   const float* Bm = g2 + (size_t)bin * S2;
 
   if (part < 2) {
@@ -209,10 +203,6 @@ __global__ __launch_bounds__(kWave) void k_prefix_bwd_mfma(
         bv[0][j] = brow[j];
       }
       TT_LOADS_DONE();
-#ifdef TT_EMB_TRACE
-      if (av[0][0].x + bv[0][7].w == 1.2345f) dg1part[0] = 0.f;
-      if (nt == 0) TT_TRACE(ctr, unit, 2);
-#endif
       f16v acc = TT_ZERO16;
 #pragma unroll
       for (int kb = 0; kb < KB; ++kb) {
@@ -264,10 +254,6 @@ __global__ __launch_bounds__(kWave) void k_prefix_bwd_mfma(
     for (int j = 0; j < 32; ++j)
       b[0][j] = dPsum[(size_t)(qh[j / 4] >= 0 ? qh[j / 4] : 0) * PN + (j % 4) * W + nt0 * 32 + l32];
     TT_LOADS_DONE();
-#ifdef TT_EMB_TRACE
-    if (a[0][0] + b[0][31] == 1.2345f) dg1part[0] = 0.f;
-    TT_TRACE(ctr, unit, 2);
-#endif
 #pragma unroll
     for (int mt = 0; mt < MT; ++mt) {
       const int m = mrow0 + mt * 32 + l32;
@@ -297,7 +283,6 @@ __global__ __launch_bounds__(kWave) void k_prefix_bwd_mfma(
       }
     }
   }
-  TT_TRACE(ctr, unit, 5);
 }
 
 // ---------------------------------------------------------------------------------------------
@@ -482,9 +467,6 @@ __global__ __launch_bounds__(mid_waves<R>() * kWave, 6) void k_bwd_mid_mfma(
   __shared__ int q_of[16], i1_of[16], u0_of[16], u1_of[16];
   constexpr int kMidWaves = mid_waves<R>(), kMidThreads = kMidWaves * kWave;
   const int tid = threadIdx.x, w = tid / kWave, lane = tid % kWave;
-  const int trace_id = blockIdx.x * kMidWaves + w;
-  (void)trace_id;
-  TT_TRACE(ctr, trace_id, 0);
   // Blocks past the by-i2 chunk range take the by-i3 chunks, one per wavefront, in the order of
   // the chunks' first prefixes.  Workgroups go to the eight XCDs round robin, so XCD x takes the
   // x-th eighth of that order and walks it front to back: the prefix products a chunk gathers
@@ -496,7 +478,6 @@ __global__ __launch_bounds__(mid_waves<R>() * kWave, 6) void k_bwd_mid_mfma(
     const int lo = (int)((long long)n * xcd / kXcds), hi = (int)((long long)n * (xcd + 1) / kXcds);
     for (int i = lo + rel / kXcds * kMidWaves + w; i < hi; i += per_xcd)
       dg3_chunk<R, D3, 4>(c3_order ? c3_order[i] : i, P, grad, gsum, c3_item, c3_desc, part3);
-    TT_TRACE(ctr, trace_id, 4);
     return;
   }
   // records, descriptor and chunk count are read together (the grid never exceeds the tables)
@@ -518,7 +499,6 @@ __global__ __launch_bounds__(mid_waves<R>() * kWave, 6) void k_bwd_mid_mfma(
     *(f4*)&Bl[((i * 4) / W) * TS + (i * 4) % W] = v;
   }
   __syncthreads();
-  TT_TRACE(ctr, trace_id, 1);
 
   const int l16 = lane % 16, kg = lane / 16;
   // rank 8: rows / columns 8..15 of the only 16-wide tile do not exist; such lanes read row 0 and
@@ -578,9 +558,7 @@ __global__ __launch_bounds__(mid_waves<R>() * kWave, 6) void k_bwd_mid_mfma(
         for (int v = 0; v < 4; ++v)
           if (rank_on) T[((2 * pw + x) * 4 + kg) * TS + v * R + nt * 16 + l16] = acc[x][nt][v];
   }
-  TT_TRACE(ctr, trace_id, 2);
   __syncthreads();
-  TT_TRACE(ctr, trace_id, 3);
 
   if (w < 4) {
     // (ii) tile rows 16w .. 16w+15 (prefixes 4w .. 4w+3) times Bm^T, 16 x 16 output tiles; lane
@@ -636,7 +614,6 @@ __global__ __launch_bounds__(mid_waves<R>() * kWave, 6) void k_bwd_mid_mfma(
       if (mrow < R) part2[(size_t)c * S2 + (size_t)mrow * W + n] = acc[v];
     }
   }
-  TT_TRACE(ctr, trace_id, 4);
 }
 
 // ---------------------------------------------------------------------------------------------

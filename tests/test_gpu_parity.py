@@ -806,3 +806,175 @@ def test_abi_error_codes():
     emb.close()
     rc, _ = lib.tt_emb_create(make_config(w.n, w.d, w.r, 100), 0, 0, 0, 0, 0)
     assert rc == TT_EMB_EINVAL
+
+
+# ----------------------------------------------------------------------------- more properties
+
+def _step_close(old, new_a, new_b, lr):
+    """The updates two runs applied to one core agree to STEP_TOL of the larger update."""
+    da = (old.astype(np.float64) - new_a) / lr
+    db = (old.astype(np.float64) - new_b) / lr
+    slack = 4 * np.finfo(np.float32).eps * np.abs(old).max() / lr
+    assert np.abs(da - db).max() <= STEP_TOL * np.abs(db).max() + slack
+
+
+def test_batch_permutation_invariance():
+    """Shuffling the batch (ids and gradient rows together) permutes the output rows and leaves the
+    update unchanged up to the order of the sums."""
+    w, cores, ids, grad = _workload(3, batch=50_000)
+    perm = np.random.default_rng(9).permutation(ids.size)
+    out_a, new_a, st_a = run_gpu(w.n, w.d, w.r, cores, ids, grad, w.lr)
+    out_b, new_b, st_b = run_gpu(w.n, w.d, w.r, cores, ids[perm], grad[perm], w.lr)
+    assert st_a == st_b
+    assert row_error(out_b, out_a[perm]) <= ROW_TOL
+    for k in range(3):
+        _step_close(cores[k], new_a[k], new_b[k], w.lr)
+
+
+def test_every_id_twice_with_halved_gradients():
+    """Every position of the batch doubled with half its gradient: the rows repeat, and the summed
+    gradient, hence the update, is the same (halving is exact in fp32)."""
+    w, cores, ids, grad = _workload(3, batch=40_000)
+    ids2 = np.concatenate([ids, ids])
+    grad2 = np.concatenate([grad * np.float32(0.5), grad * np.float32(0.5)])
+    out_a, new_a, st_a = run_gpu(w.n, w.d, w.r, cores, ids, grad, w.lr)
+    out_b, new_b, st_b = run_gpu(w.n, w.d, w.r, cores, ids2, grad2, w.lr)
+    assert (st_a["U"], st_a["Q"]) == (st_b["U"], st_b["Q"])
+    assert row_error(out_b[: ids.size], out_a) <= ROW_TOL
+    assert row_error(out_b[ids.size:], out_a) <= ROW_TOL
+    for k in range(3):
+        _step_close(cores[k], new_a[k], new_b[k], w.lr)
+
+
+# ----------------------------------------------------------------------------- sizes as quoted
+
+def test_products_shape_rank32_full_size():
+    """The paper's ogbn-products factorisation (Table "ogb-dim-tt": (125,140,140) x (4,5,5)) at the
+    rank and batch its step time is quoted at: rank 32, the 200,000-row Zipf batch."""
+    w, cores, ids, grad = _workload(7)
+    check_against_oracle(w.n, w.d, w.r, cores, ids, grad, w.lr)
+
+
+def test_rank128_through_the_slab_split_at_sweep_size():
+    """Rank 128 on the paper's ogbn-arxiv factorisation ((55,55,56) x (8,4,4): two slabs of d1 = 4),
+    50,000 uniform ids as in the rank sweep."""
+    n, d, r, B = (55, 55, 56), (8, 4, 4), (128, 128), 50_000
+    s = Shape(n, d, r)
+    rng = np.random.default_rng(128)
+    cores = tuple((rng.standard_normal(cs) / np.sqrt(128)).astype(np.float32) for cs in s.core_shapes())
+    ids = rng.integers(0, s.N, size=B, dtype=np.int64)
+    ids[:2000] = ids[0]
+    grad = rng.standard_normal((B, s.D)).astype(np.float32)
+    check_against_oracle(n, d, r, cores, ids, grad, 0.01)
+
+
+def test_prepare_then_capture_is_refused():
+    """A handle that has used tt_emb_prepare is not captured into a graph: its calls return
+    TT_EMB_ESTATE while the stream is being captured, the capture itself stays valid, and the handle
+    works as before afterwards."""
+    torch = _torch()
+    import paper_2206_10581_amd as lib
+    from paper_2206_10581_amd.binding import TT_EMB_ESTATE
+    w, cores, ids, grad = _workload(2, batch=5000)
+    s = Shape(w.n, w.d, w.r)
+    t_ids, t_grad = torch.from_numpy(ids).cuda(), torch.from_numpy(grad).cuda()
+    emb = lib.TTEmbedding(w.n, w.d, w.r, ids.size, cores)
+    out = torch.empty((ids.size, w.D), device="cuda")
+    emb.prepare(t_ids)
+    emb.forward(t_ids, out)
+    emb.backward_update(t_grad, w.lr)
+    torch.cuda.synchronize()
+    now = [c.cpu().numpy() for c in emb.cores]
+    dummy = torch.zeros(8, device="cuda")
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph):
+        st = int(torch.cuda.current_stream().cuda_stream)
+        rcs = (lib.tt_emb_prepare(emb.handle, t_ids.data_ptr(), ids.size, st),
+               lib.tt_emb_forward(emb.handle, t_ids.data_ptr(), ids.size, out.data_ptr(), st),
+               lib.tt_emb_forward_eval(emb.handle, t_ids.data_ptr(), ids.size, out.data_ptr(), st))
+        dummy.add_(1.0)
+    assert rcs == (TT_EMB_ESTATE,) * 3
+    graph.replay()
+    torch.cuda.synchronize()
+    assert float(dummy[0]) == 1.0
+    o = emb.forward(t_ids, out)                      # eager again: unchanged behaviour
+    emb.backward_update(t_grad, w.lr)
+    torch.cuda.synchronize()
+    assert row_error(o.cpu().numpy(), ora.forward(s, *now, ids)) <= ROW_TOL
+    ref = ora.backward_update(s, *now, ids, grad, w.lr)
+    for k in range(3):
+        assert core_error(emb.cores[k].cpu().numpy(), ref[k]) <= CORE_TOL
+    emb.close()
+
+
+def test_rejected_backward_keeps_the_forward_pending():
+    torch = _torch()
+    import paper_2206_10581_amd as lib
+    from paper_2206_10581_amd.binding import TT_EMB_EINVAL
+    w, cores, ids, grad = _workload(2, batch=3000)
+    s = Shape(w.n, w.d, w.r)
+    emb = lib.TTEmbedding(w.n, w.d, w.r, ids.size, cores)
+    emb.forward(torch.from_numpy(ids).cuda())
+    t_grad = torch.from_numpy(grad).cuda()
+    assert lib.tt_emb_backward_update(emb.handle, 0, w.lr, 0) == TT_EMB_EINVAL
+    assert lib.tt_emb_backward_update(emb.handle, t_grad.data_ptr() + 4, w.lr, 0) == TT_EMB_EINVAL
+    emb.backward_update(t_grad, w.lr)                # the forward is still pending
+    torch.cuda.synchronize()
+    ref = ora.backward_update(s, *cores, ids, grad, w.lr)
+    for k in range(3):
+        assert core_error(emb.cores[k].cpu().numpy(), ref[k]) <= CORE_TOL
+    emb.close()
+
+
+# ----------------------------------------------------------------------------- the loops bench.py times
+
+@pytest.mark.parametrize("loop", ["lookahead", "plain"])
+def test_benchmark_loops_at_config3_full_size(loop):
+    """bench.py's own loop functions at the benchmark's size and launch configuration: the
+    200,000-row Zipf batches of config 3, three different batches in rotating buffers, six steps
+    without any synchronisation between them.  "lookahead" is the headline loop: a handle with
+    TT_EMB_FLAG_IDS_READY, tt_emb_prepare two batches ahead on the library's own streams,
+    tt_emb_wait_backward(1) before every step.  Every step is checked element by element against
+    the oracle started from the cores the GPU itself had before that step (device-side snapshots
+    taken on the stream, no host wait), with the usual tolerances."""
+    torch = _torch()
+    import bench
+    from paper_2206_10581_amd import TTEmbedding
+    w = wl.CONFIGS[3]
+    s = Shape(w.n, w.d, w.r)
+    seeds, steps, lr = (3, 103, 203), 6, 2e-4
+    cores = wl.make_cores(w, 3)
+    ids_np = [wl.make_ids(w, sd) for sd in seeds]
+    grad_np = [wl.make_grads(w, sd) for sd in seeds]
+    ids = [torch.from_numpy(a).cuda() for a in ids_np]
+    grad = [torch.from_numpy(a).cuda() for a in grad_np]
+    out = [torch.empty((w.batch, w.D), device="cuda") for _ in seeds]
+    torch.cuda.synchronize()
+    emb = TTEmbedding(w.n, w.d, w.r, w.batch, cores, flags=4 if loop == "lookahead" else 0)
+    core_snaps = [[c.clone() for c in emb.cores]]
+    out_snaps = []
+
+    def after(k):
+        out_snaps.append(out[k % 3].clone())
+        core_snaps.append([c.clone() for c in emb.cores])
+
+    if loop == "lookahead":
+        bench.prime_lookahead(emb, ids)
+        bench.run_lookahead(emb, ids, grad, out, lr, steps, after_step=after)
+    else:
+        bench.run_plain(emb, ids, grad, out, lr, steps, after_step=after)
+    torch.cuda.synchronize()
+    emb.stats()                                              # raises on an internal-error flag
+    for k in range(steps):
+        before = [c.cpu().numpy() for c in core_snaps[k]]
+        after_k = [c.cpu().numpy() for c in core_snaps[k + 1]]
+        i, g = ids_np[k % 3], grad_np[k % 3]
+        assert row_error(out_snaps[k].cpu().numpy(), ora.forward(s, *before, i)) <= ROW_TOL, k
+        ref = ora.backward_update(s, *before, i, g, lr)
+        for c in range(3):
+            assert core_error(after_k[c], ref[c]) <= CORE_TOL, (k, c)
+            step_gpu = (before[c].astype(np.float64) - after_k[c]) / lr
+            step_ref = (before[c].astype(np.float64) - ref[c]) / lr
+            slack = 2 * np.finfo(np.float32).eps * np.abs(before[c]).max() / lr
+            assert np.abs(step_gpu - step_ref).max() <= STEP_TOL * np.abs(step_ref).max() + slack, (k, c)
+    emb.close()

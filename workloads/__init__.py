@@ -150,7 +150,8 @@ def make_orthogonal_cores(n, d, r, seed: int):
             raise ValueError(f"core {i + 1}: {cols} orthogonal vectors of length {rows} do not exist")
         q, _ = np.linalg.qr(rng.standard_normal((rows, cols)))     # columns: orthonormal vectors v
         v = q.T.reshape(ranks[i], int(d[i]), int(n[i]), ranks[i + 1])  # v[r, j, i_k, s]
-        # paper: G_i(r, :, j, :) = reshape(v_{n_i r + j}, [m_i, R_i]);  ours: g[i_k][r][j][s]
+        # layout per Algorithm 2 (Section 4.1): vector number n_i*r + j fills the (r, j) fibre of
+        # core i over (node index, outgoing rank); stored here as g[i_k][r][j][s]
         cores.append(np.ascontiguousarray(np.transpose(v, (2, 0, 1, 3))).astype(np.float32))
     g1 = cores[0].reshape(int(n[0]), int(d[0]), ranks[1])
     g2 = cores[1]
