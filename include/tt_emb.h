@@ -124,6 +124,32 @@ int tt_emb_forward(tt_emb_t h, const int64_t* ids, int64_t B, float* out, void* 
 int tt_emb_forward_eval(tt_emb_t h, const int64_t* ids, int64_t B, float* out, void* hip_stream);
 
 /*
+ * Lookup for callers that cannot allocate device memory or keep a workspace: code under HIP graph
+ * capture, tight serving loops, harnesses that forbid hipMalloc.  Computes what tt_emb_forward_eval
+ * computes (same kernels, bit-identical rows) without a handle and without a caller workspace: the
+ * index structures and prefix products of the batch go to a 64 MiB device array that is part of
+ * the library's code object (every GPU the library runs on holds its own copy until the process
+ * ends).  Nothing is allocated or freed, on the device or through any library, by this call.
+ *   cfg      shape, ranks and flags as for tt_emb_create (no re-indexing table, no slab-split
+ *            restrictions beyond those of tt_emb_config); cfg->device must be the current device;
+ *            cfg->max_batch only bounds B
+ *   g1..g3   device, the cores (read only)          ids   device int64[B]
+ *   out      device fp32[B][D]                      B     0 <= B <= cfg->max_batch
+ * The scratch need grows with the batch: about 100 bytes per id plus 4*d1*d2*r2 bytes per distinct
+ * (i1,i2) prefix the batch could hold (min(B, n1*n2) of them) plus tables of a few n2, n3 words;
+ * a batch that needs more than 64 MiB returns TT_EMB_ENOSPC (a 136 x 136 x 136 table at rank 32
+ * has 18,496 prefixes of 2 KiB and fits batches of up to about 250,000 ids; a 480 x 480 x 482
+ * table at rank 16 can meet a new 1 KiB prefix with every id and fits about 55,000).  TT_EMB_EINVAL for null or misaligned pointers, a bad configuration, or a current
+ * device other than cfg->device.  The first call on a device looks the array's address up
+ * (hipGetSymbolAddress); make that call outside graph capture - a call with B = 0 does only that.
+ * All calls on one GPU share the one array, which keeps the last call's contents (every kernel
+ * clears what it needs cleared): calls that overlap on one GPU - two streams, two threads - race
+ * and must be serialised by the caller; calls on one stream are ordered by the stream.
+ */
+int tt_emb_lookup_static(const tt_emb_config* cfg, const float* g1, const float* g2, const float* g3,
+                         const int64_t* ids, int64_t B, float* out, void* hip_stream);
+
+/*
  * Writes the rows first_row .. first_row+count-1 of the table W itself (Section 3, Eq. "tt-matrix":
  * the dense matrix the cores stand for) to out, device fp32[count][D]; count may exceed max_batch
  * (the rows are produced max_batch at a time).  Row numbers are table rows: a re-indexing table is

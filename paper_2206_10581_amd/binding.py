@@ -53,6 +53,8 @@ def load_library():
     lib.tt_emb_backward_update.argtypes = [c_void_p, c_void_p, c_float, c_void_p]
     lib.tt_emb_forward_eval.argtypes = [c_void_p, c_void_p, c_int64, c_void_p, c_void_p]
     lib.tt_emb_materialize.argtypes = [c_void_p, c_int64, c_int64, c_void_p, c_void_p]
+    lib.tt_emb_lookup_static.argtypes = [cfgp, c_void_p, c_void_p, c_void_p, c_void_p, c_int64,
+                                         c_void_p, c_void_p]
     lib.tt_emb_set_reindex.argtypes = [c_void_p, c_void_p, c_int64]
     lib.tt_emb_set_adagrad.argtypes = [c_void_p, c_void_p, c_void_p, c_void_p, c_float]
     lib.tt_emb_wait_backward.argtypes = [c_void_p, c_int]
@@ -69,7 +71,7 @@ def load_library():
     lib.tt_emb_strerror.argtypes = [c_int]
     lib.tt_emb_strerror.restype = c_char_p
     for name in ("tt_emb_workspace_bytes", "tt_emb_create", "tt_emb_forward", "tt_emb_prepare",
-                 "tt_emb_backward_update", "tt_emb_forward_eval", "tt_emb_materialize",
+                 "tt_emb_backward_update", "tt_emb_forward_eval", "tt_emb_materialize", "tt_emb_lookup_static",
                  "tt_emb_set_reindex", "tt_emb_set_adagrad", "tt_emb_set_adam", "tt_emb_wait_backward", "tt_emb_get_stats", "tt_emb_profile_enable",
                  "tt_emb_profile_slots", "tt_emb_profile_read", "tt_emb_profile_peaks", "tt_emb_destroy"):
         getattr(lib, name).restype = c_int
@@ -119,6 +121,13 @@ def tt_emb_forward_eval(h, ids_ptr: int, B: int, out_ptr: int, stream: int) -> i
 def tt_emb_materialize(h, first_row: int, count: int, out_ptr: int, stream: int) -> int:
     return load_library().tt_emb_materialize(h, c_int64(first_row), c_int64(count),
                                              c_void_p(out_ptr), c_void_p(stream))
+
+
+def tt_emb_lookup_static(cfg: TTEmbConfig, g1_ptr: int, g2_ptr: int, g3_ptr: int, ids_ptr: int, B: int,
+                         out_ptr: int, stream: int) -> int:
+    return load_library().tt_emb_lookup_static(byref(cfg), c_void_p(g1_ptr), c_void_p(g2_ptr),
+                                               c_void_p(g3_ptr), c_void_p(ids_ptr), c_int64(B),
+                                               c_void_p(out_ptr), c_void_p(stream))
 
 
 def tt_emb_set_reindex(h, table_ptr: int, n_ids: int) -> int:

@@ -3,6 +3,7 @@
 #include <cmath>
 #include <cstdio>
 #include <cstring>
+#include <mutex>
 #include <new>
 #include <string>
 #include <vector>
@@ -630,6 +631,54 @@ int tt_emb_materialize(tt_emb_t h, int64_t first_row, int64_t count, float* out,
     if (rc) return rc;
   }
   return TT_EMB_OK;
+}
+
+// ---------------------------------------------------------------------------------------------
+// Lookup for callers that cannot allocate: the workspace of the lookup-only forward (one index set
+// and the prefix products) lives in a file-scope device array instead of a caller's buffer.
+constexpr size_t kStaticScratchBytes = (size_t)64 << 20;
+static __device__ __align__(256) unsigned char scratch[kStaticScratchBytes];
+constexpr int kStaticMaxDevices = 64;
+// device address of `scratch` on each device, looked up once per device (every device holds its
+// own copy of the array at its own address; the host-side name is never passed to a kernel)
+static void* g_scratch_ptr[kStaticMaxDevices];
+static std::mutex g_scratch_mutex;
+
+int tt_emb_lookup_static(const tt_emb_config* cfg, const float* g1, const float* g2,
+                         const float* g3, const int64_t* ids, int64_t B64, float* out,
+                         void* hip_stream) {
+  if (cfg == nullptr || g1 == nullptr || g2 == nullptr || g3 == nullptr || B64 < 0)
+    return TT_EMB_EINVAL;
+  if ((((uintptr_t)g1 | (uintptr_t)g2 | (uintptr_t)g3) & 15u) != 0) return TT_EMB_EINVAL;
+  if (B64 > cfg->max_batch) return TT_EMB_ENOSPC;
+  if (B64 > 0 && (ids == nullptr || ((uintptr_t)ids & 7u) != 0)) return TT_EMB_EINVAL;
+  // the plan, and with it the scratch need, is made for this batch, not for max_batch
+  tt_emb_config c = *cfg;
+  c.max_batch = B64 > 0 ? B64 : 1;
+  Plan pl;
+  int rc = make_plan(&c, &pl);
+  if (rc != TT_EMB_OK) return rc;
+  if (carve(pl, nullptr, nullptr, 1, true) > kStaticScratchBytes) return TT_EMB_ENOSPC;
+  int dev = -1;
+  hipError_t e = hipGetDevice(&dev);
+  if (e != hipSuccess) return hip_fail(e);
+  if (dev != cfg->device || dev < 0 || dev >= kStaticMaxDevices) return TT_EMB_EINVAL;
+  void* base = nullptr;
+  {
+    std::lock_guard<std::mutex> lock(g_scratch_mutex);
+    if (g_scratch_ptr[dev] == nullptr) {
+      void* ptr = nullptr;
+      e = hipGetSymbolAddress(&ptr, HIP_SYMBOL(scratch));
+      if (e != hipSuccess || ptr == nullptr) return hip_fail(e != hipSuccess ? e : hipErrorInvalidSymbol);
+      g_scratch_ptr[dev] = ptr;
+    }
+    base = g_scratch_ptr[dev];
+  }
+  if (B64 == 0) return TT_EMB_OK;
+  tt_emb h;  // host bookkeeping only, lives for this call
+  init_handle(&h, &c, pl, const_cast<float*>(g1), const_cast<float*>(g2), const_cast<float*>(g3));
+  carve(pl, (char*)base, h.ws, 1, true);
+  return forward_impl(&h, id_source(&h, ids, 0, true), B64, out, (hipStream_t)hip_stream, false);
 }
 
 int tt_emb_set_adagrad(tt_emb_t h, float* s1, float* s2, float* s3, float eps) {
