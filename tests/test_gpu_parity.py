@@ -978,3 +978,19 @@ def test_benchmark_loops_at_config3_full_size(loop):
             slack = 2 * np.finfo(np.float32).eps * np.abs(before[c]).max() / lr
             assert np.abs(step_gpu - step_ref).max() <= STEP_TOL * np.abs(step_ref).max() + slack, (k, c)
     emb.close()
+
+
+def test_ttsvd_initialisation_on_the_gpu():
+    """Algorithm 1 of the paper (TT-SVD initialisation) at full ranks reproduces the matrix it
+    decomposes; the HIP forward over every id gives that matrix back (no oracle involved), on an
+    any-shape table and on a matrix-core shape."""
+    torch = _torch()
+    from paper_2206_10581_amd import TTEmbedding
+    for n, d, r in [((6, 5, 7), (2, 2, 3), (12, 21)), ((4, 5, 4), (4, 4, 4), (16, 16))]:
+        s = Shape(n, d, r)
+        cores, info = wl.make_ttsvd_cores(n, d, r, seed=17, return_info=True)
+        emb = TTEmbedding(n, d, r, s.N, cores)
+        W = emb.forward(torch.arange(s.N, dtype=torch.int64, device="cuda")).double().cpu().numpy()
+        emb.close()
+        np.testing.assert_allclose(W, info["matrix"], atol=2e-5)
+        np.testing.assert_allclose(W.T @ W, np.eye(s.D), atol=1e-4)

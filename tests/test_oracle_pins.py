@@ -21,6 +21,7 @@ import pytest
 
 from oracle import tt_oracle as ora
 from oracle.tt_oracle import Shape
+import workloads as wl
 
 GOLDEN = os.path.join(os.path.dirname(__file__), "golden")
 
@@ -474,3 +475,36 @@ def test_eps_sits_outside_the_square_root():
         for got in (Ga, Gm):
             np.testing.assert_allclose((G.astype(np.float64) - got)[moved], want[moved], rtol=2e-5,
                                        atol=2e-7)
+
+
+def test_ttsvd_initialisation_reproduces_its_matrix():
+    """Algorithm 1 of the paper (TT-SVD of a matrix into the TT-matrix format).  With ranks as large
+    as the unfoldings' ranks the decomposition is exact, so the oracle's forward over every id must
+    give back the matrix that was decomposed - for the default input, a random matrix with
+    orthonormal columns, that is W^T W = I, the property the paper wants from this initialisation.
+    With smaller ranks the result is an approximation whose Frobenius error TT-SVD bounds by the
+    discarded singular values (the root of their summed squares over both steps)."""
+    n, d = (6, 5, 7), (2, 2, 3)
+    N = 6 * 5 * 7
+    # ranks of the unfoldings: at most n1*d1 = 12 rows in the first, at most n3*d3 = 21 columns in
+    # the second
+    cores, info = wl.make_ttsvd_cores(n, d, (12, 21), seed=8, return_info=True)
+    s = Shape(n, d, (12, 21))
+    for g, cs in zip(cores, s.core_shapes()):
+        assert g.shape == cs and g.dtype == np.float32
+    assert all(t.size == 0 or np.abs(t).max() < 1e-12 for t in info["dropped"])
+    W = ora.forward_f64(s, *cores, np.arange(N, dtype=np.int64))
+    np.testing.assert_allclose(W, info["matrix"], atol=5e-6)
+    np.testing.assert_allclose(W.T @ W, np.eye(s.D), atol=2e-5)
+    # an arbitrary matrix, truncated ranks: the error bound of the decomposition
+    rng = np.random.default_rng(80)
+    A = rng.standard_normal((N, 12))
+    cores, info = wl.make_ttsvd_cores(n, d, (5, 6), seed=0, matrix=A, return_info=True)
+    s = Shape(n, d, (5, 6))
+    W = ora.forward_f64(s, *cores, np.arange(N, dtype=np.int64))
+    err = np.linalg.norm(W - A)
+    bound = np.sqrt(sum(float((t * t).sum()) for t in info["dropped"]))
+    assert 0.05 * bound < err <= bound * (1 + 1e-5) + 1e-4
+    # the first core's unfolding has orthonormal columns (left singular vectors)
+    U1 = cores[0].reshape(6 * 2, 5).astype(np.float64)
+    np.testing.assert_allclose(U1.T @ U1, np.eye(5), atol=1e-5)

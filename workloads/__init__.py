@@ -157,3 +157,56 @@ def make_orthogonal_cores(n, d, r, seed: int):
     g2 = cores[1]
     g3 = cores[2].reshape(int(n[2]), ranks[2], int(d[2]))
     return g1, g2, g3
+
+
+def make_ttsvd_cores(n, d, r, seed: int, matrix: np.ndarray | None = None, return_info: bool = False):
+    """Cores from the paper's Algorithm 1 ("TTM Decomposition", Section 4.1): a TT-SVD of a given
+    N x D matrix - by default a random matrix with orthonormal columns, which is the initialisation
+    the paper calls decomp-ortho - in the TT-matrix format of Eq. "tt-matrix".  The matrix is viewed
+    as a tensor over (i1, i2, i3, j1, j2, j3), its modes are paired as (i1 j1), (i2 j2), (i3 j3), and
+    the cores are peeled off left to right: unfold with (incoming rank, i_k, j_k) as rows, take the
+    leading R_k left singular vectors as core k, carry diag(singular values) times the right
+    singular vectors on; what is left after the second step is the third core.  With ranks at
+    least the unfoldings' ranks the product of the cores reproduces the matrix exactly; otherwise
+    the Frobenius error is at most the root of the summed squares of the discarded singular values
+    of both steps.  Host-side SVDs of dense unfoldings: for small tables only (the paper reports
+    31 minutes for its largest one).  Returns fp32 cores in slice-contiguous layout
+    g1[n1,d1,r1], g2[n2,r1,d2,r2], g3[n3,r2,d3]; with return_info also a dict holding the matrix
+    and the discarded singular values.  This is input generation for tests; it is not on the lookup
+    path."""
+    n1, n2, n3 = (int(x) for x in n)
+    d1, d2, d3 = (int(x) for x in d)
+    r1, r2 = int(r[0]), int(r[1])
+    N, D = n1 * n2 * n3, d1 * d2 * d3
+    rng = np.random.default_rng(seed)
+    if matrix is None:
+        if D > N:
+            raise ValueError("a matrix with orthonormal columns needs at least as many rows as columns")
+        matrix, _ = np.linalg.qr(rng.standard_normal((N, D)))
+    W = np.asarray(matrix, dtype=np.float64)
+    if W.shape != (N, D):
+        raise ValueError(f"matrix shape {W.shape} != {(N, D)}")
+    Y = W.reshape(n1, n2, n3, d1, d2, d3).transpose(0, 3, 1, 4, 2, 5)      # (i1,j1,i2,j2,i3,j3)
+    dropped = []
+    # first core: rows (i1, j1)
+    U, S, Vt = np.linalg.svd(Y.reshape(n1 * d1, -1), full_matrices=False)
+    k1 = min(r1, S.size)
+    dropped.append(S[k1:].copy())
+    G1 = np.zeros((n1, d1, r1))
+    G1[:, :, :k1] = U[:, :k1].reshape(n1, d1, k1)
+    Y = np.zeros((r1, n2 * d2 * n3 * d3))
+    Y[:k1] = S[:k1, None] * Vt[:k1]
+    # second core: rows (incoming rank, i2, j2)
+    U, S, Vt = np.linalg.svd(Y.reshape(r1 * n2 * d2, n3 * d3), full_matrices=False)
+    k2 = min(r2, S.size)
+    dropped.append(S[k2:].copy())
+    G2 = np.zeros((r1, n2, d2, r2))
+    G2[..., :k2] = U[:, :k2].reshape(r1, n2, d2, k2)
+    G3 = np.zeros((r2, n3, d3))
+    G3[:k2] = (S[:k2, None] * Vt[:k2]).reshape(k2, n3, d3)
+    g1 = np.ascontiguousarray(G1, dtype=np.float32)
+    g2 = np.ascontiguousarray(G2.transpose(1, 0, 2, 3), dtype=np.float32)
+    g3 = np.ascontiguousarray(G3.transpose(1, 0, 2), dtype=np.float32)
+    if return_info:
+        return (g1, g2, g3), {"matrix": W, "dropped": dropped}
+    return g1, g2, g3
