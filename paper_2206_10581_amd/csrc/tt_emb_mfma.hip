@@ -464,7 +464,7 @@ __global__ __launch_bounds__(mid_waves<R>() * kWave, 6) void k_bwd_mid_mfma(
   constexpr int NT16 = (R + 15) / 16, KS = D3 / 4, UB = 4;
   __shared__ __align__(16) float T[64 * TS];
   __shared__ __align__(16) float Bl[R * TS];
-  __shared__ int q_of[16], i1_of[16];
+  __shared__ int q_of[16], i1_of[16], u0_of[16], u1_of[16];
   constexpr int kMidWaves = mid_waves<R>(), kMidThreads = kMidWaves * kWave;
   const int tid = threadIdx.x, w = tid / kWave, lane = tid % kWave;
   // Blocks past the by-i2 chunk range take the by-i3 chunks, one per wavefront, in the order of
@@ -487,26 +487,12 @@ __global__ __launch_bounds__(mid_waves<R>() * kWave, 6) void k_bwd_mid_mfma(
   if (c >= ctr->nchunk2) return;
   const int bin = desc.x, cnt = desc.z;
   const float* Bm = g2 + (size_t)bin * S2;
-  const bool item_on = tid % kChunk2 < cnt;  // records past the chunk's count are unwritten
   if (tid < 16) {
-    q_of[tid] = item_on ? item.x : -1;
-    i1_of[tid] = item_on ? item.y : 0;
-  }
-  // The records {gradient-row code, i3} of the ids of this wavefront's prefixes are fetched now,
-  // beside the G2 slice: lanes 0..31 hold the first 32 ids of the pair's first prefix, lanes 32..63
-  // those of its second (lanes 0..15 of every wavefront hold the chunk's sixteen prefix records).
-  constexpr int kPairs = 8 / kMidWaves;  // pairs of prefixes per wavefront
-  const int half = lane / 32, l32 = lane % 32;
-  int pu0[kPairs], pn[kPairs], idcode[kPairs], idi3[kPairs];
-#pragma unroll
-  for (int k = 0; k < kPairs; ++k) {
-    const int p = 2 * (w + k * kMidWaves) + half;  // local prefix of this lane's half
-    const int u0 = __shfl(item.z, p), u1 = __shfl(item.w, p);
-    pu0[k] = u0;
-    pn[k] = __shfl((int)item_on, p) ? u1 - u0 : 0;
-    const int uu = l32 < pn[k] ? u0 + l32 : 0;
-    idcode[k] = u_code[uu];
-    idi3[k] = u_i3[uu];
+    const bool on = tid < cnt;  // records past the chunk's count are unwritten
+    q_of[tid] = on ? item.x : -1;
+    i1_of[tid] = on ? item.y : 0;
+    u0_of[tid] = on ? item.z : 0;
+    u1_of[tid] = on ? item.w : 0;
   }
   for (int i = tid; i < R * W / 4; i += kMidThreads) {
     const f4 v = ((const f4*)Bm)[i];
@@ -520,51 +506,45 @@ __global__ __launch_bounds__(mid_waves<R>() * kWave, 6) void k_bwd_mid_mfma(
   const bool rank_on = R >= 16 || l16 < R;
   const int lrow = rank_on ? l16 : 0;
   // (i) this wavefront's pairs of prefixes (local numbers 2*pw, 2*pw+1)
-#pragma unroll
-  for (int k = 0; k < kPairs; ++k) {
-    const int pw = w + k * kMidWaves;
+  for (int pw = w; pw < 8; pw += kMidWaves) {
     f4 acc[2][NT16];
 #pragma unroll
     for (int x = 0; x < 2; ++x)
 #pragma unroll
       for (int nt = 0; nt < NT16; ++nt) acc[x][nt] = f4{0.f, 0.f, 0.f, 0.f};
-    const int na = lane_value(pn[k], 0), nb = lane_value(pn[k], 32);
+    const int u0a = u0_of[2 * pw], u0b = u0_of[2 * pw + 1];
+    const int na = u1_of[2 * pw] - u0a, nb = u1_of[2 * pw + 1] - u0b;
     const int rounds = (max(na, nb) + UB - 1) / UB;
-    int mycode = idcode[k], myi3 = idi3[k];
     for (int r = 0; r < rounds; ++r) {
-      // ids 32, 33, ... of a long list: the next 32 records replace the ones in the registers
-      if (r > 0 && (r * UB) % 32 == 0) {
-        const int first = r * UB;
-        const int uu = first + l32 < pn[k] ? pu0[k] + first + l32 : 0;
-        mycode = u_code[uu];
-        myi3 = u_i3[uu];
-      }
-      const int i0 = (r * UB) % 32;  // position of the round's ids among the 32 in the registers
+      // lanes 0..7 hold the round's slots: prefix x = lane/4, id r*UB + lane%4 of its list
+      const int si = r * UB + lane % UB;
+      const bool second = (lane / UB) & 1;
+      const bool slot_on = lane < 2 * UB && si < (second ? nb : na);
+      const int uu = slot_on ? (second ? u0b : u0a) + si : 0;
+      const int mycode = u_code[uu], myi3 = u_i3[uu];
       float a[2 * UB][KS], b[2 * UB][NT16][KS];
 #pragma unroll
       for (int sl = 0; sl < 2 * UB; ++sl) {
-        // slot sl: prefix sl / UB of the pair, id r*UB + sl % UB of its list; slots past the end of
-        // a list read the record of id 0 (a valid row) and are skipped below
-        const int src = 32 * (sl / UB) + i0 + sl % UB;
-        const float* gp = grad_row_ptr(lane_value(mycode, src), grad, gsum, D) + l16 * D3 + KS * kg;
-        const float* cp = g3 + (size_t)lane_value(myi3, src) * S3 + lrow * D3 + KS * kg;
+        const float* gp = grad_row_ptr(lane_value(mycode, sl), grad, gsum, D) + l16 * D3 + KS * kg;
+        const float* cp = g3 + (size_t)lane_value(myi3, sl) * S3 + lrow * D3 + KS * kg;
 #pragma unroll
-        for (int kk = 0; kk < KS; ++kk) a[sl][kk] = gp[kk];
+        for (int k = 0; k < KS; ++k) a[sl][k] = gp[k];
 #pragma unroll
         for (int nt = 0; nt < NT16; ++nt)
 #pragma unroll
-          for (int kk = 0; kk < KS; ++kk) b[sl][nt][kk] = cp[nt * 16 * D3 + kk];
+          for (int k = 0; k < KS; ++k) b[sl][nt][k] = cp[nt * 16 * D3 + k];
       }
       TT_LOADS_DONE();
+      const unsigned long long on_mask = __ballot(slot_on);
 #pragma unroll
       for (int sl = 0; sl < 2 * UB; ++sl) {
         // wavefront-uniform: empty slots cost no matrix-core time
-        if (r * UB + sl % UB < (sl / UB ? nb : na)) {
+        if ((on_mask >> sl) & 1ull) {
 #pragma unroll
           for (int nt = 0; nt < NT16; ++nt)
 #pragma unroll
-            for (int kk = 0; kk < KS; ++kk)
-              acc[sl / UB][nt] = mfma16(a[sl][kk], b[sl][nt][kk], acc[sl / UB][nt]);
+            for (int k = 0; k < KS; ++k)
+              acc[sl / UB][nt] = mfma16(a[sl][k], b[sl][nt][k], acc[sl / UB][nt]);
         }
       }
     }
@@ -577,18 +557,6 @@ __global__ __launch_bounds__(mid_waves<R>() * kWave, 6) void k_bwd_mid_mfma(
 #pragma unroll
         for (int v = 0; v < 4; ++v)
           if (rank_on) T[((2 * pw + x) * 4 + kg) * TS + v * R + nt * 16 + l16] = acc[x][nt][v];
-  }
-  // (iii) multiplies G1 rows of the chunk's prefixes: their loads are issued before the barrier,
-  // so that the wait for the block's slowest wavefront hides them
-  const int w3 = kMidWaves == 8 ? w - 4 : w;
-  const bool does3 = w3 >= 0 && w3 < W / 32;
-  float a3[32];
-  if (does3) {
-#pragma unroll
-    for (int j = 0; j < 32; ++j) {
-      const int ql = 8 * half + j / 4;
-      a3[j] = g1[(size_t)i1_of[ql] * S1 + (j % 4) * R + (l32 < R ? l32 : 0)];
-    }
   }
   __syncthreads();
 
@@ -622,15 +590,24 @@ __global__ __launch_bounds__(mid_waves<R>() * kWave, 6) void k_bwd_mid_mfma(
           if (rank_on) dg1part[(size_t)qv * S1 + v * R + 16 * nt + l16] = acc[nt][v];
     }
   }
-  if (does3) {
+  const int w3 = kMidWaves == 8 ? w - 4 : w;
+  if (w3 >= 0 && w3 < W / 32) {
     // (iii) G1 rows of the sixteen prefixes (as the contraction index) times 32 columns of the tile
+    const int half = lane / 32, l32 = lane % 32;
+    float a[32];
+#pragma unroll
+    for (int j = 0; j < 32; ++j) {
+      const int ql = 8 * half + j / 4;
+      a[j] = g1[(size_t)i1_of[ql] * S1 + (j % 4) * R + (l32 < R ? l32 : 0)];
+    }
+    TT_LOADS_DONE();
 #pragma unroll
     for (int j = 0; j < 32; ++j)
-      if (q_of[8 * half + j / 4] < 0 || l32 >= R) a3[j] = 0.f;
+      if (q_of[8 * half + j / 4] < 0 || l32 >= R) a[j] = 0.f;
     const int n = w3 * 32 + l32;
     f16v acc = TT_ZERO16;
 #pragma unroll
-    for (int j = 0; j < 32; ++j) acc = mfma32(a3[j], T[(32 * half + j) * TS + n], acc);
+    for (int j = 0; j < 32; ++j) acc = mfma32(a[j], T[(32 * half + j) * TS + n], acc);
 #pragma unroll
     for (int v = 0; v < 16; ++v) {
       const int mrow = 8 * (v / 4) + 4 * half + (v % 4);
