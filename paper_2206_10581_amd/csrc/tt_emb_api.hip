@@ -17,7 +17,7 @@ void launch_sort_pass(const Plan&, const Workspace&, const IdSource& src, int B,
                       int which);
 void launch_seg_count(const Plan&, const Workspace&, int B, hipStream_t);
 void launch_seg_write(const Plan&, const Workspace&, int B, hipStream_t);
-void launch_group(const Plan&, const Workspace&, int B, hipStream_t);
+void launch_group(const Plan&, const Workspace&, int B, hipStream_t, int which);
 void launch_prefix_fwd(const Plan&, const Workspace&, const float* g1, const float* g2, int B,
                        hipStream_t);
 void launch_row_fwd(const Plan&, const Workspace&, const float* g3, int B, float* out, hipStream_t);
@@ -168,6 +168,7 @@ static size_t carve(const Plan& pl, char* base, Workspace* ws /* [kSets] or null
   Workspace set[kSets];
   for (int i = 0; i < sets; ++i) {
     Workspace& w = set[i];
+    w.has_order = false;
     w.ctr = (Counters*)take(sizeof(Counters));
     for (int k = 0; k < 2; ++k) w.key[k] = (uint32_t*)take(mB * 4);
     for (int k = 0; k < 2; ++k) w.val[k] = (uint32_t*)take(mB * 4);
@@ -432,7 +433,10 @@ static int setup_side_streams(tt_emb* h) {
 }
 
 // Index pipeline of one batch into index set `set`, on stream st.
-static int run_index(tt_emb* h, int set, const IdSource& src, int B, hipStream_t st) {
+// how: 0 = everything, including the prefix-ordered schedule of the by-i3 chunks (worth its launch
+// only where the pipeline runs beside other work, as in tt_emb_prepare); 1 = no schedule; 2 = a
+// lookup: the structures that only the backward pass reads (unique ids by i3) are not built either.
+static int run_index(tt_emb* h, int set, const IdSource& src, int B, hipStream_t st, int how) {
   const Plan& pl = h->plan;
   const Workspace& ws = h->ws[set];
   int rc;
@@ -450,7 +454,8 @@ static int run_index(tt_emb* h, int set, const IdSource& src, int B, hipStream_t
   if (rc) return rc;
   rc = run_slot(h, kSlotSegWrite, st, [&] { launch_seg_write(pl, ws, B, st); });
   if (rc) return rc;
-  return run_slot(h, kSlotGroup, st, [&] { launch_group(pl, ws, B, st); });
+  h->ws[set].has_order = how == 0;
+  return run_slot(h, kSlotGroup, st, [&] { launch_group(pl, ws, B, st, how); });
 }
 
 int tt_emb_prepare(tt_emb_t h, const int64_t* ids, int64_t B64, void* hip_stream) {
@@ -493,7 +498,7 @@ int tt_emb_prepare(tt_emb_t h, const int64_t* ids, int64_t B64, void* hip_stream
     if (e != hipSuccess) return hip_fail(e);
   }
   int rc = run_index(h, target, id_source(h, ids, 0, true), (int)(B64 * h->plan.split),
-                     h->side[target]);
+                     h->side[target], 0);
   if (rc) return rc;
   e = hipEventRecord(h->prep[target].ready, h->side[target]);
   if (e != hipSuccess) return hip_fail(e);
@@ -574,7 +579,7 @@ static int forward_impl(tt_emb* h, const IdSource& src, int64_t B64, float* out,
       if (e != hipSuccess) return hip_fail(e);
     }
     h->cur = target;
-    rc = run_index(h, h->cur, src, B, st);
+    rc = run_index(h, h->cur, src, B, st, arm ? 1 : 2);
     if (rc) return rc;
   }
   h->done_valid[h->cur] = false;  // a new use of this set begins

@@ -703,15 +703,18 @@ void launch_seg_write(const Plan& pl, const Workspace& ws, int B, hipStream_t st
       ws.u_code, ws.q_us, ws.q_i1, ws.q_i2, ws.cnt3, ws.cnt2, ws.g1_first, ws.g1_end, ws.ctr);
 }
 
-void launch_group(const Plan& pl, const Workspace& ws, int B, hipStream_t st) {
+// which: 0 = both groupings and the chunk schedule; 1 = both groupings, no schedule (c3_order is
+// not written: the gradient kernel then walks the by-i3 chunks in index order); 2 = prefixes by i2
+// only (all a lookup needs)
+void launch_group(const Plan& pl, const Workspace& ws, int B, hipStream_t st, int which) {
   // blocks are sized from upper bounds (U <= B, Q <= min(B, n1*n2)); surplus blocks return at once
-  const int ub = cdiv(B, kSortItems);
+  const int ub = which == 2 ? 0 : cdiv(B, kSortItems);
   const int qb = cdiv(std::min((int64_t)B, pl.maxQ), kSortItems);
   k_group<<<ub + qb, kSortThreads, 0, st>>>(pl.sh, ub, chunk3_fill(B), pl.bits3, pl.bits2, ws.cnt3, ws.cnt2, ws.u_i3, ws.u_code, ws.u_q, ws.q_i2, ws.q_i1,
                                            ws.q_us, ws.g3_list, ws.g3_start, ws.c3_start, ws.c3_desc,
                                            ws.c3_item, ws.g2_list, ws.g2_start, ws.c2_start,
                                            ws.c2_desc, ws.c2_item, ws.band_cnt, ws.ctr);
-  if (chunks_ordered(pl, B))
+  if (which == 0 && chunks_ordered(pl, B))
     k_chunk_order<<<cdiv(cdiv(B, chunk3_fill(B)) + (int64_t)pl.sh.n3, kSortThreads), kSortThreads, 0,
                     st>>>(
       ws.c3_item, ws.band_cnt, ws.band_cur, ws.c3_order, ws.ctr);

@@ -114,6 +114,7 @@ struct Workspace {
   int4* c3_desc;      // chunk -> {i3, first list item, items, 0}  [maxChunk3]
   int2* c3_item;      // chunk, t -> {gradient-row code, prefix} of its t-th id [maxChunk3][kChunk3]
   int* c3_order;      // by-i3 chunks in the order of the prefix of their first id [maxChunk3]
+  bool has_order;     // host side: the batch in this set has had c3_order written
   int* g2_list;       // prefixes grouped by i2 (stable) [maxQ]
   int* g2_start;      // [n2+1]
   int* c2_start;      // [n2+1]

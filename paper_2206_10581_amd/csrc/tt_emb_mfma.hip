@@ -984,7 +984,7 @@ void launch_bwd_mid_mfma(const Plan& pl, const Workspace& ws, const float* g1, c
                          const float* g3, const float* grad, int B, hipStream_t st) {
   const int chunk_blocks = cdivi(std::min<int64_t>(B, pl.maxQ), kChunk2) + (int)pl.sh.n2;
   const int waves = pl.sh.r1 <= 16 ? mid_waves<16>() : mid_waves<32>();
-  const int* order = chunks_ordered(pl, B) ? ws.c3_order : nullptr;
+  const int* order = (ws.has_order && chunks_ordered(pl, B)) ? ws.c3_order : nullptr;
   // the same number of by-i3 blocks on every XCD
   const int dg3_blocks =
       kXcds * cdivi(cdivi(cdivi(B, chunk3_fill(B)) + (int64_t)pl.sh.n3, kXcds), waves);
