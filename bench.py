@@ -339,7 +339,7 @@ def main() -> int:
 
     # ---- device calibration in the same run: streaming copy and fp32 matrix-core loop
     cal = torch.empty(1 << 30, dtype=torch.uint8, device=dev)
-    rc, copy_bps, mfma_fps = lib.tt_emb_profile_peaks(cal.data_ptr(), cal.numel(),
+    rc, copy_bps, mfma_fps, gather_bps = lib.tt_emb_profile_peaks(cal.data_ptr(), cal.numel(),
                                                       int(torch.cuda.current_stream().cuda_stream))
     del cal
     if rc:
@@ -513,8 +513,10 @@ def main() -> int:
                          {"loop": "the plain step of one batch captured once, replayed",
                           "ms_per_step": graph_ms, "value": B / (graph_ms * 1e-3)}),
         "peaks_measured": {"copy_GBps": round(copy_bps / 1e9, 1), "mfma_fp32_TFLOPs": round(mfma_fps / 1e12, 1),
+                           "l2_gather_GBps": round(gather_bps / 1e9, 1),
                            "how": "tt_emb_profile_peaks in this run: 512 MiB streaming copy (read + "
-                                  "written bytes), register-resident v_mfma_f32_32x32x2f32 loop"},
+                                  "written bytes), register-resident v_mfma_f32_32x32x2f32 loop, "
+                                  "1 KiB records gathered from an L2-resident table without L1 reuse"},
         "roofline": roofline, "cpu_baseline": cpu, "path_roofline": path, "check": check,
         "kernels": kernels,
     }

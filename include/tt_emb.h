@@ -254,14 +254,19 @@ int tt_emb_profile_slots(void);
 int tt_emb_profile_read(tt_emb_t h, int slot, const char** name, int64_t* launches, double* ms);
 
 /*
- * Device calibration for roofline figures (not part of the path): times a plain streaming copy of
- * the first half of device_buf (caller-owned, 256-byte aligned, at least 4 MiB; the larger, the
- * closer to the HBM rate) onto its second half, and a register-resident loop of fp32 matrix-core
- * instructions on every compute unit; best of five launches each.  Reports bytes read + written
- * per second and fp32 flop per second.  Synchronises hip_stream; overwrites device_buf.
+ * Device calibration for roofline figures (not part of the path), best of five launches each:
+ *   copy    a plain streaming copy of the first half of device_buf onto its second half; bytes
+ *           read + written per second (the larger the buffer, the closer to the HBM rate)
+ *   mfma    a register-resident loop of fp32 matrix-core instructions on every compute unit; flop
+ *           per second
+ *   gather  1 KiB records fetched from pseudo-random places of a 1 MiB table (resident in every
+ *           L2), eight in flight per wavefront, no reuse in the vector L1: bytes per second that
+ *           the path L2 -> L1 -> registers delivers to per-id operand gathers
+ * device_buf: caller-owned, 256-byte aligned, at least 8 MiB.  Synchronises hip_stream; overwrites
+ * device_buf.
  */
 int tt_emb_profile_peaks(void* device_buf, size_t bytes, void* hip_stream, double* copy_bytes_per_s,
-                         double* mfma_flops_per_s);
+                         double* mfma_flops_per_s, double* gather_bytes_per_s);
 
 /* Frees the handle (host memory only). */
 int tt_emb_destroy(tt_emb_t h);

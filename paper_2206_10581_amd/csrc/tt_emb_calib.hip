@@ -46,9 +46,33 @@ __global__ __launch_bounds__(256) void k_calib_mfma(float* __restrict__ sink, in
   sink[(size_t)blockIdx.x * blockDim.x + threadIdx.x] = s;
 }
 
+// Gathers of 1 KiB records (one 16-byte word per lane, a whole record per load instruction) at
+// pseudo-random places of a table small enough to stay in every XCD's L2, eight records in flight
+// per wavefront: what the path from L2 through a compute unit's vector L1 delivers when nothing
+// is reused in the L1, as in the per-id operand gathers of the gradient kernels.
+__global__ __launch_bounds__(256) void k_calib_gather(const f4c* __restrict__ table, unsigned rec_mask,
+                                                     int iters, float* __restrict__ sink) {
+  const unsigned lane = threadIdx.x % 64;
+  unsigned state = (blockIdx.x * 4u + threadIdx.x / 64u) * 2654435761u + 12345u;  // per wavefront
+  f4c acc = {0.f, 0.f, 0.f, 0.f};
+  for (int it = 0; it < iters; ++it) {
+    f4c v[8];
+#pragma unroll
+    for (int k = 0; k < 8; ++k) {
+      state = state * 1664525u + 1013904223u;
+      const unsigned rec = (state >> 8) & rec_mask;
+      v[k] = table[(size_t)rec * 64 + lane];
+    }
+    __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+    for (int k = 0; k < 8; ++k) acc += v[k];
+  }
+  sink[(size_t)blockIdx.x * blockDim.x + threadIdx.x] = acc.x + acc.y + acc.z + acc.w;
+}
+
 // Best of `reps` timed launches each; returns a HIP error or hipSuccess.
 hipError_t calibrate(void* buf, size_t bytes, hipStream_t st, double* copy_bytes_per_s,
-                     double* mfma_flops_per_s) {
+                     double* mfma_flops_per_s, double* gather_bytes_per_s) {
   hipEvent_t a = nullptr, b = nullptr;
   hipError_t e = hipEventCreate(&a);
   if (e == hipSuccess) e = hipEventCreate(&b);
@@ -83,8 +107,24 @@ hipError_t calibrate(void* buf, size_t bytes, hipStream_t st, double* copy_bytes
     const double flops = (double)mgrid * 4 /*wavefronts*/ * 4 /*chains*/ * iters * (32.0 * 32 * 2 * 2);
     if (e == hipSuccess && ms > 0.f) best_mfma = std::max(best_mfma, flops / (ms * 1e-3));
   }
+  // gathers: a 1 MiB table at the start of the buffer (1024 records), results 2 MiB further on
+  double best_gather = 0.0;
+  const int ggrid = 256 * 8, giters = 256;
+  for (int r = 0; r < reps && e == hipSuccess; ++r) {
+    e = hipEventRecord(a, st);
+    if (e != hipSuccess) break;
+    k_calib_gather<<<ggrid, 256, 0, st>>>((const f4c*)buf, 1023u, giters, (float*)buf + (1u << 19));
+    e = hipGetLastError();
+    if (e == hipSuccess) e = hipEventRecord(b, st);
+    if (e == hipSuccess) e = hipEventSynchronize(b);
+    float ms = 0.f;
+    if (e == hipSuccess) e = hipEventElapsedTime(&ms, a, b);
+    const double gbytes = (double)ggrid * 4 /*wavefronts*/ * giters * 8 * 1024.0;
+    if (e == hipSuccess && ms > 0.f) best_gather = std::max(best_gather, gbytes / (ms * 1e-3));
+  }
   if (a) (void)hipEventDestroy(a);
   if (b) (void)hipEventDestroy(b);
+  *gather_bytes_per_s = best_gather;
   *copy_bytes_per_s = best_copy;
   *mfma_flops_per_s = best_mfma;
   return e;
