@@ -994,3 +994,32 @@ def test_ttsvd_initialisation_on_the_gpu():
         emb.close()
         np.testing.assert_allclose(W, info["matrix"], atol=2e-5)
         np.testing.assert_allclose(W.T @ W, np.eye(s.D), atol=1e-4)
+
+
+@pytest.mark.parametrize("seed", range(12))
+def test_random_shapes_and_batches(seed):
+    """Seeded random tables and batches: factors, ranks, batch size, share of repeated ids, of ids
+    sharing a prefix and of out-of-range ids all drawn at random; even seeds draw from the shapes
+    that have matrix-core kernels (d1 a multiple of 4, d2 = 4, equal ranks), odd seeds from anything."""
+    rng = np.random.default_rng(7000 + seed)
+    if seed % 2 == 0:
+        R = int(rng.choice([8, 16, 32, 64]))
+        d = (int(rng.choice([4, 8])), 4, int(rng.choice([4, 8])))
+        r = (R, R)
+    else:
+        d = tuple(int(x) for x in rng.integers(1, 7, size=3))
+        r = tuple(int(x) for x in rng.integers(1, 20, size=2))
+    n = tuple(int(x) for x in rng.integers(2, 40, size=3))
+    s = Shape(n, d, r)
+    B = int(rng.integers(1, 9000))
+    cores = tuple((rng.standard_normal(cs) / np.sqrt(max(r))).astype(np.float32) for cs in s.core_shapes())
+    ids = rng.integers(0, s.N, size=B, dtype=np.int64)
+    k = int(B * rng.random() * 0.5)
+    ids[:k] = ids[rng.integers(0, B)]                               # one id many times
+    k2 = int(B * rng.random() * 0.3)
+    ids[k:k + k2] = np.minimum(ids[0] // n[2] * n[2] + rng.integers(0, n[2], size=k2), s.N - 1)  # one prefix
+    bad = rng.random(B) < 0.01
+    ids[bad] = rng.choice([-1, s.N, s.N + 7, -(1 << 40), 1 << 40], size=int(bad.sum()))
+    rng.shuffle(ids)
+    grad = rng.standard_normal((B, s.D)).astype(np.float32)
+    check_against_oracle(n, d, r, cores, ids, grad, 0.01, max_batch=B + int(rng.integers(0, 100)))
