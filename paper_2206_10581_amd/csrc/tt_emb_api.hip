@@ -125,6 +125,7 @@ static int make_plan(const tt_emb_config* c, Plan* pl) {
   s.S2 = s.r1 * s.W;
   s.S3 = s.r2 * s.d3;
 
+  pl->mfma = mfma_shape(s) && !(c->flags & TT_EMB_FLAG_GENERIC_KERNELS);
   pl->maxB = maxB;
   pl->maxQ = std::min<int64_t>(maxB, n12);
   pl->sortBlocksMax = (int)cdiv64(pl->maxB, kSortItems);
@@ -206,8 +207,9 @@ static size_t carve(const Plan& pl, char* base, Workspace* ws /* [kSets] or null
   }
   Workspace& w = set[0];
   w.P = (float*)take(mQ * s.PN * 4);
-  w.gsum = w.carry = w.dPsum = w.dg1part = w.part3 = w.part2 = nullptr;
+  w.Pt = w.gsum = w.carry = w.dPsum = w.dg1part = w.part3 = w.part2 = nullptr;
   if (!lookup_only) {
+    if (pl.mfma && s.r1 >= 64) w.Pt = (float*)take(mQ * s.PN * 4);  // ranks with the two-launch backward
     w.gsum = (float*)take(mB * s.D * 4);
     w.carry = (float*)take((size_t)pl.tilesMax * 2 * s.D * 4);
     w.dPsum = (float*)take(mQ * s.PN * 4);
@@ -218,6 +220,7 @@ static size_t carve(const Plan& pl, char* base, Workspace* ws /* [kSets] or null
   for (int i = sets; i < kSets; ++i) set[i] = set[0];
   for (int i = 1; i < sets; ++i) {
     set[i].P = w.P;
+    set[i].Pt = w.Pt;
     set[i].gsum = w.gsum;
     set[i].carry = w.carry;
     set[i].dPsum = w.dPsum;
@@ -355,7 +358,7 @@ static void init_handle(tt_emb* h, const tt_emb_config* cfg, const Plan& pl, flo
   h->have_forward = false;
   h->last_stream = nullptr;
   h->profiling = false;
-  h->mfma = mfma_shape(pl.sh) && !(cfg->flags & TT_EMB_FLAG_GENERIC_KERNELS);
+  h->mfma = pl.mfma;
   std::memset(h->prof_launches, 0, sizeof(h->prof_launches));
   std::memset(h->prof_ms, 0, sizeof(h->prof_ms));
 }

@@ -125,6 +125,8 @@ struct Workspace {
   uint32_t* band_cnt;  // by-i3 chunks per band of their first prefix; directly follows g1_end
   uint32_t* band_cur;  // chunks placed so far per band; directly follows band_cnt [kOrderBands]
   float* P;           // prefix products G1[i1] G2[i2]   [maxQ][PN]
+  float* Pt;          // the same products in the layout the G3-gradient step reads: [maxQ][d2][r2][d1]
+                      // (matrix-core shapes of rank 64 and 128 with a backward pass only, else null)
   float* gsum;        // per unique id, sum of its rows' gradients [maxB][D]
   float* carry;       // per tile: head and tail partial sums [tiles][2][D]
   float* dPsum;       // per prefix: gradient of its product  [maxQ][PN]
@@ -141,6 +143,7 @@ struct Plan {
   // of that table, out/grad [B][D] are its [split*B][D/split] arrays, and the cores are the same
   // memory.  sh, maxB and maxQ describe the table the kernels see; user_* what the caller sees.
   int split;
+  bool mfma;  // the shape runs on the matrix-core kernels (and they are not switched off)
   int64_t user_maxB, user_N;
   int user_D;
   Shape sh;

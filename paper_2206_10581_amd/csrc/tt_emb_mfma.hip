@@ -90,7 +90,8 @@ constexpr int pf_units(int R) { return R >= 128 ? 32 : R >= 32 ? 4 : 2; }
 template <int R>
 __global__ __launch_bounds__(kWave) void k_prefix_fwd_mfma(
     const float* __restrict__ g1, const float* __restrict__ g2, const int4* __restrict__ c2_item,
-    const int4* __restrict__ c2_desc, float* __restrict__ P, const Counters* __restrict__ ctr) {
+    const int4* __restrict__ c2_desc, float* __restrict__ P, float* __restrict__ Pt,
+    const Counters* __restrict__ ctr) {
   constexpr int W = 4 * R, PN = 16 * R, S1 = 4 * R, S2 = R * W, KH = R / 2, NT = W / 32;
   constexpr int kPfUnits = pf_units(R);
   constexpr int UC = kPfUnits < NT ? kPfUnits : NT;  // units side by side over the columns
@@ -148,6 +149,20 @@ __global__ __launch_bounds__(kWave) void k_prefix_fwd_mfma(
       for (int v = 0; v < 16; ++v) {
         const int q = qrow[mt][v / 4];
         if (q >= 0) P[(size_t)q * PN + (v % 4) * W + (nt0 + t) * 32 + l32] = acc[v];
+      }
+      // Second copy for the G3-gradient step, which contracts over the 16 rows (j1,j2) of the
+      // product: Pt[q][j2][b][j1], so that a lane of that step finds the four j1 of its (j2, b) in
+      // one 16-byte word.  Accumulator elements 4x .. 4x+3 are j1 = 0..3 of one prefix at column
+      // j2*R + b = (nt0+t)*32 + l32: one vector store per prefix, 512 contiguous bytes per half.
+      if (Pt != nullptr) {
+        const int col = (nt0 + t) * 32 + l32, j2 = col / R, b2 = col % R;
+#pragma unroll
+        for (int x = 0; x < 4; ++x) {
+          const int q = qrow[mt][x];
+          if (q >= 0)
+            *(f4*)&Pt[(size_t)q * PN + j2 * (4 * R) + b2 * 4] =
+                f4{acc[4 * x], acc[4 * x + 1], acc[4 * x + 2], acc[4 * x + 3]};
+        }
       }
     }
   }
@@ -403,6 +418,93 @@ __device__ __forceinline__ void dg3_chunk(
   }
 }
 
+// ---------------------------------------------------------------------------------------------
+// Value of v in the lane `by` places further on in the same row of 16 lanes (a cross-lane move in
+// the vector ALU; lanes whose source falls outside the row get their own value back, and are not
+// used).
+template <int BY>
+__device__ __forceinline__ float row_lane_up(float v) {
+  if constexpr (BY == 0) return v;
+  else
+    return __builtin_bit_cast(
+        float, __builtin_amdgcn_update_dpp(__builtin_bit_cast(int, v), __builtin_bit_cast(int, v),
+                                           0x100 + BY /* row_shl:BY */, 0xf, 0xf, false));
+}
+
+// The same partial sum for ranks 64 and 128, where a prefix product is 4 to 8 KiB and the loads
+// above would be 16 to 32 four-byte loads per id.  The contraction runs over the 16 rows m = 4*j1 + j2 of the product; lane group kg takes j2 = kg
+// and the four j1.  The product comes from its second copy Pt[q][j2][b][j1]: one 16-byte load per
+// 16 columns b.  The gradient row (16 x D3, row-major) is read with 4/G loads that together cover
+// it contiguously, G = 16/D3: lane l16 = jj*D3 + j3 of group kg reads g[4*(x*G + jj) + kg][j3], and
+// the lanes j3 < D3 that feed the matrix cores fetch the values of jj > 0 from their row.
+template <int R, int D3, int UB>
+__device__ __forceinline__ void dg3_chunk_pt(
+    int c, const float* __restrict__ Pt, const float* __restrict__ grad,
+    const float* __restrict__ gsum, const int2* __restrict__ c3_item,
+    const int4* __restrict__ c3_desc, float* __restrict__ part3) {
+  constexpr int PN = 16 * R, S3 = R * D3, D = 16 * D3, NT = (R + 15) / 16;
+  constexpr int G = 16 / D3, NL = 4 / G;  // lanes groups per row of 16 lanes; loads per gradient row
+  const int lane = threadIdx.x % kWave;
+  const int l16 = lane % 16, kg = lane / 16;
+  const int j3 = l16 % D3, jj = l16 / D3;
+  // rank 8: half of the 16 columns of the only tile exist; the others load column 0 and are dropped
+  const bool col_on = R >= 16 || l16 < R;
+  const int lcol = col_on ? l16 : 0;
+  {
+    const int2 item = c3_item[(size_t)c * kChunk3 + lane % kChunk3];
+    const int cnt = c3_desc[c].z;
+    // records past the chunk's count are unwritten; only lanes below cnt are ever read
+    const int mycode = item.x, myq = item.y;
+    f4 acc[NT];
+#pragma unroll
+    for (int nt = 0; nt < NT; ++nt) acc[nt] = f4{0.f, 0.f, 0.f, 0.f};
+    for (int i0 = 0; i0 < cnt; i0 += UB) {
+      float ld[UB][NL];
+      f4 b[UB][NT];
+#pragma unroll
+      for (int x = 0; x < UB; ++x) {
+        const int i = min(i0 + x, cnt - 1);
+        const float* gp = grad_row_ptr(lane_value(mycode, i), grad, gsum, D) + kg * D3 + j3;
+        const float* pp = Pt + (size_t)lane_value(myq, i) * PN + kg * (4 * R) + lcol * 4;
+#pragma unroll
+        for (int y = 0; y < NL; ++y) ld[x][y] = gp[4 * (y * G + jj) * D3];
+#pragma unroll
+        for (int nt = 0; nt < NT; ++nt) b[x][nt] = *(const f4*)(pp + nt * 64);
+      }
+      TT_LOADS_DONE();
+#pragma unroll
+      for (int x = 0; x < UB; ++x) {
+        const bool on = (i0 + x < cnt) && (l16 < D3);
+        float a[4];  // a[j1] = g[4*j1 + kg][j3]
+#pragma unroll
+        for (int y = 0; y < NL; ++y) {
+          if constexpr (G == 2) {
+            a[2 * y] = ld[x][y];
+            a[2 * y + 1] = row_lane_up<8>(ld[x][y]);
+          } else {
+            a[0] = ld[x][y];
+            a[1] = row_lane_up<4>(ld[x][y]);
+            a[2] = row_lane_up<8>(ld[x][y]);
+            a[3] = row_lane_up<12>(ld[x][y]);
+          }
+        }
+#pragma unroll
+        for (int nt = 0; nt < NT; ++nt)
+#pragma unroll
+          for (int s = 0; s < 4; ++s) acc[nt] = mfma16(on ? a[s] : 0.f, b[x][nt][s], acc[nt]);
+      }
+    }
+    float* dst = part3 + (size_t)c * S3;
+#pragma unroll
+    for (int nt = 0; nt < NT; ++nt)
+#pragma unroll
+      for (int v = 0; v < 4; ++v) {
+        const int o3 = 4 * kg + v;
+        if (o3 < D3 && col_on) dst[(nt * 16 + l16) * D3 + o3] = acc[nt][v];
+      }
+  }
+}
+
 // chunks wave, wave + nwaves, ... in index order
 template <int R, int D3, int UB>
 __device__ __forceinline__ void dg3_role(
@@ -411,7 +513,7 @@ __device__ __forceinline__ void dg3_role(
     const int4* __restrict__ c3_desc, float* __restrict__ part3, const Counters* __restrict__ ctr) {
   const int nchunk = ctr->nchunk3;
   for (int c = wave; c < nchunk; c += nwaves)
-    dg3_chunk<R, D3, UB>(c, P, grad, gsum, c3_item, c3_desc, part3);
+    dg3_chunk_pt<R, D3, UB>(c, P, grad, gsum, c3_item, c3_desc, part3);
 }
 
 // ---------------------------------------------------------------------------------------------
@@ -955,7 +1057,7 @@ void launch_prefix_fwd_mfma(const Plan& pl, const Workspace& ws, const float* g1
   const int64_t chunks = cdivi(std::min<int64_t>(B, pl.maxQ), kChunk2) + pl.sh.n2;
   const int grid = (int)(chunks * pf_units(pl.sh.r1));
   TT_DISPATCH_R8(pl.sh.r1, (k_prefix_fwd_mfma<R><<<grid, kWave, 0, st>>>(
-                               g1, g2, ws.c2_item, ws.c2_desc, ws.P, ws.ctr)));
+                               g1, g2, ws.c2_item, ws.c2_desc, ws.P, ws.Pt, ws.ctr)));
 }
 
 void launch_prefix_bwd_mfma(const Plan& pl, const Workspace& ws, const float* g1, const float* g2,
@@ -973,7 +1075,7 @@ void launch_id_bwd_mfma(const Plan& pl, const Workspace& ws, const float* g3, co
   const int64_t waves_q = std::min<int64_t>(B, pl.maxQ), waves_c = cdivi(B, chunk3_fill(B)) + (int64_t)pl.sh.n3;
   const int per_role = grid_cap(cdivi(std::max(waves_q, waves_c), kMWaves), kMGridCap);
   TT_DISPATCH_RD(pl.sh.r1, pl.sh.d3, (k_id_bwd_mfma<R, D3><<<2 * per_role, kMThreads, 0, st>>>(
-                                         g3, ws.P, grad, ws.gsum, ws.u_code, ws.u_i3, ws.q_us,
+                                         g3, ws.Pt, grad, ws.gsum, ws.u_code, ws.u_i3, ws.q_us,
                                          ws.c3_item, ws.c3_desc, ws.dPsum, ws.part3, ws.ctr)));
 }
 
