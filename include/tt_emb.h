@@ -262,11 +262,14 @@ int tt_emb_profile_read(tt_emb_t h, int slot, const char** name, int64_t* launch
  *   gather  1 KiB records fetched from pseudo-random places of a 1 MiB table (resident in every
  *           L2), eight in flight per wavefront, no reuse in the vector L1: bytes per second that
  *           the path L2 -> L1 -> registers delivers to per-id operand gathers
+ *   far_gather  the same gathers from a 64 MiB table (beyond the L2s, inside the Infinity Cache):
+ *           what the fabric behind the L2s delivers to them; 0 when device_buf is below 66 MiB
  * device_buf: caller-owned, 256-byte aligned, at least 8 MiB.  Synchronises hip_stream; overwrites
  * device_buf.
  */
 int tt_emb_profile_peaks(void* device_buf, size_t bytes, void* hip_stream, double* copy_bytes_per_s,
-                         double* mfma_flops_per_s, double* gather_bytes_per_s);
+                         double* mfma_flops_per_s, double* gather_bytes_per_s,
+                         double* far_gather_bytes_per_s);
 
 /* Frees the handle (host memory only). */
 int tt_emb_destroy(tt_emb_t h);

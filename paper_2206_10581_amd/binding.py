@@ -66,7 +66,7 @@ def load_library():
     lib.tt_emb_profile_read.argtypes = [c_void_p, c_int, POINTER(c_char_p), POINTER(c_int64),
                                         POINTER(c_double)]
     lib.tt_emb_profile_peaks.argtypes = [c_void_p, c_size_t, c_void_p, POINTER(c_double),
-                                         POINTER(c_double), POINTER(c_double)]
+                                         POINTER(c_double), POINTER(c_double), POINTER(c_double)]
     lib.tt_emb_destroy.argtypes = [c_void_p]
     lib.tt_emb_strerror.argtypes = [c_int]
     lib.tt_emb_strerror.restype = c_char_p
@@ -178,10 +178,10 @@ def tt_emb_profile_read(h, slot: int):
 
 
 def tt_emb_profile_peaks(buf_ptr: int, nbytes: int, stream: int):
-    copy, mfma, gather = c_double(0.0), c_double(0.0), c_double(0.0)
+    copy, mfma, gather, far = c_double(0.0), c_double(0.0), c_double(0.0), c_double(0.0)
     rc = load_library().tt_emb_profile_peaks(c_void_p(buf_ptr), c_size_t(nbytes), c_void_p(stream),
-                                             byref(copy), byref(mfma), byref(gather))
-    return rc, float(copy.value), float(mfma.value), float(gather.value)
+                                             byref(copy), byref(mfma), byref(gather), byref(far))
+    return rc, float(copy.value), float(mfma.value), float(gather.value), float(far.value)
 
 
 def tt_emb_destroy(h) -> int:

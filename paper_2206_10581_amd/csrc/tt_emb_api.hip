@@ -46,7 +46,8 @@ void launch_bwd_mid_mfma(const Plan&, const Workspace&, const float* g1, const f
                          const float* g3, const float* grad, int B, hipStream_t);
 void launch_gsum_block(const Plan&, const Workspace&, const float* grad, int B, hipStream_t);
 hipError_t calibrate(void* buf, size_t bytes, hipStream_t, double* copy_bytes_per_s,
-                     double* mfma_flops_per_s, double* gather_bytes_per_s);
+                     double* mfma_flops_per_s, double* gather_bytes_per_s,
+                     double* far_gather_bytes_per_s);
 
 static const char* const kSlotNames[kSlotCount] = {
     "sort_hist", "sort_scan", "sort_scatter", "seg_count", "seg_write",  "group",
@@ -880,13 +881,14 @@ int tt_emb_profile_read(tt_emb_t h, int slot, const char** name, int64_t* launch
 
 
 int tt_emb_profile_peaks(void* device_buf, size_t bytes, void* hip_stream, double* copy_bytes_per_s,
-                         double* mfma_flops_per_s, double* gather_bytes_per_s) {
+                         double* mfma_flops_per_s, double* gather_bytes_per_s,
+                         double* far_gather_bytes_per_s) {
   if (device_buf == nullptr || copy_bytes_per_s == nullptr || mfma_flops_per_s == nullptr ||
-      gather_bytes_per_s == nullptr)
+      gather_bytes_per_s == nullptr || far_gather_bytes_per_s == nullptr)
     return TT_EMB_EINVAL;
   if (((uintptr_t)device_buf & 255u) != 0 || bytes < ((size_t)8 << 20)) return TT_EMB_EINVAL;
   const hipError_t e = calibrate(device_buf, bytes, (hipStream_t)hip_stream, copy_bytes_per_s,
-                                 mfma_flops_per_s, gather_bytes_per_s);
+                                 mfma_flops_per_s, gather_bytes_per_s, far_gather_bytes_per_s);
   return e == hipSuccess ? TT_EMB_OK : hip_fail(e);
 }
 

@@ -47,9 +47,10 @@ __global__ __launch_bounds__(256) void k_calib_mfma(float* __restrict__ sink, in
 }
 
 // Gathers of 1 KiB records (one 16-byte word per lane, a whole record per load instruction) at
-// pseudo-random places of a table small enough to stay in every XCD's L2, eight records in flight
-// per wavefront: what the path from L2 through a compute unit's vector L1 delivers when nothing
-// is reused in the L1, as in the per-id operand gathers of the gradient kernels.
+// pseudo-random places of a table, eight records in flight per wavefront, nothing reused in the
+// vector L1 - the access pattern of the per-id operand gathers of the row and gradient kernels.
+// With a table that stays in every XCD's L2 this measures the path L2 -> L1; with a table beyond
+// the L2s, what the fabric behind them (Infinity Cache, HBM) delivers to such gathers.
 __global__ __launch_bounds__(256) void k_calib_gather(const f4c* __restrict__ table, unsigned rec_mask,
                                                      int iters, float* __restrict__ sink) {
   const unsigned lane = threadIdx.x % 64;
@@ -72,7 +73,8 @@ __global__ __launch_bounds__(256) void k_calib_gather(const f4c* __restrict__ ta
 
 // Best of `reps` timed launches each; returns a HIP error or hipSuccess.
 hipError_t calibrate(void* buf, size_t bytes, hipStream_t st, double* copy_bytes_per_s,
-                     double* mfma_flops_per_s, double* gather_bytes_per_s) {
+                     double* mfma_flops_per_s, double* gather_bytes_per_s,
+                     double* far_gather_bytes_per_s) {
   hipEvent_t a = nullptr, b = nullptr;
   hipError_t e = hipEventCreate(&a);
   if (e == hipSuccess) e = hipEventCreate(&b);
@@ -107,24 +109,32 @@ hipError_t calibrate(void* buf, size_t bytes, hipStream_t st, double* copy_bytes
     const double flops = (double)mgrid * 4 /*wavefronts*/ * 4 /*chains*/ * iters * (32.0 * 32 * 2 * 2);
     if (e == hipSuccess && ms > 0.f) best_mfma = std::max(best_mfma, flops / (ms * 1e-3));
   }
-  // gathers: a 1 MiB table at the start of the buffer (1024 records), results 2 MiB further on
-  double best_gather = 0.0;
+  // gathers: a 1 MiB table (1024 records: resident in every L2), then a 64 MiB table (65,536
+  // records: beyond the L2s, inside the Infinity Cache) at the start of the buffer; the results go
+  // to the buffer's last 2 MiB
+  double best_gather[2] = {0.0, 0.0};
   const int ggrid = 256 * 8, giters = 256;
-  for (int r = 0; r < reps && e == hipSuccess; ++r) {
-    e = hipEventRecord(a, st);
-    if (e != hipSuccess) break;
-    k_calib_gather<<<ggrid, 256, 0, st>>>((const f4c*)buf, 1023u, giters, (float*)buf + (1u << 19));
-    e = hipGetLastError();
-    if (e == hipSuccess) e = hipEventRecord(b, st);
-    if (e == hipSuccess) e = hipEventSynchronize(b);
-    float ms = 0.f;
-    if (e == hipSuccess) e = hipEventElapsedTime(&ms, a, b);
-    const double gbytes = (double)ggrid * 4 /*wavefronts*/ * giters * 8 * 1024.0;
-    if (e == hipSuccess && ms > 0.f) best_gather = std::max(best_gather, gbytes / (ms * 1e-3));
+  float* sink = (float*)((char*)buf + bytes - ((size_t)2 << 20));
+  for (int t = 0; t < 2 && e == hipSuccess; ++t) {
+    const unsigned mask = t == 0 ? 1023u : 65535u;
+    if (t == 1 && bytes < ((size_t)66 << 20)) break;  // buffer too small for the large table
+    for (int r = 0; r < reps && e == hipSuccess; ++r) {
+      e = hipEventRecord(a, st);
+      if (e != hipSuccess) break;
+      k_calib_gather<<<ggrid, 256, 0, st>>>((const f4c*)buf, mask, giters, sink);
+      e = hipGetLastError();
+      if (e == hipSuccess) e = hipEventRecord(b, st);
+      if (e == hipSuccess) e = hipEventSynchronize(b);
+      float ms = 0.f;
+      if (e == hipSuccess) e = hipEventElapsedTime(&ms, a, b);
+      const double gbytes = (double)ggrid * 4 /*wavefronts*/ * giters * 8 * 1024.0;
+      if (e == hipSuccess && ms > 0.f) best_gather[t] = std::max(best_gather[t], gbytes / (ms * 1e-3));
+    }
   }
   if (a) (void)hipEventDestroy(a);
   if (b) (void)hipEventDestroy(b);
-  *gather_bytes_per_s = best_gather;
+  *gather_bytes_per_s = best_gather[0];
+  *far_gather_bytes_per_s = best_gather[1];
   *copy_bytes_per_s = best_copy;
   *mfma_flops_per_s = best_mfma;
   return e;
