@@ -139,8 +139,6 @@ static int make_plan(const tt_emb_config* c, Plan* pl) {
   pl->keyBits = bits_for(s.N);  // the sentinel N itself must be representable
   pl->passes = (pl->keyBits + 10) / 11;
   pl->bitsPerPass = (pl->keyBits + pl->passes - 1) / pl->passes;
-  pl->bits2 = bits_for(s.n2 - 1);
-  pl->bits3 = bits_for(s.n3 - 1);
   return TT_EMB_OK;
 }
 

@@ -38,22 +38,38 @@ __device__ __forceinline__ uint32_t key_of_id(const IdSource& src, int idx, uint
   return (uint32_t)id;
 }
 
-// band of the prefix range [0, Q) that prefix q falls in
+// band of the prefix range [0, Q) that prefix q falls in (single precision: bands only order a
+// schedule, and both users call this one function)
 __device__ __forceinline__ int chunk_band(int q, int Q) {
-  const long long b = (long long)max(q, 0) * kOrderBands / max(Q, 1);
-  return (int)min(b, (long long)kOrderBands - 1);
+  const float b = (float)max(q, 0) * ((float)kOrderBands / (float)max(Q, 1));
+  return min((int)b, kOrderBands - 1);
 }
 
 // ---------------------------------------------------------------------------------------------
 // block-wide helpers; ldsw holds at least one word per wavefront of the block
 
-__device__ __forceinline__ uint32_t wave_inclusive_scan(uint32_t v, int lane) {
-#pragma unroll
-  for (int off = 1; off < kWave; off <<= 1) {
-    const uint32_t t = __shfl_up(v, off);
-    if (lane >= off) v += t;
+// Inclusive prefix sum over the wavefront: inside every row of 16 lanes with cross-lane moves in
+// the vector ALU (row_shr by 1, 2, 4, 8; lanes without a source add zero), then the totals of the
+// rows before a lane's own are added.
+__device__ __forceinline__ uint32_t row_shr_or_zero(uint32_t v, int by) {
+  // by is a compile-time constant after unrolling
+  switch (by) {
+    case 1: return (uint32_t)__builtin_amdgcn_update_dpp(0, (int)v, 0x111, 0xf, 0xf, false);
+    case 2: return (uint32_t)__builtin_amdgcn_update_dpp(0, (int)v, 0x112, 0xf, 0xf, false);
+    case 4: return (uint32_t)__builtin_amdgcn_update_dpp(0, (int)v, 0x114, 0xf, 0xf, false);
+    default: return (uint32_t)__builtin_amdgcn_update_dpp(0, (int)v, 0x118, 0xf, 0xf, false);
   }
-  return v;
+}
+__device__ __forceinline__ uint32_t wave_inclusive_scan(uint32_t v, int lane) {
+  v += row_shr_or_zero(v, 1);
+  v += row_shr_or_zero(v, 2);
+  v += row_shr_or_zero(v, 4);
+  v += row_shr_or_zero(v, 8);
+  const uint32_t r0 = (uint32_t)__builtin_amdgcn_readlane((int)v, 15);
+  const uint32_t r1 = (uint32_t)__builtin_amdgcn_readlane((int)v, 31);
+  const uint32_t r2 = (uint32_t)__builtin_amdgcn_readlane((int)v, 47);
+  const int row = lane / 16;
+  return v + (row >= 1 ? r0 : 0u) + (row >= 2 ? r1 : 0u) + (row >= 3 ? r2 : 0u);
 }
 
 // Exclusive prefix of v over the block's threads; *total receives the block sum.
@@ -92,18 +108,25 @@ __device__ uint32_t block_exclusive_scan(uint32_t* arr, int n, uint32_t* ldsw) {
   return total;
 }
 
-// Lanes of a wavefront that hold the same digit (among lanes with valid set); one ballot per bit.
-__device__ __forceinline__ unsigned long long match_digit(int digit, bool valid, int nbits) {
-  unsigned long long peers = __ballot(valid);
-  for (int bit = 0; bit < nbits; ++bit) {
-    const bool one = valid && ((digit >> bit) & 1);
-    const unsigned long long vote = __ballot(one);
-    peers &= one ? vote : ~vote;
+// Lanes of a wavefront that hold the same digit (among lanes with valid set).  One ballot per bit of
+// the widest digit (higher bits are zero everywhere and cost nothing but their ballot): a lane
+// collects the lanes that differ from it in some bit as (vote xor own bit replicated).
+constexpr int kMaxBits = 11;
+static_assert((1 << kMaxBits) == kMaxBins, "digits have at most kMaxBits bits");
+__device__ __forceinline__ unsigned long long match_digit(int digit, bool valid) {
+  const int d = valid ? digit : 0;
+  uint32_t lo = 0u, hi = 0u;
+#pragma unroll
+  for (int bit = 0; bit < kMaxBits; ++bit) {
+    const int t = (d << (31 - bit)) >> 31;  // 0 or -1
+    const unsigned long long vote = __ballot(t < 0);
+    lo |= (uint32_t)vote ^ (uint32_t)t;
+    hi |= (uint32_t)(vote >> 32) ^ (uint32_t)t;
   }
-  return peers;
+  return ~(((unsigned long long)hi << 32) | lo) & __ballot(valid);
 }
 
-struct ScatterLds {
+struct alignas(16) ScatterLds {
   // per-wavefront bucket counts, later block-local output offsets; two 16-bit buckets per word
   // (a wavefront owns 256 items and a block 4096, so both fit)
   uint32_t wh[kSortWaves][kMaxBins / 2];
@@ -114,6 +137,9 @@ struct ScatterLds {
 };
 
 constexpr int kSteps = kSortWaveItems / kWave;  // items per lane
+static_assert((kChunk2 & (kChunk2 - 1)) == 0 && (kChunk3 & (kChunk3 - 1)) == 0 &&
+                  (kChunk3Min & (kChunk3Min - 1)) == 0,
+              "chunk sizes are powers of two: positions inside a bucket are cut with shifts");
 
 // One block's share of a stable counting-sort pass over n_items items (block blk owns items
 // [blk*kSortItems, +kSortItems), wavefront w of it the w-th sixteenth).  With tot != nullptr,
@@ -129,7 +155,7 @@ constexpr int kSteps = kSortWaveItems / kWave;  // items per lane
 // {bucket, first item, item count, 0} for all chunks c in bucket order, chunk_starts[bucket] the
 // first chunk of each bucket (bins+1 entries), *n_chunks the number of chunks.
 template <class ItemOps>
-__device__ void stable_scatter_block(ScatterLds& L, int blk, int n_items, int bins, int nbits,
+__device__ void stable_scatter_block(ScatterLds& L, int blk, int n_items, int bins,
                                      const uint32_t* __restrict__ cnt,
                                      const uint32_t* __restrict__ tot, ItemOps ops, int* starts,
                                      int chunk, int* chunk_starts, int4* chunk_desc,
@@ -137,6 +163,7 @@ __device__ void stable_scatter_block(ScatterLds& L, int blk, int n_items, int bi
   const int tid = threadIdx.x;
   const int nblk = (n_items + kSortItems - 1) / kSortItems;
   const bool publishes = (starts != nullptr && blk == 0);
+  const int chunk_sh = chunk > 0 ? 31 - __clz(chunk) : 0;  // chunk sizes are powers of two
   if (blk >= nblk && !publishes) return;  // uniform for the whole block
 
   // items first: their loads overlap the table work below
@@ -178,7 +205,7 @@ __device__ void stable_scatter_block(ScatterLds& L, int blk, int n_items, int bi
     }
     if (bin < bins) {
       L.tot[bin] = total;
-      if (chunk > 0) L.aux[bin] = (total + chunk - 1) / chunk;
+      if (chunk > 0) L.aux[bin] = (total + chunk - 1) >> chunk_sh;
     }
   }
   __builtin_amdgcn_sched_barrier(0);  // keep the loads together: their latencies overlap
@@ -230,28 +257,39 @@ __device__ void stable_scatter_block(ScatterLds& L, int blk, int n_items, int bi
     const int bin = tid + k * kSortThreads;
     if (bin < bins) L.tot[bin] += before[k];
   }
+  // every wavefront clears its own counters, 16 bytes per lane and write (no barrier: nobody else
+  // touches them before the next one)
   const int words = (bins + 1) / 2;
-  for (int i = tid; i < kSortWaves * words; i += kSortThreads) L.wh[i / words][i % words] = 0u;
-  __syncthreads();
+  for (int i = lane; i < (words + 3) / 4; i += kWave) ((uint4*)L.wh[w])[i] = make_uint4(0u, 0u, 0u, 0u);
 
   // Each wavefront walks its items in order, 64 at a time.  Lanes holding the same digit find each
   // other by ballots; the lowest of them advances the wavefront's bucket counter for all, which
   // gives every item its rank among the wavefront's items of that bucket.
   const unsigned long long lt_mask = (1ull << lane) - 1ull;
   uint32_t rank[kSteps];
+  unsigned long long peers[kSteps];
+#pragma unroll
+  for (int step = 0; step < kSteps; ++step) {
+    const bool valid = digits[step] >= 0;
+    peers[step] = 0ull;
+    if (__ballot(valid) != 0ull) peers[step] = match_digit(digits[step], valid);  // wave-uniform
+  }
+  // the counter updates of the steps go out back to back (the LDS keeps a wavefront's atomics in
+  // program order, which is what makes the ranks stable), their results are picked up afterwards
+  uint32_t old[kSteps];
 #pragma unroll
   for (int step = 0; step < kSteps; ++step) {
     const int digit = digits[step];
-    const bool valid = digit >= 0;
-    rank[step] = 0;
-    if (__ballot(valid) == 0ull) continue;  // wave-uniform
-    const unsigned long long peers = match_digit(digit, valid, nbits);
-    const int leader = valid ? (__ffsll((long long)peers) - 1) : lane;
-    const int sh = 16 * (digit & 1);
-    uint32_t old = 0;
-    if (valid && lane == leader)
-      old = atomicAdd(&L.wh[w][digit >> 1], (uint32_t)__popcll(peers) << sh);
-    rank[step] = ((__shfl(old, leader) >> sh) & 0xffffu) + (uint32_t)__popcll(peers & lt_mask);
+    old[step] = 0;
+    if (digit >= 0 && lane == __ffsll((long long)peers[step]) - 1)
+      old[step] = atomicAdd(&L.wh[w][digit >> 1], (uint32_t)__popcll(peers[step]) << (16 * (digit & 1)));
+  }
+#pragma unroll
+  for (int step = 0; step < kSteps; ++step) {
+    const int digit = digits[step];
+    const int leader = digit >= 0 ? (__ffsll((long long)peers[step]) - 1) : lane;
+    rank[step] = ((__shfl(old[step], leader) >> (16 * (digit & 1))) & 0xffffu) +
+                 (uint32_t)__popcll(peers[step] & lt_mask);
   }
   __syncthreads();
   // per bucket: counts of the wavefronts -> offsets inside the block (one thread per word)
@@ -274,7 +312,7 @@ __device__ void stable_scatter_block(ScatterLds& L, int blk, int n_items, int bi
       const uint32_t pos = L.tot[digit] + off + rank[step];
       if constexpr (ItemOps::kChunked) {
         const uint32_t in_bucket = pos - L.base[digit];
-        ops.emit_chunked(pos, L.aux[digit] + in_bucket / (uint32_t)chunk, in_bucket % (uint32_t)chunk,
+        ops.emit_chunked(pos, L.aux[digit] + (in_bucket >> chunk_sh), in_bucket & (uint32_t)(chunk - 1),
                          items[step]);
       } else {
         ops.emit(pos, items[step]);
@@ -352,7 +390,7 @@ __global__ __launch_bounds__(kSortThreads) void k_sort_hist(
     const bool valid = idx < B;
     if (__ballot(valid) == 0ull) continue;
     const int digit = (int)((keys[step] >> shift) & mask);
-    const unsigned long long peers = match_digit(digit, valid, bits);
+    const unsigned long long peers = match_digit(digit, valid);
     if (valid && lane == __ffsll((long long)peers) - 1)
       atomicAdd(&h[digit], (uint32_t)__popcll(peers));
   }
@@ -366,7 +404,7 @@ __global__ __launch_bounds__(kSortThreads) void k_sort_scatter(SortOps<FROM_IDS>
                                                                const uint32_t* __restrict__ cnt,
                                                                const uint32_t* __restrict__ tot) {
   __shared__ ScatterLds L;
-  stable_scatter_block(L, (int)blockIdx.x, B, 1 << bits, bits, cnt, tot, ops, nullptr, 0, nullptr,
+  stable_scatter_block(L, (int)blockIdx.x, B, 1 << bits, cnt, tot, ops, nullptr, 0, nullptr,
                        nullptr, nullptr);
 }
 
@@ -603,7 +641,7 @@ struct GroupOps2 {
 };
 
 __global__ __launch_bounds__(kSortThreads) void k_group(
-    Shape sh, int u_blocks, int chunk3, int bits3, int bits2, const uint32_t* __restrict__ cnt3,
+    Shape sh, int u_blocks, int chunk3, const uint32_t* __restrict__ cnt3,
     const uint32_t* __restrict__ cnt2, const int* __restrict__ u_i3, const int* __restrict__ u_code,
     const int* __restrict__ u_q, const int* __restrict__ q_i2, const int* __restrict__ q_i1,
     const int* __restrict__ q_us, int* g3_list, int* g3_start, int* c3_start, int4* c3_desc,
@@ -612,11 +650,11 @@ __global__ __launch_bounds__(kSortThreads) void k_group(
   __shared__ ScatterLds L;
   if ((int)blockIdx.x < u_blocks) {
     GroupOps3 ops{u_i3, u_code, u_q, g3_list, c3_item, band_cnt, ctr->Q};
-    stable_scatter_block(L, (int)blockIdx.x, ctr->U, (int)sh.n3, bits3, cnt3, nullptr, ops, g3_start,
+    stable_scatter_block(L, (int)blockIdx.x, ctr->U, (int)sh.n3, cnt3, nullptr, ops, g3_start,
                          chunk3, c3_start, c3_desc, &ctr->nchunk3);
   } else {
     GroupOps2 ops{q_i2, q_i1, q_us, g2_list, c2_item};
-    stable_scatter_block(L, (int)blockIdx.x - u_blocks, ctr->Q, (int)sh.n2, bits2, cnt2, nullptr, ops,
+    stable_scatter_block(L, (int)blockIdx.x - u_blocks, ctr->Q, (int)sh.n2, cnt2, nullptr, ops,
                          g2_start, kChunk2, c2_start, c2_desc, &ctr->nchunk2);
   }
 }
@@ -710,7 +748,7 @@ void launch_group(const Plan& pl, const Workspace& ws, int B, hipStream_t st, in
   // blocks are sized from upper bounds (U <= B, Q <= min(B, n1*n2)); surplus blocks return at once
   const int ub = which == 2 ? 0 : cdiv(B, kSortItems);
   const int qb = cdiv(std::min((int64_t)B, pl.maxQ), kSortItems);
-  k_group<<<ub + qb, kSortThreads, 0, st>>>(pl.sh, ub, chunk3_fill(B), pl.bits3, pl.bits2, ws.cnt3, ws.cnt2, ws.u_i3, ws.u_code, ws.u_q, ws.q_i2, ws.q_i1,
+  k_group<<<ub + qb, kSortThreads, 0, st>>>(pl.sh, ub, chunk3_fill(B), ws.cnt3, ws.cnt2, ws.u_i3, ws.u_code, ws.u_q, ws.q_i2, ws.q_i1,
                                            ws.q_us, ws.g3_list, ws.g3_start, ws.c3_start, ws.c3_desc,
                                            ws.c3_item, ws.g2_list, ws.g2_start, ws.c2_start,
                                            ws.c2_desc, ws.c2_item, ws.band_cnt, ws.ctr);
@@ -721,3 +759,4 @@ void launch_group(const Plan& pl, const Workspace& ws, int B, hipStream_t st, in
 }
 
 }  // namespace ttemb
+

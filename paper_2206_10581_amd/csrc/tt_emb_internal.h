@@ -151,7 +151,6 @@ struct Plan {
   int sortBlocksMax, segBlocksMax, uBlocksMax, qBlocksMax, tilesMax;
   int64_t maxChunk3, maxChunk2;
   int keyBits, passes, bitsPerPass;
-  int bits2, bits3;  // bits of n2-1, n3-1 (for the ballot match in the grouping scatter)
 };
 
 // The by-i3 chunks are put in prefix order only when the prefix products of a batch of B ids can
