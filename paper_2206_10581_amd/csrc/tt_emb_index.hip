@@ -615,7 +615,8 @@ struct GroupOps3 {
   __device__ void emit_chunked(uint32_t pos, uint32_t chunk, uint32_t t, Item it) const {
     list[pos] = it.u;
     item[(size_t)chunk * kChunk3 + t] = make_int2(it.code, it.q);
-    if (t == 0) atomicAdd(&band_cnt[chunk_band(it.q, Q)], 1u);  // a chunk counts where it starts
+    // a chunk counts where it starts (only when a schedule will be built from the counts)
+    if (band_cnt != nullptr && t == 0) atomicAdd(&band_cnt[chunk_band(it.q, Q)], 1u);
   }
 };
 
@@ -748,11 +749,12 @@ void launch_group(const Plan& pl, const Workspace& ws, int B, hipStream_t st, in
   // blocks are sized from upper bounds (U <= B, Q <= min(B, n1*n2)); surplus blocks return at once
   const int ub = which == 2 ? 0 : cdiv(B, kSortItems);
   const int qb = cdiv(std::min((int64_t)B, pl.maxQ), kSortItems);
+  const bool ordered = which == 0 && chunks_ordered(pl, B);
   k_group<<<ub + qb, kSortThreads, 0, st>>>(pl.sh, ub, chunk3_fill(B), ws.cnt3, ws.cnt2, ws.u_i3, ws.u_code, ws.u_q, ws.q_i2, ws.q_i1,
                                            ws.q_us, ws.g3_list, ws.g3_start, ws.c3_start, ws.c3_desc,
                                            ws.c3_item, ws.g2_list, ws.g2_start, ws.c2_start,
-                                           ws.c2_desc, ws.c2_item, ws.band_cnt, ws.ctr);
-  if (which == 0 && chunks_ordered(pl, B))
+                                           ws.c2_desc, ws.c2_item, ordered ? ws.band_cnt : nullptr, ws.ctr);
+  if (ordered)
     k_chunk_order<<<cdiv(cdiv(B, chunk3_fill(B)) + (int64_t)pl.sh.n3, kSortThreads), kSortThreads, 0,
                     st>>>(
       ws.c3_item, ws.band_cnt, ws.band_cur, ws.c3_order, ws.ctr);
