@@ -117,9 +117,9 @@ def run_lookahead(emb, ids_seq, grad_seq, out_seq, lr, steps, first=0, flow_cont
             emb.wait_backward(1)     # at most two steps ahead of the device; enqueues nothing
         if before_step is not None:
             before_step(k)
-        emb.prepare(ids_seq[(k + 2) % n])       # index pipeline of the batch after next
         emb.forward(ids_seq[k % n], out_seq[k % n])
         emb.backward_update(grad_seq[k % n], lr)
+        emb.prepare(ids_seq[(k + 2) % n])       # index pipeline of the batch after next
         if after_step is not None:
             after_step(k)
 
