@@ -996,6 +996,29 @@ def test_ttsvd_initialisation_on_the_gpu():
         np.testing.assert_allclose(W.T @ W, np.eye(s.D), atol=1e-4)
 
 
+@pytest.mark.parametrize("flags", [0, 2])
+def test_table_at_the_size_limits(flags):
+    """The largest table the library accepts: 2048 values of i2 and of i3 (the bucket limit of the
+    grouping passes, eleven-bit digits with the top bit in use) and N just below 2^31 (31-bit sort
+    keys: three radix passes of eleven bits).  Ids from all over the range, the two ends of it,
+    repeats, and ids just past the table."""
+    n, d, r = (511, 2048, 2048), (4, 4, 4), (8, 8)
+    s = Shape(n, d, r)
+    assert 2 ** 31 - 2 ** 23 < s.N < 2 ** 31
+    rng = np.random.default_rng(77 + flags)
+    cores = tuple((rng.standard_normal(cs) * 0.35).astype(np.float32) for cs in s.core_shapes())
+    ids = np.concatenate([
+        rng.integers(0, s.N, size=4000, dtype=np.int64),
+        rng.integers(s.N - 3000, s.N, size=700, dtype=np.int64),
+        rng.integers(0, 3000, size=700, dtype=np.int64),
+        np.array([0, s.N - 1, s.N - 1, s.N, s.N + 1, 2 ** 31, 2 ** 40, -1, -2 ** 35], dtype=np.int64),
+    ])
+    ids = np.concatenate([ids, ids[:600]])        # every one of these twice
+    rng.shuffle(ids)
+    grad = rng.standard_normal((ids.size, s.D)).astype(np.float32)
+    check_against_oracle(n, d, r, cores, ids, grad, 0.01, flags=flags)
+
+
 @pytest.mark.parametrize("seed", range(12))
 def test_random_shapes_and_batches(seed):
     """Seeded random tables and batches: factors, ranks, batch size, share of repeated ids, of ids
