@@ -151,6 +151,9 @@ struct Plan {
   int sortBlocksMax, segBlocksMax, uBlocksMax, qBlocksMax, tilesMax;
   int64_t maxChunk3, maxChunk2;
   int keyBits, passes, bitsPerPass;
+  // single-wavefront blocks of the per-chunk matrix-core kernels that the device holds at once
+  // (forward, backward); asked of the runtime at the first launch, 0 until then
+  mutable int unit_slots[2] = {0, 0};
 };
 
 // The by-i3 chunks are put in prefix order only when the prefix products of a batch of B ids can

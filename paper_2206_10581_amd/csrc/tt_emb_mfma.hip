@@ -91,22 +91,27 @@ template <int R>
 __global__ __launch_bounds__(kWave) void k_prefix_fwd_mfma(
     const float* __restrict__ g1, const float* __restrict__ g2, const int4* __restrict__ c2_item,
     const int4* __restrict__ c2_desc, float* __restrict__ P, float* __restrict__ Pt,
-    const Counters* __restrict__ ctr) {
+    int max_units, const Counters* __restrict__ ctr) {
   constexpr int W = 4 * R, PN = 16 * R, S1 = 4 * R, S2 = R * W, KH = R / 2, NT = W / 32;
   constexpr int kPfUnits = pf_units(R);
   constexpr int UC = kPfUnits < NT ? kPfUnits : NT;  // units side by side over the columns
   constexpr int UM = kPfUnits / UC;                  // 1: both row tiles in one unit, 2: one each
   constexpr int NTH = NT / UC, MTH = 2 / UM;         // column and row tiles of one unit
   const int lane = threadIdx.x, half = lane / 32, l32 = lane % 32;
-  const int unit = blockIdx.x;
+  // The grid is sized from an upper bound of the chunk count (the real one is only known on the
+  // device) and capped: a batch with far fewer chunks than its size allows would otherwise spend
+  // its time dispatching empty blocks.  Blocks walk the units with the grid's stride.
+  const int nchunk = ctr->nchunk2;
+  auto do_unit = [&](const int unit) -> bool {  // false: no unit from here on has work
   const int c = unit / kPfUnits, sub = unit % kPfUnits;
   const int nt0 = (sub / UM) * NTH, mt0 = (sub % UM) * MTH;
-  // the chunk's records and descriptor are read together (the grid never exceeds the tables)
+  // the chunk's records and descriptor are read together with the count (max_units keeps the
+  // reads inside the tables)
   const int4 item = c2_item[(size_t)c * kChunk2 + lane % kChunk2];
   const int4 desc = c2_desc[c];
-  if (c >= ctr->nchunk2) return;
+  if (c >= nchunk) return false;
   const int bin = desc.x, cnt = desc.z;
-  if (mt0 * 8 >= cnt) return;  // the chunk has no prefix in this unit's row tile
+  if (mt0 * 8 >= cnt) return true;  // the chunk has no prefix in this unit's row tile
   const float* Bm = g2 + (size_t)bin * S2 + (size_t)(KH * half) * W + nt0 * 32 + l32;
   float b[NTH][KH];
 #pragma unroll
@@ -166,50 +171,66 @@ __global__ __launch_bounds__(kWave) void k_prefix_fwd_mfma(
       }
     }
   }
+  return true;
+  };
+  // rank 64 walks the units with the grid's stride (its grid is capped at what the device holds at
+  // once); the other ranks have one block per possible unit
+  if constexpr (R == 64) {
+    for (int unit = blockIdx.x; unit < max_units; unit += gridDim.x)
+      if (!do_unit(unit)) break;
+  } else {
+    if ((int)blockIdx.x < max_units) (void)do_unit((int)blockIdx.x);
+  }
 }
 
 // ---------------------------------------------------------------------------------------------
-// Gradients at prefix level for one by-i2 chunk (<= 16 prefixes q, Bm = G2[i2]).  Four work units
-// per chunk, one single-wavefront block each:
-//   unit 0,1  dg1part[q] = dPsum_q Bm^T for the first / second eight prefixes: their dPsum rows
-//             stacked (32 x 4R) times Bm^T (4R x R)
-//   unit 2..  one half of the columns of part2[c] = sum_q G1[i1(q)]^T dPsum_q (rank 128: and one
-//             half of its rows)
-//             ((R x 4 cnt) times (4 cnt x 4R))
-// (At rank 128 the part2 units are split over the rows as well, two by two: six units.)
-constexpr int pb_units(int R) { return R >= 128 ? 6 : 4; }
+// Gradients at prefix level for one by-i2 chunk (<= 16 prefixes q, Bm = G2[i2]).  Work units of a
+// chunk, one single-wavefront block (or one turn of a block's loop) each:
+//   row units  dg1part[q] = dPsum_q Bm^T for the first / second eight prefixes: their dPsum rows
+//              stacked (32 x 4R) times Bm^T (4R x R); at rank 64 one unit per 32 of the R columns
+//   col units  a share of the columns of part2[c] = sum_q G1[i1(q)]^T dPsum_q
+//              ((R x 4 cnt) times (4 cnt x 4R)): halves; eighths at rank 64, where a half is a chain
+//              of 256 MFMAs behind 17 us of loads and a batch of few chunks waits for its longest
+//              unit; at rank 128 halves of the columns times halves of the rows
+constexpr int pb_col_units(int R) { return R == 64 ? 8 : 2; }  // units side by side over part2's columns
+constexpr int pb_row_units(int R) { return R == 64 ? 4 : 2; }  // dg1part: two row tiles, at rank 64 times two column tiles
+constexpr int pb_units(int R) { return pb_row_units(R) + pb_col_units(R) * (R >= 128 ? 2 : 1); }
 
 template <int R>
 __global__ __launch_bounds__(kWave) void k_prefix_bwd_mfma(
     const float* __restrict__ g1, const float* __restrict__ g2, const float* __restrict__ dPsum,
     const int4* __restrict__ c2_item, const int4* __restrict__ c2_desc, float* __restrict__ dg1part,
-    float* __restrict__ part2, Counters* __restrict__ ctr) {
+    float* __restrict__ part2, int max_units, Counters* __restrict__ ctr) {
   constexpr int W = 4 * R, PN = 16 * R, S1 = 4 * R, S2 = R * W;
   const int lane = threadIdx.x, half = lane / 32, l32 = lane % 32;
-  const int unit = blockIdx.x;
   constexpr int kPbUnits = pb_units(R);
+  // capped grid, units walked with its stride (see k_prefix_fwd_mfma)
+  const int nchunk = ctr->nchunk2;
+  auto do_unit = [&](const int unit) -> bool {  // false: no unit from here on has work
   const int c = unit / kPbUnits, part = unit % kPbUnits;
   const int4 item = c2_item[(size_t)c * kChunk2 + lane % kChunk2];
   const int4 desc = c2_desc[c];
-  if (c >= ctr->nchunk2) return;
+  if (c >= nchunk) return false;
   const int bin = desc.x, cnt = desc.z;
-  if (part == 1 && cnt <= 8) return;
+  constexpr int kRowUnits = pb_row_units(R);
+  if (part < kRowUnits && (part % 2) == 1 && cnt <= 8) return true;
   const bool mine = lane < cnt;  // records past the chunk's count are unwritten
   const int myq = mine ? item.x : -1;
   const int myi1 = mine ? item.y : 0;
   const float* Bm = g2 + (size_t)bin * S2;
 
-  if (part < 2) {
-    constexpr int NT = (R + 31) / 32, KB = W / 64;
-    const int mt = part;
+  if (part < kRowUnits) {
+    constexpr int KB = W / 64;
+    const int mt = part % 2;
     const int q = __shfl(myq, mt * 8 + l32 / 4), j1 = l32 % 4;
     const f4* arow = (const f4*)(dPsum + (size_t)(q >= 0 ? q : 0) * PN + j1 * W + 32 * half);
     int qrow[4];
 #pragma unroll
     for (int x = 0; x < 4; ++x) qrow[x] = __shfl(myq, mt * 8 + 2 * x + half);
+    constexpr int NTU = (R + 31) / 32 / (kRowUnits / 2);  // 32-column tiles of this unit
 #pragma unroll
-    for (int nt = 0; nt < NT; ++nt) {
-      const int n = nt * 32 + l32;
+    for (int nti = 0; nti < NTU; ++nti) {
+      const int n = ((part / 2) * NTU + nti) * 32 + l32;
       const f4* brow = (const f4*)(Bm + (size_t)(n < R ? n : 0) * W + 32 * half);
       f4 av[2][8], bv[2][8];
 #pragma unroll
@@ -248,9 +269,11 @@ __global__ __launch_bounds__(kWave) void k_prefix_bwd_mfma(
     }
   } else {
     constexpr int MSPLIT = R >= 128 ? 2 : 1;                // units over the rows of part2
-    constexpr int MT = (R + 31) / 32 / MSPLIT, NT = W / 32, NTH = NT / 2;
-    const int nt0 = ((part - 2) % 2) * NTH;
-    const int mrow0 = ((part - 2) / 2) * MT * 32;           // first row of this unit
+    constexpr int CU = pb_col_units(R);
+    constexpr int MT = (R + 31) / 32 / MSPLIT, NT = W / 32, NTH = NT / CU;
+    static_assert(NT % CU == 0, "column tiles divide evenly over the units");
+    const int nt0 = ((part - kRowUnits) % CU) * NTH;
+    const int mrow0 = ((part - kRowUnits) / CU) * MT * 32;  // first row of this unit
     int qh[8], ih[8];  // the eight prefixes whose rows this half of the wavefront feeds as k
 #pragma unroll
     for (int jq = 0; jq < 8; ++jq) {
@@ -297,6 +320,16 @@ __global__ __launch_bounds__(kWave) void k_prefix_bwd_mfma(
         }
       }
     }
+  }
+  return true;
+  };
+  // rank 64 walks the units with the grid's stride (its grid is capped at what the device holds at
+  // once); the other ranks have one block per possible unit
+  if constexpr (R == 64) {
+    for (int unit = blockIdx.x; unit < max_units; unit += gridDim.x)
+      if (!do_unit(unit)) break;
+  } else {
+    if ((int)blockIdx.x < max_units) (void)do_unit((int)blockIdx.x);
   }
 }
 
@@ -1026,6 +1059,22 @@ static inline int grid_cap(int64_t items, int cap) {
 }
 constexpr int kMGridCap = 256 * 8;
 
+// Blocks of `threads` threads of a kernel that the current device holds at once (what the
+// runtime's occupancy calculation says for the kernel's registers and LDS, times the compute
+// units).  The per-chunk kernels launch that many blocks at most and walk their work units with
+// the grid's stride: every block is resident from the start, none waits for another to end.
+template <class K>
+static int resident_blocks(K kernel, int threads) {
+  int per_cu = 0, dev = 0, cus = 0;
+  if (hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, kernel, threads, 0) != hipSuccess ||
+      per_cu < 1)
+    per_cu = 8;
+  if (hipGetDevice(&dev) != hipSuccess ||
+      hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || cus < 1)
+    cus = 256;
+  return per_cu * cus;
+}
+
 #define TT_DISPATCH_R(R_, CALL)      \
   switch (R_) {                      \
     case 16: { constexpr int R = 16; CALL; } break; \
@@ -1055,18 +1104,32 @@ void launch_prefix_fwd_mfma(const Plan& pl, const Workspace& ws, const float* g1
                             int B, hipStream_t st) {
   // one block per possible work unit (upper bound from B); blocks past the real count return at once
   const int64_t chunks = cdivi(std::min<int64_t>(B, pl.maxQ), kChunk2) + pl.sh.n2;
-  const int grid = (int)(chunks * pf_units(pl.sh.r1));
+  const int units = (int)(chunks * pf_units(pl.sh.r1));
+  // Rank 64 launches no more blocks than the device holds at once and lets them walk the units: its
+  // batches often have far fewer chunks than their size allows (clustered ids), and the blocks
+  // that would find no work cost more to dispatch than the work itself.  The other ranks measured
+  // better with one block per possible unit.
+  int grid = units;
+  if (pl.sh.r1 == 64) {
+    if (pl.unit_slots[0] == 0) pl.unit_slots[0] = resident_blocks(k_prefix_fwd_mfma<64>, kWave);
+    grid = std::min(units, pl.unit_slots[0]);
+  }
   TT_DISPATCH_R8(pl.sh.r1, (k_prefix_fwd_mfma<R><<<grid, kWave, 0, st>>>(
-                               g1, g2, ws.c2_item, ws.c2_desc, ws.P, ws.Pt, ws.ctr)));
+                               g1, g2, ws.c2_item, ws.c2_desc, ws.P, ws.Pt, units, ws.ctr)));
 }
 
 void launch_prefix_bwd_mfma(const Plan& pl, const Workspace& ws, const float* g1, const float* g2,
                             int B, hipStream_t st) {
   const int64_t chunks = cdivi(std::min<int64_t>(B, pl.maxQ), kChunk2) + pl.sh.n2;
-  const int grid = (int)(chunks * pb_units(pl.sh.r1));
+  const int units = (int)(chunks * pb_units(pl.sh.r1));
+  int grid = units;  // as for the forward kernel
+  if (pl.sh.r1 == 64) {
+    if (pl.unit_slots[1] == 0) pl.unit_slots[1] = resident_blocks(k_prefix_bwd_mfma<64>, kWave);
+    grid = std::min(units, pl.unit_slots[1]);
+  }
   TT_DISPATCH_R(pl.sh.r1, (k_prefix_bwd_mfma<R><<<grid, kWave, 0, st>>>(
                               g1, g2, ws.dPsum, ws.c2_item, ws.c2_desc, ws.dg1part, ws.part2,
-                              ws.ctr)));
+                              units, ws.ctr)));
 }
 
 void launch_id_bwd_mfma(const Plan& pl, const Workspace& ws, const float* g3, const float* grad,
