@@ -189,9 +189,10 @@ __global__ __launch_bounds__(kWave) void k_prefix_fwd_mfma(
 //   row units  dg1part[q] = dPsum_q Bm^T for the first / second eight prefixes: their dPsum rows
 //              stacked (32 x 4R) times Bm^T (4R x R); at rank 64 one unit per 32 of the R columns
 //   col units  a share of the columns of part2[c] = sum_q G1[i1(q)]^T dPsum_q
-//              ((R x 4 cnt) times (4 cnt x 4R)): halves; eighths at rank 64, where a half is a chain
-//              of 256 MFMAs behind 17 us of loads and a batch of few chunks waits for its longest
-//              unit; at rank 128 halves of the columns times halves of the rows
+//              ((R x 4 cnt) times (4 cnt x 4R)): halves; eighths at rank 64; at rank 128 halves of
+//              the columns times halves of the rows
+// (Rank 64 is cut finer because its batches often have few chunks: the launch then lasts as long
+// as its longest unit, a chain of dependent load and multiply stages.)
 constexpr int pb_col_units(int R) { return R == 64 ? 8 : 2; }  // units side by side over part2's columns
 constexpr int pb_row_units(int R) { return R == 64 ? 4 : 2; }  // dg1part: two row tiles, at rank 64 times two column tiles
 constexpr int pb_units(int R) { return pb_row_units(R) + pb_col_units(R) * (R >= 128 ? 2 : 1); }
