@@ -579,8 +579,11 @@ __global__ __launch_bounds__(kMThreads) void k_id_bwd_mfma(
 // Blocks past the chunk range take the by-i3 chunks of the G3 gradient (dg3_role), one per
 // wavefront; that step only needs the per-id gradient sums and the cached prefix products, so
 // both run side by side.
-// Rank 16 needs half the LDS, so its blocks have four wavefronts (each takes two pairs of prefixes
-// in (i), then (ii), then wavefronts 0 and 1 take (iii)) and twice as many fit a compute unit.
+// Rank 16 needs half the LDS, so its blocks have four wavefronts and twice as many fit a compute
+// unit: in (i) each takes four prefixes, two ids of each in flight together (the same eight id
+// slots per round; tables with many prefixes and few ids per prefix are what these ranks meet, and
+// one pass over four prefixes has half the dependent round trips of two passes over two), then
+// (ii), then wavefronts 0 and 1 take (iii).
 template <int R>
 constexpr int mid_waves() { return R >= 32 ? 8 : 4; }
 constexpr int kXcds = 8;
@@ -597,7 +600,7 @@ __global__ __launch_bounds__(mid_waves<R>() * kWave, 6) void k_bwd_mid_mfma(
   static_assert(R == 8 || R == 16 || R == 32, "the LDS tiles are sized for ranks up to 32");
   constexpr int W = 4 * R, S1 = 4 * R, S2 = R * W, S3 = R * D3, D = 16 * D3;
   constexpr int TS = W + 4;  // padded row stride of the LDS tiles (keeps 16-byte alignment)
-  constexpr int NT16 = (R + 15) / 16, KS = D3 / 4, UB = 4;
+  constexpr int NT16 = (R + 15) / 16, KS = D3 / 4;
   __shared__ __align__(16) float T[64 * TS];
   __shared__ __align__(16) float Bl[R * TS];
   __shared__ int q_of[16], i1_of[16], u0_of[16], u1_of[16];
@@ -641,26 +644,30 @@ __global__ __launch_bounds__(mid_waves<R>() * kWave, 6) void k_bwd_mid_mfma(
   // their results are dropped
   const bool rank_on = R >= 16 || l16 < R;
   const int lrow = rank_on ? l16 : 0;
-  // (i) this wavefront's pairs of prefixes (local numbers 2*pw, 2*pw+1)
-  for (int pw = w; pw < 8; pw += kMidWaves) {
-    f4 acc[2][NT16];
+  // (i) this wavefront's G prefixes (local numbers G*w .. G*w+G-1; two with eight wavefronts, four
+  // with four) in one pass: eight id slots per round, 8/G ids of each prefix.  Lanes 0..7 hold the
+  // round's slots: prefix g = lane / UB of the wavefront, id r*UB + lane % UB of its list.
+  {
+    constexpr int G = 16 / kMidWaves, UB = 8 / G;
+    f4 acc[G][NT16];
 #pragma unroll
-    for (int x = 0; x < 2; ++x)
+    for (int g = 0; g < G; ++g)
 #pragma unroll
-      for (int nt = 0; nt < NT16; ++nt) acc[x][nt] = f4{0.f, 0.f, 0.f, 0.f};
-    const int u0a = u0_of[2 * pw], u0b = u0_of[2 * pw + 1];
-    const int na = u1_of[2 * pw] - u0a, nb = u1_of[2 * pw + 1] - u0b;
-    const int rounds = (max(na, nb) + UB - 1) / UB;
+      for (int nt = 0; nt < NT16; ++nt) acc[g][nt] = f4{0.f, 0.f, 0.f, 0.f};
+    int nmax = 0;
+#pragma unroll
+    for (int g = 0; g < G; ++g) nmax = max(nmax, u1_of[G * w + g] - u0_of[G * w + g]);
+    const int myp = G * w + (lane % 8) / UB;  // the prefix of this lane's slot
+    const int myu0 = u0_of[myp], myn = u1_of[myp] - myu0;
+    const int rounds = (nmax + UB - 1) / UB;
     for (int r = 0; r < rounds; ++r) {
-      // lanes 0..7 hold the round's slots: prefix x = lane/4, id r*UB + lane%4 of its list
       const int si = r * UB + lane % UB;
-      const bool second = (lane / UB) & 1;
-      const bool slot_on = lane < 2 * UB && si < (second ? nb : na);
-      const int uu = slot_on ? (second ? u0b : u0a) + si : 0;
+      const bool slot_on = lane < 8 && si < myn;
+      const int uu = slot_on ? myu0 + si : 0;
       const int mycode = u_code[uu], myi3 = u_i3[uu];
-      float a[2 * UB][KS], b[2 * UB][NT16][KS];
+      float a[8][KS], b[8][NT16][KS];
 #pragma unroll
-      for (int sl = 0; sl < 2 * UB; ++sl) {
+      for (int sl = 0; sl < 8; ++sl) {
         const float* gp = grad_row_ptr(lane_value(mycode, sl), grad, gsum, D) + l16 * D3 + KS * kg;
         const float* cp = g3 + (size_t)lane_value(myi3, sl) * S3 + lrow * D3 + KS * kg;
 #pragma unroll
@@ -673,7 +680,7 @@ __global__ __launch_bounds__(mid_waves<R>() * kWave, 6) void k_bwd_mid_mfma(
       TT_LOADS_DONE();
       const unsigned long long on_mask = __ballot(slot_on);
 #pragma unroll
-      for (int sl = 0; sl < 2 * UB; ++sl) {
+      for (int sl = 0; sl < 8; ++sl) {
         // wavefront-uniform: empty slots cost no matrix-core time
         if ((on_mask >> sl) & 1ull) {
 #pragma unroll
@@ -687,12 +694,12 @@ __global__ __launch_bounds__(mid_waves<R>() * kWave, 6) void k_bwd_mid_mfma(
     // accumulator element v of lane (kg, l16) is dPsum_q[m = 4*kg + v][n = nt*16 + l16], i.e. row
     // j1 = kg of the prefix and column j2*R + n with j2 = v
 #pragma unroll
-    for (int x = 0; x < 2; ++x)
+    for (int g = 0; g < G; ++g)
 #pragma unroll
       for (int nt = 0; nt < NT16; ++nt)
 #pragma unroll
         for (int v = 0; v < 4; ++v)
-          if (rank_on) T[((2 * pw + x) * 4 + kg) * TS + v * R + nt * 16 + l16] = acc[x][nt][v];
+          if (rank_on) T[((G * w + g) * 4 + kg) * TS + v * R + nt * 16 + l16] = acc[g][nt][v];
   }
   __syncthreads();
 
