@@ -118,8 +118,8 @@ def run_lookahead(emb, ids_seq, grad_seq, out_seq, lr, steps, first=0, flow_cont
         if before_step is not None:
             before_step(k)
         emb.forward(ids_seq[k % n], out_seq[k % n])
-        emb.backward_update(grad_seq[k % n], lr)
         emb.prepare(ids_seq[(k + 2) % n])       # index pipeline of the batch after next
+        emb.backward_update(grad_seq[k % n], lr)
         if after_step is not None:
             after_step(k)
 

@@ -212,8 +212,9 @@ int tt_emb_wait_backward(tt_emb_t h, int age);
  * forward asks for is eventually overwritten (the oldest first).  The workspace holds four index
  * sets, which take turns on the library's two streams: one set may be in use by a forward/backward
  * pair while two others are filled, so up to two batches can be ahead, and an index pipeline that is
- * started two steps early has two steps to finish.  Typical use, once per step, before or after the calls of the
- * current batch: forward(ids); ...; backward_update(...); prepare(ids of the batch after next) - the index
+ * started two steps early has two steps to finish.  Typical use, once per step, anywhere around
+ * the calls of the current batch: forward(ids); prepare(ids of the batch after next); ...;
+ * backward_update(...) - the index
  * work of coming batches then overlaps this batch's arithmetic (minibatch samplers know the next
  * ids early).  An ids buffer must keep its contents until the forward that uses it has been enqueued.
  * Results are identical with or without it.  tt_emb_get_stats refers to the latest forward only
